@@ -1,0 +1,145 @@
+"""Benchmark of the mixed-batch serving step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg1|cfg2] [--no-cpu-baseline]
+
+A step is one pass of the whole layer (RMSNorm, QKV, rotary + KV append, paged attention,
+O-projection, SwiGLU feed-forward) over one batch of synthetic input that is already resident
+in HBM.  The default workload is the decode-only batch (64 decode tokens, KV lengths uniform in
+[512, 4096], 8B-shaped layer).  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg2"])
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def cpu_baseline(batch, weights, n_runs=2):
+    """The oracle as it stands, timed on the host cores on the same workload (whole step)."""
+    import numpy as np
+    from oracle import run as orun
+    from paper_2507_17769_amd import workloads as W
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    model = W.MODELS[batch.model]
+    pool = orun.make_pool(model, batch.n_pool_pages)
+    for i, s in enumerate(batch.seqs):
+        if s.prefix > 0:
+            k, v = batch.prefix_kv(i)
+            pool.write_bits(0, [int(p) for p in s.pages], 0, k, v)
+    x = batch.activations()
+    times = []
+    for _ in range(n_runs):
+        t0 = time.perf_counter()
+        orun.run_step(model, [weights], batch.seqs, x, pool)
+        times.append(time.perf_counter() - t0)
+    t = sorted(times)[len(times) // 2] if len(times) % 2 else min(times)
+    return {"value": batch.n_tokens / t, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"the whole {batch.name} step (all {batch.n_tokens} tokens, {batch.total_kv} KV tokens), "
+                      f"best of {n_runs} runs, {t * 1e3:.0f} ms per step, numpy fp32",
+            "ms_per_step": t * 1e3}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2507_17769_amd import workloads as W
+    from paper_2507_17769_amd.binding import STAGE_NAMES, SeqArray
+    from paper_2507_17769_amd.runner import Engine, bits_to_dev
+
+    cfg = {"cfg1": 1, "cfg2": 2}[a.workload]
+    batch = W.config_batch(cfg, a.seed)
+    model = W.MODELS[batch.model]
+    weights = W.layer_weights(batch.model, a.seed, 0)
+    eng = Engine(batch.model, batch.n_pool_pages, max_position=max(s.kv_len for s in batch.seqs) + 16)
+    eng.load_layer(0, weights)
+    eng.load_prefixes(batch)
+    x = bits_to_dev(batch.activations(), eng.device)
+    out = torch.empty_like(x)
+    seqs = SeqArray(batch.seqs)
+    T, total_kv = batch.n_tokens, batch.total_kv
+
+    for _ in range(a.warmup):
+        eng.ctx.step(seqs, x.data_ptr(), out.data_ptr())
+    eng.ctx.sync()
+    eng.ctx.set_option("time_attention", 1)          # two event records per step, on the step's stream
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        eng.ctx.step(seqs, x.data_ptr(), out.data_ptr())
+    eng.ctx.sync()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    attn_ms = eng.ctx.attention_times()
+    eng.ctx.set_option("time_attention", 0)
+    ms_per_step = (t1 - t0) * 1e3 / a.steps
+
+    # per-stage split (separate, synchronous passes; not part of the timed region)
+    stage = np.zeros(len(STAGE_NAMES))
+    n_stat = 10
+    for _ in range(n_stat):
+        st = eng.ctx.step(seqs, x.data_ptr(), out.data_ptr(), want_stats=True)
+        stage += np.array(list(st.ms_stage))
+    stage /= n_stat
+
+    H, F = model["hidden"], model["ffn"]
+    nq, nkv, d = model["n_q"], model["n_kv"], model["head_dim"]
+    params = H * (nq + 2 * nkv) * d + nq * d * H + 3 * H * F
+    kv_bytes_per_token = 2 * nkv * d * 2
+    attn_avg_ms = float(np.mean(attn_ms)) if attn_ms else float("nan")
+    # dominant kernel of the decode-only step: paged attention, bound by the KV bytes it must read
+    attn_bytes = kv_bytes_per_token * total_kv
+    achieved = attn_bytes / (attn_avg_ms * 1e-3) / 1e9
+    gemm_ms = float(stage[1] + stage[4] + stage[6] + stage[7])
+    res = {
+        "metric": "mixed_batch_step_throughput", "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{batch.name}: 8B-shaped layer (hidden 4096, 32 q / 8 kv heads, d 128, ffn 14336), "
+                               f"{T} new tokens ({sum(1 for s in batch.seqs if s.n_new == 1)} decodes"
+                               f"{', 512-token chunk at prefix 2048' if cfg == 2 else ''}), {total_kv} KV tokens, "
+                               f"16-token pages, seed {a.seed}",
+                   "n_tokens": T, "total_kv": total_kv, "n_layers": 1},
+        "roofline": {"bound": "hbm", "kernel": "attn_kernel (paged attention, split merge excluded)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None, "algorithmic_bytes_per_launch": attn_bytes, "avg_launch_ms": attn_avg_ms,
+                     "launches_timed": len(attn_ms)},
+        "stage_ms": {n: round(float(v), 4) for n, v in zip(STAGE_NAMES, stage)},
+        "gemm": {"ms": gemm_ms, "weight_GBs": 2 * params / (gemm_ms * 1e-3) / 1e9,
+                 "tflops": 2 * params * T / (gemm_ms * 1e-3) / 1e12,
+                 "frac_hbm": 2 * params / (gemm_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                 "frac_mfma": 2 * params * T / (gemm_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
+    }
+    if not a.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(batch, weights)
+    eng.close()
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,245 @@
+/*
+ * polystep — one mixed-batch serving iteration of a decoder-only transformer on one
+ * AMD MI355X (gfx950): a chunk of prefill tokens plus one token per running decode
+ * request, over a paged KV cache with 16-token pages.
+ *
+ * This is the engine iteration that PolyServe's router profiles and schedules
+ * (Sec. 2.1 "LLM Inference Workflow": the layer; Sec. 2.4: chunked prefill batches all
+ * current decodes with a prefill chunk; Sec. 4.5 "Profile-Based Batch Formation": the
+ * router consumes a (batch size, KV cache size) -> iteration time table measured on the
+ * engine).  The paper's router owns the request queues and dispatches batches to the
+ * engine (Sec. 6.1), which is the shape of this interface: the caller describes a batch,
+ * the library runs it.
+ *
+ * Conventions
+ *  - Every call returns ps_status; nothing throws or aborts across this boundary.
+ *    ps_last_error() gives a human-readable reason for the last failure.
+ *  - "device" pointers are HIP device memory on the context's GPU; "host" pointers are
+ *    ordinary process memory.  The caller owns every buffer it passes in; the library owns
+ *    the context, its repacked weight copies, the KV pool, allocator state and workspaces.
+ *  - All floating-point tensors crossing the boundary are bfloat16 (bits of the upper half
+ *    of an IEEE binary32), row-major.  Accumulation is fp32 on the device.
+ *  - Calls that launch work are asynchronous on the stream given to ps_create unless
+ *    stated otherwise; ps_sync() waits for it.  A context is not thread-safe.
+ *  - A batch is validated completely on the host before anything is launched: a failing
+ *    call leaves device state untouched.
+ */
+#ifndef POLYSTEP_H
+#define POLYSTEP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ps_ctx ps_ctx;
+
+typedef enum {
+    PS_OK = 0,
+    PS_EINVAL = 1,  /* null pointer, unsupported shape, malformed batch record          */
+    PS_ERANGE = 2,  /* page id / position / layer index outside its range               */
+    PS_ENOMEM = 3,  /* KV pool exhausted, or a host/device allocation failed            */
+    PS_ESTATE = 4,  /* call out of order: layer not initialised, no KV pool, host-only  */
+    PS_EDEVICE = 5  /* a HIP call failed; ps_last_error() carries HIP's message         */
+} ps_status;
+
+#define PS_PAGE_SIZE 16
+#define PS_N_STAGES 8
+#define PS_GRID_MAX_DRAWS 8
+
+/* ps_model_desc.flags */
+#define PS_FLAG_HOST_ONLY 1u /* no device is touched: allocator, index and planning calls only */
+
+/* Layer shape (Sec. 5.1 "Model and GPU": a GQA decoder of the LLaMA family).
+ * Supported: head_dim 64 or 128; n_q_heads / n_kv_heads in {1,2,4,8,16}; hidden, ffn and
+ * n_q_heads*head_dim multiples of 64; page_size 16.  rms_eps <= 0 selects 1e-5. */
+typedef struct {
+    int32_t hidden, n_q_heads, n_kv_heads, head_dim, ffn, n_layers;
+    int32_t page_size;    /* must be 16 */
+    int32_t max_position; /* largest kv_len any sequence may reach (rotary table size) */
+    float rms_eps, rope_base;
+    uint32_t flags;
+} ps_model_desc;
+
+/* One layer's weights: device pointers, bfloat16, math layout [in][out] row-major, no
+ * biases.  w_qkv has the query, key and value column blocks in that order
+ * ([hidden][(n_q + 2 n_kv) * head_dim]); w_o [n_q*head_dim][hidden]; w_gate, w_up
+ * [hidden][ffn]; w_down [ffn][hidden]; g_attn, g_ffn [hidden] RMSNorm gains. */
+typedef struct {
+    const void *w_qkv, *w_o, *w_gate, *w_up, *w_down, *g_attn, *g_ffn;
+} ps_layer_weights;
+
+/* One sequence of a batch (Sec. 2.4): n_new tokens are fed this step (1 for a decode,
+ * the chunk size for a prefill chunk); kv_len is the attended span AFTER the step, the
+ * new tokens included, so the cached prefix is kv_len - n_new and a decode with
+ * kv_len 1 attends to its own key only.  page_table (host, caller-owned) lists physical
+ * page ids: logical position p lives in page page_table[p / 16], slot p % 16.
+ * Requirements: n_new >= 1, n_new <= kv_len <= max_position, n_pages >= ceil(kv_len/16),
+ * page ids inside the pool, no page shared by two sequences of one batch, req_ids unique. */
+typedef struct {
+    int64_t req_id;
+    int32_t n_new;
+    int32_t kv_len;
+    const int32_t* page_table;
+    int32_t n_pages;
+} ps_seq;
+
+/* Per-step measurements.  Stages, summed over layers:
+ * 0 RMSNorm(attn)  1 QKV GEMM  2 RoPE + KV append  3 attention (+ split merge)
+ * 4 O GEMM + residual  5 RMSNorm(ffn)  6 gate/up GEMM + SwiGLU  7 down GEMM + residual */
+typedef struct {
+    int32_t n_tokens;        /* sum of n_new */
+    int64_t total_kv;        /* sum of kv_len */
+    int32_t n_attn_items;    /* work items of the attention launch (per layer) */
+    int32_t n_attn_partials; /* of which wrote a split partial */
+    float ms_total;          /* first launch to last, HIP events */
+    float ms_stage[PS_N_STAGES];
+} ps_step_stats;
+
+/* Optional copies of one layer's intermediates, for numerical checks.  Any pointer may be
+ * null.  Device buffers, written during ps_step: xn, xn2 [T][hidden] bf16; q [T][n_q][d]
+ * bf16 after rotation; attn [T][n_q*d] bf16; x1 [T][hidden] fp32 (input + attention
+ * branch); act [T][ffn] bf16 (silu(gate)*up). */
+typedef struct {
+    void *xn, *q, *attn, *x1, *xn2, *act;
+} ps_taps;
+
+/* ---- lifetime ------------------------------------------------------------------- */
+
+/* Create a context for `desc` on the current HIP device.  hip_stream is a hipStream_t
+ * (null = the default stream) on which all work is enqueued.  With PS_FLAG_HOST_ONLY no
+ * HIP call is ever made and every call that needs the device returns PS_ESTATE.
+ * Errors: PS_EINVAL (null, unsupported shape), PS_ENOMEM, PS_EDEVICE. */
+ps_status ps_create(const ps_model_desc* desc, void* hip_stream, ps_ctx** out);
+
+/* Wait for all work enqueued by this context. */
+ps_status ps_sync(ps_ctx* ctx);
+
+/* Free everything the context owns (waits for outstanding work first).  Null is a no-op. */
+void ps_destroy(ps_ctx* ctx);
+
+/* Reason for the most recent failing call on ctx (or, with ctx == NULL, of the most
+ * recent failing ps_create on this thread).  Never null; valid until the next call. */
+const char* ps_last_error(const ps_ctx* ctx);
+
+/* Tuning knobs, mainly for tests: "attn_split_pages" (target KV pages per attention
+ * work item; different values must give the same results within rounding),
+ * "gemm_split_k" (0 = automatic), "out_f32" (1: ps_step writes x_out as fp32 [T][hidden],
+ * the precision the residual stream is kept in, instead of rounding it to bf16).
+ * "time_attention" (1: bracket every attention kernel launch with HIP events, see
+ * ps_attention_times).  PS_EINVAL for an unknown name or bad value. */
+ps_status ps_set_option(ps_ctx* ctx, const char* name, int64_t value);
+
+/* ---- weights (Sec. 2.1: attention module, O-projection, gated feed-forward) -------- */
+
+/* Copy layer `layer`'s weights into the library's own MFMA-friendly layout (W^T for the
+ * GEMMs; gate and up columns interleaved so SwiGLU runs in the GEMM epilogue).  The
+ * caller may free its buffers once ps_sync() has returned.  May be called again to
+ * replace a layer.  Errors: PS_ERANGE (layer), PS_EINVAL (null pointer), PS_ENOMEM. */
+ps_status ps_init_layer(ps_ctx* ctx, int32_t layer, const ps_layer_weights* w);
+
+/* ---- paged KV cache (Sec. 2.1: prefill fills the KV cache, decode extends it) --------- */
+
+/* Allocate a pool of n_pages pages for n_kv_layers physical KV layer slots (layer l uses
+ * slot l mod n_kv_layers), zero it, and seed the allocator: the free list is the
+ * Fisher-Yates shuffle of 0..n_pages-1 driven by splitmix64(perm_seed) (i from n_pages-1
+ * down to 1, j = next() mod (i+1), swap).  Replaces any previous pool and forgets all
+ * reservations.  Errors: PS_EINVAL, PS_ENOMEM. */
+ps_status ps_kv_alloc(ps_ctx* ctx, int32_t n_pages, int32_t n_kv_layers, uint64_t perm_seed);
+
+/* Make request req_id own ceil(kv_len/16) pages, popping new ones from the front of the
+ * free list; writes its whole page list to pages_out[0..*n_out).  All-or-nothing:
+ * PS_ENOMEM if the pool cannot cover the growth, PS_ERANGE if cap is too small. */
+ps_status ps_kv_reserve(ps_ctx* ctx, int64_t req_id, int32_t kv_len, int32_t* pages_out, int32_t cap, int32_t* n_out);
+
+/* Return req_id's pages to the back of the free list, in hand-out order.  PS_EINVAL if unknown. */
+ps_status ps_kv_release(ps_ctx* ctx, int64_t req_id);
+
+/* Number of pages currently on the free list (negative if there is no pool). */
+int32_t ps_kv_free_pages(const ps_ctx* ctx);
+
+/* Store / fetch keys and values of logical positions pos0 .. pos0+n-1 of `seq` in KV layer
+ * slot `layer mod n_kv_layers`.  k and v are device bf16 [n][n_kv_heads][head_dim]; keys
+ * are stored as given (the cache holds keys after rotation).  Only seq->page_table and
+ * n_pages are used.  Used to load a cached prefix, to snapshot, and as the payload of a
+ * prefill->decode hand-off (Sec. 2.4).  Errors: PS_ERANGE (position or page id). */
+ps_status ps_kv_write(ps_ctx* ctx, int32_t layer, const ps_seq* seq, int32_t pos0, int32_t n, const void* k, const void* v);
+ps_status ps_kv_read(ps_ctx* ctx, int32_t layer, const ps_seq* seq, int32_t pos0, int32_t n, void* k, void* v);
+
+/* ---- the step (Sec. 2.1 layer, Sec. 2.4 mixed batch) ------------------------------- */
+
+/* Run all n_layers layers over the batch.  x_in, x_out: device bf16 [T][hidden] (x_out is
+ * fp32 [T][hidden] while option "out_f32" is set),
+ * T = sum of n_new, sequences concatenated in the order given; x_out may alias x_in.
+ * Between layers, and between the two halves of a layer, the residual stream is kept in
+ * fp32; queries, keys and values are rounded to bf16 once, after rotation.
+ * Per layer: RMSNorm -> QKV -> rotary embedding on q,k -> append k,v to the pages ->
+ * causal attention of each new token over cache positions 0..its own (Softmax(QK^T/sqrt d)V,
+ * query head h reading KV head h / (n_q/n_kv)) -> O-projection + residual -> RMSNorm ->
+ * silu(gate) * up -> down projection + residual.
+ * n_seqs == 0 is a valid empty step (nothing is launched).  With stats != NULL the call
+ * records HIP events per stage and returns only after the step has finished.
+ * Errors: PS_EINVAL / PS_ERANGE for a malformed batch (see ps_seq), PS_ESTATE if a layer
+ * or the pool is missing; on any error nothing has been launched. */
+ps_status ps_step(ps_ctx* ctx, const ps_seq* seqs, int32_t n_seqs, const void* x_in, void* x_out, ps_step_stats* stats);
+
+/* Integer side of a step, host only, no launch: cu_seqlens [n_seqs+1] (exclusive scan of
+ * n_new), positions [T] (kv_len - n_new + i), slot_mapping [T] (page id * 16 + position
+ * % 16): the cache slots the step's KV append writes.  Output arrays are host memory; any
+ * may be null.  Same validation as ps_step (the pool-size check is skipped when no pool exists). */
+ps_status ps_step_indices(ps_ctx* ctx, const ps_seq* seqs, int32_t n_seqs, int32_t* cu_seqlens, int32_t* positions, int32_t* slot_mapping);
+
+/* The attention work list the step would launch, host only.  Each item is 8 int32:
+ * {seq index, kv head, first new-token index of its query block, number of query tokens,
+ *  first KV page (logical), one past last KV page, partial slot or -1 when the item
+ *  writes final output, merge group}.  Writes min(*n_items, cap) items. */
+ps_status ps_plan_attention(ps_ctx* ctx, const ps_seq* seqs, int32_t n_seqs, int32_t* items, int32_t cap, int32_t* n_items);
+
+/* Durations (ms) of the attention kernel launches (one per layer per step, split merge
+ * excluded) recorded since the previous call while option "time_attention" was on; at most
+ * 2048 are kept.  Waits for the stream.  Writes min(count, cap) values to ms (host) and the
+ * number written to *n.  This is the kernel the roofline of a decode-heavy step is quoted on
+ * (Sec. 2.2: decode attention does not batch; its cost follows the KV bytes read). */
+ps_status ps_attention_times(ps_ctx* ctx, float* ms, int32_t cap, int32_t* n);
+
+/* Ask subsequent steps to copy layer `layer`'s intermediates; taps == NULL switches it off. */
+ps_status ps_set_taps(ps_ctx* ctx, int32_t layer, const ps_taps* taps);
+
+/* ---- latency profile (Sec. 4.5: the (batch size, KV cache size) -> time map) -------- */
+
+/* One cell of the grid: a prefill chunk of `chunk` tokens (0 = none) plus n_decode decode
+ * tokens, timed for n_draws (<= PS_GRID_MAX_DRAWS) draws of the lengths: chunk_prefix
+ * [n_draws] is the chunk's cached prefix, decode_kv [n_draws][n_decode] the decode KV
+ * lengths after the step (host arrays drawn by the caller). */
+typedef struct {
+    int32_t chunk, n_decode, n_draws;
+    const int32_t* chunk_prefix;
+    const int32_t* decode_kv;
+} ps_grid_cell_spec;
+
+typedef struct {
+    int32_t warmup; /* untimed steps per draw */
+    int32_t iters;  /* timed steps per draw; the draw's time is their median */
+} ps_grid_opts;
+
+typedef struct {
+    int32_t chunk, n_decode, n_tokens, n_draws;
+    int64_t total_kv;               /* of the median draw */
+    float median_ms;                /* median over draws of the per-draw median step time */
+    float stage_ms[PS_N_STAGES];    /* per-stage times of the median draw */
+    float draw_ms[PS_GRID_MAX_DRAWS];
+    int64_t draw_total_kv[PS_GRID_MAX_DRAWS];
+} ps_grid_cell;
+
+/* Time every cell.  Pages for the synthetic requests come from the context's allocator
+ * and are released again; x_in / x_out are device bf16 [max tokens of any cell][hidden]
+ * scratch supplied by the caller (x_in's contents are the activations used).  Synchronous.
+ * Errors: PS_ENOMEM if the free pages cannot hold a cell, plus ps_step's. */
+ps_status ps_profile_grid(ps_ctx* ctx, const ps_grid_cell_spec* cells, int32_t n_cells, const ps_grid_opts* opts,
+                          const void* x_in, void* x_out, ps_grid_cell* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* POLYSTEP_H */

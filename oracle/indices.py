@@ -10,8 +10,8 @@ prefill tokens.  Each sequence s in the batch is described by
                 page pages[s][p // 16], slot p % 16
 
 so the cached prefix is kv_len - n_new and the new tokens sit at positions
-prefix ... kv_len-1.  A decode is the n_new = 1 case ("the previous token is fed
-into the model", Sec. 2.1).
+prefix ... kv_len-1.  A decode is the n_new = 1 case: each decode iteration feeds
+the one token generated last (Sec. 2.1).
 """
 import numpy as np
 

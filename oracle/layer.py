@@ -146,7 +146,7 @@ def silu(z):
     return z / (1.0 + np.exp(-z))
 
 
-def layer_forward(x, w, seqs, pool, slot, shape, taps=None):
+def layer_forward(x, w, seqs, pool, slot, shape, taps=None, bf16_activations=False):
     """One decoder layer over the concatenated new tokens.
 
     x [T][hidden] float; w maps names to float arrays in math layout [in][out]
@@ -154,7 +154,17 @@ def layer_forward(x, w, seqs, pool, slot, shape, taps=None):
     gains g_attn, g_ffn).  Appends this step's keys/values to pool[slot] and
     returns the layer output [T][hidden].  `taps`, if a dict, receives the
     intermediates by name.
+
+    bf16_activations=False is the definition.  With True, the tensors that a
+    bf16-storage implementation feeds to its matrix units (normalised inputs,
+    rotated queries, attention output, gated activation) are additionally rounded
+    to bfloat16 where they are produced, everything else unchanged; comparing an
+    implementation against this variant separates "rounds in the stated places"
+    from "computes something else".
     """
+    def stored(a):
+        return bf16.round_trip(a.astype(np.float32)).astype(a.dtype) if bf16_activations else a
+
     T = x.shape[0]
     nq, nkv, d = shape.n_q, shape.n_kv, shape.head_dim
     dt = x.dtype
@@ -162,12 +172,12 @@ def layer_forward(x, w, seqs, pool, slot, shape, taps=None):
 
     pos = np.concatenate([np.arange(s.kv_len - s.n_new, s.kv_len) for s in seqs]) if seqs else np.zeros(0, int)
 
-    xn = rmsnorm(x, w["g_attn"].astype(dt), shape.rms_eps)
+    xn = stored(rmsnorm(x, w["g_attn"].astype(dt), shape.rms_eps))
     qkv = xn @ w["w_qkv"].astype(dt)
     q = qkv[:, :nq * d].reshape(T, nq, d)
     k = qkv[:, nq * d:(nq + nkv) * d].reshape(T, nkv, d)
     v = qkv[:, (nq + nkv) * d:].reshape(T, nkv, d)
-    q = rope(q, pos, shape.rope_base)
+    q = stored(rope(q, pos, shape.rope_base))
     k = rope(k, pos, shape.rope_base)
 
     t0 = 0
@@ -176,14 +186,14 @@ def layer_forward(x, w, seqs, pool, slot, shape, taps=None):
                    k[t0:t0 + sq.n_new].astype(np.float32), v[t0:t0 + sq.n_new].astype(np.float32))
         t0 += sq.n_new
 
-    attn = attention_paged(q, seqs, pool, slot, nkv)
+    attn = stored(attention_paged(q, seqs, pool, slot, nkv))
     o = attn.reshape(T, nq * d) @ w["w_o"].astype(dt)
     x1 = x + o
 
-    xn2 = rmsnorm(x1, w["g_ffn"].astype(dt), shape.rms_eps)
+    xn2 = stored(rmsnorm(x1, w["g_ffn"].astype(dt), shape.rms_eps))
     gate = xn2 @ w["w_gate"].astype(dt)
     up = xn2 @ w["w_up"].astype(dt)
-    act = silu(gate) * up
+    act = stored(silu(gate) * up)
     f = act @ w["w_down"].astype(dt)
     out = x1 + f
 
@@ -192,13 +202,13 @@ def layer_forward(x, w, seqs, pool, slot, shape, taps=None):
     return out
 
 
-def stack_forward(x, layers, seqs, pool, shape, taps=None):
+def stack_forward(x, layers, seqs, pool, shape, taps=None, bf16_activations=False):
     """Run `layers` (a list of weight dicts) in order; layer l uses KV slot
     l mod n_slots.  Activations stay in x's dtype between layers."""
     n_slots = pool.bits.shape[0]
     for l, w in enumerate(layers):
         t = {} if taps is not None else None
-        x = layer_forward(x, w, seqs, pool, l % n_slots, shape, t)
+        x = layer_forward(x, w, seqs, pool, l % n_slots, shape, t, bf16_activations)
         if taps is not None:
             taps[l] = t
     return x

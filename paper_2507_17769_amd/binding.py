@@ -1,0 +1,232 @@
+"""ctypes binding over libpolystep.so: argument marshalling only.
+
+Function names and argument order mirror include/polystep.h.  Device buffers are passed as
+integer addresses (e.g. torch.Tensor.data_ptr()); every step of the path runs inside the
+library's HIP kernels.  Importing this module fails loudly if the library has not been built
+(`python -m paper_2507_17769_amd.build`): there is no fallback path.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+import torch  # noqa: F401  -- first, on purpose: the process must hold ONE HIP runtime.  torch ships its own
+#                libamdhip64; loading it before libpolystep makes the dynamic loader resolve our
+#                dependency to that same copy, so device pointers and streams are shared.
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpolystep.so")
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2507_17769_amd.build`")
+lib = C.CDLL(LIB_PATH)
+
+PS_OK, PS_EINVAL, PS_ERANGE, PS_ENOMEM, PS_ESTATE, PS_EDEVICE = range(6)
+STATUS_NAMES = ["PS_OK", "PS_EINVAL", "PS_ERANGE", "PS_ENOMEM", "PS_ESTATE", "PS_EDEVICE"]
+PS_PAGE_SIZE = 16
+PS_N_STAGES = 8
+PS_GRID_MAX_DRAWS = 8
+PS_FLAG_HOST_ONLY = 1
+STAGE_NAMES = ["rmsnorm_attn", "gemm_qkv", "rope_append", "attention", "gemm_o", "rmsnorm_ffn", "gemm_gate_up", "gemm_down"]
+
+
+class ps_model_desc(C.Structure):
+    _fields_ = [("hidden", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("ffn", C.c_int32), ("n_layers", C.c_int32), ("page_size", C.c_int32), ("max_position", C.c_int32),
+                ("rms_eps", C.c_float), ("rope_base", C.c_float), ("flags", C.c_uint32)]
+
+
+class ps_layer_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("w_qkv", "w_o", "w_gate", "w_up", "w_down", "g_attn", "g_ffn")]
+
+
+class ps_seq(C.Structure):
+    _fields_ = [("req_id", C.c_int64), ("n_new", C.c_int32), ("kv_len", C.c_int32),
+                ("page_table", C.POINTER(C.c_int32)), ("n_pages", C.c_int32)]
+
+
+class ps_step_stats(C.Structure):
+    _fields_ = [("n_tokens", C.c_int32), ("total_kv", C.c_int64), ("n_attn_items", C.c_int32),
+                ("n_attn_partials", C.c_int32), ("ms_total", C.c_float), ("ms_stage", C.c_float * PS_N_STAGES)]
+
+
+class ps_taps(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("xn", "q", "attn", "x1", "xn2", "act")]
+
+
+class ps_grid_cell_spec(C.Structure):
+    _fields_ = [("chunk", C.c_int32), ("n_decode", C.c_int32), ("n_draws", C.c_int32),
+                ("chunk_prefix", C.POINTER(C.c_int32)), ("decode_kv", C.POINTER(C.c_int32))]
+
+
+class ps_grid_opts(C.Structure):
+    _fields_ = [("warmup", C.c_int32), ("iters", C.c_int32)]
+
+
+class ps_grid_cell(C.Structure):
+    _fields_ = [("chunk", C.c_int32), ("n_decode", C.c_int32), ("n_tokens", C.c_int32), ("n_draws", C.c_int32),
+                ("total_kv", C.c_int64), ("median_ms", C.c_float), ("stage_ms", C.c_float * PS_N_STAGES),
+                ("draw_ms", C.c_float * PS_GRID_MAX_DRAWS), ("draw_total_kv", C.c_int64 * PS_GRID_MAX_DRAWS)]
+
+
+_P = C.c_void_p
+_I32P = C.POINTER(C.c_int32)
+_SIGS = {
+    "ps_create": (C.c_int, [C.POINTER(ps_model_desc), _P, C.POINTER(_P)]),
+    "ps_sync": (C.c_int, [_P]),
+    "ps_destroy": (None, [_P]),
+    "ps_last_error": (C.c_char_p, [_P]),
+    "ps_set_option": (C.c_int, [_P, C.c_char_p, C.c_int64]),
+    "ps_init_layer": (C.c_int, [_P, C.c_int32, C.POINTER(ps_layer_weights)]),
+    "ps_kv_alloc": (C.c_int, [_P, C.c_int32, C.c_int32, C.c_uint64]),
+    "ps_kv_reserve": (C.c_int, [_P, C.c_int64, C.c_int32, _I32P, C.c_int32, _I32P]),
+    "ps_kv_release": (C.c_int, [_P, C.c_int64]),
+    "ps_kv_free_pages": (C.c_int32, [_P]),
+    "ps_kv_write": (C.c_int, [_P, C.c_int32, C.POINTER(ps_seq), C.c_int32, C.c_int32, _P, _P]),
+    "ps_kv_read": (C.c_int, [_P, C.c_int32, C.POINTER(ps_seq), C.c_int32, C.c_int32, _P, _P]),
+    "ps_step": (C.c_int, [_P, C.POINTER(ps_seq), C.c_int32, _P, _P, C.POINTER(ps_step_stats)]),
+    "ps_step_indices": (C.c_int, [_P, C.POINTER(ps_seq), C.c_int32, _I32P, _I32P, _I32P]),
+    "ps_plan_attention": (C.c_int, [_P, C.POINTER(ps_seq), C.c_int32, _I32P, C.c_int32, _I32P]),
+    "ps_set_taps": (C.c_int, [_P, C.c_int32, C.POINTER(ps_taps)]),
+    "ps_attention_times": (C.c_int, [_P, C.POINTER(C.c_float), C.c_int32, _I32P]),
+    "ps_profile_grid": (C.c_int, [_P, C.POINTER(ps_grid_cell_spec), C.c_int32, C.POINTER(ps_grid_opts), _P, _P,
+                                  C.POINTER(ps_grid_cell)]),
+}
+EXPORTS = sorted(_SIGS)
+for _name, (_res, _args) in _SIGS.items():
+    _f = getattr(lib, _name)
+    _f.restype, _f.argtypes = _res, _args
+
+
+class PolystepError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"{STATUS_NAMES[status] if 0 <= status < 6 else status}: {message}")
+        self.status = status
+
+
+def _as_i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+class SeqArray:
+    """A C array of ps_seq plus the int32 page tables it points into (kept alive here)."""
+
+    def __init__(self, seqs):
+        """seqs: iterable of (req_id, n_new, kv_len, pages) or objects with those attributes."""
+        rows = [s if isinstance(s, tuple) else (s.req_id, s.n_new, s.kv_len, s.pages) for s in seqs]
+        self.n = len(rows)
+        self._tables = [_as_i32(r[3]) for r in rows]
+        self.array = (ps_seq * max(self.n, 1))()
+        for i, (r, t) in enumerate(zip(rows, self._tables)):
+            self.array[i] = ps_seq(int(r[0]), int(r[1]), int(r[2]), t.ctypes.data_as(_I32P), len(t))
+        self.n_tokens = sum(int(r[1]) for r in rows)
+
+
+class Context:
+    """Owns one ps_ctx.  Methods are the C entry points with the ps_ prefix dropped."""
+
+    def __init__(self, hidden, n_q_heads, n_kv_heads, head_dim, ffn, n_layers=1, max_position=8192, rms_eps=1e-5,
+                 rope_base=10000.0, host_only=False, stream=0):
+        self.desc = ps_model_desc(hidden, n_q_heads, n_kv_heads, head_dim, ffn, n_layers, PS_PAGE_SIZE, max_position,
+                                  rms_eps, rope_base, PS_FLAG_HOST_ONLY if host_only else 0)
+        h = _P()
+        st = lib.ps_create(C.byref(self.desc), _P(stream), C.byref(h))
+        if st != PS_OK:
+            raise PolystepError(st, lib.ps_last_error(None).decode())
+        self.handle = h
+
+    def _check(self, st):
+        if st != PS_OK:
+            raise PolystepError(st, lib.ps_last_error(self.handle).decode())
+
+    def destroy(self):
+        if getattr(self, "handle", None):
+            lib.ps_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        self.destroy()
+
+    def sync(self):
+        self._check(lib.ps_sync(self.handle))
+
+    def set_option(self, name, value):
+        self._check(lib.ps_set_option(self.handle, name.encode(), int(value)))
+
+    def init_layer(self, layer, **ptrs):
+        w = ps_layer_weights(*[int(ptrs[n]) for n, _ in ps_layer_weights._fields_])
+        self._check(lib.ps_init_layer(self.handle, layer, C.byref(w)))
+
+    def kv_alloc(self, n_pages, n_kv_layers=1, perm_seed=0):
+        self._check(lib.ps_kv_alloc(self.handle, n_pages, n_kv_layers, perm_seed))
+
+    def kv_reserve(self, req_id, kv_len):
+        cap = max(1, (kv_len + PS_PAGE_SIZE - 1) // PS_PAGE_SIZE + 4096)
+        buf = np.zeros(cap, dtype=np.int32)
+        n = C.c_int32(0)
+        self._check(lib.ps_kv_reserve(self.handle, req_id, kv_len, buf.ctypes.data_as(_I32P), cap, C.byref(n)))
+        return buf[:n.value].copy()
+
+    def kv_release(self, req_id):
+        self._check(lib.ps_kv_release(self.handle, req_id))
+
+    def kv_free_pages(self):
+        return lib.ps_kv_free_pages(self.handle)
+
+    def kv_write(self, layer, pages, pos0, n, k_ptr, v_ptr):
+        sa = SeqArray([(0, 1, 1, pages)])
+        self._check(lib.ps_kv_write(self.handle, layer, sa.array, pos0, n, _P(k_ptr), _P(v_ptr)))
+
+    def kv_read(self, layer, pages, pos0, n, k_ptr, v_ptr):
+        sa = SeqArray([(0, 1, 1, pages)])
+        self._check(lib.ps_kv_read(self.handle, layer, sa.array, pos0, n, _P(k_ptr), _P(v_ptr)))
+
+    def step(self, seqs, x_in_ptr, x_out_ptr, want_stats=False):
+        sa = seqs if isinstance(seqs, SeqArray) else SeqArray(seqs)
+        stats = ps_step_stats() if want_stats else None
+        self._check(lib.ps_step(self.handle, sa.array, sa.n, _P(x_in_ptr), _P(x_out_ptr),
+                                C.byref(stats) if want_stats else None))
+        return stats
+
+    def step_indices(self, seqs):
+        sa = seqs if isinstance(seqs, SeqArray) else SeqArray(seqs)
+        cu = np.zeros(sa.n + 1, dtype=np.int32)
+        pos = np.zeros(max(sa.n_tokens, 1), dtype=np.int32)
+        slots = np.zeros(max(sa.n_tokens, 1), dtype=np.int32)
+        self._check(lib.ps_step_indices(self.handle, sa.array, sa.n, cu.ctypes.data_as(_I32P),
+                                        pos.ctypes.data_as(_I32P), slots.ctypes.data_as(_I32P)))
+        return cu, pos[:sa.n_tokens], slots[:sa.n_tokens]
+
+    def plan_attention(self, seqs):
+        sa = seqs if isinstance(seqs, SeqArray) else SeqArray(seqs)
+        n = C.c_int32(0)
+        self._check(lib.ps_plan_attention(self.handle, sa.array, sa.n, None, 0, C.byref(n)))
+        items = np.zeros((max(n.value, 1), 8), dtype=np.int32)
+        self._check(lib.ps_plan_attention(self.handle, sa.array, sa.n, items.ctypes.data_as(_I32P), n.value, C.byref(n)))
+        return items[:n.value]
+
+    def attention_times(self, cap=2048):
+        buf = (C.c_float * cap)()
+        n = C.c_int32(0)
+        self._check(lib.ps_attention_times(self.handle, buf, cap, C.byref(n)))
+        return [buf[i] for i in range(n.value)]
+
+    def set_taps(self, layer, **ptrs):
+        if not ptrs:
+            self._check(lib.ps_set_taps(self.handle, layer, None))
+            return
+        t = ps_taps(*[int(ptrs.get(n, 0)) or None for n, _ in ps_taps._fields_])
+        self._check(lib.ps_set_taps(self.handle, layer, C.byref(t)))
+
+    def profile_grid(self, cells, x_in_ptr, x_out_ptr, warmup=2, iters=5):
+        """cells: list of (chunk, n_decode, chunk_prefix[n_draws], decode_kv[n_draws][n_decode])."""
+        n = len(cells)
+        specs = (ps_grid_cell_spec * max(n, 1))()
+        keep = []
+        for i, (chunk, n_dec, prefixes, dkv) in enumerate(cells):
+            pf = _as_i32(prefixes)
+            dk = _as_i32(dkv).reshape(len(pf), n_dec) if n_dec else np.zeros((len(pf), 0), dtype=np.int32)
+            keep += [pf, dk]
+            specs[i] = ps_grid_cell_spec(chunk, n_dec, len(pf), pf.ctypes.data_as(_I32P), dk.ctypes.data_as(_I32P))
+        out = (ps_grid_cell * max(n, 1))()
+        opts = ps_grid_opts(warmup, iters)
+        self._check(lib.ps_profile_grid(self.handle, specs, n, C.byref(opts), _P(x_in_ptr), _P(x_out_ptr), out))
+        return [out[i] for i in range(n)]

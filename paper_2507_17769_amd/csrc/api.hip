@@ -1,0 +1,763 @@
+// C-ABI of libpolystep: context, weights, paged KV pool + allocator, the mixed-batch step and
+// the latency-profile grid.  See include/polystep.h for the contract of every entry point.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <deque>
+#include <new>
+
+#include "planner.h"
+#include "ps_common.h"
+
+namespace ps {
+
+int attn_prefill_tokens_per_item(int G);
+
+struct LayerWeights {
+    bf16_t *wqkv_t = nullptr, *wo_t = nullptr, *wgu_t = nullptr, *wd_t = nullptr, *g_attn = nullptr, *g_ffn = nullptr;
+    bool ready = false;
+};
+
+struct Staging {  // pinned host buffer + the event that says its last copy has been consumed
+    void* host = nullptr;
+    size_t bytes = 0;
+    hipEvent_t done = nullptr;
+    bool in_flight = false;
+};
+
+}  // namespace ps
+
+using namespace ps;
+
+struct ps_ctx {
+    ps_model_desc desc{};
+    bool host_only = false;
+    hipStream_t stream = nullptr;
+    std::string err;
+
+    std::vector<LayerWeights> layers;
+    float* rope_cs = nullptr;  // [max_position][d/2] (cos, sin)
+
+    // KV pool + allocator
+    bf16_t* pool = nullptr;
+    int n_pool_pages = -1;
+    int n_kv_slots = 0;
+    size_t slot_elems = 0;  // elements per physical layer slot
+    std::deque<int32_t> free_list;
+    std::unordered_map<int64_t, std::vector<int32_t>> owned;
+    std::vector<uint8_t> page_seen;
+
+    // workspaces
+    int cap_tokens = 0;
+    bf16_t *ws_xn = nullptr, *ws_q = nullptr, *ws_attn = nullptr, *ws_act = nullptr;
+    float *ws_qkv = nullptr, *ws_x1 = nullptr, *ws_xmid = nullptr;
+    float* ws_splitk = nullptr;
+    size_t splitk_bytes = 0;
+    float *part_o = nullptr, *part_ml = nullptr;
+    int cap_part_slots = 0;
+    void* dev_meta = nullptr;
+    size_t dev_meta_bytes = 0;
+    Staging staging[4];
+    int staging_next = 0;
+
+    // options / debug
+    int opt_split_pages = 0;
+    int opt_gemm_split_k = 0;
+    bool opt_out_f32 = false;
+    int tap_layer = -1;
+    ps_taps taps{};
+
+    // optional event pairs around every attention launch (see ps_attention_times)
+    bool opt_time_attention = false;
+    std::vector<hipEvent_t> attn_ev;  // ring of 2 * ATTN_EV_PAIRS events
+    int attn_ev_count = 0;            // pairs recorded since the last ps_attention_times
+
+    hipEvent_t ev[PS_N_STAGES * 2 + 2] = {};
+    bool have_events = false;
+    StepPlan plan;
+};
+
+static constexpr int ATTN_EV_PAIRS = 2048;
+static thread_local std::string g_create_err;
+
+static ps_status fail(ps_ctx* c, ps_status s, const std::string& msg) {
+    if (c) c->err = msg; else g_create_err = msg;
+    return s;
+}
+static ps_status hip_fail(ps_ctx* c, hipError_t e, const char* what) {
+    return fail(c, e == hipErrorOutOfMemory ? PS_ENOMEM : PS_EDEVICE, std::string(what) + ": " + hipGetErrorString(e));
+}
+#define HIP_TRY(c, call)                                   \
+    do {                                                   \
+        hipError_t e__ = (call);                           \
+        if (e__ != hipSuccess) return hip_fail(c, e__, #call); \
+    } while (0)
+
+template <typename T>
+static ps_status dev_alloc(ps_ctx* c, T** p, size_t bytes, const char* what) {
+    *p = nullptr;
+    if (bytes == 0) return PS_OK;
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(p), bytes);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        *p = nullptr;
+        return fail(c, PS_ENOMEM, std::string("device allocation failed for ") + what + " (" + std::to_string(bytes) + " bytes): " + hipGetErrorString(e));
+    }
+    return PS_OK;
+}
+template <typename T>
+static void dev_free(T*& p) {
+    if (p) (void)hipFree(p);
+    p = nullptr;
+}
+
+static int qkv_cols(const ps_model_desc& d) { return (d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim; }
+
+static PlanConfig plan_config(const ps_ctx* c) {
+    PlanConfig pc;
+    pc.n_kv_heads = c->desc.n_kv_heads;
+    pc.group = c->desc.n_q_heads / c->desc.n_kv_heads;
+    pc.max_position = c->desc.max_position;
+    pc.n_pool_pages = c->n_pool_pages;
+    pc.split_pages = c->opt_split_pages;
+    pc.prefill_tokens = attn_prefill_tokens_per_item(pc.group);
+    return pc;
+}
+
+// ------------------------------------------------------------------------------ lifetime
+extern "C" ps_status ps_create(const ps_model_desc* desc, void* hip_stream, ps_ctx** out) {
+    if (!desc || !out) return fail(nullptr, PS_EINVAL, "ps_create: null argument");
+    *out = nullptr;
+    const ps_model_desc& d = *desc;
+    if (d.hidden <= 0 || d.n_q_heads <= 0 || d.n_kv_heads <= 0 || d.head_dim <= 0 || d.ffn <= 0 || d.n_layers <= 0 || d.max_position <= 0)
+        return fail(nullptr, PS_EINVAL, "ps_create: every dimension must be positive");
+    if (d.page_size != PS_PAGE_SIZE) return fail(nullptr, PS_EINVAL, "ps_create: page_size must be 16");
+    if (d.head_dim != 64 && d.head_dim != 128) return fail(nullptr, PS_EINVAL, "ps_create: head_dim must be 64 or 128");
+    if (d.n_q_heads % d.n_kv_heads) return fail(nullptr, PS_EINVAL, "ps_create: n_q_heads must be a multiple of n_kv_heads");
+    const int G = d.n_q_heads / d.n_kv_heads;
+    if (G != 1 && G != 2 && G != 4 && G != 8 && G != 16) return fail(nullptr, PS_EINVAL, "ps_create: n_q_heads / n_kv_heads must be 1, 2, 4, 8 or 16");
+    if (d.hidden % 64 || d.ffn % 64 || (d.n_q_heads * d.head_dim) % 64)
+        return fail(nullptr, PS_EINVAL, "ps_create: hidden, ffn and n_q_heads*head_dim must be multiples of 64");
+    if (!(d.rope_base > 1.0f)) return fail(nullptr, PS_EINVAL, "ps_create: rope_base must be > 1");
+    if (d.max_position > (1 << 22)) return fail(nullptr, PS_ERANGE, "ps_create: max_position above 2^22");
+
+    ps_ctx* c = new (std::nothrow) ps_ctx();
+    if (!c) return fail(nullptr, PS_ENOMEM, "ps_create: out of host memory");
+    c->desc = d;
+    if (!(c->desc.rms_eps > 0.f)) c->desc.rms_eps = 1e-5f;
+    c->host_only = (d.flags & PS_FLAG_HOST_ONLY) != 0;
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    c->layers.resize(d.n_layers);
+    if (c->host_only) {
+        *out = c;
+        return PS_OK;
+    }
+    // rotary table, angles in fp64: theta_j = base^(-2j/d), entry = (cos, sin)(pos * theta_j)
+    const int half = d.head_dim / 2;
+    std::vector<float> cs((size_t)d.max_position * half * 2);
+    std::vector<double> theta(half);
+    for (int j = 0; j < half; j++) theta[j] = std::pow((double)d.rope_base, -2.0 * j / d.head_dim);
+    for (int p = 0; p < d.max_position; p++)
+        for (int j = 0; j < half; j++) {
+            const double phi = (double)p * theta[j];
+            cs[((size_t)p * half + j) * 2] = (float)std::cos(phi);
+            cs[((size_t)p * half + j) * 2 + 1] = (float)std::sin(phi);
+        }
+    ps_status st = dev_alloc(nullptr, &c->rope_cs, cs.size() * sizeof(float), "rotary table");
+    if (st != PS_OK) { delete c; return st; }
+    hipError_t e = hipMemcpy(c->rope_cs, cs.data(), cs.size() * sizeof(float), hipMemcpyHostToDevice);
+    if (e != hipSuccess) { ps_destroy(c); return hip_fail(nullptr, e, "hipMemcpy(rotary table)"); }
+    *out = c;
+    return PS_OK;
+}
+
+extern "C" ps_status ps_sync(ps_ctx* c) {
+    if (!c) return PS_EINVAL;
+    if (c->host_only) return PS_OK;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    for (auto& s : c->staging) s.in_flight = false;
+    return PS_OK;
+}
+
+static void free_workspaces(ps_ctx* c) {
+    dev_free(c->ws_xn); dev_free(c->ws_qkv); dev_free(c->ws_q); dev_free(c->ws_attn); dev_free(c->ws_act);
+    dev_free(c->ws_xmid); dev_free(c->ws_x1); dev_free(c->ws_splitk);
+    c->cap_tokens = 0;
+    c->splitk_bytes = 0;
+}
+
+extern "C" void ps_destroy(ps_ctx* c) {
+    if (!c) return;
+    if (!c->host_only) {
+        (void)hipStreamSynchronize(c->stream);
+        for (auto& l : c->layers) {
+            dev_free(l.wqkv_t); dev_free(l.wo_t); dev_free(l.wgu_t); dev_free(l.wd_t); dev_free(l.g_attn); dev_free(l.g_ffn);
+        }
+        dev_free(c->rope_cs);
+        dev_free(c->pool);
+        free_workspaces(c);
+        dev_free(c->part_o); dev_free(c->part_ml);
+        if (c->dev_meta) (void)hipFree(c->dev_meta);
+        for (auto& s : c->staging) {
+            if (s.host) (void)hipHostFree(s.host);
+            if (s.done) (void)hipEventDestroy(s.done);
+        }
+        if (c->have_events) for (auto& e : c->ev) if (e) (void)hipEventDestroy(e);
+        for (auto& e : c->attn_ev) if (e) (void)hipEventDestroy(e);
+    }
+    delete c;
+}
+
+extern "C" const char* ps_last_error(const ps_ctx* c) { return c ? c->err.c_str() : g_create_err.c_str(); }
+
+extern "C" ps_status ps_set_option(ps_ctx* c, const char* name, int64_t value) {
+    if (!c || !name) return fail(c, PS_EINVAL, "ps_set_option: null argument");
+    if (!strcmp(name, "attn_split_pages")) {
+        if (value < 0 || value > (1 << 20)) return fail(c, PS_EINVAL, "attn_split_pages must be in [0, 2^20]");
+        c->opt_split_pages = (int)value;
+        return PS_OK;
+    }
+    if (!strcmp(name, "gemm_split_k")) {
+        if (value < 0 || value > 64) return fail(c, PS_EINVAL, "gemm_split_k must be in [0, 64]");
+        c->opt_gemm_split_k = (int)value;
+        if (!c->host_only) { (void)hipStreamSynchronize(c->stream); free_workspaces(c); }
+        return PS_OK;
+    }
+    if (!strcmp(name, "time_attention")) {
+        if (value != 0 && value != 1) return fail(c, PS_EINVAL, "time_attention must be 0 or 1");
+        if (c->host_only) return fail(c, PS_ESTATE, "time_attention: host-only context");
+        if (value && c->attn_ev.empty()) {
+            c->attn_ev.assign(2 * ATTN_EV_PAIRS, nullptr);
+            for (auto& e : c->attn_ev) HIP_TRY(c, hipEventCreate(&e));
+        }
+        c->opt_time_attention = value != 0;
+        c->attn_ev_count = 0;
+        return PS_OK;
+    }
+    if (!strcmp(name, "out_f32")) {
+        if (value != 0 && value != 1) return fail(c, PS_EINVAL, "out_f32 must be 0 or 1");
+        c->opt_out_f32 = value != 0;
+        return PS_OK;
+    }
+    return fail(c, PS_EINVAL, std::string("unknown option ") + name);
+}
+
+// ------------------------------------------------------------------------------ weights
+extern "C" ps_status ps_init_layer(ps_ctx* c, int32_t layer, const ps_layer_weights* w) {
+    if (!c || !w) return fail(c, PS_EINVAL, "ps_init_layer: null argument");
+    if (c->host_only) return fail(c, PS_ESTATE, "ps_init_layer: host-only context");
+    if (layer < 0 || layer >= c->desc.n_layers) return fail(c, PS_ERANGE, "ps_init_layer: layer index out of range");
+    if (!w->w_qkv || !w->w_o || !w->w_gate || !w->w_up || !w->w_down || !w->g_attn || !w->g_ffn)
+        return fail(c, PS_EINVAL, "ps_init_layer: null weight pointer");
+    const ps_model_desc& d = c->desc;
+    const int H = d.hidden, F = d.ffn, NQ = d.n_q_heads * d.head_dim, NQKV = qkv_cols(d);
+    LayerWeights& L = c->layers[layer];
+    ps_status st;
+    if (!L.wqkv_t) {
+        if ((st = dev_alloc(c, &L.wqkv_t, (size_t)NQKV * H * 2, "w_qkv")) != PS_OK) return st;
+        if ((st = dev_alloc(c, &L.wo_t, (size_t)H * NQ * 2, "w_o")) != PS_OK) return st;
+        if ((st = dev_alloc(c, &L.wgu_t, (size_t)2 * F * H * 2, "w_gate/up")) != PS_OK) return st;
+        if ((st = dev_alloc(c, &L.wd_t, (size_t)H * F * 2, "w_down")) != PS_OK) return st;
+        if ((st = dev_alloc(c, &L.g_attn, (size_t)H * 2, "g_attn")) != PS_OK) return st;
+        if ((st = dev_alloc(c, &L.g_ffn, (size_t)H * 2, "g_ffn")) != PS_OK) return st;
+    }
+    L.ready = false;
+    HIP_TRY(c, launch_transpose_weight(static_cast<const bf16_t*>(w->w_qkv), L.wqkv_t, H, NQKV, c->stream));
+    HIP_TRY(c, launch_transpose_weight(static_cast<const bf16_t*>(w->w_o), L.wo_t, NQ, H, c->stream));
+    HIP_TRY(c, launch_interleave_gate_up(static_cast<const bf16_t*>(w->w_gate), static_cast<const bf16_t*>(w->w_up), L.wgu_t, H, F, c->stream));
+    HIP_TRY(c, launch_transpose_weight(static_cast<const bf16_t*>(w->w_down), L.wd_t, F, H, c->stream));
+    HIP_TRY(c, launch_copy_bytes(w->g_attn, L.g_attn, (size_t)H * 2, c->stream));
+    HIP_TRY(c, launch_copy_bytes(w->g_ffn, L.g_ffn, (size_t)H * 2, c->stream));
+    L.ready = true;
+    return PS_OK;
+}
+
+// ------------------------------------------------------------------------------ KV pool
+static inline uint64_t splitmix64_next(uint64_t& s) {
+    s += 0x9E3779B97F4A7C15ull;
+    uint64_t z = s;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+extern "C" ps_status ps_kv_alloc(ps_ctx* c, int32_t n_pages, int32_t n_kv_layers, uint64_t perm_seed) {
+    if (!c) return PS_EINVAL;
+    if (n_pages <= 0 || n_kv_layers <= 0) return fail(c, PS_EINVAL, "ps_kv_alloc: n_pages and n_kv_layers must be positive");
+    if (n_pages > (1 << 26)) return fail(c, PS_ERANGE, "ps_kv_alloc: more than 2^26 pages");
+    const ps_model_desc& d = c->desc;
+    const size_t slot_elems = (size_t)n_pages * d.n_kv_heads * 2 * PS_PAGE_SIZE * d.head_dim;
+    if (!c->host_only) {
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        dev_free(c->pool);
+        c->n_pool_pages = -1;
+        ps_status st = dev_alloc(c, &c->pool, slot_elems * n_kv_layers * 2, "KV pool");
+        if (st != PS_OK) return st;
+        HIP_TRY(c, hipMemsetAsync(c->pool, 0, slot_elems * n_kv_layers * 2, c->stream));
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+    }
+    c->n_pool_pages = n_pages;
+    c->n_kv_slots = n_kv_layers;
+    c->slot_elems = slot_elems;
+    c->page_seen.assign(n_pages, 0);
+    c->owned.clear();
+    std::vector<int32_t> order(n_pages);
+    for (int i = 0; i < n_pages; i++) order[i] = i;
+    uint64_t s = perm_seed;
+    for (int i = n_pages - 1; i >= 1; i--) {
+        const uint64_t j = splitmix64_next(s) % (uint64_t)(i + 1);
+        std::swap(order[i], order[(size_t)j]);
+    }
+    c->free_list.assign(order.begin(), order.end());
+    return PS_OK;
+}
+
+extern "C" ps_status ps_kv_reserve(ps_ctx* c, int64_t req_id, int32_t kv_len, int32_t* pages_out, int32_t cap, int32_t* n_out) {
+    if (!c || !n_out || (!pages_out && cap > 0)) return fail(c, PS_EINVAL, "ps_kv_reserve: null argument");
+    if (c->n_pool_pages < 0) return fail(c, PS_ESTATE, "ps_kv_reserve: no KV pool (call ps_kv_alloc)");
+    if (kv_len < 0 || kv_len > c->desc.max_position) return fail(c, PS_ERANGE, "ps_kv_reserve: kv_len outside [0, max_position]");
+    const int want = (kv_len + PS_PAGE_SIZE - 1) / PS_PAGE_SIZE;
+    auto it = c->owned.find(req_id);
+    const int have = it == c->owned.end() ? 0 : (int)it->second.size();
+    const int need = want - have;
+    const int total = std::max(have, want);
+    if (cap < total) return fail(c, PS_ERANGE, "ps_kv_reserve: pages_out too small");
+    if (need > (int)c->free_list.size()) return fail(c, PS_ENOMEM, "ps_kv_reserve: KV pool exhausted");
+    std::vector<int32_t>& v = c->owned[req_id];
+    for (int i = 0; i < need; i++) {
+        v.push_back(c->free_list.front());
+        c->free_list.pop_front();
+    }
+    for (int i = 0; i < total; i++) pages_out[i] = v[i];
+    *n_out = total;
+    return PS_OK;
+}
+
+extern "C" ps_status ps_kv_release(ps_ctx* c, int64_t req_id) {
+    if (!c) return PS_EINVAL;
+    auto it = c->owned.find(req_id);
+    if (it == c->owned.end()) return fail(c, PS_EINVAL, "ps_kv_release: unknown req_id");
+    for (int32_t p : it->second) c->free_list.push_back(p);
+    c->owned.erase(it);
+    return PS_OK;
+}
+
+extern "C" int32_t ps_kv_free_pages(const ps_ctx* c) {
+    if (!c || c->n_pool_pages < 0) return -1;
+    return (int32_t)c->free_list.size();
+}
+
+// pinned staging: returns a host buffer of at least `bytes`, safe to overwrite
+static ps_status staging_acquire(ps_ctx* c, size_t bytes, Staging** out) {
+    Staging& s = c->staging[c->staging_next];
+    c->staging_next = (c->staging_next + 1) % 4;
+    if (!s.done) HIP_TRY(c, hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
+    if (s.in_flight) {
+        HIP_TRY(c, hipEventSynchronize(s.done));
+        s.in_flight = false;
+    }
+    if (s.bytes < bytes) {
+        if (s.host) (void)hipHostFree(s.host);
+        s.host = nullptr;
+        s.bytes = 0;
+        const size_t want = std::max(bytes + bytes / 2, (size_t)1 << 16);
+        hipError_t e = hipHostMalloc(&s.host, want, hipHostMallocDefault);
+        if (e != hipSuccess) { (void)hipGetLastError(); s.host = nullptr; return fail(c, PS_ENOMEM, "pinned staging allocation failed"); }
+        s.bytes = want;
+    }
+    *out = &s;
+    return PS_OK;
+}
+
+static ps_status ensure_dev_meta(ps_ctx* c, size_t bytes) {
+    if (c->dev_meta_bytes >= bytes) return PS_OK;
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (c->dev_meta) (void)hipFree(c->dev_meta);
+    c->dev_meta = nullptr;
+    c->dev_meta_bytes = 0;
+    const size_t want = std::max(bytes + bytes / 2, (size_t)1 << 16);
+    ps_status st = dev_alloc(c, &c->dev_meta, want, "step metadata");
+    if (st != PS_OK) return st;
+    c->dev_meta_bytes = want;
+    return PS_OK;
+}
+
+static ps_status kv_copy(ps_ctx* c, bool to_pool, int32_t layer, const ps_seq* seq, int32_t pos0, int32_t n, void* k, void* v) {
+    const char* name = to_pool ? "ps_kv_write" : "ps_kv_read";
+    if (!c || !seq || !seq->page_table) return fail(c, PS_EINVAL, std::string(name) + ": null argument");
+    if (c->host_only) return fail(c, PS_ESTATE, std::string(name) + ": host-only context");
+    if (!c->pool) return fail(c, PS_ESTATE, std::string(name) + ": no KV pool (call ps_kv_alloc)");
+    if (layer < 0 || layer >= c->desc.n_layers) return fail(c, PS_ERANGE, std::string(name) + ": layer index out of range");
+    if (n == 0) return PS_OK;
+    if (!k || !v) return fail(c, PS_EINVAL, std::string(name) + ": null k or v");
+    if (n < 0 || pos0 < 0 || (int64_t)pos0 + n > (int64_t)seq->n_pages * PS_PAGE_SIZE)
+        return fail(c, PS_ERANGE, std::string(name) + ": positions outside the sequence's pages");
+    for (int p = pos0 / PS_PAGE_SIZE; p <= (pos0 + n - 1) / PS_PAGE_SIZE; p++)
+        if (seq->page_table[p] < 0 || seq->page_table[p] >= c->n_pool_pages)
+            return fail(c, PS_ERANGE, std::string(name) + ": page id outside the pool");
+    Staging* s;
+    ps_status st = staging_acquire(c, (size_t)n * 4, &s);
+    if (st != PS_OK) return st;
+    if ((st = ensure_dev_meta(c, (size_t)n * 4)) != PS_OK) return st;
+    int32_t* slots = static_cast<int32_t*>(s->host);
+    for (int i = 0; i < n; i++) {
+        const int p = pos0 + i;
+        slots[i] = seq->page_table[p / PS_PAGE_SIZE] * PS_PAGE_SIZE + p % PS_PAGE_SIZE;
+    }
+    HIP_TRY(c, hipMemcpyAsync(c->dev_meta, s->host, (size_t)n * 4, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipEventRecord(s->done, c->stream));
+    s->in_flight = true;
+    bf16_t* slot_base = c->pool + (size_t)(layer % c->n_kv_slots) * c->slot_elems;
+    HIP_TRY(c, launch_kv_copy(to_pool, slot_base, static_cast<const int32_t*>(c->dev_meta), n, c->desc.n_kv_heads,
+                              c->desc.head_dim, static_cast<bf16_t*>(k), static_cast<bf16_t*>(v), c->stream));
+    return PS_OK;
+}
+
+extern "C" ps_status ps_kv_write(ps_ctx* c, int32_t layer, const ps_seq* seq, int32_t pos0, int32_t n, const void* k, const void* v) {
+    return kv_copy(c, true, layer, seq, pos0, n, const_cast<void*>(k), const_cast<void*>(v));
+}
+extern "C" ps_status ps_kv_read(ps_ctx* c, int32_t layer, const ps_seq* seq, int32_t pos0, int32_t n, void* k, void* v) {
+    return kv_copy(c, false, layer, seq, pos0, n, k, v);
+}
+
+// ------------------------------------------------------------------------------ planning
+static ps_status make_plan(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, bool with_attention) {
+    const PlanConfig pc = plan_config(c);
+    std::string err;
+    ps_status st = validate_batch(seqs, n_seqs, pc, c->page_seen, err);
+    if (st != PS_OK) return fail(c, st, err);
+    build_indices(seqs, n_seqs, c->plan);
+    if (with_attention) build_attention_plan(pc, c->plan);
+    return PS_OK;
+}
+
+extern "C" ps_status ps_step_indices(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, int32_t* cu_seqlens, int32_t* positions, int32_t* slot_mapping) {
+    if (!c) return PS_EINVAL;
+    ps_status st = make_plan(c, seqs, n_seqs, false);
+    if (st != PS_OK) return st;
+    const StepPlan& p = c->plan;
+    if (cu_seqlens) std::copy(p.cu_seqlens.begin(), p.cu_seqlens.end(), cu_seqlens);
+    if (positions) std::copy(p.positions.begin(), p.positions.end(), positions);
+    if (slot_mapping) std::copy(p.slots.begin(), p.slots.end(), slot_mapping);
+    return PS_OK;
+}
+
+extern "C" ps_status ps_plan_attention(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, int32_t* items, int32_t cap, int32_t* n_items) {
+    if (!c || !n_items || (!items && cap > 0)) return fail(c, PS_EINVAL, "ps_plan_attention: null argument");
+    ps_status st = make_plan(c, seqs, n_seqs, true);
+    if (st != PS_OK) return st;
+    const StepPlan& p = c->plan;
+    *n_items = (int32_t)p.items.size();
+    const int n = std::min<int>(cap, (int)p.items.size());
+    static_assert(sizeof(AttnItem) == 8 * sizeof(int32_t), "item is 8 int32");
+    if (n > 0) memcpy(items, p.items.data(), (size_t)n * sizeof(AttnItem));
+    return PS_OK;
+}
+
+extern "C" ps_status ps_set_taps(ps_ctx* c, int32_t layer, const ps_taps* taps) {
+    if (!c) return PS_EINVAL;
+    if (!taps) { c->tap_layer = -1; return PS_OK; }
+    if (layer < 0 || layer >= c->desc.n_layers) return fail(c, PS_ERANGE, "ps_set_taps: layer index out of range");
+    c->tap_layer = layer;
+    c->taps = *taps;
+    return PS_OK;
+}
+
+// ------------------------------------------------------------------------------ the step
+static size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
+
+static ps_status ensure_workspaces(ps_ctx* c, int T, int n_part_slots) {
+    const ps_model_desc& d = c->desc;
+    if (T > c->cap_tokens) {
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        free_workspaces(c);
+        const int cap = std::max(T + T / 4, 64);
+        const int H = d.hidden, F = d.ffn, NQ = d.n_q_heads * d.head_dim, NQKV = qkv_cols(d);
+        ps_status st;
+        if ((st = dev_alloc(c, &c->ws_xn, (size_t)cap * H * 2, "xn")) != PS_OK) return st;
+        if ((st = dev_alloc(c, &c->ws_qkv, (size_t)cap * NQKV * 4, "qkv")) != PS_OK) return st;
+        if ((st = dev_alloc(c, &c->ws_q, (size_t)cap * NQ * 2, "q")) != PS_OK) return st;
+        if ((st = dev_alloc(c, &c->ws_attn, (size_t)cap * NQ * 2, "attn")) != PS_OK) return st;
+        if ((st = dev_alloc(c, &c->ws_act, (size_t)cap * F * 2, "act")) != PS_OK) return st;
+        if ((st = dev_alloc(c, &c->ws_x1, (size_t)cap * H * 4, "x1")) != PS_OK) return st;
+        if (d.n_layers > 1 && (st = dev_alloc(c, &c->ws_xmid, (size_t)cap * H * 4, "inter-layer x")) != PS_OK) return st;
+        size_t sk = 0;
+        sk = std::max(sk, gemm_splitk_ws_bytes(cap, NQKV, H, c->opt_gemm_split_k));
+        sk = std::max(sk, gemm_splitk_ws_bytes(cap, H, NQ, c->opt_gemm_split_k));
+        sk = std::max(sk, gemm_splitk_ws_bytes(cap, 2 * F, H, c->opt_gemm_split_k));
+        sk = std::max(sk, gemm_splitk_ws_bytes(cap, H, F, c->opt_gemm_split_k));
+        // the plan for the actual T may split more than the plan for cap: allow for the worst split (16) at small T
+        sk = std::max(sk, (size_t)16 * std::min(cap, 64) * (size_t)std::max(2 * F, NQKV) * 4);
+        sk = std::max(sk, (size_t)64 << 20);
+        if ((st = dev_alloc(c, &c->ws_splitk, sk, "split-K partials")) != PS_OK) return st;
+        c->splitk_bytes = sk;
+        c->cap_tokens = cap;
+    }
+    if (n_part_slots > c->cap_part_slots) {
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        dev_free(c->part_o); dev_free(c->part_ml);
+        c->cap_part_slots = 0;
+        const int cap = n_part_slots + n_part_slots / 2 + 64;
+        ps_status st;
+        if ((st = dev_alloc(c, &c->part_o, (size_t)cap * 16 * d.head_dim * 4, "attention partials")) != PS_OK) return st;
+        if ((st = dev_alloc(c, &c->part_ml, (size_t)cap * 16 * 2 * 4, "attention partial stats")) != PS_OK) return st;
+        c->cap_part_slots = cap;
+    }
+    return PS_OK;
+}
+
+struct MetaLayout {
+    size_t positions, slots, seqs, pages, items, groups, total;
+};
+static MetaLayout meta_layout(const StepPlan& p) {
+    MetaLayout m;
+    size_t at = 0;
+    m.positions = at; at = align16(at + p.positions.size() * 4);
+    m.slots = at;     at = align16(at + p.slots.size() * 4);
+    m.seqs = at;      at = align16(at + p.seqs.size() * sizeof(SeqInfo));
+    m.pages = at;     at = align16(at + p.pages.size() * 4);
+    m.items = at;     at = align16(at + p.items.size() * sizeof(AttnItem));
+    m.groups = at;    at = align16(at + p.groups.size() * sizeof(MergeGroup));
+    m.total = at;
+    return m;
+}
+
+extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const void* x_in, void* x_out, ps_step_stats* stats) {
+    if (!c) return PS_EINVAL;
+    if (c->host_only) return fail(c, PS_ESTATE, "ps_step: host-only context");
+    if (!c->pool) return fail(c, PS_ESTATE, "ps_step: no KV pool (call ps_kv_alloc)");
+    for (int l = 0; l < c->desc.n_layers; l++)
+        if (!c->layers[l].ready) return fail(c, PS_ESTATE, "ps_step: layer " + std::to_string(l) + " has no weights (call ps_init_layer)");
+    ps_status st = make_plan(c, seqs, n_seqs, true);
+    if (st != PS_OK) return st;
+    const StepPlan& p = c->plan;
+    if (stats) {
+        memset(stats, 0, sizeof(*stats));
+        stats->n_tokens = p.n_tokens;
+        stats->total_kv = p.total_kv;
+        stats->n_attn_items = (int32_t)p.items.size();
+        stats->n_attn_partials = p.n_partial_items;
+    }
+    if (n_seqs == 0) return PS_OK;
+    if (!x_in || !x_out) return fail(c, PS_EINVAL, "ps_step: null activation pointer");
+
+    const ps_model_desc& d = c->desc;
+    const int T = p.n_tokens, H = d.hidden, F = d.ffn, NQ = d.n_q_heads * d.head_dim, NQKV = qkv_cols(d);
+    if ((st = ensure_workspaces(c, T, p.n_partial_slots)) != PS_OK) return st;
+
+    // one pinned buffer, one host-to-device copy for all of the step's integer metadata
+    const MetaLayout ml = meta_layout(p);
+    Staging* sg;
+    if ((st = staging_acquire(c, ml.total, &sg)) != PS_OK) return st;
+    if ((st = ensure_dev_meta(c, ml.total)) != PS_OK) return st;
+    char* hb = static_cast<char*>(sg->host);
+    memcpy(hb + ml.positions, p.positions.data(), p.positions.size() * 4);
+    memcpy(hb + ml.slots, p.slots.data(), p.slots.size() * 4);
+    memcpy(hb + ml.seqs, p.seqs.data(), p.seqs.size() * sizeof(SeqInfo));
+    memcpy(hb + ml.pages, p.pages.data(), p.pages.size() * 4);
+    memcpy(hb + ml.items, p.items.data(), p.items.size() * sizeof(AttnItem));
+    if (!p.groups.empty()) memcpy(hb + ml.groups, p.groups.data(), p.groups.size() * sizeof(MergeGroup));
+    HIP_TRY(c, hipMemcpyAsync(c->dev_meta, sg->host, ml.total, hipMemcpyHostToDevice, c->stream));
+    HIP_TRY(c, hipEventRecord(sg->done, c->stream));
+    sg->in_flight = true;
+    const char* db = static_cast<const char*>(c->dev_meta);
+    const int32_t* d_pos = reinterpret_cast<const int32_t*>(db + ml.positions);
+    const int32_t* d_slots = reinterpret_cast<const int32_t*>(db + ml.slots);
+
+    if (stats && !c->have_events) {
+        for (auto& e : c->ev) HIP_TRY(c, hipEventCreate(&e));
+        c->have_events = true;
+    }
+    // with stats, events bracket every stage of every layer; stage times are summed over layers
+    std::vector<float> stage_ms(PS_N_STAGES, 0.f);
+    float total_ms = 0.f;
+    hipStream_t s = c->stream;
+
+    // The residual stream stays fp32 inside the stack: only x_in and x_out are bf16.
+    const void* x_cur = x_in;
+    bool x_cur_f32 = false;
+    for (int l = 0; l < d.n_layers; l++) {
+        const LayerWeights& L = c->layers[l];
+        const bool tap = (l == c->tap_layer);
+        const bool last = (l == d.n_layers - 1);
+        void* x_next = last ? x_out : static_cast<void*>(c->ws_xmid);
+        bf16_t* pool_slot = c->pool + (size_t)(l % c->n_kv_slots) * c->slot_elems;
+        int e = 0;
+        if (stats) HIP_TRY(c, hipEventRecord(c->ev[e], s));
+        // 0: RMSNorm
+        HIP_TRY(c, launch_rmsnorm(x_cur, x_cur_f32, L.g_attn, c->ws_xn, T, H, d.rms_eps, s));
+        if (tap && c->taps.xn) HIP_TRY(c, launch_copy_bytes(c->ws_xn, c->taps.xn, (size_t)T * H * 2, s));
+        if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
+        // 1: QKV projection, kept in fp32 so that rotation happens before the only bf16 rounding
+        GemmArgs g{};
+        g.A = c->ws_xn; g.Bt = L.wqkv_t; g.M = T; g.N = NQKV; g.K = H; g.kind = GemmEpilogue::STORE;
+        g.resid_f32 = false; g.out_f32 = true; g.resid = nullptr; g.out = c->ws_qkv;
+        g.splitk_ws = c->ws_splitk; g.splitk_ws_bytes = c->splitk_bytes; g.split_k = c->opt_gemm_split_k;
+        HIP_TRY(c, launch_gemm(g, s));
+        if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
+        // 2: rotary + append
+        HIP_TRY(c, launch_rope_append(c->ws_qkv, c->ws_q, T, d.n_q_heads, d.n_kv_heads, d.head_dim, d_pos, d_slots,
+                                      c->rope_cs, pool_slot, s));
+        if (tap && c->taps.q) HIP_TRY(c, launch_copy_bytes(c->ws_q, c->taps.q, (size_t)T * NQ * 2, s));
+        if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
+        // 3: attention
+        AttnArgs a{};
+        a.q = c->ws_q; a.ldq = NQ; a.pool_slot = pool_slot;
+        a.seqs = reinterpret_cast<const SeqInfo*>(db + ml.seqs);
+        a.pages = reinterpret_cast<const int32_t*>(db + ml.pages);
+        a.items = reinterpret_cast<const AttnItem*>(db + ml.items);
+        a.n_items = (int)p.items.size();
+        a.groups = reinterpret_cast<const MergeGroup*>(db + ml.groups);
+        a.n_groups = (int)p.groups.size();
+        a.part_o = c->part_o; a.part_ml = c->part_ml; a.out = c->ws_attn;
+        a.n_q = d.n_q_heads; a.n_kv = d.n_kv_heads; a.d = d.head_dim;
+        const bool time_attn = c->opt_time_attention && c->attn_ev_count < ATTN_EV_PAIRS;
+        a.ev_begin = time_attn ? c->attn_ev[2 * c->attn_ev_count] : nullptr;
+        a.ev_end = time_attn ? c->attn_ev[2 * c->attn_ev_count + 1] : nullptr;
+        HIP_TRY(c, launch_attention(a, s));
+        if (time_attn) c->attn_ev_count++;
+        if (tap && c->taps.attn) HIP_TRY(c, launch_copy_bytes(c->ws_attn, c->taps.attn, (size_t)T * NQ * 2, s));
+        if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
+        // 4: O projection + residual
+        g.A = c->ws_attn; g.Bt = L.wo_t; g.N = H; g.K = NQ; g.kind = GemmEpilogue::RESID;
+        g.resid = x_cur; g.resid_f32 = x_cur_f32; g.out = c->ws_x1; g.out_f32 = true;
+        HIP_TRY(c, launch_gemm(g, s));
+        if (tap && c->taps.x1) HIP_TRY(c, launch_copy_bytes(c->ws_x1, c->taps.x1, (size_t)T * H * 4, s));
+        if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
+        // 5: RMSNorm
+        HIP_TRY(c, launch_rmsnorm(c->ws_x1, true, L.g_ffn, c->ws_xn, T, H, d.rms_eps, s));
+        if (tap && c->taps.xn2) HIP_TRY(c, launch_copy_bytes(c->ws_xn, c->taps.xn2, (size_t)T * H * 2, s));
+        if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
+        // 6: gate/up + SwiGLU
+        g.A = c->ws_xn; g.Bt = L.wgu_t; g.N = 2 * F; g.K = H; g.kind = GemmEpilogue::SWIGLU_BF16;
+        g.resid = nullptr; g.resid_f32 = false; g.out = c->ws_act; g.out_f32 = false;
+        HIP_TRY(c, launch_gemm(g, s));
+        if (tap && c->taps.act) HIP_TRY(c, launch_copy_bytes(c->ws_act, c->taps.act, (size_t)T * F * 2, s));
+        if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
+        // 7: down + residual
+        g.A = c->ws_act; g.Bt = L.wd_t; g.N = H; g.K = F; g.kind = GemmEpilogue::RESID;
+        g.resid = c->ws_x1; g.resid_f32 = true; g.out = x_next; g.out_f32 = !last || c->opt_out_f32;
+        HIP_TRY(c, launch_gemm(g, s));
+        if (stats) {
+            HIP_TRY(c, hipEventRecord(c->ev[++e], s));
+            HIP_TRY(c, hipEventSynchronize(c->ev[e]));
+            for (int i = 0; i < PS_N_STAGES; i++) {
+                float ms = 0.f;
+                HIP_TRY(c, hipEventElapsedTime(&ms, c->ev[i], c->ev[i + 1]));
+                stage_ms[i] += ms;
+            }
+            float ms = 0.f;
+            HIP_TRY(c, hipEventElapsedTime(&ms, c->ev[0], c->ev[PS_N_STAGES]));
+            total_ms += ms;
+        }
+        x_cur = x_next;
+        x_cur_f32 = true;
+    }
+    if (stats) {
+        stats->ms_total = total_ms;
+        for (int i = 0; i < PS_N_STAGES; i++) stats->ms_stage[i] = stage_ms[i];
+    }
+    return PS_OK;
+}
+
+extern "C" ps_status ps_attention_times(ps_ctx* c, float* ms, int32_t cap, int32_t* n) {
+    if (!c || !n || (!ms && cap > 0)) return fail(c, PS_EINVAL, "ps_attention_times: null argument");
+    if (c->host_only) return fail(c, PS_ESTATE, "ps_attention_times: host-only context");
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    const int cnt = std::min<int>(c->attn_ev_count, cap);
+    for (int i = 0; i < cnt; i++) HIP_TRY(c, hipEventElapsedTime(&ms[i], c->attn_ev[2 * i], c->attn_ev[2 * i + 1]));
+    *n = cnt;
+    c->attn_ev_count = 0;
+    return PS_OK;
+}
+
+// ------------------------------------------------------------------------------ latency grid
+static float median_of(std::vector<float> v) {
+    std::sort(v.begin(), v.end());
+    const size_t n = v.size();
+    return n == 0 ? 0.f : (n & 1 ? v[n / 2] : 0.5f * (v[n / 2 - 1] + v[n / 2]));
+}
+
+extern "C" ps_status ps_profile_grid(ps_ctx* c, const ps_grid_cell_spec* cells, int32_t n_cells, const ps_grid_opts* opts,
+                                     const void* x_in, void* x_out, ps_grid_cell* out) {
+    if (!c || !cells || !opts || !out || n_cells < 0) return fail(c, PS_EINVAL, "ps_profile_grid: null argument");
+    if (c->host_only) return fail(c, PS_ESTATE, "ps_profile_grid: host-only context");
+    if (opts->iters < 1 || opts->warmup < 0) return fail(c, PS_EINVAL, "ps_profile_grid: iters must be >= 1, warmup >= 0");
+    hipEvent_t t0 = nullptr, t1 = nullptr;
+    HIP_TRY(c, hipEventCreate(&t0));
+    HIP_TRY(c, hipEventCreate(&t1));
+    ps_status rc = PS_OK;
+    const int64_t id_base = INT64_MIN / 2;  // request ids of the synthetic sequences
+    for (int ci = 0; ci < n_cells && rc == PS_OK; ci++) {
+        const ps_grid_cell_spec& cs = cells[ci];
+        ps_grid_cell& oc = out[ci];
+        memset(&oc, 0, sizeof(oc));
+        oc.chunk = cs.chunk;
+        oc.n_decode = cs.n_decode;
+        oc.n_draws = cs.n_draws;
+        oc.n_tokens = cs.chunk + cs.n_decode;
+        if (cs.chunk < 0 || cs.n_decode < 0 || cs.n_draws < 1 || cs.n_draws > PS_GRID_MAX_DRAWS ||
+            (cs.chunk > 0 && !cs.chunk_prefix) || (cs.n_decode > 0 && !cs.decode_kv)) {
+            rc = fail(c, PS_EINVAL, "ps_profile_grid: malformed cell " + std::to_string(ci));
+            break;
+        }
+        std::vector<float> draw_ms;
+        std::vector<ps_step_stats> draw_stats(cs.n_draws);
+        for (int dr = 0; dr < cs.n_draws && rc == PS_OK; dr++) {
+            // build the batch: chunk first, then the decodes; pages from the allocator
+            const int n_seqs = (cs.chunk > 0 ? 1 : 0) + cs.n_decode;
+            std::vector<ps_seq> seqs(n_seqs);
+            std::vector<std::vector<int32_t>> tables(n_seqs);
+            int si = 0, reserved = 0;
+            auto add = [&](int n_new, int kv_len) -> ps_status {
+                std::vector<int32_t>& t = tables[si];
+                t.resize((kv_len + PS_PAGE_SIZE - 1) / PS_PAGE_SIZE);
+                int32_t n = 0;
+                ps_status st = ps_kv_reserve(c, id_base + si, kv_len, t.data(), (int32_t)t.size(), &n);
+                if (st != PS_OK) return st;
+                reserved = si + 1;
+                seqs[si] = ps_seq{id_base + si, n_new, kv_len, t.data(), n};
+                si++;
+                return PS_OK;
+            };
+            if (cs.chunk > 0) rc = add(cs.chunk, cs.chunk_prefix[dr] + cs.chunk);
+            for (int j = 0; j < cs.n_decode && rc == PS_OK; j++) rc = add(1, cs.decode_kv[(size_t)dr * cs.n_decode + j]);
+            if (rc == PS_OK) {
+                for (int w = 0; w < opts->warmup && rc == PS_OK; w++) rc = ps_step(c, seqs.data(), n_seqs, x_in, x_out, nullptr);
+                std::vector<float> it_ms;
+                for (int it = 0; it < opts->iters && rc == PS_OK; it++) {
+                    hipError_t e = hipEventRecord(t0, c->stream);
+                    if (e == hipSuccess) rc = ps_step(c, seqs.data(), n_seqs, x_in, x_out, nullptr);
+                    if (rc != PS_OK) break;
+                    if (e == hipSuccess) e = hipEventRecord(t1, c->stream);
+                    if (e == hipSuccess) e = hipEventSynchronize(t1);
+                    float ms = 0.f;
+                    if (e == hipSuccess) e = hipEventElapsedTime(&ms, t0, t1);
+                    if (e != hipSuccess) { rc = hip_fail(c, e, "ps_profile_grid timing"); break; }
+                    it_ms.push_back(ms);
+                }
+                if (rc == PS_OK) {
+                    draw_ms.push_back(median_of(it_ms));
+                    rc = ps_step(c, seqs.data(), n_seqs, x_in, x_out, &draw_stats[dr]);  // one more pass for the stage split
+                }
+            }
+            for (int k = 0; k < reserved; k++) (void)ps_kv_release(c, id_base + k);
+        }
+        if (rc != PS_OK) break;
+        // median draw = the one whose time is the (lower) median
+        std::vector<int> order(cs.n_draws);
+        for (int i = 0; i < cs.n_draws; i++) order[i] = i;
+        std::sort(order.begin(), order.end(), [&](int a, int b) { return draw_ms[a] < draw_ms[b]; });
+        const int med = order[(cs.n_draws - 1) / 2];
+        oc.median_ms = median_of(draw_ms);
+        oc.total_kv = draw_stats[med].total_kv;
+        for (int i = 0; i < PS_N_STAGES; i++) oc.stage_ms[i] = draw_stats[med].ms_stage[i];
+        for (int i = 0; i < cs.n_draws; i++) {
+            oc.draw_ms[i] = draw_ms[i];
+            oc.draw_total_kv[i] = draw_stats[i].total_kv;
+        }
+    }
+    (void)hipEventDestroy(t0);
+    (void)hipEventDestroy(t1);
+    return rc;
+}

@@ -1,0 +1,114 @@
+// Internal declarations shared by the host code and the gfx950 kernels of libpolystep.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "../../include/polystep.h"
+
+namespace ps {
+
+typedef uint16_t bf16_t;  // bfloat16 bit pattern
+
+// ---------------------------------------------------------------------------------
+// KV pool layout (one physical layer slot):  [page][kv_head][K|V][16 * head_dim] bf16.
+// Inside a 16-token x head_dim chunk the elements are ordered so that a wavefront's
+// 16-byte-per-lane loads are both contiguous (1 KiB per instruction) and already in
+// MFMA operand order:
+//   K chunk: [s = d/32][g = 4][tok = 16][8]      element (tok, dd): s = dd/32, g = (dd%32)/8
+//   V chunk: [p = d/32][g = 4][dl = 16][h = 2][4] element (tok, dd): p = dd/32, h = (dd/16)%2,
+//                                                 dl = dd%16, g = tok/4, i = tok%4
+// ---------------------------------------------------------------------------------
+__host__ __device__ inline int k_elem_offset(int tok, int dd) {
+    return (((dd >> 5) * 4 + ((dd & 31) >> 3)) * 16 + tok) * 8 + (dd & 7);
+}
+__host__ __device__ inline int v_elem_offset(int tok, int dd) {
+    return ((((dd >> 5) * 4 + (tok >> 2)) * 16 + (dd & 15)) * 2 + ((dd >> 4) & 1)) * 4 + (tok & 3);
+}
+
+// Attention work item (8 x int32, mirrored by ps_plan_attention's output).
+struct AttnItem {
+    int32_t seq;         // index into the step's sequence table
+    int32_t kv_head;
+    int32_t q_tok0;      // first new-token index (within the sequence) of the query block
+    int32_t q_ntok;      // query tokens in the block
+    int32_t page_begin;  // logical KV pages [page_begin, page_end)
+    int32_t page_end;
+    int32_t partial;     // first partial slot, or -1: the item covers its whole KV span
+    int32_t group;       // merge group of its first tile (-1 when partial == -1)
+};
+
+// Split-KV merge group: one 16-row query tile of one (sequence, kv head).
+struct MergeGroup {
+    int32_t tok0;        // global token index of the tile's first token
+    int32_t n_tok;       // valid tokens in the tile
+    int32_t kv_head;
+    int32_t first_slot;  // slot of split j is first_slot + j * stride
+    int32_t n_splits;
+    int32_t stride;
+    int32_t pad0, pad1;
+};
+
+// Per-sequence record on the device.
+struct SeqInfo {
+    int32_t tok0;      // cu_seqlens
+    int32_t n_new;
+    int32_t kv_len;
+    int32_t page_off;  // offset of its page list in the flat page array
+};
+
+struct GemmEpilogue {
+    enum Kind : int { STORE = 0, RESID = 1, SWIGLU_BF16 = 2 };
+};
+
+// ------------------------------------------------------------------ launchers (device side)
+// All take the stream explicitly and return hipGetLastError() of the launch.
+hipError_t launch_rmsnorm(const void* x, bool x_is_f32, const bf16_t* gain, bf16_t* out, int T, int H, float eps,
+                          hipStream_t st);
+hipError_t launch_rope_append(const float* qkv, bf16_t* q_out, int T, int n_q, int n_kv, int d,
+                              const int32_t* positions, const int32_t* slots, const float* rope_cs, bf16_t* pool_slot,
+                              hipStream_t st);
+hipError_t launch_kv_copy(bool to_pool, bf16_t* pool_slot, const int32_t* slots_dev, int n, int n_kv, int d, bf16_t* k,
+                          bf16_t* v, hipStream_t st);
+hipError_t launch_transpose_weight(const bf16_t* w, bf16_t* wt, int K, int N, hipStream_t st);
+hipError_t launch_interleave_gate_up(const bf16_t* wg, const bf16_t* wu, bf16_t* wt, int K, int F, hipStream_t st);
+hipError_t launch_copy_bytes(const void* src, void* dst, size_t n, hipStream_t st);
+
+struct GemmArgs {
+    const bf16_t* A;   // [M][K] activations
+    const bf16_t* Bt;  // [N][K] weights, transposed
+    int M, N, K;
+    int kind;          // GemmEpilogue::Kind
+    bool resid_f32;    // residual is fp32 (else bf16)
+    bool out_f32;      // output is fp32 (else bf16)
+    const void* resid; // [M][N], RESID only
+    void* out;         // [M][N], or [M][N/2] bf16 for SWIGLU
+    float* splitk_ws;  // fp32 [split][M][N] scratch when split_k > 1
+    size_t splitk_ws_bytes;
+    int split_k;       // 0 = choose
+};
+hipError_t launch_gemm(const GemmArgs& a, hipStream_t st);
+size_t gemm_splitk_ws_bytes(int M, int N, int K, int split_k_opt);
+
+struct AttnArgs {
+    const bf16_t* q;   // rotated queries [T][n_q * d]: row stride ldq elements
+    int ldq;
+    const bf16_t* pool_slot;
+    const SeqInfo* seqs;
+    const int32_t* pages;
+    const AttnItem* items;
+    int n_items;
+    const MergeGroup* groups;
+    int n_groups;
+    float* part_o;     // [slot][16][d]
+    float* part_ml;    // [slot][16][2]
+    bf16_t* out;       // [T][n_q * d]
+    int n_q, n_kv, d;
+    hipEvent_t ev_begin, ev_end;  // optional: recorded right before / after the main kernel (not the merge)
+};
+hipError_t launch_attention(const AttnArgs& a, hipStream_t st);
+
+}  // namespace ps

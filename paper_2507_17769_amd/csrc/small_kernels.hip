@@ -1,0 +1,205 @@
+// Bandwidth-trivial kernels of the step: RMSNorm, rotary embedding + KV append, logical
+// KV read/write, and the one-time weight repacks.  (Sec. 2.1: each module is preceded by an RMS
+// normalisation; the prefill pass fills the KV cache that later decode steps extend.)
+#include "ps_device.h"
+
+namespace ps {
+
+// ---------------------------------------------------------------------------- RMSNorm
+// One 256-thread block per token row: out = x * rsqrt(mean(x^2) + eps) * gain, fp32 math.
+template <bool X_F32>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const void* __restrict__ xin, const bf16_t* __restrict__ gain,
+                                                      bf16_t* __restrict__ out, int H, float eps) {
+    const int row = blockIdx.x;
+    const int tid = threadIdx.x;
+    __shared__ float red[4];
+    float ss = 0.f;
+    // every thread owns groups of 8 consecutive elements: tid*8 + k*2048
+    for (int c = tid * 8; c < H; c += 2048) {
+        float v[8];
+        if (X_F32) {
+            const float4* p = reinterpret_cast<const float4*>(static_cast<const float*>(xin) + (size_t)row * H + c);
+            float4 a = p[0], b = p[1];
+            v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+        } else {
+            uint4 w = ldg16(static_cast<const bf16_t*>(xin) + (size_t)row * H + c);
+            v[0] = bf16_lo(w.x); v[1] = bf16_hi(w.x); v[2] = bf16_lo(w.y); v[3] = bf16_hi(w.y);
+            v[4] = bf16_lo(w.z); v[5] = bf16_hi(w.z); v[6] = bf16_lo(w.w); v[7] = bf16_hi(w.w);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; i++) ss += v[i] * v[i];
+    }
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    __syncthreads();
+    const float tot = red[0] + red[1] + red[2] + red[3];
+    const float r = 1.0f / sqrtf(tot / (float)H + eps);
+    for (int c = tid * 8; c < H; c += 2048) {
+        float v[8];
+        if (X_F32) {
+            const float4* p = reinterpret_cast<const float4*>(static_cast<const float*>(xin) + (size_t)row * H + c);
+            float4 a = p[0], b = p[1];
+            v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+        } else {
+            uint4 w = ldg16(static_cast<const bf16_t*>(xin) + (size_t)row * H + c);
+            v[0] = bf16_lo(w.x); v[1] = bf16_hi(w.x); v[2] = bf16_lo(w.y); v[3] = bf16_hi(w.y);
+            v[4] = bf16_lo(w.z); v[5] = bf16_hi(w.z); v[6] = bf16_lo(w.w); v[7] = bf16_hi(w.w);
+        }
+        uint4 gw = ldg16(gain + c);
+        float g[8] = {bf16_lo(gw.x), bf16_hi(gw.x), bf16_lo(gw.y), bf16_hi(gw.y),
+                      bf16_lo(gw.z), bf16_hi(gw.z), bf16_lo(gw.w), bf16_hi(gw.w)};
+        uint4 o;
+        o.x = pack_bf16(v[0] * r * g[0], v[1] * r * g[1]);
+        o.y = pack_bf16(v[2] * r * g[2], v[3] * r * g[3]);
+        o.z = pack_bf16(v[4] * r * g[4], v[5] * r * g[5]);
+        o.w = pack_bf16(v[6] * r * g[6], v[7] * r * g[7]);
+        *reinterpret_cast<uint4*>(out + (size_t)row * H + c) = o;
+    }
+}
+
+hipError_t launch_rmsnorm(const void* x, bool x_is_f32, const bf16_t* gain, bf16_t* out, int T, int H, float eps,
+                          hipStream_t st) {
+    if (T <= 0) return hipSuccess;
+    if (x_is_f32)
+        hipLaunchKernelGGL(rmsnorm_kernel<true>, dim3(T), dim3(256), 0, st, x, gain, out, H, eps);
+    else
+        hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3(T), dim3(256), 0, st, x, gain, out, H, eps);
+    return hipGetLastError();
+}
+
+// --------------------------------------------------------------- rotary + KV append
+// grid (T, n_q + 2 n_kv), 64 threads.  Thread j < d/2 owns the pair (j, j + d/2).
+// Input is the fp32 QKV projection [T][(n_q + 2 n_kv) d]; every value is rounded to bf16
+// exactly once, after the rotation: query heads go to q_out [T][n_q][d], key heads (rotated)
+// and value heads to their cache slot.  cs is the fp64-built table [position][d/2] of (cos, sin).
+__global__ __launch_bounds__(64) void rope_append_kernel(const float* __restrict__ qkv, bf16_t* __restrict__ q_out,
+                                                         int n_q, int n_kv, int d,
+                                                         const int32_t* __restrict__ positions,
+                                                         const int32_t* __restrict__ slots,
+                                                         const float2* __restrict__ cs, bf16_t* __restrict__ pool) {
+    const int t = blockIdx.x;
+    const int hh = blockIdx.y;
+    const int j = threadIdx.x;
+    const int half = d >> 1;
+    if (j >= half) return;
+    const int ld = (n_q + 2 * n_kv) * d;
+    const float* row = qkv + (size_t)t * ld + (size_t)hh * d;
+    const float lo = row[j];
+    const float hi = row[j + half];
+    if (hh < n_q + n_kv) {
+        const float2 c = cs[(size_t)positions[t] * half + j];
+        const bf16_t blo = f32_to_bf16(lo * c.x - hi * c.y);
+        const bf16_t bhi = f32_to_bf16(hi * c.x + lo * c.y);
+        if (hh < n_q) {
+            bf16_t* qr = q_out + ((size_t)t * n_q + hh) * d;
+            qr[j] = blo;
+            qr[j + half] = bhi;
+        } else {
+            const int h = hh - n_q;
+            const int slot = slots[t];
+            bf16_t* kc = pool + (((size_t)(slot >> 4) * n_kv + h) * 2 + 0) * (size_t)(16 * d);
+            kc[k_elem_offset(slot & 15, j)] = blo;
+            kc[k_elem_offset(slot & 15, j + half)] = bhi;
+        }
+    } else {
+        const int h = hh - n_q - n_kv;
+        const int slot = slots[t];
+        bf16_t* vc = pool + (((size_t)(slot >> 4) * n_kv + h) * 2 + 1) * (size_t)(16 * d);
+        vc[v_elem_offset(slot & 15, j)] = f32_to_bf16(lo);
+        vc[v_elem_offset(slot & 15, j + half)] = f32_to_bf16(hi);
+    }
+}
+
+hipError_t launch_rope_append(const float* qkv, bf16_t* q_out, int T, int n_q, int n_kv, int d,
+                              const int32_t* positions, const int32_t* slots, const float* rope_cs, bf16_t* pool_slot,
+                              hipStream_t st) {
+    if (T <= 0) return hipSuccess;
+    hipLaunchKernelGGL(rope_append_kernel, dim3(T, n_q + 2 * n_kv), dim3(64), 0, st, qkv, q_out, n_q, n_kv, d,
+                       positions, slots, reinterpret_cast<const float2*>(rope_cs), pool_slot);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------- logical KV write / read
+// grid (n, n_kv), 64 threads; k, v are [n][n_kv][d] in logical order.
+template <bool TO_POOL>
+__global__ __launch_bounds__(64) void kv_copy_kernel(bf16_t* __restrict__ pool, const int32_t* __restrict__ slots,
+                                                     int n_kv, int d, bf16_t* __restrict__ k, bf16_t* __restrict__ v) {
+    const int i = blockIdx.x, h = blockIdx.y;
+    const int slot = slots[i];
+    bf16_t* kc = pool + (((size_t)(slot >> 4) * n_kv + h) * 2 + 0) * (size_t)(16 * d);
+    bf16_t* vc = kc + 16 * d;
+    bf16_t* kr = k + ((size_t)i * n_kv + h) * d;
+    bf16_t* vr = v + ((size_t)i * n_kv + h) * d;
+    const int tok = slot & 15;
+    for (int dd = threadIdx.x; dd < d; dd += 64) {
+        if (TO_POOL) {
+            kc[k_elem_offset(tok, dd)] = kr[dd];
+            vc[v_elem_offset(tok, dd)] = vr[dd];
+        } else {
+            kr[dd] = kc[k_elem_offset(tok, dd)];
+            vr[dd] = vc[v_elem_offset(tok, dd)];
+        }
+    }
+}
+
+hipError_t launch_kv_copy(bool to_pool, bf16_t* pool_slot, const int32_t* slots_dev, int n, int n_kv, int d, bf16_t* k,
+                          bf16_t* v, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    if (to_pool)
+        hipLaunchKernelGGL(kv_copy_kernel<true>, dim3(n, n_kv), dim3(64), 0, st, pool_slot, slots_dev, n_kv, d, k, v);
+    else
+        hipLaunchKernelGGL(kv_copy_kernel<false>, dim3(n, n_kv), dim3(64), 0, st, pool_slot, slots_dev, n_kv, d, k, v);
+    return hipGetLastError();
+}
+
+// ----------------------------------------------------------------- weight repacks
+// W [K][N] (math layout) -> Wt [row(n)][K].  interleave = 0: row(n) = n.  interleave = 1/2
+// (gate / up): row(f) = (f/32)*64 + f%32 + (interleave == 2 ? 32 : 0), so that every aligned
+// group of 64 rows of the fused matrix holds gate rows f..f+31 then up rows f..f+31.
+__global__ __launch_bounds__(256) void transpose_weight_kernel(const bf16_t* __restrict__ w, bf16_t* __restrict__ wt,
+                                                               int K, int N, int interleave) {
+    __shared__ bf16_t tile[64][66];
+    const int n0 = blockIdx.x * 64, k0 = blockIdx.y * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int r = ty; r < 64; r += 4) {
+        const int k = k0 + r, n = n0 + tx;
+        tile[r][tx] = (k < K && n < N) ? w[(size_t)k * N + n] : (bf16_t)0;
+    }
+    __syncthreads();
+    for (int r = ty; r < 64; r += 4) {
+        const int n = n0 + r, k = k0 + tx;
+        if (n < N && k < K) {
+            int row = n;
+            if (interleave) row = (n >> 5) * 64 + (n & 31) + (interleave == 2 ? 32 : 0);
+            wt[(size_t)row * K + k] = tile[tx][r];
+        }
+    }
+}
+
+hipError_t launch_transpose_weight(const bf16_t* w, bf16_t* wt, int K, int N, hipStream_t st) {
+    hipLaunchKernelGGL(transpose_weight_kernel, dim3((N + 63) / 64, (K + 63) / 64), dim3(256), 0, st, w, wt, K, N, 0);
+    return hipGetLastError();
+}
+
+hipError_t launch_interleave_gate_up(const bf16_t* wg, const bf16_t* wu, bf16_t* wt, int K, int F, hipStream_t st) {
+    dim3 grid((F + 63) / 64, (K + 63) / 64);
+    hipLaunchKernelGGL(transpose_weight_kernel, grid, dim3(256), 0, st, wg, wt, K, F, 1);
+    hipLaunchKernelGGL(transpose_weight_kernel, grid, dim3(256), 0, st, wu, wt, K, F, 2);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void copy_bytes_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+    for (size_t i = blockIdx.x * (size_t)256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+// Device-to-device copy of n bytes (n a multiple of 16, both pointers 16-byte aligned).
+hipError_t launch_copy_bytes(const void* src, void* dst, size_t n, hipStream_t st) {
+    const size_t n16 = n / 16;
+    if (n16 == 0) return hipSuccess;
+    const int blocks = (int)((n16 + 255) / 256 < 4096 ? (n16 + 255) / 256 : 4096);
+    hipLaunchKernelGGL(copy_bytes_kernel, dim3(blocks), dim3(256), 0, st, static_cast<const uint4*>(src),
+                       static_cast<uint4*>(dst), n16);
+    return hipGetLastError();
+}
+
+}  // namespace ps

@@ -41,18 +41,18 @@ def normal_bf16(rng, shape, std=1.0):
     return _to_bf16_bits(x)
 
 
-def layer_weights(model, seed, layer=0):
-    """bfloat16 N(0, 0.02^2) weights in math layout [in][out]; unit gains."""
+def layer_weights(model, seed, layer=0, std=WEIGHT_STD):
+    """bfloat16 N(0, std^2) weights (std 0.02 by default) in math layout [in][out]; unit gains."""
     m = MODELS[model] if isinstance(model, str) else model
     rng = np.random.Generator(np.random.PCG64([int(seed), 7919, int(layer)]))
     H, nq, nkv, d, F = m["hidden"], m["n_q"], m["n_kv"], m["head_dim"], m["ffn"]
     one = np.uint16(0x3F80)
     return {
-        "w_qkv": normal_bf16(rng, (H, (nq + 2 * nkv) * d), WEIGHT_STD),
-        "w_o": normal_bf16(rng, (nq * d, H), WEIGHT_STD),
-        "w_gate": normal_bf16(rng, (H, F), WEIGHT_STD),
-        "w_up": normal_bf16(rng, (H, F), WEIGHT_STD),
-        "w_down": normal_bf16(rng, (F, H), WEIGHT_STD),
+        "w_qkv": normal_bf16(rng, (H, (nq + 2 * nkv) * d), std),
+        "w_o": normal_bf16(rng, (nq * d, H), std),
+        "w_gate": normal_bf16(rng, (H, F), std),
+        "w_up": normal_bf16(rng, (H, F), std),
+        "w_down": normal_bf16(rng, (F, H), std),
         "g_attn": np.full(H, one, dtype=np.uint16),
         "g_ffn": np.full(H, one, dtype=np.uint16),
     }

@@ -1,0 +1,201 @@
+"""GPU parity: libpolystep (through its C ABI) against the CPU oracle, element by element, on
+the same seeded inputs.  Bar: max |err| <= 2e-2 x RMS of the oracle tensor for every
+floating-point tensor checked; integer results (slots written, untouched cache) bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2507_17769_amd import binding as B
+from paper_2507_17769_amd import workloads as W
+from gpu_harness import TOL, Case, bits_to_dev, dev_to_bits, f32, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def _assert_errs(errs, tag=""):
+    bad = {k: v for k, v in errs.items() if not v <= TOL}
+    assert not bad, f"{tag} over tolerance: {bad} (all: {errs})"
+
+
+def test_cfg0_tiny_mixed_batch_all_tensors():
+    c = Case(W.config_batch(0, seed=0))
+    errs = c.run()
+    print("cfg0 errors", errs, "append mismatch frac", c.check_pool())
+    _assert_errs(errs, "cfg0")
+    assert c.stats.n_tokens == 68 and c.stats.total_kv == 128 + 17 + 64 + 100 + 128
+    c.close()
+
+
+@pytest.mark.parametrize("chunk,prefix,decodes", [
+    (1, 0, []), (1, 1, [1]), (3, 15, [2, 16]), (15, 0, [17]), (16, 16, [31, 32, 33]), (17, 100, [1, 1, 1]),
+    (33, 1, [64]), (100, 37, [5, 250]), (0, 0, [1]), (0, 0, [1, 2, 3, 15, 16, 17, 18, 255, 256, 257]),
+    (130, 0, []), (257, 300, [300]),
+])
+def test_ragged_shapes_tiny_model(chunk, prefix, decodes):
+    b = W.custom_batch("tiny", 11, chunk, prefix, decodes, name="ragged")
+    c = Case(b)
+    errs = c.run()
+    _assert_errs(errs, f"chunk={chunk} prefix={prefix} decodes={decodes}")
+    c.check_pool()
+    c.close()
+
+
+def test_unit_scale_branches():
+    # weights of std 1/sqrt(hidden) make the attention and FFN branches as large as the residual
+    # stream, so an error in the O or down projection cannot hide behind it in `out`
+    b = W.custom_batch("tiny", 21, 48, 80, [1, 30, 200, 700], name="unit")
+    c = Case(b, weight_std=1.0 / 16.0)
+    errs = c.run()
+    print("unit-scale errors", errs)
+    _assert_errs(errs, "unit scale")
+    c.close()
+
+
+@pytest.mark.parametrize("n_q,n_kv,d", [(4, 4, 64), (8, 4, 128), (8, 2, 64), (8, 1, 128), (16, 1, 64), (16, 1, 128)])
+def test_gqa_group_sizes_and_head_dims(n_q, n_kv, d):
+    model = dict(hidden=256, n_q=n_q, n_kv=n_kv, head_dim=d, ffn=320, rope_base=10000.0, n_layers=1)
+    W.MODELS["_t"] = model
+    try:
+        b = W.custom_batch("_t", 5, 21, 40, [1, 17, 90], name="gqa")
+        c = Case(b)
+        errs = c.run()
+        _assert_errs(errs, f"nq={n_q} nkv={n_kv} d={d}")
+        c.check_pool()
+        c.close()
+    finally:
+        del W.MODELS["_t"]
+
+
+def test_split_plans_agree_and_runs_are_deterministic():
+    b = W.custom_batch("tiny", 3, 40, 200, [1, 33, 500, 1000], name="splits")
+    outs = []
+    for split in (0, 2, 4, 6, 1000):
+        c = Case(b, options={"attn_split_pages": split})
+        errs = c.run()
+        _assert_errs(errs, f"split={split}")
+        first = c.out_bits.copy()
+        # same plan twice: bitwise identical
+        x_dev = bits_to_dev(c.x_bits, c.eng.device)
+        again, _ = c.eng.step(b.seqs, x_dev)
+        c.eng.ctx.sync()
+        assert np.array_equal(dev_to_bits(again), first)
+        outs.append(c.out32.copy())
+        c.close()
+    for o in outs[1:]:
+        assert rel_err(o, outs[0]) <= TOL
+
+
+def test_chunked_prefill_on_gpu_matches_one_shot_and_oracle():
+    # Sec. 2.4 / 4.7: any chunking of a prompt must give the same cache and outputs
+    L = 150
+    base = W.custom_batch("tiny", 9, L, 0, [], name="oneshot")
+    one = Case(base)
+    errs = one.run()
+    _assert_errs(errs, "one-shot")
+    x_bits = one.x_bits
+    ref = f32(one.out_bits)
+    hb = 2.0 ** -8        # the hand-driven chunks below produce bf16 output: allow its storage rounding
+    for chunks in ([1, 149], [64, 64, 22], [17, 1, 100, 32]):
+        c = Case(base)                       # same pages, weights; we drive the chunks by hand
+        outs, done = [], 0
+        for n in chunks:
+            seqs = [(7, n, done + n, base.seqs[0].pages)]
+            x_dev = bits_to_dev(x_bits[done:done + n], c.eng.device)
+            o, _ = c.eng.step(seqs, x_dev)
+            c.eng.ctx.sync()
+            outs.append(f32(dev_to_bits(o)))
+            done += n
+        got = np.concatenate(outs)
+        w64 = one.want.astype(np.float64)
+        rms = np.sqrt(np.mean(w64 * w64))
+        assert np.all(np.abs(got - w64) <= TOL * rms + hb * np.abs(w64))
+        assert np.all(np.abs(got - ref) <= TOL * rms + 2 * hb * np.abs(ref))
+        k1, v1 = one.eng.read_kv(0, base.seqs[0].pages, 0, L)
+        k2, v2 = c.eng.read_kv(0, base.seqs[0].pages, 0, L)
+        from gpu_harness import bf16_ulp_distance
+        for a_, b_ in ((k1, k2), (v1, v2)):
+            fa, fb = f32(a_).astype(np.float64), f32(b_).astype(np.float64)
+            assert np.all(np.abs(fa - fb) <= 2.0 ** -7 * np.abs(fa) + 1e-3 * np.sqrt(np.mean(fa * fa)))
+        c.close()
+    one.close()
+
+
+def test_decode_with_kv_len_one_returns_v():
+    b = W.custom_batch("tiny", 2, 0, 0, [1, 1, 1], name="kv1")
+    c = Case(b)
+    T = 3
+    taps = c.eng.alloc_taps(T)
+    c.eng.ctx.set_taps(0, **{k: t.data_ptr() for k, t in taps.items()})
+    x_dev = bits_to_dev(c.x_bits, c.eng.device)
+    c.eng.step(b.seqs, x_dev)
+    c.eng.ctx.sync()
+    attn = dev_to_bits(taps["attn"]).reshape(T, 4, 64)
+    for i, s in enumerate(b.seqs):
+        k, v = c.eng.read_kv(0, s.pages, 0, 1)
+        for h in range(4):
+            assert np.array_equal(attn[i, h], v[0, h // 2])          # softmax of one logit is exactly 1
+    c.close()
+
+
+def test_three_layer_stack_with_two_kv_slots():
+    b = W.custom_batch("tiny", 4, 20, 30, [1, 40], name="stack")
+    c = Case(b, n_layers=3, n_kv_layers=3)
+    errs = c.run(tap_layer=2)
+    _assert_errs(errs, "stack")
+    c.check_pool()
+    c.close()
+
+
+def test_kv_write_read_roundtrip_is_exact():
+    b = W.custom_batch("tiny", 6, 0, 0, [77], name="rt")
+    c = Case(b)
+    rng = np.random.default_rng(0)
+    k = rng.integers(0, 0x7F80, size=(50, 2, 64)).astype(np.uint16)
+    v = rng.integers(0, 0x7F80, size=(50, 2, 64)).astype(np.uint16)
+    pages = b.seqs[0].pages
+    c.eng.write_kv(0, pages, 13, k, v)
+    k2, v2 = c.eng.read_kv(0, pages, 13, 50)
+    assert np.array_equal(k, k2) and np.array_equal(v, v2)
+    with pytest.raises(B.PolystepError) as e:
+        c.eng.read_kv(0, pages, 70, 20)
+    assert e.value.status == B.PS_ERANGE
+    c.close()
+
+
+def test_state_errors_and_empty_step():
+    m = W.MODELS["tiny"]
+    ctx = B.Context(m["hidden"], m["n_q"], m["n_kv"], m["head_dim"], m["ffn"], 1, 256, 1e-5, 1e4)
+    x = torch.zeros((4, 256), dtype=torch.int16, device="cuda")
+    with pytest.raises(B.PolystepError) as e:
+        ctx.step([(1, 1, 1, [0])], x.data_ptr(), x.data_ptr())
+    assert e.value.status == B.PS_ESTATE and "pool" in str(e.value)
+    ctx.kv_alloc(4, 1, 0)
+    with pytest.raises(B.PolystepError) as e:
+        ctx.step([(1, 1, 1, [0])], x.data_ptr(), x.data_ptr())
+    assert e.value.status == B.PS_ESTATE and "weights" in str(e.value)
+    w = W.layer_weights("tiny", 0)
+    dev = {k: bits_to_dev(v, "cuda") for k, v in w.items()}
+    ctx.init_layer(0, **{k: t.data_ptr() for k, t in dev.items()})
+    st = ctx.step([], 0, 0, want_stats=True)
+    assert st.n_tokens == 0
+    with pytest.raises(B.PolystepError) as e:          # invalid batch: nothing launched, pool untouched
+        ctx.step([(1, 1, 1, [9])], x.data_ptr(), x.data_ptr())
+    assert e.value.status == B.PS_ERANGE
+    ctx.step([(1, 1, 1, [0])], x.data_ptr(), x.data_ptr())
+    ctx.sync()
+    ctx.destroy()
+
+
+def test_profile_grid_small():
+    from paper_2507_17769_amd.runner import Engine
+    eng = Engine("tiny", 400, max_position=1024)
+    eng.load_layer(0, W.layer_weights("tiny", 0))
+    x = torch.zeros((80, 256), dtype=torch.int16, device="cuda")
+    y = torch.zeros_like(x)
+    cells = [(0, 0, [0, 0], np.zeros((2, 0))), (64, 4, [64, 10], [[17, 64, 100, 128], [1, 2, 3, 400]]), (0, 16, [0], [list(range(100, 116))])]
+    out = eng.ctx.profile_grid(cells, x.data_ptr(), y.data_ptr(), warmup=1, iters=3)
+    assert out[0].n_tokens == 0 and out[1].n_tokens == 68 and out[2].n_tokens == 16
+    assert out[1].median_ms > 0 and out[1].total_kv in (128 + 309, 74 + 406)
+    assert abs(sum(out[2].stage_ms) - out[2].median_ms) < 5 * out[2].median_ms
+    assert eng.ctx.kv_free_pages() == 400
+    eng.close()

@@ -435,3 +435,21 @@ def test_stack_uses_kv_slot_per_layer():
         y = layer.layer_forward(y, ws[l], seqs, p, 0, sh)
         assert np.array_equal(p.bits[0], pool.bits[l])
     assert np.array_equal(out, y)
+
+
+def test_bf16_activation_variant_stays_within_rounding_of_the_definition():
+    rng = np.random.default_rng(16)
+    sh = _tiny_shape()
+    w = _tiny_weights(rng, sh)
+    x = rng.standard_normal((40, sh.hidden))
+    pages = [0, 2, 1]
+    seqs = [Seq(40, 40, pages)]
+    ta, tb = {}, {}
+    a = layer.layer_forward(x, w, seqs, PagedKV(3, 1, sh.n_kv, sh.head_dim), 0, sh, ta)
+    b = layer.layer_forward(x, w, seqs, PagedKV(3, 1, sh.n_kv, sh.head_dim), 0, sh, tb, bf16_activations=True)
+    rms = np.sqrt(np.mean(a * a))
+    assert 0 < np.max(np.abs(a - b)) < 5e-2 * rms      # these test weights (std 0.2) amplify every rounding ~4x
+    for name in ("xn", "q", "attn", "xn2", "act"):
+        stored = tb[name]
+        assert np.array_equal(bf16.round_trip(stored.astype(np.float32)).astype(np.float64), stored)   # exactly bf16 values
+    assert np.max(np.abs(tb["xn"] - ta["xn"])) <= 2.0 ** -8 * np.max(np.abs(ta["xn"]))                  # half an ulp
