@@ -29,6 +29,8 @@ def parse():
     ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg2"])
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 1 GiB device-to-device copy a few times (reference for HBM byte counters)")
     return ap.parse_args()
 
 
@@ -72,6 +74,15 @@ def main():
     from paper_2507_17769_amd.binding import STAGE_NAMES, SeqArray
     from paper_2507_17769_amd.runner import Engine, bits_to_dev
 
+    if a.calibrate_copy:
+        n = 1 << 30
+        src = torch.ones(n, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes": n, "copies": 3}))
+        return
     cfg = {"cfg1": 1, "cfg2": 2}[a.workload]
     batch = W.config_batch(cfg, a.seed)
     model = W.MODELS[batch.model]

@@ -123,8 +123,9 @@ void ps_destroy(ps_ctx* ctx);
  * recent failing ps_create on this thread).  Never null; valid until the next call. */
 const char* ps_last_error(const ps_ctx* ctx);
 
-/* Tuning knobs, mainly for tests: "attn_split_pages" (target KV pages per attention
- * work item; different values must give the same results within rounding),
+/* Tuning knobs, mainly for tests: "attn_workers" (number of wavefront-workers the attention
+ * KV streams are cut across, 0 = one per resident wavefront; different values cut the streams
+ * in different places and must give the same results within rounding),
  * "gemm_split_k" (0 = automatic), "out_f32" (1: ps_step writes x_out as fp32 [T][hidden],
  * the precision the residual stream is kept in, instead of rounding it to bf16).
  * "time_attention" (1: bracket every attention kernel launch with HIP events, see
@@ -193,7 +194,8 @@ ps_status ps_step_indices(ps_ctx* ctx, const ps_seq* seqs, int32_t n_seqs, int32
 /* The attention work list the step would launch, host only.  Each item is 8 int32:
  * {seq index, kv head, first new-token index of its query block, number of query tokens,
  *  first KV page (logical), one past last KV page, partial slot or -1 when the item
- *  writes final output, merge group}.  Writes min(*n_items, cap) items. */
+ *  writes final output, worker}.  Items are listed worker by worker; every worker's items
+ * carry (nearly) the same total KV weight.  Writes min(*n_items, cap) items. */
 ps_status ps_plan_attention(ps_ctx* ctx, const ps_seq* seqs, int32_t n_seqs, int32_t* items, int32_t cap, int32_t* n_items);
 
 /* Durations (ms) of the attention kernel launches (one per layer per step, split merge

@@ -61,7 +61,8 @@ struct ps_ctx {
     int staging_next = 0;
 
     // options / debug
-    int opt_split_pages = 0;
+    int opt_attn_workers = 0;
+    int worker_slots = 2048;
     int opt_gemm_split_k = 0;
     bool opt_out_f32 = false;
     int tap_layer = -1;
@@ -119,7 +120,8 @@ static PlanConfig plan_config(const ps_ctx* c) {
     pc.group = c->desc.n_q_heads / c->desc.n_kv_heads;
     pc.max_position = c->desc.max_position;
     pc.n_pool_pages = c->n_pool_pages;
-    pc.split_pages = c->opt_split_pages;
+    pc.n_workers = c->opt_attn_workers;
+    pc.worker_slots = c->worker_slots;
     pc.prefill_tokens = attn_prefill_tokens_per_item(pc.group);
     return pc;
 }
@@ -167,6 +169,7 @@ extern "C" ps_status ps_create(const ps_model_desc* desc, void* hip_stream, ps_c
     if (st != PS_OK) { delete c; return st; }
     hipError_t e = hipMemcpy(c->rope_cs, cs.data(), cs.size() * sizeof(float), hipMemcpyHostToDevice);
     if (e != hipSuccess) { ps_destroy(c); return hip_fail(nullptr, e, "hipMemcpy(rotary table)"); }
+    c->worker_slots = attention_worker_slots();
     *out = c;
     return PS_OK;
 }
@@ -212,9 +215,9 @@ extern "C" const char* ps_last_error(const ps_ctx* c) { return c ? c->err.c_str(
 
 extern "C" ps_status ps_set_option(ps_ctx* c, const char* name, int64_t value) {
     if (!c || !name) return fail(c, PS_EINVAL, "ps_set_option: null argument");
-    if (!strcmp(name, "attn_split_pages")) {
-        if (value < 0 || value > (1 << 20)) return fail(c, PS_EINVAL, "attn_split_pages must be in [0, 2^20]");
-        c->opt_split_pages = (int)value;
+    if (!strcmp(name, "attn_workers")) {
+        if (value < 0 || value > (1 << 20)) return fail(c, PS_EINVAL, "attn_workers must be in [0, 2^20]");
+        c->opt_attn_workers = (int)value;
         return PS_OK;
     }
     if (!strcmp(name, "gemm_split_k")) {
@@ -449,8 +452,8 @@ extern "C" ps_status ps_plan_attention(ps_ctx* c, const ps_seq* seqs, int32_t n_
     const StepPlan& p = c->plan;
     *n_items = (int32_t)p.items.size();
     const int n = std::min<int>(cap, (int)p.items.size());
-    static_assert(sizeof(AttnItem) == 8 * sizeof(int32_t), "item is 8 int32");
-    if (n > 0) memcpy(items, p.items.data(), (size_t)n * sizeof(AttnItem));
+    static_assert(sizeof(AttnItem) == 12 * sizeof(int32_t), "item is 12 int32, the first 8 are reported");
+    for (int i = 0; i < n; i++) memcpy(items + (size_t)i * 8, &p.items[i], 8 * sizeof(int32_t));
     return PS_OK;
 }
 
@@ -507,7 +510,7 @@ static ps_status ensure_workspaces(ps_ctx* c, int T, int n_part_slots) {
 }
 
 struct MetaLayout {
-    size_t positions, slots, seqs, pages, items, groups, total;
+    size_t positions, slots, seqs, pages, items, workers, groups, total;
 };
 static MetaLayout meta_layout(const StepPlan& p) {
     MetaLayout m;
@@ -517,6 +520,7 @@ static MetaLayout meta_layout(const StepPlan& p) {
     m.seqs = at;      at = align16(at + p.seqs.size() * sizeof(SeqInfo));
     m.pages = at;     at = align16(at + p.pages.size() * 4);
     m.items = at;     at = align16(at + p.items.size() * sizeof(AttnItem));
+    m.workers = at;   at = align16(at + p.worker_begin.size() * 4);
     m.groups = at;    at = align16(at + p.groups.size() * sizeof(MergeGroup));
     m.total = at;
     return m;
@@ -556,6 +560,7 @@ extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, cons
     memcpy(hb + ml.seqs, p.seqs.data(), p.seqs.size() * sizeof(SeqInfo));
     memcpy(hb + ml.pages, p.pages.data(), p.pages.size() * 4);
     memcpy(hb + ml.items, p.items.data(), p.items.size() * sizeof(AttnItem));
+    memcpy(hb + ml.workers, p.worker_begin.data(), p.worker_begin.size() * 4);
     if (!p.groups.empty()) memcpy(hb + ml.groups, p.groups.data(), p.groups.size() * sizeof(MergeGroup));
     HIP_TRY(c, hipMemcpyAsync(c->dev_meta, sg->host, ml.total, hipMemcpyHostToDevice, c->stream));
     HIP_TRY(c, hipEventRecord(sg->done, c->stream));
@@ -607,6 +612,8 @@ extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, cons
         a.pages = reinterpret_cast<const int32_t*>(db + ml.pages);
         a.items = reinterpret_cast<const AttnItem*>(db + ml.items);
         a.n_items = (int)p.items.size();
+        a.worker_begin = reinterpret_cast<const int32_t*>(db + ml.workers);
+        a.n_workers = (int)p.worker_begin.size() - 1;
         a.groups = reinterpret_cast<const MergeGroup*>(db + ml.groups);
         a.n_groups = (int)p.groups.size();
         a.part_o = c->part_o; a.part_ml = c->part_ml; a.out = c->ws_attn;

@@ -3,7 +3,10 @@
 // prefix together with one-token decodes; Sec. 2.2: decode attention gets no batching
 // benefit, its cost follows the KV bytes read).
 //
-// One wavefront per work item = (sequence, kv head, query block, KV page range).  A query
+// One wavefront per worker; a worker runs a short list of work items = (sequence, kv head, query
+// block, KV page range) of equal total weight (see the planner), so all wavefronts stream for the
+// same time.  Decode items keep the next pair of pages in flight in registers while the current
+// pair is consumed.  A query
 // tile is 16 rows = (16/G tokens) x (G query heads of the kv head), so every K/V byte is
 // read once for the whole GQA group.  Per pair of 16-token pages:
 //     S^T[key][row]  = K . Q^T      (MFMA 16x16x32, K chunk is the A operand)
@@ -20,100 +23,93 @@ namespace ps {
 
 constexpr float NEG_BIG = -1.0e30f;
 
-template <int D, int G, int NT>
-__device__ __forceinline__ void attn_item(const AttnArgs& a, const AttnItem it) {
-    constexpr int KS = D / 32;   // MFMA k-steps over head_dim
-    constexpr int DT = D / 16;   // 16-row tiles of O^T
-    constexpr int TQ = 16 / G;   // tokens per query tile
-    const int lane = threadIdx.x & 63;
-    const int r = lane & 15, g = lane >> 4;
+// K and V chunks of a pair of pages, as loaded: 16 bytes per lane per register.
+template <int KS>
+struct PairRegs {
+    uint4 ka[KS], kb[KS], va[KS], vb[KS];
+};
 
-    const SeqInfo sq = a.seqs[it.seq];
-    const int prefix = sq.kv_len - sq.n_new;
-    const int32_t* pages = a.pages + sq.page_off;
-    const int q_last = it.q_tok0 + it.q_ntok - 1;
-    const int head = it.kv_head * G + (r % G);
-
-    int qi[NT], pq[NT];
-    bool rvalid[NT];
-    bf16x8_t qf[NT][KS];
+template <int D>
+__device__ __forceinline__ void load_pair(PairRegs<D / 32>& p, const bf16_t* pool_lane, size_t page_stride, int pa, int pb) {
+    constexpr int KS = D / 32;
+    const bf16_t* ca = pool_lane + (size_t)pa * page_stride;
+    const bf16_t* cb = pool_lane + (size_t)pb * page_stride;
 #pragma unroll
-    for (int nt = 0; nt < NT; nt++) {
-        const int q = it.q_tok0 + nt * TQ + r / G;
-        rvalid[nt] = q <= q_last;
-        qi[nt] = min(q, q_last);
-        pq[nt] = prefix + qi[nt];
-        const bf16_t* qrow = a.q + (size_t)(sq.tok0 + qi[nt]) * a.ldq + head * D + 8 * g;
-#pragma unroll
-        for (int s = 0; s < KS; s++) qf[nt][s] = as_bf16x8(ldg16(qrow + 32 * s));
+    for (int s = 0; s < KS; s++) {
+        p.ka[s] = ldg16(ca + s * 512);
+        p.kb[s] = ldg16(cb + s * 512);
     }
+#pragma unroll
+    for (int s = 0; s < KS; s++) {
+        p.va[s] = ldg16(ca + 16 * D + s * 512);
+        p.vb[s] = ldg16(cb + 16 * D + s * 512);
+    }
+}
 
-    f32x4_t o[NT][DT];
+// Running softmax state of NT query tiles against one KV stream.
+template <int D, int NT>
+struct TileState {
+    f32x4_t o[NT][D / 16];
     float m[NT], lsum[NT];
+};
+
+// One pair of pages (32 keys) for all NT query tiles.  kpos0 = position of the pair's first key;
+// b_valid = the second page exists.  PV16 selects how P.V is issued: per page with 16x16x16 MFMAs
+// (bandwidth-bound decode items) or per pair with one 16x16x32 MFMA (compute-bound prefill items).
+template <int D, int NT, bool PV16>
+__device__ __forceinline__ void compute_pair(TileState<D, NT>& st, const PairRegs<D / 32>& p, const bf16x8_t (&qf)[NT][D / 32],
+                                             const int (&pq)[NT], int kpos0, bool b_valid, int g, float scale2) {
+    constexpr int KS = D / 32, DT = D / 16;
+    const int kpos_a = kpos0 + 4 * g, kpos_b = kpos_a + 16;
 #pragma unroll
     for (int nt = 0; nt < NT; nt++) {
-        m[nt] = NEG_BIG;
-        lsum[nt] = 0.f;
-#pragma unroll
-        for (int dt = 0; dt < DT; dt++) o[nt][dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    }
-
-    const float scale2 = 1.4426950408889634f / sqrtf((float)D);  // log2(e)/sqrt(d): softmax in base 2
-    const size_t chunk = (size_t)16 * D;                         // elements per K or V chunk
-    const size_t page_stride = (size_t)a.n_kv * 2 * chunk;
-    const bf16_t* pool_h = a.pool_slot + (size_t)it.kv_head * 2 * chunk + (size_t)lane * 8;
-
-    for (int pp = it.page_begin; pp < it.page_end; pp += 2) {
-        const bool b_valid = pp + 1 < it.page_end;
-        const int pa = pages[pp];
-        const int pb = b_valid ? pages[pp + 1] : pa;
-        const bf16_t* ca = pool_h + (size_t)pa * page_stride;
-        const bf16_t* cb = pool_h + (size_t)pb * page_stride;
-        uint4 ka[KS], kb[KS], va[KS], vb[KS];
+        f32x4_t sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < KS; s++) {
-            ka[s] = ldg16(ca + s * 512);
-            kb[s] = ldg16(cb + s * 512);
+            sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(p.ka[s]), qf[nt][s], sa, 0, 0, 0);
+            sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(p.kb[s]), qf[nt][s], sb, 0, 0, 0);
+        }
+        float sv[8];
+        bool ok[8];
+        float mx = NEG_BIG;
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            ok[i] = kpos_a + i <= pq[nt];
+            ok[4 + i] = b_valid && (kpos_b + i <= pq[nt]);
+            sv[i] = sa[i] * scale2;
+            sv[4 + i] = sb[i] * scale2;
         }
 #pragma unroll
-        for (int s = 0; s < KS; s++) {
-            va[s] = ldg16(ca + chunk + s * 512);
-            vb[s] = ldg16(cb + chunk + s * 512);
+        for (int i = 0; i < 8; i++) mx = ok[i] ? fmaxf(mx, sv[i]) : mx;
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(st.m[nt], mx);
+        const float alpha = __builtin_amdgcn_exp2f(st.m[nt] - m_new);
+        st.m[nt] = m_new;
+        float pv[8], ps = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            pv[i] = ok[i] ? __builtin_amdgcn_exp2f(sv[i] - m_new) : 0.f;
+            ps += pv[i];
         }
-        const int kpos_a = pp * 16 + 4 * g, kpos_b = kpos_a + 16;
-
+        st.lsum[nt] = st.lsum[nt] * alpha + ps;
+        if constexpr (PV16) {
+            // one 16x16x16 MFMA per page and d-tile: each 8-byte half of a loaded V register
+            // quad is an operand as it stands, so no register moves sit between load and use
+            const uint2 pwa = {pack_bf16(pv[0], pv[1]), pack_bf16(pv[2], pv[3])};
+            const uint2 pwb = {pack_bf16(pv[4], pv[5]), pack_bf16(pv[6], pv[7])};
+            const s16x4_t pfa = __builtin_bit_cast(s16x4_t, pwa), pfb = __builtin_bit_cast(s16x4_t, pwb);
 #pragma unroll
-        for (int nt = 0; nt < NT; nt++) {
-            f32x4_t sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int s = 0; s < KS; s++) {
-                sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka[s]), qf[nt][s], sa, 0, 0, 0);
-                sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kb[s]), qf[nt][s], sb, 0, 0, 0);
+            for (int dt = 0; dt < DT; dt++) {
+                const int s = dt >> 1;
+                const uint2 wa = (dt & 1) ? uint2{p.va[s].z, p.va[s].w} : uint2{p.va[s].x, p.va[s].y};
+                const uint2 wb = (dt & 1) ? uint2{p.vb[s].z, p.vb[s].w} : uint2{p.vb[s].x, p.vb[s].y};
+                f32x4_t acc = st.o[nt][dt];
+                acc[0] *= alpha; acc[1] *= alpha; acc[2] *= alpha; acc[3] *= alpha;
+                acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, wa), pfa, acc, 0, 0, 0);
+                st.o[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, wb), pfb, acc, 0, 0, 0);
             }
-            float sv[8];
-            bool ok[8];
-            float mx = NEG_BIG;
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-                ok[i] = kpos_a + i <= pq[nt];
-                ok[4 + i] = b_valid && (kpos_b + i <= pq[nt]);
-                sv[i] = sa[i] * scale2;
-                sv[4 + i] = sb[i] * scale2;
-            }
-#pragma unroll
-            for (int i = 0; i < 8; i++) mx = ok[i] ? fmaxf(mx, sv[i]) : mx;
-            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m[nt], mx);
-            const float alpha = __builtin_amdgcn_exp2f(m[nt] - m_new);
-            m[nt] = m_new;
-            float pv[8], ps = 0.f;
-#pragma unroll
-            for (int i = 0; i < 8; i++) {
-                pv[i] = ok[i] ? __builtin_amdgcn_exp2f(sv[i] - m_new) : 0.f;
-                ps += pv[i];
-            }
-            lsum[nt] = lsum[nt] * alpha + ps;
+        } else {
             uint4 pw;
             pw.x = pack_bf16(pv[0], pv[1]);
             pw.y = pack_bf16(pv[2], pv[3]);
@@ -124,41 +120,119 @@ __device__ __forceinline__ void attn_item(const AttnArgs& a, const AttnItem it) 
             for (int dt = 0; dt < DT; dt++) {
                 const int s = dt >> 1;
                 uint4 vw;
-                if (dt & 1) { vw.x = va[s].z; vw.y = va[s].w; vw.z = vb[s].z; vw.w = vb[s].w; }
-                else        { vw.x = va[s].x; vw.y = va[s].y; vw.z = vb[s].x; vw.w = vb[s].y; }
-                f32x4_t acc = o[nt][dt];
+                if (dt & 1) { vw.x = p.va[s].z; vw.y = p.va[s].w; vw.z = p.vb[s].z; vw.w = p.vb[s].w; }
+                else        { vw.x = p.va[s].x; vw.y = p.va[s].y; vw.z = p.vb[s].x; vw.w = p.vb[s].y; }
+                f32x4_t acc = st.o[nt][dt];
                 acc[0] *= alpha; acc[1] *= alpha; acc[2] *= alpha; acc[3] *= alpha;
-                o[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vw), pf, acc, 0, 0, 0);
+                st.o[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vw), pf, acc, 0, 0, 0);
+            }
+        }
+    }
+}
+
+// One work item on one wavefront.  PIPE = true keeps the next pair of pages in flight in a second
+// register set while the current pair is consumed (decode items: the wave is bandwidth-bound).
+template <int D, int G, int NT, bool PIPE>
+__device__ __forceinline__ void attn_item(const AttnArgs& a, const AttnItem it) {
+    constexpr int KS = D / 32;   // MFMA k-steps over head_dim
+    constexpr int DT = D / 16;   // 16-row tiles of O^T
+    constexpr int TQ = 16 / G;   // tokens per query tile
+    const int lane = threadIdx.x & 63;
+    const int r = lane & 15, g = lane >> 4;
+
+    const int32_t* pages = a.pages + it.page_off;
+    const int head = it.kv_head * G + (r % G);
+
+    int qi[NT], pq[NT];  // global token index and cache position of this lane's query row, per tile
+    bool rvalid[NT];
+    bf16x8_t qf[NT][KS];
+#pragma unroll
+    for (int nt = 0; nt < NT; nt++) {
+        const int ql = nt * TQ + r / G;  // token of the row within the block
+        rvalid[nt] = ql < it.q_ntok;
+        const int qc = min(ql, it.q_ntok - 1);
+        qi[nt] = it.tok_g0 + qc;
+        pq[nt] = it.pos0 + qc;
+        const bf16_t* qrow = a.q + (size_t)qi[nt] * a.ldq + head * D + 8 * g;
+#pragma unroll
+        for (int s = 0; s < KS; s++) qf[nt][s] = as_bf16x8(ldg16(qrow + 32 * s));
+    }
+
+    TileState<D, NT> st;
+#pragma unroll
+    for (int nt = 0; nt < NT; nt++) {
+        st.m[nt] = NEG_BIG;
+        st.lsum[nt] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < DT; dt++) st.o[nt][dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    }
+
+    const float scale2 = 1.4426950408889634f / sqrtf((float)D);  // log2(e)/sqrt(d): softmax in base 2
+    const size_t page_stride = (size_t)a.n_kv * 2 * 16 * D;
+    const bf16_t* pool_lane = a.pool_slot + (size_t)it.kv_head * 2 * 16 * D + (size_t)lane * 8;
+
+    // Pages are consumed in blocks of up to 64: lane l keeps the id of the block's page l, and a
+    // uniform readlane hands the ids out, so no load sits between a pair's id and its data.
+    for (int blk = it.page_begin; blk < it.page_end; blk += 64) {
+        const int n_pg = min(64, it.page_end - blk);
+        const int my_pid = pages[blk + min(lane, n_pg - 1)];
+        const int n_pairs = (n_pg + 1) >> 1;
+        auto pid = [&](int j) { return __builtin_amdgcn_readlane(my_pid, min(j, n_pg - 1)); };
+        if constexpr (PIPE) {
+            // Two register sets; the steady-state body issues its loads unconditionally so that the
+            // wait before each compute covers exactly the older set (a conditional load would force
+            // a wait for everything at the join).
+            PairRegs<KS> b0, b1;
+            load_pair<D>(b0, pool_lane, page_stride, pid(0), pid(1));
+            int i = 0;
+            for (; i + 2 < n_pairs; i += 2) {
+                load_pair<D>(b1, pool_lane, page_stride, pid(2 * i + 2), pid(2 * i + 3));
+                compute_pair<D, NT, PIPE>(st, b0, qf, pq, (blk + 2 * i) * 16, true, g, scale2);
+                load_pair<D>(b0, pool_lane, page_stride, pid(2 * i + 4), pid(2 * i + 5));
+                compute_pair<D, NT, PIPE>(st, b1, qf, pq, (blk + 2 * i + 2) * 16, true, g, scale2);
+            }
+            if (i + 2 == n_pairs) {
+                load_pair<D>(b1, pool_lane, page_stride, pid(2 * i + 2), pid(2 * i + 3));
+                compute_pair<D, NT, PIPE>(st, b0, qf, pq, (blk + 2 * i) * 16, true, g, scale2);
+                compute_pair<D, NT, PIPE>(st, b1, qf, pq, (blk + 2 * i + 2) * 16, 2 * i + 3 < n_pg, g, scale2);
+            } else {
+                compute_pair<D, NT, PIPE>(st, b0, qf, pq, (blk + 2 * i) * 16, 2 * i + 1 < n_pg, g, scale2);
+            }
+        } else {
+            PairRegs<KS> b0;
+            for (int i = 0; i < n_pairs; i++) {
+                load_pair<D>(b0, pool_lane, page_stride, pid(2 * i), pid(2 * i + 1));
+                compute_pair<D, NT, PIPE>(st, b0, qf, pq, (blk + 2 * i) * 16, 2 * i + 1 < n_pg, g, scale2);
             }
         }
     }
 
 #pragma unroll
     for (int nt = 0; nt < NT; nt++) {
-        float l = lsum[nt];
+        float l = st.lsum[nt];
         l += __shfl_xor(l, 16, 64);
         l += __shfl_xor(l, 32, 64);
         if (it.partial < 0) {
             if (rvalid[nt]) {
                 const float inv = 1.0f / l;
-                bf16_t* orow = a.out + (size_t)(sq.tok0 + qi[nt]) * (a.n_q * D) + head * D + 4 * g;
+                bf16_t* orow = a.out + (size_t)qi[nt] * (a.n_q * D) + head * D + 4 * g;
 #pragma unroll
                 for (int dt = 0; dt < DT; dt++) {
                     uint2 w;
-                    w.x = pack_bf16(o[nt][dt][0] * inv, o[nt][dt][1] * inv);
-                    w.y = pack_bf16(o[nt][dt][2] * inv, o[nt][dt][3] * inv);
+                    w.x = pack_bf16(st.o[nt][dt][0] * inv, st.o[nt][dt][1] * inv);
+                    w.y = pack_bf16(st.o[nt][dt][2] * inv, st.o[nt][dt][3] * inv);
                     *reinterpret_cast<uint2*>(orow + 16 * dt) = w;
                 }
             }
-        } else {
+        } else if (rvalid[nt]) {  // rows beyond the block's tokens are never merged: do not store them
             const size_t slot = (size_t)it.partial + nt;
             float* po = a.part_o + (slot * 16 + r) * D + 4 * g;
 #pragma unroll
             for (int dt = 0; dt < DT; dt++)
-                *reinterpret_cast<float4*>(po + 16 * dt) = float4{o[nt][dt][0], o[nt][dt][1], o[nt][dt][2], o[nt][dt][3]};
+                *reinterpret_cast<float4*>(po + 16 * dt) = float4{st.o[nt][dt][0], st.o[nt][dt][1], st.o[nt][dt][2], st.o[nt][dt][3]};
             if (g == 0) {
                 float* pm = a.part_ml + (slot * 16 + r) * 2;
-                pm[0] = m[nt];
+                pm[0] = st.m[nt];
                 pm[1] = l;
             }
         }
@@ -168,47 +242,47 @@ __device__ __forceinline__ void attn_item(const AttnArgs& a, const AttnItem it) 
 constexpr int PREFILL_NT = 2;  // query tiles per wave for multi-tile (prefill) items
 
 template <int D, int G>
-__global__ __launch_bounds__(64) void attn_kernel(AttnArgs a) {
-    const AttnItem it = a.items[blockIdx.x];
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_kernel(AttnArgs a) {
+    // one wavefront = one worker: it runs the items the planner assigned to it, in order
     constexpr int TQ = 16 / G;
-    if (it.q_ntok <= TQ)
-        attn_item<D, G, 1>(a, it);
-    else
-        attn_item<D, G, PREFILL_NT>(a, it);
+    const int i0 = a.worker_begin[blockIdx.x], i1 = a.worker_begin[blockIdx.x + 1];
+    for (int i = i0; i < i1; i++) {
+        const AttnItem it = a.items[i];
+        if (it.q_ntok <= TQ)
+            attn_item<D, G, 1, true>(a, it);
+        else
+            attn_item<D, G, PREFILL_NT, false>(a, it);
+    }
 }
 
 // Combine split partials of one query tile: out = sum_j 2^(m_j - M) O_j / sum_j 2^(m_j - M) l_j.
-// One 64-thread block per merge group; thread = (row r = tid%16, quarter of d = tid/16).
+// One 64-thread block per merge group; each thread owns float4 pieces of the valid rows.
 template <int D, int G>
 __global__ __launch_bounds__(64) void attn_merge_kernel(AttnArgs a) {
     const MergeGroup mg = a.groups[blockIdx.x];
-    const int r = threadIdx.x & 15, part = threadIdx.x >> 4;
-    const int tok = r / G;
-    if (tok >= mg.n_tok) return;
-    const int head = mg.kv_head * G + r % G;
-    float M = NEG_BIG;
-    for (int j = 0; j < mg.n_splits; j++)
-        M = fmaxf(M, a.part_ml[((size_t)(mg.first_slot + j * mg.stride) * 16 + r) * 2]);
-    float acc[D / 4];
-#pragma unroll
-    for (int i = 0; i < D / 4; i++) acc[i] = 0.f;
-    float L = 0.f;
-    for (int j = 0; j < mg.n_splits; j++) {
-        const size_t slot = (size_t)(mg.first_slot + j * mg.stride);
-        const float w = __builtin_amdgcn_exp2f(a.part_ml[(slot * 16 + r) * 2] - M);
-        L += w * a.part_ml[(slot * 16 + r) * 2 + 1];
-        const float4* po = reinterpret_cast<const float4*>(a.part_o + (slot * 16 + r) * D + part * (D / 4));
-#pragma unroll
-        for (int i = 0; i < D / 16; i++) {
-            const float4 v = po[i];
-            acc[4 * i + 0] += w * v.x; acc[4 * i + 1] += w * v.y; acc[4 * i + 2] += w * v.z; acc[4 * i + 3] += w * v.w;
+    const int n_rows = mg.n_tok * G;  // valid rows are the first n_tok * G of the tile
+    for (int c = threadIdx.x; c < n_rows * (D / 4); c += 64) {
+        const int r = c / (D / 4), col = (c % (D / 4)) * 4;
+        float M = NEG_BIG;
+        for (int j = 0; j < mg.n_splits; j++)
+            M = fmaxf(M, a.part_ml[((size_t)(mg.first_slot + j * mg.stride) * 16 + r) * 2]);
+        float4 acc = {0.f, 0.f, 0.f, 0.f};
+        float L = 0.f;
+        for (int j = 0; j < mg.n_splits; j++) {
+            const size_t row = (size_t)(mg.first_slot + j * mg.stride) * 16 + r;
+            const float2 ml = *reinterpret_cast<const float2*>(a.part_ml + row * 2);
+            const float w = __builtin_amdgcn_exp2f(ml.x - M);
+            const float4 v = *reinterpret_cast<const float4*>(a.part_o + row * D + col);
+            L += w * ml.y;
+            acc.x += w * v.x; acc.y += w * v.y; acc.z += w * v.z; acc.w += w * v.w;
         }
+        const float inv = 1.0f / L;
+        const int head = mg.kv_head * G + r % G;
+        uint2 w;
+        w.x = pack_bf16(acc.x * inv, acc.y * inv);
+        w.y = pack_bf16(acc.z * inv, acc.w * inv);
+        *reinterpret_cast<uint2*>(a.out + (size_t)(mg.tok0 + r / G) * (a.n_q * D) + head * D + col) = w;
     }
-    const float inv = 1.0f / L;
-    bf16_t* orow = a.out + (size_t)(mg.tok0 + tok) * (a.n_q * D) + head * D + part * (D / 4);
-#pragma unroll
-    for (int i = 0; i < D / 8; i++)
-        *reinterpret_cast<uint32_t*>(orow + 2 * i) = pack_bf16(acc[2 * i] * inv, acc[2 * i + 1] * inv);
 }
 
 int attn_prefill_tokens_per_item(int G) { return PREFILL_NT * (16 / G); }
@@ -216,7 +290,7 @@ int attn_prefill_tokens_per_item(int G) { return PREFILL_NT * (16 / G); }
 template <int D, int G>
 static hipError_t launch_dg(const AttnArgs& a, hipStream_t st) {
     if (a.ev_begin) (void)hipEventRecord(a.ev_begin, st);
-    hipLaunchKernelGGL((attn_kernel<D, G>), dim3(a.n_items), dim3(64), 0, st, a);
+    hipLaunchKernelGGL((attn_kernel<D, G>), dim3(a.n_workers), dim3(64), 0, st, a);
     hipError_t e = hipGetLastError();
     if (a.ev_end) (void)hipEventRecord(a.ev_end, st);
     if (e != hipSuccess || a.n_groups == 0) return e;
@@ -236,8 +310,17 @@ static hipError_t launch_d(const AttnArgs& a, hipStream_t st) {
     return hipErrorInvalidValue;
 }
 
+// Resident wavefronts of the attention kernel: CUs x 4 SIMDs x 2 (the kernel is built for two
+// wavefronts per SIMD).
+int attention_worker_slots() {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 2048;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 2048;
+    return cus * 4 * 2;
+}
+
 hipError_t launch_attention(const AttnArgs& a, hipStream_t st) {
-    if (a.n_items <= 0) return hipSuccess;
+    if (a.n_items <= 0 || a.n_workers <= 0) return hipSuccess;
     if (a.d == 128) return launch_d<128>(a, st);
     if (a.d == 64) return launch_d<64>(a, st);
     return hipErrorInvalidValue;

@@ -89,65 +89,97 @@ void build_indices(const ps_seq* seqs, int n_seqs, StepPlan& plan) {
     }
 }
 
+// Attention plan.  The KV stream of every (sequence, kv head, query block) is a segment of page
+// pairs; a decode token's cost is the bytes of its KV span (Sec. 2.2, 3.4: decode attention does
+// not batch, it scales with the KV tokens read).  Instead of fixed-size splits handed out
+// dynamically, the concatenation of all segments is cut into n_workers runs of equal weight, one
+// per resident wavefront, so that all wavefronts stream for the same time and the launch has no
+// tail.  A run that ends inside a segment leaves a partial; a merge pass combines the partials.
 void build_attention_plan(const PlanConfig& cfg, StepPlan& plan) {
     plan.items.clear();
     plan.groups.clear();
+    plan.worker_begin.clear();
     plan.n_partial_slots = 0;
     plan.n_partial_items = 0;
     const int TQ = 16 / cfg.group;                 // tokens per 16-row query tile
     const int multi_nt = cfg.prefill_tokens / TQ;  // tiles a multi-tile item always reserves
+    const int W_SINGLE = 2, W_MULTI = 3;           // relative cost of a page pair: one tile (bandwidth) / several (MFMA)
 
-    // total KV pages the launch will stream, to pick the split size
-    int split = cfg.split_pages;
-    if (split <= 0) {
-        int64_t page_heads = 0;
-        for (const SeqInfo& sq : plan.seqs) {
-            const int qb = sq.n_new <= TQ ? TQ : cfg.prefill_tokens;
-            const int prefix = sq.kv_len - sq.n_new;
-            for (int q0 = 0; q0 < sq.n_new; q0 += qb)
-                page_heads += (int64_t)ceil_div(prefix + std::min(sq.n_new, q0 + qb), PS_PAGE_SIZE) * cfg.n_kv_heads;
-        }
-        int64_t s = (page_heads + 4095) / 4096;
-        s = std::max<int64_t>(8, std::min<int64_t>(64, s));
-        split = (int)s;
-    }
-    split = std::max(2, split + (split & 1));  // even: pages are consumed in pairs
-
+    struct Segment { int seq, q0, qn, np, w; };
+    std::vector<Segment> segs;
+    int64_t units = 0;
     for (int si = 0; si < plan.n_seqs; si++) {
         const SeqInfo& sq = plan.seqs[si];
         const int prefix = sq.kv_len - sq.n_new;
         const int qb = sq.n_new <= TQ ? TQ : cfg.prefill_tokens;
         for (int q0 = 0; q0 < sq.n_new; q0 += qb) {
             const int qn = std::min(qb, sq.n_new - q0);
-            const int nt_alloc = qn <= TQ ? 1 : multi_nt;
-            const int n_tiles = ceil_div(qn, TQ);
             const int np = ceil_div(prefix + q0 + qn, PS_PAGE_SIZE);
-            int n_splits = ceil_div(np, split);
-            int pps = ceil_div(np, n_splits);
-            pps += pps & 1;
-            n_splits = ceil_div(np, pps);
-            for (int h = 0; h < cfg.n_kv_heads; h++) {
-                if (n_splits == 1) {
-                    plan.items.push_back(AttnItem{si, h, q0, qn, 0, np, -1, -1});
-                    continue;
+            const int w = qn <= TQ ? W_SINGLE : W_MULTI;
+            segs.push_back(Segment{si, q0, qn, np, w});
+            units += (int64_t)ceil_div(np, 2) * w * cfg.n_kv_heads;
+        }
+    }
+    if (segs.empty()) { plan.worker_begin.assign(1, 0); return; }
+    int n_workers = cfg.n_workers > 0 ? cfg.n_workers : cfg.worker_slots;
+    // do not spread thinner than ~4 decode page pairs per worker
+    n_workers = (int)std::max<int64_t>(1, std::min<int64_t>(n_workers, units / (4 * W_SINGLE)));
+    // worker w ends where the cumulative weight reaches (w+1) * units / n_workers, so rounding
+    // to whole pairs never accumulates
+    auto boundary = [&](int w) { return (int64_t)(((__int128)units * (w + 1)) / n_workers); };
+
+    plan.worker_begin.reserve(n_workers + 1);
+    plan.items.reserve(n_workers + segs.size() * cfg.n_kv_heads);
+    int worker = 0;
+    int64_t done = 0;                // cumulative weight handed out so far
+    int64_t left = boundary(0);      // weight the current worker may still take
+    plan.worker_begin.push_back(0);
+    auto next_worker = [&]() {
+        if (worker + 1 < n_workers) {
+            worker++;
+            plan.worker_begin.push_back((int32_t)plan.items.size());
+            left = boundary(worker) - done;
+        } else {
+            left = INT64_MAX / 4;  // whatever is left belongs to the last worker
+        }
+    };
+    for (const Segment& sg : segs) {
+        const SeqInfo& sq = plan.seqs[sg.seq];
+        const int n_pairs = ceil_div(sg.np, 2);
+        const int nt_alloc = sg.qn <= TQ ? 1 : multi_nt;
+        const int n_tiles = ceil_div(sg.qn, TQ);
+        for (int h = 0; h < cfg.n_kv_heads; h++) {
+            const size_t first = plan.items.size();
+            int pair = 0;
+            while (pair < n_pairs) {
+                int take = (int)std::min<int64_t>(n_pairs - pair, left / sg.w);
+                if (take <= 0) {
+                    // quota smaller than one pair: hand over, unless the worker is still empty
+                    if ((int)plan.items.size() > plan.worker_begin.back()) { next_worker(); continue; }
+                    take = 1;
                 }
+                plan.items.push_back(AttnItem{sg.seq, h, sg.q0, sg.qn, 2 * pair, std::min(sg.np, 2 * (pair + take)), -1,
+                                              worker, sq.tok0 + sg.q0, sq.kv_len - sq.n_new + sg.q0, sq.page_off, 0});
+                pair += take;
+                left -= (int64_t)take * sg.w;
+                done += (int64_t)take * sg.w;
+                if (left < sg.w && pair < n_pairs) next_worker();
+            }
+            const int n_splits = (int)(plan.items.size() - first);
+            if (n_splits > 1) {
                 const int base = plan.n_partial_slots;
-                const int g0 = (int)plan.groups.size();
                 for (int t = 0; t < n_tiles; t++)
-                    plan.groups.push_back(MergeGroup{sq.tok0 + q0 + t * TQ, std::min(TQ, qn - t * TQ), h, base + t,
+                    plan.groups.push_back(MergeGroup{sq.tok0 + sg.q0 + t * TQ, std::min(TQ, sg.qn - t * TQ), h, base + t,
                                                      n_splits, nt_alloc, 0, 0});
-                for (int j = 0; j < n_splits; j++)
-                    plan.items.push_back(AttnItem{si, h, q0, qn, j * pps, std::min(np, (j + 1) * pps),
-                                                  base + j * nt_alloc, g0});
+                for (int j = 0; j < n_splits; j++) plan.items[first + j].partial = base + j * nt_alloc;
                 plan.n_partial_slots += n_splits * nt_alloc;
                 plan.n_partial_items += n_splits;
             }
         }
     }
-    // longest first, so the tail of the launch is made of short items
-    auto weight = [&](const AttnItem& it) { return (it.page_end - it.page_begin) * (it.q_ntok <= TQ ? 1 : 2 * multi_nt); };
-    std::stable_sort(plan.items.begin(), plan.items.end(),
-                     [&](const AttnItem& x, const AttnItem& y) { return weight(x) > weight(y); });
+    // workers that received nothing (possible only through rounding) get empty ranges
+    while ((int)plan.worker_begin.size() < n_workers + 1) plan.worker_begin.push_back((int32_t)plan.items.size());
+    plan.worker_begin.back() = (int32_t)plan.items.size();
 }
 
 }  // namespace ps

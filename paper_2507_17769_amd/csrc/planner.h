@@ -17,7 +17,8 @@ struct StepPlan {
     std::vector<int32_t> slots;       // [T]
     std::vector<SeqInfo> seqs;        // [n_seqs]
     std::vector<int32_t> pages;       // flat page lists (only the ceil(kv_len/16) pages in use)
-    std::vector<AttnItem> items;
+    std::vector<AttnItem> items;        // grouped by worker, in worker order
+    std::vector<int32_t> worker_begin;  // [n_workers + 1]
     std::vector<MergeGroup> groups;
     int n_partial_slots = 0;
     int n_partial_items = 0;
@@ -28,7 +29,8 @@ struct PlanConfig {
     int group = 1;             // n_q_heads / n_kv_heads
     int max_position = 0;
     int n_pool_pages = -1;     // < 0: unknown (host-only context without a pool)
-    int split_pages = 0;       // target KV pages per attention item; 0 = automatic
+    int n_workers = 0;         // attention workers; 0 = one per resident wavefront slot
+    int worker_slots = 2048;   // wavefronts of the attention kernel resident at once
     int prefill_tokens = 8;    // query tokens per multi-tile attention item
 };
 

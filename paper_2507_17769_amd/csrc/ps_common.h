@@ -29,7 +29,8 @@ __host__ __device__ inline int v_elem_offset(int tok, int dd) {
     return ((((dd >> 5) * 4 + (tok >> 2)) * 16 + (dd & 15)) * 2 + ((dd >> 4) & 1)) * 4 + (tok & 3);
 }
 
-// Attention work item (8 x int32, mirrored by ps_plan_attention's output).
+// Attention work item.  The first 8 fields are what ps_plan_attention reports; the rest is
+// what the kernel needs so that it never has to look the sequence up.
 struct AttnItem {
     int32_t seq;         // index into the step's sequence table
     int32_t kv_head;
@@ -38,7 +39,11 @@ struct AttnItem {
     int32_t page_begin;  // logical KV pages [page_begin, page_end)
     int32_t page_end;
     int32_t partial;     // first partial slot, or -1: the item covers its whole KV span
-    int32_t group;       // merge group of its first tile (-1 when partial == -1)
+    int32_t worker;      // wavefront-worker the item is assigned to
+    int32_t tok_g0;      // global token index of the block's first query token
+    int32_t pos0;        // cache position of that token
+    int32_t page_off;    // offset of the sequence's page list in the flat page array
+    int32_t pad;
 };
 
 // Split-KV merge group: one 16-row query tile of one (sequence, kv head).
@@ -101,6 +106,8 @@ struct AttnArgs {
     const int32_t* pages;
     const AttnItem* items;
     int n_items;
+    const int32_t* worker_begin;  // [n_workers + 1]: items of worker w are [worker_begin[w], worker_begin[w+1])
+    int n_workers;
     const MergeGroup* groups;
     int n_groups;
     float* part_o;     // [slot][16][d]
@@ -110,5 +117,6 @@ struct AttnArgs {
     hipEvent_t ev_begin, ev_end;  // optional: recorded right before / after the main kernel (not the merge)
 };
 hipError_t launch_attention(const AttnArgs& a, hipStream_t st);
+int attention_worker_slots();  // wavefronts of the attention kernel that are resident at once on this device
 
 }  // namespace ps

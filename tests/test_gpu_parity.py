@@ -69,8 +69,8 @@ def test_gqa_group_sizes_and_head_dims(n_q, n_kv, d):
 def test_split_plans_agree_and_runs_are_deterministic():
     b = W.custom_batch("tiny", 3, 40, 200, [1, 33, 500, 1000], name="splits")
     outs = []
-    for split in (0, 2, 4, 6, 1000):
-        c = Case(b, options={"attn_split_pages": split})
+    for split in (0, 1, 3, 16, 100, 5000):
+        c = Case(b, options={"attn_workers": split})
         errs = c.run()
         _assert_errs(errs, f"split={split}")
         first = c.out_bits.copy()

@@ -141,23 +141,26 @@ def test_allocator_matches_oracle_bit_exact():
     assert e.value.status == B.PS_EINVAL
 
 
-def _check_plan_covers(b, c, split=None):
+def _check_plan_covers(b, c, workers=None):
     """Every (sequence, kv head, query token, kv page needed by that token) is covered by exactly
-    one work item, ranges start on even pages, and partial slots do not collide."""
+    one work item, ranges start on even pages, partial slots do not collide, items are listed by
+    worker, and the workers' KV weights are balanced."""
     m = W.MODELS[b.model]
     G = m["n_q"] // m["n_kv"]
-    if split is not None:
-        c.set_option("attn_split_pages", split)
+    if workers is not None:
+        c.set_option("attn_workers", workers)
     items = c.plan_attention(b.seqs)
     cover = {}
     slots_used = set()
-    for seq, h, q0, qn, p0, p1, part, grp in items.tolist():
+    per_seg = {}
+    for seq, h, q0, qn, p0, p1, part, worker in items.tolist():
         s = b.seqs[seq]
         assert 0 <= h < m["n_kv"] and 0 <= q0 and qn >= 1 and q0 + qn <= s.n_new
         need = oi.pages_needed(s.prefix + q0 + qn)
         assert 0 <= p0 < p1 <= need and p0 % 2 == 0
         full = (p0 == 0 and p1 == need)
         assert (part < 0) == full
+        per_seg.setdefault((seq, h, q0), []).append((p0, p1, part))
         if part >= 0:
             nt = 1 if qn <= 16 // G else 2
             for k in range(nt):
@@ -173,19 +176,30 @@ def _check_plan_covers(b, c, split=None):
             for q in {0, s.n_new // 2, s.n_new - 1}:
                 for p in range(oi.pages_needed(s.prefix + q + 1)):
                     assert (si, h, q, p) in cover
+    assert np.all(np.diff(items[:, 7]) >= 0)                     # listed worker by worker
+    for ranges in per_seg.values():                              # splits of a stream tile it in order
+        assert all(a[1] == b_[0] for a, b_ in zip(ranges, ranges[1:]))
     return items
+
+
+def _worker_weights(items, G):
+    w = {}
+    for seq, h, q0, qn, p0, p1, part, worker in items.tolist():
+        w[worker] = w.get(worker, 0) + ((p1 - p0 + 1) // 2) * (2 if qn <= 16 // G else 3)
+    return np.array(list(w.values()))
 
 
 def test_attention_plan_covers_everything_once():
     c = host_ctx()
     b = W.config_batch(0)
-    for split in (0, 2, 3, 4, 1000):
-        _check_plan_covers(b, c, split)
+    for workers in (0, 1, 2, 3, 7, 1000):
+        _check_plan_covers(b, c, workers)
     b = W.custom_batch("tiny", 1, 37, 1000, [1, 15, 16, 17, 500, 2000], name="odd")
-    for split in (0, 2, 6, 64):
-        _check_plan_covers(b, c, split)
-    b8 = W.config_batch(2)
+    for workers in (0, 1, 5, 64, 100000):
+        _check_plan_covers(b, c, workers)
     c8 = host_ctx("8b")
-    items = _check_plan_covers(b8, c8)
-    w = (items[:, 5] - items[:, 4]) * np.where(items[:, 3] > 4, 4, 1)
-    assert np.all(np.diff(w) <= 0)                   # longest first
+    for cfg in (1, 2):
+        b8 = W.config_batch(cfg)
+        items = _check_plan_covers(b8, c8)
+        w = _worker_weights(items, 4)
+        assert len(w) == 2048 and w.max() - w.min() <= 6, (len(w), w.min(), w.max())
