@@ -52,8 +52,8 @@ typedef enum {
 #define PS_FLAG_HOST_ONLY 1u /* no device is touched: allocator, index and planning calls only */
 
 /* Layer shape (Sec. 5.1 "Model and GPU": a GQA decoder of the LLaMA family).
- * Supported: head_dim 64 or 128; n_q_heads / n_kv_heads in {1,2,4,8,16}; hidden, ffn and
- * n_q_heads*head_dim multiples of 64; page_size 16.  rms_eps <= 0 selects 1e-5. */
+ * Supported: head_dim 64 or 128; n_q_heads / n_kv_heads in {1,2,4,8,16}; hidden (<= 8192),
+ * ffn and n_q_heads*head_dim multiples of 64; page_size 16.  rms_eps <= 0 selects 1e-5. */
 typedef struct {
     int32_t hidden, n_q_heads, n_kv_heads, head_dim, ffn, n_layers;
     int32_t page_size;    /* must be 16 */
@@ -86,8 +86,9 @@ typedef struct {
 } ps_seq;
 
 /* Per-step measurements.  Stages, summed over layers:
- * 0 RMSNorm(attn)  1 QKV GEMM  2 RoPE + KV append  3 attention (+ split merge)
- * 4 O GEMM + residual  5 RMSNorm(ffn)  6 gate/up GEMM + SwiGLU  7 down GEMM + residual */
+ * 0 RMSNorm(attn)  1 QKV GEMM  2 split sum + RoPE + KV append  3 attention (+ split merge)
+ * 4 O GEMM  5 split sum + residual + RMSNorm(ffn)  6 gate/up GEMM + SwiGLU
+ * 7 down GEMM, split sum + residual (+ the next layer's RMSNorm) */
 typedef struct {
     int32_t n_tokens;        /* sum of n_new */
     int64_t total_kv;        /* sum of kv_len */

@@ -50,9 +50,9 @@ struct ps_ctx {
     // workspaces
     int cap_tokens = 0;
     bf16_t *ws_xn = nullptr, *ws_q = nullptr, *ws_attn = nullptr, *ws_act = nullptr;
-    float *ws_qkv = nullptr, *ws_x1 = nullptr, *ws_xmid = nullptr;
-    float* ws_splitk = nullptr;
-    size_t splitk_bytes = 0;
+    float *ws_x1 = nullptr, *ws_xmid = nullptr;
+    float* ws_part = nullptr;  // fp32 GEMM partials [splits][T][N], shared by the three projections
+    size_t part_bytes = 0;
     float *part_o = nullptr, *part_ml = nullptr;
     int cap_part_slots = 0;
     void* dev_meta = nullptr;
@@ -142,6 +142,7 @@ extern "C" ps_status ps_create(const ps_model_desc* desc, void* hip_stream, ps_c
         return fail(nullptr, PS_EINVAL, "ps_create: hidden, ffn and n_q_heads*head_dim must be multiples of 64");
     if (!(d.rope_base > 1.0f)) return fail(nullptr, PS_EINVAL, "ps_create: rope_base must be > 1");
     if (d.max_position > (1 << 22)) return fail(nullptr, PS_ERANGE, "ps_create: max_position above 2^22");
+    if (d.hidden > 8192) return fail(nullptr, PS_ERANGE, "ps_create: hidden above 8192");
 
     ps_ctx* c = new (std::nothrow) ps_ctx();
     if (!c) return fail(nullptr, PS_ENOMEM, "ps_create: out of host memory");
@@ -183,10 +184,10 @@ extern "C" ps_status ps_sync(ps_ctx* c) {
 }
 
 static void free_workspaces(ps_ctx* c) {
-    dev_free(c->ws_xn); dev_free(c->ws_qkv); dev_free(c->ws_q); dev_free(c->ws_attn); dev_free(c->ws_act);
-    dev_free(c->ws_xmid); dev_free(c->ws_x1); dev_free(c->ws_splitk);
+    dev_free(c->ws_xn); dev_free(c->ws_q); dev_free(c->ws_attn); dev_free(c->ws_act);
+    dev_free(c->ws_xmid); dev_free(c->ws_x1); dev_free(c->ws_part);
     c->cap_tokens = 0;
-    c->splitk_bytes = 0;
+    c->part_bytes = 0;
 }
 
 extern "C" void ps_destroy(ps_ctx* c) {
@@ -223,7 +224,6 @@ extern "C" ps_status ps_set_option(ps_ctx* c, const char* name, int64_t value) {
     if (!strcmp(name, "gemm_split_k")) {
         if (value < 0 || value > 64) return fail(c, PS_EINVAL, "gemm_split_k must be in [0, 64]");
         c->opt_gemm_split_k = (int)value;
-        if (!c->host_only) { (void)hipStreamSynchronize(c->stream); free_workspaces(c); }
         return PS_OK;
     }
     if (!strcmp(name, "time_attention")) {
@@ -265,10 +265,11 @@ extern "C" ps_status ps_init_layer(ps_ctx* c, int32_t layer, const ps_layer_weig
         if ((st = dev_alloc(c, &L.g_ffn, (size_t)H * 2, "g_ffn")) != PS_OK) return st;
     }
     L.ready = false;
-    HIP_TRY(c, launch_transpose_weight(static_cast<const bf16_t*>(w->w_qkv), L.wqkv_t, H, NQKV, c->stream));
-    HIP_TRY(c, launch_transpose_weight(static_cast<const bf16_t*>(w->w_o), L.wo_t, NQ, H, c->stream));
-    HIP_TRY(c, launch_interleave_gate_up(static_cast<const bf16_t*>(w->w_gate), static_cast<const bf16_t*>(w->w_up), L.wgu_t, H, F, c->stream));
-    HIP_TRY(c, launch_transpose_weight(static_cast<const bf16_t*>(w->w_down), L.wd_t, F, H, c->stream));
+    HIP_TRY(c, launch_repack_weight(static_cast<const bf16_t*>(w->w_qkv), L.wqkv_t, H, NQKV, 0, c->stream));
+    HIP_TRY(c, launch_repack_weight(static_cast<const bf16_t*>(w->w_o), L.wo_t, NQ, H, 0, c->stream));
+    HIP_TRY(c, launch_repack_weight(static_cast<const bf16_t*>(w->w_gate), L.wgu_t, H, F, 1, c->stream));
+    HIP_TRY(c, launch_repack_weight(static_cast<const bf16_t*>(w->w_up), L.wgu_t, H, F, 2, c->stream));
+    HIP_TRY(c, launch_repack_weight(static_cast<const bf16_t*>(w->w_down), L.wd_t, F, H, 0, c->stream));
     HIP_TRY(c, launch_copy_bytes(w->g_attn, L.g_attn, (size_t)H * 2, c->stream));
     HIP_TRY(c, launch_copy_bytes(w->g_ffn, L.g_ffn, (size_t)H * 2, c->stream));
     L.ready = true;
@@ -475,26 +476,32 @@ static ps_status ensure_workspaces(ps_ctx* c, int T, int n_part_slots) {
         HIP_TRY(c, hipStreamSynchronize(c->stream));
         free_workspaces(c);
         const int cap = std::max(T + T / 4, 64);
+        const int cap16 = (cap + 15) & ~15;  // operand-order buffers hold whole 16-row tiles
         const int H = d.hidden, F = d.ffn, NQ = d.n_q_heads * d.head_dim, NQKV = qkv_cols(d);
+        (void)NQKV;
         ps_status st;
-        if ((st = dev_alloc(c, &c->ws_xn, (size_t)cap * H * 2, "xn")) != PS_OK) return st;
-        if ((st = dev_alloc(c, &c->ws_qkv, (size_t)cap * NQKV * 4, "qkv")) != PS_OK) return st;
+        if ((st = dev_alloc(c, &c->ws_xn, (size_t)cap16 * H * 2, "xn")) != PS_OK) return st;
         if ((st = dev_alloc(c, &c->ws_q, (size_t)cap * NQ * 2, "q")) != PS_OK) return st;
-        if ((st = dev_alloc(c, &c->ws_attn, (size_t)cap * NQ * 2, "attn")) != PS_OK) return st;
-        if ((st = dev_alloc(c, &c->ws_act, (size_t)cap * F * 2, "act")) != PS_OK) return st;
+        if ((st = dev_alloc(c, &c->ws_attn, (size_t)cap16 * NQ * 2, "attn")) != PS_OK) return st;
+        if ((st = dev_alloc(c, &c->ws_act, (size_t)cap16 * F * 2, "act")) != PS_OK) return st;
         if ((st = dev_alloc(c, &c->ws_x1, (size_t)cap * H * 4, "x1")) != PS_OK) return st;
         if (d.n_layers > 1 && (st = dev_alloc(c, &c->ws_xmid, (size_t)cap * H * 4, "inter-layer x")) != PS_OK) return st;
-        size_t sk = 0;
-        sk = std::max(sk, gemm_splitk_ws_bytes(cap, NQKV, H, c->opt_gemm_split_k));
-        sk = std::max(sk, gemm_splitk_ws_bytes(cap, H, NQ, c->opt_gemm_split_k));
-        sk = std::max(sk, gemm_splitk_ws_bytes(cap, 2 * F, H, c->opt_gemm_split_k));
-        sk = std::max(sk, gemm_splitk_ws_bytes(cap, H, F, c->opt_gemm_split_k));
-        // the plan for the actual T may split more than the plan for cap: allow for the worst split (16) at small T
-        sk = std::max(sk, (size_t)16 * std::min(cap, 64) * (size_t)std::max(2 * F, NQKV) * 4);
-        sk = std::max(sk, (size_t)64 << 20);
-        if ((st = dev_alloc(c, &c->ws_splitk, sk, "split-K partials")) != PS_OK) return st;
-        c->splitk_bytes = sk;
         c->cap_tokens = cap;
+    }
+    {   // GEMM partial buffer: sized for this step's T (the split count depends on T)
+        const int H = d.hidden, F = d.ffn, NQ = d.n_q_heads * d.head_dim, NQKV = qkv_cols(d);
+        size_t need = gemm_out_bytes(T, NQKV, H, GemmOut::PARTIAL_F32, c->opt_gemm_split_k);
+        need = std::max(need, gemm_out_bytes(T, H, NQ, GemmOut::PARTIAL_F32, c->opt_gemm_split_k));
+        need = std::max(need, gemm_out_bytes(T, H, F, GemmOut::PARTIAL_F32, c->opt_gemm_split_k));
+        if (need > c->part_bytes) {
+            HIP_TRY(c, hipStreamSynchronize(c->stream));
+            dev_free(c->ws_part);
+            c->part_bytes = 0;
+            const size_t want = std::max(need + need / 4, (size_t)16 << 20);
+            ps_status st = dev_alloc(c, &c->ws_part, want, "GEMM partials");
+            if (st != PS_OK) return st;
+            c->part_bytes = want;
+        }
     }
     if (n_part_slots > c->cap_part_slots) {
         HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -578,31 +585,30 @@ extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, cons
     float total_ms = 0.f;
     hipStream_t s = c->stream;
 
-    // The residual stream stays fp32 inside the stack: only x_in and x_out are bf16.
+    // The residual stream stays fp32 inside the stack: only x_in and x_out are bf16.  Every
+    // projection leaves fp32 partial sums; the kernel that consumes them adds them up.
     const void* x_cur = x_in;
     bool x_cur_f32 = false;
     for (int l = 0; l < d.n_layers; l++) {
         const LayerWeights& L = c->layers[l];
         const bool tap = (l == c->tap_layer);
         const bool last = (l == d.n_layers - 1);
-        void* x_next = last ? x_out : static_cast<void*>(c->ws_xmid);
         bf16_t* pool_slot = c->pool + (size_t)(l % c->n_kv_slots) * c->slot_elems;
-        int e = 0;
+        int e = 0, n_splits = 1;
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[e], s));
-        // 0: RMSNorm
-        HIP_TRY(c, launch_rmsnorm(x_cur, x_cur_f32, L.g_attn, c->ws_xn, T, H, d.rms_eps, s));
-        if (tap && c->taps.xn) HIP_TRY(c, launch_copy_bytes(c->ws_xn, c->taps.xn, (size_t)T * H * 2, s));
+        // 0: RMSNorm of the layer input (layers after the first get it from the previous layer's last kernel)
+        if (l == 0) HIP_TRY(c, launch_rmsnorm(x_cur, x_cur_f32, L.g_attn, c->ws_xn, T, H, d.rms_eps, s));
+        if (tap && c->taps.xn) HIP_TRY(c, launch_untile(c->ws_xn, static_cast<bf16_t*>(c->taps.xn), T, H, s));
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
-        // 1: QKV projection, kept in fp32 so that rotation happens before the only bf16 rounding
+        // 1: QKV projection -> fp32 partials
         GemmArgs g{};
-        g.A = c->ws_xn; g.Bt = L.wqkv_t; g.M = T; g.N = NQKV; g.K = H; g.kind = GemmEpilogue::STORE;
-        g.resid_f32 = false; g.out_f32 = true; g.resid = nullptr; g.out = c->ws_qkv;
-        g.splitk_ws = c->ws_splitk; g.splitk_ws_bytes = c->splitk_bytes; g.split_k = c->opt_gemm_split_k;
-        HIP_TRY(c, launch_gemm(g, s));
+        g.A = c->ws_xn; g.Wp = L.wqkv_t; g.M = T; g.N = NQKV; g.K = H; g.kind = GemmOut::PARTIAL_F32;
+        g.out = c->ws_part; g.out_bytes = c->part_bytes; g.split_k = c->opt_gemm_split_k;
+        HIP_TRY(c, launch_gemm(g, &n_splits, s));
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
-        // 2: rotary + append
-        HIP_TRY(c, launch_rope_append(c->ws_qkv, c->ws_q, T, d.n_q_heads, d.n_kv_heads, d.head_dim, d_pos, d_slots,
-                                      c->rope_cs, pool_slot, s));
+        // 2: sum the partials, rotate, round once to bf16, append k/v to the pages
+        HIP_TRY(c, launch_rope_append(c->ws_part, n_splits, c->ws_q, T, d.n_q_heads, d.n_kv_heads, d.head_dim, d_pos,
+                                      d_slots, c->rope_cs, pool_slot, s));
         if (tap && c->taps.q) HIP_TRY(c, launch_copy_bytes(c->ws_q, c->taps.q, (size_t)T * NQ * 2, s));
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
         // 3: attention
@@ -623,28 +629,42 @@ extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, cons
         a.ev_end = time_attn ? c->attn_ev[2 * c->attn_ev_count + 1] : nullptr;
         HIP_TRY(c, launch_attention(a, s));
         if (time_attn) c->attn_ev_count++;
-        if (tap && c->taps.attn) HIP_TRY(c, launch_copy_bytes(c->ws_attn, c->taps.attn, (size_t)T * NQ * 2, s));
+        if (tap && c->taps.attn) HIP_TRY(c, launch_untile(c->ws_attn, static_cast<bf16_t*>(c->taps.attn), T, NQ, s));
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
-        // 4: O projection + residual
-        g.A = c->ws_attn; g.Bt = L.wo_t; g.N = H; g.K = NQ; g.kind = GemmEpilogue::RESID;
-        g.resid = x_cur; g.resid_f32 = x_cur_f32; g.out = c->ws_x1; g.out_f32 = true;
-        HIP_TRY(c, launch_gemm(g, s));
+        // 4: O projection -> fp32 partials
+        g.A = c->ws_attn; g.Wp = L.wo_t; g.N = H; g.K = NQ;
+        HIP_TRY(c, launch_gemm(g, &n_splits, s));
+        if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
+        // 5: x1 = x + sum(partials) (fp32), xn = RMSNorm(x1)
+        ReduceAddNormArgs r{};
+        r.resid = x_cur; r.resid_f32 = x_cur_f32; r.partials = c->ws_part; r.n_splits = n_splits; r.T = T; r.H = H;
+        r.x_f32 = c->ws_x1; r.x_bf16 = nullptr; r.gain = L.g_ffn; r.xn = c->ws_xn; r.eps = d.rms_eps;
+        HIP_TRY(c, launch_reduce_add_norm(r, s));
         if (tap && c->taps.x1) HIP_TRY(c, launch_copy_bytes(c->ws_x1, c->taps.x1, (size_t)T * H * 4, s));
-        if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
-        // 5: RMSNorm
-        HIP_TRY(c, launch_rmsnorm(c->ws_x1, true, L.g_ffn, c->ws_xn, T, H, d.rms_eps, s));
-        if (tap && c->taps.xn2) HIP_TRY(c, launch_copy_bytes(c->ws_xn, c->taps.xn2, (size_t)T * H * 2, s));
+        if (tap && c->taps.xn2) HIP_TRY(c, launch_untile(c->ws_xn, static_cast<bf16_t*>(c->taps.xn2), T, H, s));
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
         // 6: gate/up + SwiGLU
-        g.A = c->ws_xn; g.Bt = L.wgu_t; g.N = 2 * F; g.K = H; g.kind = GemmEpilogue::SWIGLU_BF16;
-        g.resid = nullptr; g.resid_f32 = false; g.out = c->ws_act; g.out_f32 = false;
-        HIP_TRY(c, launch_gemm(g, s));
-        if (tap && c->taps.act) HIP_TRY(c, launch_copy_bytes(c->ws_act, c->taps.act, (size_t)T * F * 2, s));
+        g.A = c->ws_xn; g.Wp = L.wgu_t; g.N = 2 * F; g.K = H; g.kind = GemmOut::SWIGLU_BF16;
+        g.out = c->ws_act; g.out_bytes = 0;
+        HIP_TRY(c, launch_gemm(g, nullptr, s));
+        if (tap && c->taps.act) HIP_TRY(c, launch_untile(c->ws_act, static_cast<bf16_t*>(c->taps.act), T, F, s));
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
-        // 7: down + residual
-        g.A = c->ws_act; g.Bt = L.wd_t; g.N = H; g.K = F; g.kind = GemmEpilogue::RESID;
-        g.resid = c->ws_x1; g.resid_f32 = true; g.out = x_next; g.out_f32 = !last || c->opt_out_f32;
-        HIP_TRY(c, launch_gemm(g, s));
+        // 7: down projection -> fp32 partials; out = x1 + sum(partials); for an inner layer also the
+        //    next layer's normalised input
+        g.A = c->ws_act; g.Wp = L.wd_t; g.N = H; g.K = F; g.kind = GemmOut::PARTIAL_F32;
+        g.out = c->ws_part; g.out_bytes = c->part_bytes;
+        HIP_TRY(c, launch_gemm(g, &n_splits, s));
+        r.resid = c->ws_x1; r.resid_f32 = true; r.n_splits = n_splits;
+        if (last) {
+            r.x_f32 = c->opt_out_f32 ? static_cast<float*>(x_out) : nullptr;
+            r.x_bf16 = c->opt_out_f32 ? nullptr : static_cast<bf16_t*>(x_out);
+            r.gain = nullptr; r.xn = nullptr;
+        } else {
+            r.x_f32 = c->ws_xmid; r.x_bf16 = nullptr;
+            r.gain = c->layers[l + 1].g_attn; r.xn = c->ws_xn;
+        }
+        HIP_TRY(c, launch_reduce_add_norm(r, s));
+        void* x_next = last ? x_out : static_cast<void*>(c->ws_xmid);
         if (stats) {
             HIP_TRY(c, hipEventRecord(c->ev[++e], s));
             HIP_TRY(c, hipEventSynchronize(c->ev[e]));

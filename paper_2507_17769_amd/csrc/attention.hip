@@ -186,10 +186,15 @@ __device__ __forceinline__ void attn_item(const AttnArgs& a, const AttnItem it) 
             load_pair<D>(b0, pool_lane, page_stride, pid(0), pid(1));
             int i = 0;
             for (; i + 2 < n_pairs; i += 2) {
+                // scheduling barriers: keep every batch of loads ahead of the previous batch's math
                 load_pair<D>(b1, pool_lane, page_stride, pid(2 * i + 2), pid(2 * i + 3));
+                __builtin_amdgcn_sched_barrier(0);
                 compute_pair<D, NT, PIPE>(st, b0, qf, pq, (blk + 2 * i) * 16, true, g, scale2);
+                __builtin_amdgcn_sched_barrier(0);
                 load_pair<D>(b0, pool_lane, page_stride, pid(2 * i + 4), pid(2 * i + 5));
+                __builtin_amdgcn_sched_barrier(0);
                 compute_pair<D, NT, PIPE>(st, b1, qf, pq, (blk + 2 * i + 2) * 16, true, g, scale2);
+                __builtin_amdgcn_sched_barrier(0);
             }
             if (i + 2 == n_pairs) {
                 load_pair<D>(b1, pool_lane, page_stride, pid(2 * i + 2), pid(2 * i + 3));
@@ -215,13 +220,12 @@ __device__ __forceinline__ void attn_item(const AttnArgs& a, const AttnItem it) 
         if (it.partial < 0) {
             if (rvalid[nt]) {
                 const float inv = 1.0f / l;
-                bf16_t* orow = a.out + (size_t)qi[nt] * (a.n_q * D) + head * D + 4 * g;
 #pragma unroll
                 for (int dt = 0; dt < DT; dt++) {
                     uint2 w;
                     w.x = pack_bf16(st.o[nt][dt][0] * inv, st.o[nt][dt][1] * inv);
                     w.y = pack_bf16(st.o[nt][dt][2] * inv, st.o[nt][dt][3] * inv);
-                    *reinterpret_cast<uint2*>(orow + 16 * dt) = w;
+                    *reinterpret_cast<uint2*>(a.out + act_offset(qi[nt], head * D + 16 * dt + 4 * g, a.n_q * D)) = w;
                 }
             }
         } else if (rvalid[nt]) {  // rows beyond the block's tokens are never merged: do not store them
@@ -281,7 +285,7 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(AttnArgs a) {
         uint2 w;
         w.x = pack_bf16(acc.x * inv, acc.y * inv);
         w.y = pack_bf16(acc.z * inv, acc.w * inv);
-        *reinterpret_cast<uint2*>(a.out + (size_t)(mg.tok0 + r / G) * (a.n_q * D) + head * D + col) = w;
+        *reinterpret_cast<uint2*>(a.out + act_offset(mg.tok0 + r / G, head * D + col, a.n_q * D)) = w;
     }
 }
 

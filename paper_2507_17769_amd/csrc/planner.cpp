@@ -17,27 +17,28 @@ ps_status validate_batch(const ps_seq* seqs, int n_seqs, const PlanConfig& cfg, 
     if (n_seqs > 0 && !seqs) { err = "seqs is null"; return PS_EINVAL; }
     const bool have_pool = cfg.n_pool_pages >= 0;
     if (have_pool && (int)page_seen.size() < cfg.n_pool_pages) page_seen.assign(cfg.n_pool_pages, 0);
-    std::unordered_set<int64_t> ids;
     std::unordered_set<int32_t> pages_nopool;
-    std::vector<int32_t> marked;  // pages flagged in page_seen, cleared again before returning
-    ids.reserve(n_seqs * 2);
+    static thread_local std::vector<int32_t> marked;  // pages flagged in page_seen, cleared again before returning
+    static thread_local std::vector<int64_t> ids;
+    marked.clear();
+    ids.clear();
     int64_t tokens = 0;
     ps_status rc = PS_OK;
+    auto who = [&](int s) { return "seq " + std::to_string(s) + " (req " + std::to_string(seqs[s].req_id) + "): "; };
     for (int s = 0; s < n_seqs && rc == PS_OK; s++) {
         const ps_seq& q = seqs[s];
-        const std::string who = "seq " + std::to_string(s) + " (req " + std::to_string(q.req_id) + "): ";
-        if (q.n_new < 1) { err = who + "n_new must be >= 1"; rc = PS_EINVAL; break; }
-        if (q.kv_len < q.n_new) { err = who + "kv_len is smaller than n_new"; rc = PS_EINVAL; break; }
-        if (q.kv_len > cfg.max_position) { err = who + "kv_len exceeds max_position"; rc = PS_ERANGE; break; }
-        if (!q.page_table) { err = who + "page_table is null"; rc = PS_EINVAL; break; }
-        if (q.n_pages < ceil_div(q.kv_len, PS_PAGE_SIZE)) { err = who + "page_table is shorter than ceil(kv_len/16)"; rc = PS_EINVAL; break; }
-        if (!ids.insert(q.req_id).second) { err = who + "duplicate req_id in batch"; rc = PS_EINVAL; break; }
+        if (q.n_new < 1) { err = who(s) + "n_new must be >= 1"; rc = PS_EINVAL; break; }
+        if (q.kv_len < q.n_new) { err = who(s) + "kv_len is smaller than n_new"; rc = PS_EINVAL; break; }
+        if (q.kv_len > cfg.max_position) { err = who(s) + "kv_len exceeds max_position"; rc = PS_ERANGE; break; }
+        if (!q.page_table) { err = who(s) + "page_table is null"; rc = PS_EINVAL; break; }
+        if (q.n_pages < ceil_div(q.kv_len, PS_PAGE_SIZE)) { err = who(s) + "page_table is shorter than ceil(kv_len/16)"; rc = PS_EINVAL; break; }
+        ids.push_back(q.req_id);
         tokens += q.n_new;
         if (tokens > (1 << 24)) { err = "batch has more than 2^24 new tokens"; rc = PS_ERANGE; break; }
         for (int i = 0; i < q.n_pages; i++) {
             const int32_t pg = q.page_table[i];
             if (pg < 0 || (have_pool && pg >= cfg.n_pool_pages)) {
-                err = who + "page id " + std::to_string(pg) + " outside the pool";
+                err = who(s) + "page id " + std::to_string(pg) + " outside the pool";
                 rc = PS_ERANGE;
                 break;
             }
@@ -49,13 +50,24 @@ ps_status validate_batch(const ps_seq* seqs, int n_seqs, const PlanConfig& cfg, 
                 dup = !pages_nopool.insert(pg).second;
             }
             if (dup) {
-                err = who + "page id " + std::to_string(pg) + " appears twice in the batch";
+                err = who(s) + "page id " + std::to_string(pg) + " appears twice in the batch";
                 rc = PS_EINVAL;
                 break;
             }
         }
     }
     for (int32_t pg : marked) page_seen[pg] = 0;
+    if (rc == PS_OK && n_seqs > 1) {
+        std::sort(ids.begin(), ids.end());
+        const auto dup = std::adjacent_find(ids.begin(), ids.end());
+        if (dup != ids.end()) {
+            int s = 0, seen = 0;
+            for (int i = 0; i < n_seqs; i++)
+                if (seqs[i].req_id == *dup && ++seen == 2) { s = i; break; }
+            err = who(s) + "duplicate req_id in batch";
+            rc = PS_EINVAL;
+        }
+    }
     return rc;
 }
 
@@ -126,7 +138,8 @@ void build_attention_plan(const PlanConfig& cfg, StepPlan& plan) {
     n_workers = (int)std::max<int64_t>(1, std::min<int64_t>(n_workers, units / (4 * W_SINGLE)));
     // worker w ends where the cumulative weight reaches (w+1) * units / n_workers, so rounding
     // to whole pairs never accumulates
-    auto boundary = [&](int w) { return (int64_t)(((__int128)units * (w + 1)) / n_workers); };
+    const int64_t q_units = units / n_workers, r_units = units % n_workers;
+    auto boundary = [&](int w) { return q_units * (w + 1) + r_units * (w + 1) / n_workers; };
 
     plan.worker_begin.reserve(n_workers + 1);
     plan.items.reserve(n_workers + segs.size() * cfg.n_kv_heads);

@@ -29,6 +29,17 @@ __host__ __device__ inline int v_elem_offset(int tok, int dd) {
     return ((((dd >> 5) * 4 + (tok >> 2)) * 16 + (dd & 15)) * 2 + ((dd >> 4) & 1)) * 4 + (tok & 3);
 }
 
+// Activation matrices that feed a GEMM (normalised inputs, attention output, gated activation)
+// are kept in MFMA operand order rather than row-major:
+//   [m_tile = m/16][k_block = k/32][g = (k%32)/8][mm = m%16][8]          (1 KiB per tile-block)
+// so that the consumer's operand load is one contiguous KiB per wavefront instruction (a
+// row-major gather of 16 rows x 64 bytes costs twice the cache-line requests and measurably
+// starves the weight stream).  Storage holds ceil(M/16)*16 rows; rows beyond M are never read
+// into a stored result.
+__host__ __device__ inline size_t act_offset(int m, int k, int K) {
+    return ((((size_t)(m >> 4) * (K >> 5) + (k >> 5)) * 4 + ((k & 31) >> 3)) * 16 + (m & 15)) * 8 + (k & 7);
+}
+
 // Attention work item.  The first 8 fields are what ps_plan_attention reports; the rest is
 // what the kernel needs so that it never has to look the sequence up.
 struct AttnItem {
@@ -65,38 +76,53 @@ struct SeqInfo {
     int32_t page_off;  // offset of its page list in the flat page array
 };
 
-struct GemmEpilogue {
-    enum Kind : int { STORE = 0, RESID = 1, SWIGLU_BF16 = 2 };
+struct GemmOut {
+    enum Kind : int { PARTIAL_F32 = 0, SWIGLU_BF16 = 1 };
 };
 
 // ------------------------------------------------------------------ launchers (device side)
 // All take the stream explicitly and return hipGetLastError() of the launch.
+// out is written in operand order (act_offset)
 hipError_t launch_rmsnorm(const void* x, bool x_is_f32, const bf16_t* gain, bf16_t* out, int T, int H, float eps,
                           hipStream_t st);
-hipError_t launch_rope_append(const float* qkv, bf16_t* q_out, int T, int n_q, int n_kv, int d,
+// operand-order [M][K] bf16 matrix -> row-major (for the debug taps)
+hipError_t launch_untile(const bf16_t* src, bf16_t* dst, int M, int K, hipStream_t st);
+// qkv: fp32 partials [n_splits][T][(n_q + 2 n_kv) d] of the QKV projection (summed here)
+hipError_t launch_rope_append(const float* qkv, int n_splits, bf16_t* q_out, int T, int n_q, int n_kv, int d,
                               const int32_t* positions, const int32_t* slots, const float* rope_cs, bf16_t* pool_slot,
                               hipStream_t st);
+// x = resid + sum of n_splits fp32 partials [n_splits][T][H]; writes any of: x as fp32, x as bf16,
+// rmsnorm(x) * gain as bf16 (gain == null: no normalisation)
+struct ReduceAddNormArgs {
+    const void* resid;
+    bool resid_f32;
+    const float* partials;
+    int n_splits;
+    int T, H;
+    float* x_f32;          // may be null
+    bf16_t* x_bf16;        // may be null
+    const bf16_t* gain;    // may be null
+    bf16_t* xn;            // required when gain != null; operand order (act_offset)
+    float eps;
+};
+hipError_t launch_reduce_add_norm(const ReduceAddNormArgs& a, hipStream_t st);
 hipError_t launch_kv_copy(bool to_pool, bf16_t* pool_slot, const int32_t* slots_dev, int n, int n_kv, int d, bf16_t* k,
                           bf16_t* v, hipStream_t st);
-hipError_t launch_transpose_weight(const bf16_t* w, bf16_t* wt, int K, int N, hipStream_t st);
-hipError_t launch_interleave_gate_up(const bf16_t* wg, const bf16_t* wu, bf16_t* wt, int K, int F, hipStream_t st);
+hipError_t launch_repack_weight(const bf16_t* w, bf16_t* wp, int K, int N, int interleave, hipStream_t st);
 hipError_t launch_copy_bytes(const void* src, void* dst, size_t n, hipStream_t st);
 
 struct GemmArgs {
-    const bf16_t* A;   // [M][K] activations
-    const bf16_t* Bt;  // [N][K] weights, transposed
+    const bf16_t* A;   // [M][K] activations in operand order (act_offset)
+    const bf16_t* Wp;  // repacked weights (launch_repack_weight)
     int M, N, K;
-    int kind;          // GemmEpilogue::Kind
-    bool resid_f32;    // residual is fp32 (else bf16)
-    bool out_f32;      // output is fp32 (else bf16)
-    const void* resid; // [M][N], RESID only
-    void* out;         // [M][N], or [M][N/2] bf16 for SWIGLU
-    float* splitk_ws;  // fp32 [split][M][N] scratch when split_k > 1
-    size_t splitk_ws_bytes;
+    int kind;          // GemmOut::Kind
+    void* out;         // PARTIAL_F32: fp32 [splits][M][N] row-major; SWIGLU_BF16: bf16 [M][N/2] in operand order
+    size_t out_bytes;  // PARTIAL_F32: capacity of out
     int split_k;       // 0 = choose
 };
-hipError_t launch_gemm(const GemmArgs& a, hipStream_t st);
-size_t gemm_splitk_ws_bytes(int M, int N, int K, int split_k_opt);
+// *n_splits receives the number of partial buffers written (1 for SWIGLU_BF16)
+hipError_t launch_gemm(const GemmArgs& a, int* n_splits, hipStream_t st);
+size_t gemm_out_bytes(int M, int N, int K, int kind, int split_k_opt);
 
 struct AttnArgs {
     const bf16_t* q;   // rotated queries [T][n_q * d]: row stride ldq elements
@@ -112,7 +138,7 @@ struct AttnArgs {
     int n_groups;
     float* part_o;     // [slot][16][d]
     float* part_ml;    // [slot][16][2]
-    bf16_t* out;       // [T][n_q * d]
+    bf16_t* out;       // [T][n_q * d] in operand order (act_offset)
     int n_q, n_kv, d;
     hipEvent_t ev_begin, ev_end;  // optional: recorded right before / after the main kernel (not the merge)
 };

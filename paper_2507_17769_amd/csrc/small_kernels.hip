@@ -1,6 +1,8 @@
-// Bandwidth-trivial kernels of the step: RMSNorm, rotary embedding + KV append, logical
-// KV read/write, and the one-time weight repacks.  (Sec. 2.1: each module is preceded by an RMS
+// Bandwidth-trivial kernels of the step: RMSNorm, rotary embedding + KV append, the fused
+// split-reduce + residual + RMSNorm, and logical KV read/write.  (Sec. 2.1: each module is preceded by an RMS
 // normalisation; the prefill pass fills the KV cache that later decode steps extend.)
+#include <algorithm>
+
 #include "ps_device.h"
 
 namespace ps {
@@ -53,7 +55,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const void* __restrict__ x
         o.y = pack_bf16(v[2] * r * g[2], v[3] * r * g[3]);
         o.z = pack_bf16(v[4] * r * g[4], v[5] * r * g[5]);
         o.w = pack_bf16(v[6] * r * g[6], v[7] * r * g[7]);
-        *reinterpret_cast<uint4*>(out + (size_t)row * H + c) = o;
+        *reinterpret_cast<uint4*>(out + act_offset(row, c, H)) = o;
     }
 }
 
@@ -69,11 +71,12 @@ hipError_t launch_rmsnorm(const void* x, bool x_is_f32, const bf16_t* gain, bf16
 
 // --------------------------------------------------------------- rotary + KV append
 // grid (T, n_q + 2 n_kv), 64 threads.  Thread j < d/2 owns the pair (j, j + d/2).
-// Input is the fp32 QKV projection [T][(n_q + 2 n_kv) d]; every value is rounded to bf16
-// exactly once, after the rotation: query heads go to q_out [T][n_q][d], key heads (rotated)
-// and value heads to their cache slot.  cs is the fp64-built table [position][d/2] of (cos, sin).
-__global__ __launch_bounds__(64) void rope_append_kernel(const float* __restrict__ qkv, bf16_t* __restrict__ q_out,
-                                                         int n_q, int n_kv, int d,
+// Input is the fp32 QKV projection as n_splits partial sums [n_splits][T][(n_q + 2 n_kv) d],
+// added up here; every value is rounded to bf16 exactly once, after the rotation: query heads
+// go to q_out [T][n_q][d], key heads (rotated) and value heads to their cache slot.  cs is the
+// fp64-built table [position][d/2] of (cos, sin).
+__global__ __launch_bounds__(64) void rope_append_kernel(const float* __restrict__ qkv, int n_splits, size_t split_stride,
+                                                         bf16_t* __restrict__ q_out, int n_q, int n_kv, int d,
                                                          const int32_t* __restrict__ positions,
                                                          const int32_t* __restrict__ slots,
                                                          const float2* __restrict__ cs, bf16_t* __restrict__ pool) {
@@ -84,8 +87,11 @@ __global__ __launch_bounds__(64) void rope_append_kernel(const float* __restrict
     if (j >= half) return;
     const int ld = (n_q + 2 * n_kv) * d;
     const float* row = qkv + (size_t)t * ld + (size_t)hh * d;
-    const float lo = row[j];
-    const float hi = row[j + half];
+    float lo = 0.f, hi = 0.f;
+    for (int s = 0; s < n_splits; s++) {
+        lo += row[s * split_stride + j];
+        hi += row[s * split_stride + j + half];
+    }
     if (hh < n_q + n_kv) {
         const float2 c = cs[(size_t)positions[t] * half + j];
         const bf16_t blo = f32_to_bf16(lo * c.x - hi * c.y);
@@ -110,11 +116,13 @@ __global__ __launch_bounds__(64) void rope_append_kernel(const float* __restrict
     }
 }
 
-hipError_t launch_rope_append(const float* qkv, bf16_t* q_out, int T, int n_q, int n_kv, int d,
+hipError_t launch_rope_append(const float* qkv, int n_splits, bf16_t* q_out, int T, int n_q, int n_kv, int d,
                               const int32_t* positions, const int32_t* slots, const float* rope_cs, bf16_t* pool_slot,
                               hipStream_t st) {
     if (T <= 0) return hipSuccess;
-    hipLaunchKernelGGL(rope_append_kernel, dim3(T, n_q + 2 * n_kv), dim3(64), 0, st, qkv, q_out, n_q, n_kv, d,
+    const size_t split_stride = (size_t)T * (n_q + 2 * n_kv) * d;
+    hipLaunchKernelGGL(rope_append_kernel, dim3(T, n_q + 2 * n_kv), dim3(64), 0, st, qkv, n_splits, split_stride, q_out,
+                       n_q, n_kv, d,
                        positions, slots, reinterpret_cast<const float2*>(rope_cs), pool_slot);
     return hipGetLastError();
 }
@@ -152,44 +160,102 @@ hipError_t launch_kv_copy(bool to_pool, bf16_t* pool_slot, const int32_t* slots_
     return hipGetLastError();
 }
 
-// ----------------------------------------------------------------- weight repacks
-// W [K][N] (math layout) -> Wt [row(n)][K].  interleave = 0: row(n) = n.  interleave = 1/2
-// (gate / up): row(f) = (f/32)*64 + f%32 + (interleave == 2 ? 32 : 0), so that every aligned
-// group of 64 rows of the fused matrix holds gate rows f..f+31 then up rows f..f+31.
-__global__ __launch_bounds__(256) void transpose_weight_kernel(const bf16_t* __restrict__ w, bf16_t* __restrict__ wt,
-                                                               int K, int N, int interleave) {
-    __shared__ bf16_t tile[64][66];
-    const int n0 = blockIdx.x * 64, k0 = blockIdx.y * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int r = ty; r < 64; r += 4) {
-        const int k = k0 + r, n = n0 + tx;
-        tile[r][tx] = (k < K && n < N) ? w[(size_t)k * N + n] : (bf16_t)0;
+// ------------------------------------------------- split reduce + residual + RMSNorm
+// One 256-thread block per token row.  x = resid + sum_s partials[s]; optionally stored as fp32
+// and/or bf16; optionally followed by RMSNorm (x * rsqrt(mean(x^2) + eps) * gain) stored as bf16.
+// The row stays in registers between the two phases (H <= 8192).
+template <bool RESID_F32>
+__global__ __launch_bounds__(256) void reduce_add_norm_kernel(ReduceAddNormArgs a) {
+    const int row = blockIdx.x, tid = threadIdx.x;
+    const int H = a.H;
+    const size_t split_stride = (size_t)a.T * H;
+    __shared__ float red[4];
+    float v[4][8];
+    float ss = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+        const int c = tid * 8 + k * 2048;
+        if (c < H) {
+            if (RESID_F32) {
+                const float4* p = reinterpret_cast<const float4*>(static_cast<const float*>(a.resid) + (size_t)row * H + c);
+                const float4 x0 = p[0], x1 = p[1];
+                v[k][0] = x0.x; v[k][1] = x0.y; v[k][2] = x0.z; v[k][3] = x0.w;
+                v[k][4] = x1.x; v[k][5] = x1.y; v[k][6] = x1.z; v[k][7] = x1.w;
+            } else {
+                const uint4 w = ldg16(static_cast<const bf16_t*>(a.resid) + (size_t)row * H + c);
+                v[k][0] = bf16_lo(w.x); v[k][1] = bf16_hi(w.x); v[k][2] = bf16_lo(w.y); v[k][3] = bf16_hi(w.y);
+                v[k][4] = bf16_lo(w.z); v[k][5] = bf16_hi(w.z); v[k][6] = bf16_lo(w.w); v[k][7] = bf16_hi(w.w);
+            }
+            for (int s = 0; s < a.n_splits; s++) {
+                const float4* p = reinterpret_cast<const float4*>(a.partials + s * split_stride + (size_t)row * H + c);
+                const float4 x0 = p[0], x1 = p[1];
+                v[k][0] += x0.x; v[k][1] += x0.y; v[k][2] += x0.z; v[k][3] += x0.w;
+                v[k][4] += x1.x; v[k][5] += x1.y; v[k][6] += x1.z; v[k][7] += x1.w;
+            }
+            if (a.x_f32) {
+                float4* o = reinterpret_cast<float4*>(a.x_f32 + (size_t)row * H + c);
+                o[0] = float4{v[k][0], v[k][1], v[k][2], v[k][3]};
+                o[1] = float4{v[k][4], v[k][5], v[k][6], v[k][7]};
+            }
+            if (a.x_bf16) {
+                uint4 o;
+                o.x = pack_bf16(v[k][0], v[k][1]); o.y = pack_bf16(v[k][2], v[k][3]);
+                o.z = pack_bf16(v[k][4], v[k][5]); o.w = pack_bf16(v[k][6], v[k][7]);
+                *reinterpret_cast<uint4*>(a.x_bf16 + (size_t)row * H + c) = o;
+            }
+#pragma unroll
+            for (int i = 0; i < 8; i++) ss += v[k][i] * v[k][i];
+        }
     }
+    if (!a.gain) return;
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
     __syncthreads();
-    for (int r = ty; r < 64; r += 4) {
-        const int n = n0 + r, k = k0 + tx;
-        if (n < N && k < K) {
-            int row = n;
-            if (interleave) row = (n >> 5) * 64 + (n & 31) + (interleave == 2 ? 32 : 0);
-            wt[(size_t)row * K + k] = tile[tx][r];
+    const float r = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)H + a.eps);
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+        const int c = tid * 8 + k * 2048;
+        if (c < H) {
+            const uint4 gw = ldg16(a.gain + c);
+            uint4 o;
+            o.x = pack_bf16(v[k][0] * r * bf16_lo(gw.x), v[k][1] * r * bf16_hi(gw.x));
+            o.y = pack_bf16(v[k][2] * r * bf16_lo(gw.y), v[k][3] * r * bf16_hi(gw.y));
+            o.z = pack_bf16(v[k][4] * r * bf16_lo(gw.z), v[k][5] * r * bf16_hi(gw.z));
+            o.w = pack_bf16(v[k][6] * r * bf16_lo(gw.w), v[k][7] * r * bf16_hi(gw.w));
+            *reinterpret_cast<uint4*>(a.xn + act_offset(row, c, H)) = o;
         }
     }
 }
 
-hipError_t launch_transpose_weight(const bf16_t* w, bf16_t* wt, int K, int N, hipStream_t st) {
-    hipLaunchKernelGGL(transpose_weight_kernel, dim3((N + 63) / 64, (K + 63) / 64), dim3(256), 0, st, w, wt, K, N, 0);
-    return hipGetLastError();
-}
-
-hipError_t launch_interleave_gate_up(const bf16_t* wg, const bf16_t* wu, bf16_t* wt, int K, int F, hipStream_t st) {
-    dim3 grid((F + 63) / 64, (K + 63) / 64);
-    hipLaunchKernelGGL(transpose_weight_kernel, grid, dim3(256), 0, st, wg, wt, K, F, 1);
-    hipLaunchKernelGGL(transpose_weight_kernel, grid, dim3(256), 0, st, wu, wt, K, F, 2);
+hipError_t launch_reduce_add_norm(const ReduceAddNormArgs& a, hipStream_t st) {
+    if (a.T <= 0) return hipSuccess;
+    if (a.H > 8192 || a.H % 8) return hipErrorInvalidValue;
+    if (a.resid_f32)
+        hipLaunchKernelGGL(reduce_add_norm_kernel<true>, dim3(a.T), dim3(256), 0, st, a);
+    else
+        hipLaunchKernelGGL(reduce_add_norm_kernel<false>, dim3(a.T), dim3(256), 0, st, a);
     return hipGetLastError();
 }
 
 __global__ __launch_bounds__(256) void copy_bytes_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
     for (size_t i = blockIdx.x * (size_t)256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+// operand order -> row-major, 16 bytes (8 elements of one row) per thread
+__global__ __launch_bounds__(256) void untile_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst, int M, int K) {
+    const size_t total = (size_t)M * (K / 8);
+    for (size_t i = blockIdx.x * (size_t)256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+        const int m = (int)(i / (K / 8)), k = (int)(i % (K / 8)) * 8;
+        *reinterpret_cast<uint4*>(dst + (size_t)m * K + k) = *reinterpret_cast<const uint4*>(src + act_offset(m, k, K));
+    }
+}
+
+hipError_t launch_untile(const bf16_t* src, bf16_t* dst, int M, int K, hipStream_t st) {
+    const size_t total = (size_t)M * (K / 8);
+    if (total == 0) return hipSuccess;
+    const int blocks = (int)std::min<size_t>((total + 255) / 256, 4096);
+    hipLaunchKernelGGL(untile_kernel, dim3(blocks), dim3(256), 0, st, src, dst, M, K);
+    return hipGetLastError();
 }
 
 // Device-to-device copy of n bytes (n a multiple of 16, both pointers 16-byte aligned).
