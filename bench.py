@@ -29,6 +29,7 @@ def parse():
     ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg2"])
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--null-stream", action="store_true", help="run on the default stream instead of a dedicated one")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy a few times (reference for HBM byte counters)")
     return ap.parse_args()
@@ -83,6 +84,8 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes": n, "copies": 3}))
         return
+    if not a.null_stream:   # a stream of our own (default priority); torch only allocates and copies
+        torch.cuda.set_stream(torch.cuda.Stream(device="cuda:0"))
     cfg = {"cfg1": 1, "cfg2": 2}[a.workload]
     batch = W.config_batch(cfg, a.seed)
     model = W.MODELS[batch.model]
@@ -98,7 +101,7 @@ def main():
     for _ in range(a.warmup):
         eng.ctx.step(seqs, x.data_ptr(), out.data_ptr())
     eng.ctx.sync()
-    eng.ctx.set_option("time_attention", 1)          # two event records per step, on the step's stream
+    eng.ctx.set_option("time_attention", 8)          # two event records on the step's stream, every 8th step
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(a.steps):

@@ -129,8 +129,8 @@ const char* ps_last_error(const ps_ctx* ctx);
  * in different places and must give the same results within rounding),
  * "gemm_split_k" (0 = automatic), "out_f32" (1: ps_step writes x_out as fp32 [T][hidden],
  * the precision the residual stream is kept in, instead of rounding it to bf16).
- * "time_attention" (1: bracket every attention kernel launch with HIP events, see
- * ps_attention_times).  PS_EINVAL for an unknown name or bad value. */
+ * "time_attention" (N >= 1: bracket the attention kernel launch of every Nth step with HIP
+ * events, see ps_attention_times; the two event records cost a few microseconds of stream time).  PS_EINVAL for an unknown name or bad value. */
 ps_status ps_set_option(ps_ctx* ctx, const char* name, int64_t value);
 
 /* ---- weights (Sec. 2.1: attention module, O-projection, gated feed-forward) -------- */

@@ -18,11 +18,9 @@ struct LayerWeights {
     bool ready = false;
 };
 
-struct Staging {  // pinned host buffer + the event that says its last copy has been consumed
+struct Staging {  // pinned host buffer for one step's metadata
     void* host = nullptr;
     size_t bytes = 0;
-    hipEvent_t done = nullptr;
-    bool in_flight = false;
 };
 
 }  // namespace ps
@@ -57,7 +55,12 @@ struct ps_ctx {
     int cap_part_slots = 0;
     void* dev_meta = nullptr;
     size_t dev_meta_bytes = 0;
-    Staging staging[4];
+    // Ring of 8 pinned buffers in two halves.  One event per half, recorded after the half's last
+    // copy has been enqueued, tells when all four buffers of that half may be overwritten: one
+    // event record per four steps instead of one per step.
+    Staging staging[8];
+    hipEvent_t half_done[2] = {nullptr, nullptr};
+    bool half_pending[2] = {false, false};
     int staging_next = 0;
 
     // options / debug
@@ -69,7 +72,8 @@ struct ps_ctx {
     ps_taps taps{};
 
     // optional event pairs around every attention launch (see ps_attention_times)
-    bool opt_time_attention = false;
+    int opt_time_attention = 0;   // 0 = off, N = bracket the attention launch of every Nth step
+    int64_t step_counter = 0;
     std::vector<hipEvent_t> attn_ev;  // ring of 2 * ATTN_EV_PAIRS events
     int attn_ev_count = 0;            // pairs recorded since the last ps_attention_times
 
@@ -179,7 +183,7 @@ extern "C" ps_status ps_sync(ps_ctx* c) {
     if (!c) return PS_EINVAL;
     if (c->host_only) return PS_OK;
     HIP_TRY(c, hipStreamSynchronize(c->stream));
-    for (auto& s : c->staging) s.in_flight = false;
+    c->half_pending[0] = c->half_pending[1] = false;
     return PS_OK;
 }
 
@@ -202,10 +206,10 @@ extern "C" void ps_destroy(ps_ctx* c) {
         free_workspaces(c);
         dev_free(c->part_o); dev_free(c->part_ml);
         if (c->dev_meta) (void)hipFree(c->dev_meta);
-        for (auto& s : c->staging) {
+        for (auto& s : c->staging)
             if (s.host) (void)hipHostFree(s.host);
-            if (s.done) (void)hipEventDestroy(s.done);
-        }
+        for (auto& e : c->half_done)
+            if (e) (void)hipEventDestroy(e);
         if (c->have_events) for (auto& e : c->ev) if (e) (void)hipEventDestroy(e);
         for (auto& e : c->attn_ev) if (e) (void)hipEventDestroy(e);
     }
@@ -227,13 +231,13 @@ extern "C" ps_status ps_set_option(ps_ctx* c, const char* name, int64_t value) {
         return PS_OK;
     }
     if (!strcmp(name, "time_attention")) {
-        if (value != 0 && value != 1) return fail(c, PS_EINVAL, "time_attention must be 0 or 1");
+        if (value < 0 || value > 1024) return fail(c, PS_EINVAL, "time_attention must be in [0, 1024]");
         if (c->host_only) return fail(c, PS_ESTATE, "time_attention: host-only context");
         if (value && c->attn_ev.empty()) {
             c->attn_ev.assign(2 * ATTN_EV_PAIRS, nullptr);
             for (auto& e : c->attn_ev) HIP_TRY(c, hipEventCreate(&e));
         }
-        c->opt_time_attention = value != 0;
+        c->opt_time_attention = (int)value;
         c->attn_ev_count = 0;
         return PS_OK;
     }
@@ -352,13 +356,14 @@ extern "C" int32_t ps_kv_free_pages(const ps_ctx* c) {
 }
 
 // pinned staging: returns a host buffer of at least `bytes`, safe to overwrite
-static ps_status staging_acquire(ps_ctx* c, size_t bytes, Staging** out) {
-    Staging& s = c->staging[c->staging_next];
-    c->staging_next = (c->staging_next + 1) % 4;
-    if (!s.done) HIP_TRY(c, hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
-    if (s.in_flight) {
-        HIP_TRY(c, hipEventSynchronize(s.done));
-        s.in_flight = false;
+static ps_status staging_acquire(ps_ctx* c, size_t bytes, Staging** out, int* index) {
+    const int idx = c->staging_next, half = idx / 4;
+    c->staging_next = (idx + 1) % 8;
+    *index = idx;
+    Staging& s = c->staging[idx];
+    if (idx % 4 == 0 && c->half_pending[half]) {  // entering a half: its previous copies must be done
+        HIP_TRY(c, hipEventSynchronize(c->half_done[half]));
+        c->half_pending[half] = false;
     }
     if (s.bytes < bytes) {
         if (s.host) (void)hipHostFree(s.host);
@@ -370,6 +375,16 @@ static ps_status staging_acquire(ps_ctx* c, size_t bytes, Staging** out) {
         s.bytes = want;
     }
     *out = &s;
+    return PS_OK;
+}
+
+// call after the copy out of staging buffer `index` has been enqueued
+static ps_status staging_commit(ps_ctx* c, int index) {
+    if (index % 4 != 3) return PS_OK;
+    const int half = index / 4;
+    if (!c->half_done[half]) HIP_TRY(c, hipEventCreateWithFlags(&c->half_done[half], hipEventDisableTiming));
+    HIP_TRY(c, hipEventRecord(c->half_done[half], c->stream));
+    c->half_pending[half] = true;
     return PS_OK;
 }
 
@@ -400,7 +415,8 @@ static ps_status kv_copy(ps_ctx* c, bool to_pool, int32_t layer, const ps_seq* s
         if (seq->page_table[p] < 0 || seq->page_table[p] >= c->n_pool_pages)
             return fail(c, PS_ERANGE, std::string(name) + ": page id outside the pool");
     Staging* s;
-    ps_status st = staging_acquire(c, (size_t)n * 4, &s);
+    int s_idx = 0;
+    ps_status st = staging_acquire(c, (size_t)n * 4, &s, &s_idx);
     if (st != PS_OK) return st;
     if ((st = ensure_dev_meta(c, (size_t)n * 4)) != PS_OK) return st;
     int32_t* slots = static_cast<int32_t*>(s->host);
@@ -409,8 +425,7 @@ static ps_status kv_copy(ps_ctx* c, bool to_pool, int32_t layer, const ps_seq* s
         slots[i] = seq->page_table[p / PS_PAGE_SIZE] * PS_PAGE_SIZE + p % PS_PAGE_SIZE;
     }
     HIP_TRY(c, hipMemcpyAsync(c->dev_meta, s->host, (size_t)n * 4, hipMemcpyHostToDevice, c->stream));
-    HIP_TRY(c, hipEventRecord(s->done, c->stream));
-    s->in_flight = true;
+    if ((st = staging_commit(c, s_idx)) != PS_OK) return st;
     bf16_t* slot_base = c->pool + (size_t)(layer % c->n_kv_slots) * c->slot_elems;
     HIP_TRY(c, launch_kv_copy(to_pool, slot_base, static_cast<const int32_t*>(c->dev_meta), n, c->desc.n_kv_heads,
                               c->desc.head_dim, static_cast<bf16_t*>(k), static_cast<bf16_t*>(v), c->stream));
@@ -552,6 +567,7 @@ extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, cons
     if (n_seqs == 0) return PS_OK;
     if (!x_in || !x_out) return fail(c, PS_EINVAL, "ps_step: null activation pointer");
 
+    c->step_counter++;
     const ps_model_desc& d = c->desc;
     const int T = p.n_tokens, H = d.hidden, F = d.ffn, NQ = d.n_q_heads * d.head_dim, NQKV = qkv_cols(d);
     if ((st = ensure_workspaces(c, T, p.n_partial_slots)) != PS_OK) return st;
@@ -559,7 +575,8 @@ extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, cons
     // one pinned buffer, one host-to-device copy for all of the step's integer metadata
     const MetaLayout ml = meta_layout(p);
     Staging* sg;
-    if ((st = staging_acquire(c, ml.total, &sg)) != PS_OK) return st;
+    int sg_idx = 0;
+    if ((st = staging_acquire(c, ml.total, &sg, &sg_idx)) != PS_OK) return st;
     if ((st = ensure_dev_meta(c, ml.total)) != PS_OK) return st;
     char* hb = static_cast<char*>(sg->host);
     memcpy(hb + ml.positions, p.positions.data(), p.positions.size() * 4);
@@ -570,8 +587,7 @@ extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, cons
     memcpy(hb + ml.workers, p.worker_begin.data(), p.worker_begin.size() * 4);
     if (!p.groups.empty()) memcpy(hb + ml.groups, p.groups.data(), p.groups.size() * sizeof(MergeGroup));
     HIP_TRY(c, hipMemcpyAsync(c->dev_meta, sg->host, ml.total, hipMemcpyHostToDevice, c->stream));
-    HIP_TRY(c, hipEventRecord(sg->done, c->stream));
-    sg->in_flight = true;
+    if ((st = staging_commit(c, sg_idx)) != PS_OK) return st;
     const char* db = static_cast<const char*>(c->dev_meta);
     const int32_t* d_pos = reinterpret_cast<const int32_t*>(db + ml.positions);
     const int32_t* d_slots = reinterpret_cast<const int32_t*>(db + ml.slots);
@@ -624,7 +640,8 @@ extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, cons
         a.n_groups = (int)p.groups.size();
         a.part_o = c->part_o; a.part_ml = c->part_ml; a.out = c->ws_attn;
         a.n_q = d.n_q_heads; a.n_kv = d.n_kv_heads; a.d = d.head_dim;
-        const bool time_attn = c->opt_time_attention && c->attn_ev_count < ATTN_EV_PAIRS;
+        const bool time_attn = c->opt_time_attention > 0 && c->attn_ev_count < ATTN_EV_PAIRS &&
+                               (c->step_counter % c->opt_time_attention) == 0;
         a.ev_begin = time_attn ? c->attn_ev[2 * c->attn_ev_count] : nullptr;
         a.ev_end = time_attn ? c->attn_ev[2 * c->attn_ev_count + 1] : nullptr;
         HIP_TRY(c, launch_attention(a, s));

@@ -267,18 +267,36 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(AttnArgs a) {
     const int n_rows = mg.n_tok * G;  // valid rows are the first n_tok * G of the tile
     for (int c = threadIdx.x; c < n_rows * (D / 4); c += 64) {
         const int r = c / (D / 4), col = (c % (D / 4)) * 4;
+        // splits are handled eight at a time with all loads of a batch issued together
         float M = NEG_BIG;
-        for (int j = 0; j < mg.n_splits; j++)
-            M = fmaxf(M, a.part_ml[((size_t)(mg.first_slot + j * mg.stride) * 16 + r) * 2]);
+        for (int j0 = 0; j0 < mg.n_splits; j0 += 8) {
+            float mv[8];
+#pragma unroll
+            for (int j = 0; j < 8; j++)
+                if (j0 + j < mg.n_splits) mv[j] = a.part_ml[((size_t)(mg.first_slot + (j0 + j) * mg.stride) * 16 + r) * 2];
+#pragma unroll
+            for (int j = 0; j < 8; j++)
+                if (j0 + j < mg.n_splits) M = fmaxf(M, mv[j]);
+        }
         float4 acc = {0.f, 0.f, 0.f, 0.f};
         float L = 0.f;
-        for (int j = 0; j < mg.n_splits; j++) {
-            const size_t row = (size_t)(mg.first_slot + j * mg.stride) * 16 + r;
-            const float2 ml = *reinterpret_cast<const float2*>(a.part_ml + row * 2);
-            const float w = __builtin_amdgcn_exp2f(ml.x - M);
-            const float4 v = *reinterpret_cast<const float4*>(a.part_o + row * D + col);
-            L += w * ml.y;
-            acc.x += w * v.x; acc.y += w * v.y; acc.z += w * v.z; acc.w += w * v.w;
+        for (int j0 = 0; j0 < mg.n_splits; j0 += 8) {
+            float2 ml[8];
+            float4 v[8];
+#pragma unroll
+            for (int j = 0; j < 8; j++)
+                if (j0 + j < mg.n_splits) {
+                    const size_t row = (size_t)(mg.first_slot + (j0 + j) * mg.stride) * 16 + r;
+                    ml[j] = *reinterpret_cast<const float2*>(a.part_ml + row * 2);
+                    v[j] = *reinterpret_cast<const float4*>(a.part_o + row * D + col);
+                }
+#pragma unroll
+            for (int j = 0; j < 8; j++)
+                if (j0 + j < mg.n_splits) {
+                    const float w = __builtin_amdgcn_exp2f(ml[j].x - M);
+                    L += w * ml[j].y;
+                    acc.x += w * v[j].x; acc.y += w * v[j].y; acc.z += w * v[j].z; acc.w += w * v[j].w;
+                }
         }
         const float inv = 1.0f / L;
         const int head = mg.kv_head * G + r % G;

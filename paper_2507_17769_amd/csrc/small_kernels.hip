@@ -87,11 +87,21 @@ __global__ __launch_bounds__(64) void rope_append_kernel(const float* __restrict
     if (j >= half) return;
     const int ld = (n_q + 2 * n_kv) * d;
     const float* row = qkv + (size_t)t * ld + (size_t)hh * d;
+    // all split loads are issued before the first add (n_splits <= 8)
+    float plo[8], phi[8];
+#pragma unroll
+    for (int s = 0; s < 8; s++)
+        if (s < n_splits) {
+            plo[s] = row[s * split_stride + j];
+            phi[s] = row[s * split_stride + j + half];
+        }
     float lo = 0.f, hi = 0.f;
-    for (int s = 0; s < n_splits; s++) {
-        lo += row[s * split_stride + j];
-        hi += row[s * split_stride + j + half];
-    }
+#pragma unroll
+    for (int s = 0; s < 8; s++)
+        if (s < n_splits) {
+            lo += plo[s];
+            hi += phi[s];
+        }
     if (hh < n_q + n_kv) {
         const float2 c = cs[(size_t)positions[t] * half + j];
         const bf16_t blo = f32_to_bf16(lo * c.x - hi * c.y);
@@ -120,6 +130,7 @@ hipError_t launch_rope_append(const float* qkv, int n_splits, bf16_t* q_out, int
                               const int32_t* positions, const int32_t* slots, const float* rope_cs, bf16_t* pool_slot,
                               hipStream_t st) {
     if (T <= 0) return hipSuccess;
+    if (n_splits > 8) return hipErrorInvalidValue;
     const size_t split_stride = (size_t)T * (n_q + 2 * n_kv) * d;
     hipLaunchKernelGGL(rope_append_kernel, dim3(T, n_q + 2 * n_kv), dim3(64), 0, st, qkv, n_splits, split_stride, q_out,
                        n_q, n_kv, d,
@@ -186,12 +197,21 @@ __global__ __launch_bounds__(256) void reduce_add_norm_kernel(ReduceAddNormArgs 
                 v[k][0] = bf16_lo(w.x); v[k][1] = bf16_hi(w.x); v[k][2] = bf16_lo(w.y); v[k][3] = bf16_hi(w.y);
                 v[k][4] = bf16_lo(w.z); v[k][5] = bf16_hi(w.z); v[k][6] = bf16_lo(w.w); v[k][7] = bf16_hi(w.w);
             }
-            for (int s = 0; s < a.n_splits; s++) {
-                const float4* p = reinterpret_cast<const float4*>(a.partials + s * split_stride + (size_t)row * H + c);
-                const float4 x0 = p[0], x1 = p[1];
-                v[k][0] += x0.x; v[k][1] += x0.y; v[k][2] += x0.z; v[k][3] += x0.w;
-                v[k][4] += x1.x; v[k][5] += x1.y; v[k][6] += x1.z; v[k][7] += x1.w;
-            }
+            // all split loads are issued before the first add (n_splits <= 8)
+            float4 q0[8], q1[8];
+#pragma unroll
+            for (int s = 0; s < 8; s++)
+                if (s < a.n_splits) {
+                    const float4* p = reinterpret_cast<const float4*>(a.partials + s * split_stride + (size_t)row * H + c);
+                    q0[s] = p[0];
+                    q1[s] = p[1];
+                }
+#pragma unroll
+            for (int s = 0; s < 8; s++)
+                if (s < a.n_splits) {
+                    v[k][0] += q0[s].x; v[k][1] += q0[s].y; v[k][2] += q0[s].z; v[k][3] += q0[s].w;
+                    v[k][4] += q1[s].x; v[k][5] += q1[s].y; v[k][6] += q1[s].z; v[k][7] += q1[s].w;
+                }
             if (a.x_f32) {
                 float4* o = reinterpret_cast<float4*>(a.x_f32 + (size_t)row * H + c);
                 o[0] = float4{v[k][0], v[k][1], v[k][2], v[k][3]};
@@ -229,7 +249,7 @@ __global__ __launch_bounds__(256) void reduce_add_norm_kernel(ReduceAddNormArgs 
 
 hipError_t launch_reduce_add_norm(const ReduceAddNormArgs& a, hipStream_t st) {
     if (a.T <= 0) return hipSuccess;
-    if (a.H > 8192 || a.H % 8) return hipErrorInvalidValue;
+    if (a.H > 8192 || a.H % 8 || a.n_splits > 8) return hipErrorInvalidValue;
     if (a.resid_f32)
         hipLaunchKernelGGL(reduce_add_norm_kernel<true>, dim3(a.T), dim3(256), 0, st, a);
     else
