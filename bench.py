@@ -64,6 +64,24 @@ def cpu_baseline(batch, weights, n_runs=2):
             "ms_per_step": t * 1e3}
 
 
+def measured_traffic(workload, seed):
+    """HBM bytes per attention launch from the committed rocprofv3 counter runs (FETCH_SIZE and
+    WRITE_SIZE, each scaled by what the same counter reads for a plain copy).  None when there is no
+    record for this workload or the kernel source has changed since the counters were taken."""
+    import hashlib
+    path = os.path.join(ROOT, "paper_2507_17769_amd", "measured_traffic.json")
+    try:
+        rec = json.load(open(path))
+        if rec.get("workload") != f"{workload} seed {seed}":
+            return None
+        for rel, sha in rec["source_sha256"].items():
+            if hashlib.sha256(open(os.path.join(ROOT, rel), "rb").read()).hexdigest() != sha:
+                return None
+        return float(rec["fetch_bytes"]) + float(rec["write_bytes"])
+    except Exception:
+        return None
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -141,7 +159,7 @@ def main():
                    "n_tokens": T, "total_kv": total_kv, "n_layers": 1},
         "roofline": {"bound": "hbm", "kernel": "attn_kernel (paged attention, split merge excluded)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None, "algorithmic_bytes_per_launch": attn_bytes, "avg_launch_ms": attn_avg_ms,
+                     "traffic": measured_traffic(a.workload, a.seed), "algorithmic_bytes_per_launch": attn_bytes, "avg_launch_ms": attn_avg_ms,
                      "launches_timed": len(attn_ms)},
         "stage_ms": {n: round(float(v), 4) for n, v in zip(STAGE_NAMES, stage)},
         "gemm": {"ms": gemm_ms, "weight_GBs": 2 * params / (gemm_ms * 1e-3) / 1e9,
