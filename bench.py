@@ -1,11 +1,15 @@
 """Benchmark of the mixed-batch serving step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg1|cfg2] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg1|cfg2|grid] [--no-cpu-baseline]
 
 A step is one pass of the whole layer (RMSNorm, QKV, rotary + KV append, paged attention,
 O-projection, SwiGLU feed-forward) over one batch of synthetic input that is already resident
 in HBM.  The default workload is the decode-only batch (64 decode tokens, KV lengths uniform in
 [512, 4096], 8B-shaped layer).  Prints ONE JSON line.
+
+--workload grid times the latency-profile grid instead (prefill chunk sizes x decode counts, five
+draws of the lengths per cell, median step time): the (batch size, KV cache size) -> iteration
+time table that the paper's router consumes (Sec. 4.5).  It prints one JSON object with the cells.
 """
 import argparse
 import json
@@ -26,7 +30,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg2"])
+    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg2", "grid"])
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--null-stream", action="store_true", help="run on the default stream instead of a dedicated one")
@@ -82,6 +86,60 @@ def measured_traffic(workload, seed):
         return None
 
 
+def run_grid(a):
+    import numpy as np
+    import torch
+    from paper_2507_17769_amd import workloads as W
+    from paper_2507_17769_amd.binding import STAGE_NAMES
+    from paper_2507_17769_amd.runner import Engine, bits_to_dev
+
+    model = "8b"
+    m = W.MODELS[model]
+    cells, worst_pages, worst_tokens = [], 0, 0
+    for chunk in W.GRID_CHUNKS:
+        for n_dec in W.GRID_DECODES:
+            draws = [W.grid_cell_lengths(chunk, n_dec, s) for s in W.GRID_SEEDS]
+            prefixes = [d[0] for d in draws]
+            dkv = np.array([d[1] for d in draws], dtype=np.int32).reshape(len(draws), n_dec)
+            cells.append((chunk, n_dec, prefixes, dkv))
+            for off, kv in draws:
+                pages = sum((int(L) + 15) // 16 for L in kv) + ((off + chunk + 15) // 16 if chunk else 0)
+                worst_pages = max(worst_pages, pages)
+            worst_tokens = max(worst_tokens, chunk + n_dec)
+    n_pool = worst_pages + worst_pages // 8 + 64
+    eng = Engine(model, n_pool, max_position=8192 + 4096 + 2048 + 16)
+    eng.load_layer(0, W.layer_weights(model, a.seed, 0))
+    # fill every page with N(0,1) keys and values (timing must not run on an all-zero cache)
+    rng = np.random.Generator(np.random.PCG64([a.seed, 2718281]))
+    blk = 8192
+    k = bits_to_dev(W.normal_bf16(rng, (blk, m["n_kv"], m["head_dim"])), eng.device)
+    v = bits_to_dev(W.normal_bf16(rng, (blk, m["n_kv"], m["head_dim"])), eng.device)
+    rid = 0
+    while eng.ctx.kv_free_pages() > 0:
+        n_tok = min(blk, eng.ctx.kv_free_pages() * 16)
+        pages = eng.ctx.kv_reserve(10_000 + rid, n_tok)
+        eng.ctx.kv_write(0, pages, 0, n_tok, k.data_ptr(), v.data_ptr())
+        rid += 1
+    eng.ctx.sync()
+    for r in range(rid):
+        eng.ctx.kv_release(10_000 + r)
+    x = bits_to_dev(W.normal_bf16(rng, (max(worst_tokens, 1), m["hidden"])), eng.device)
+    y = torch.empty_like(x)
+    t0 = time.perf_counter()
+    res = eng.ctx.profile_grid(cells, x.data_ptr(), y.data_ptr(), warmup=a.warmup if a.warmup < 20 else 3, iters=min(a.steps, 10))
+    wall = time.perf_counter() - t0
+    out = []
+    for c in res:
+        out.append({"chunk": c.chunk, "n_decode": c.n_decode, "n_tokens": c.n_tokens, "total_kv": int(c.total_kv),
+                    "median_ms": round(float(c.median_ms), 4),
+                    "draw_ms": [round(float(c.draw_ms[i]), 4) for i in range(c.n_draws)],
+                    "draw_total_kv": [int(c.draw_total_kv[i]) for i in range(c.n_draws)],
+                    "stage_ms": {n: round(float(c.stage_ms[i]), 4) for i, n in enumerate(STAGE_NAMES)}})
+    eng.close()
+    print(json.dumps({"metric": "latency_profile_grid", "unit": "ms", "model": "8B-shaped layer", "seeds": list(W.GRID_SEEDS),
+                      "pool_pages": n_pool, "wall_s": round(wall, 2), "cells": out}))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -104,6 +162,9 @@ def main():
         return
     if not a.null_stream:   # a stream of our own (default priority); torch only allocates and copies
         torch.cuda.set_stream(torch.cuda.Stream(device="cuda:0"))
+    if a.workload == "grid":
+        run_grid(a)
+        return
     cfg = {"cfg1": 1, "cfg2": 2}[a.workload]
     batch = W.config_batch(cfg, a.seed)
     model = W.MODELS[batch.model]
