@@ -53,8 +53,12 @@ struct ps_ctx {
     size_t part_bytes = 0;
     float *part_o = nullptr, *part_ml = nullptr;
     int cap_part_slots = 0;
-    void* dev_meta = nullptr;
-    size_t dev_meta_bytes = 0;
+    // Device copies of the staging ring (same 8 slots).  The copy of step n+1's metadata runs on
+    // copy_stream while step n's kernels execute; the main stream only waits for the slot's event.
+    char* dev_meta = nullptr;
+    size_t dev_meta_slot = 0;  // bytes per slot
+    hipStream_t copy_stream = nullptr;
+    hipEvent_t meta_ready[8] = {};
     // Ring of 8 pinned buffers in two halves.  One event per half, recorded after the half's last
     // copy has been enqueued, tells when all four buffers of that half may be overwritten: one
     // event record per four steps instead of one per step.
@@ -206,6 +210,9 @@ extern "C" void ps_destroy(ps_ctx* c) {
         free_workspaces(c);
         dev_free(c->part_o); dev_free(c->part_ml);
         if (c->dev_meta) (void)hipFree(c->dev_meta);
+        for (auto& e : c->meta_ready)
+            if (e) (void)hipEventDestroy(e);
+        if (c->copy_stream) { (void)hipStreamSynchronize(c->copy_stream); (void)hipStreamDestroy(c->copy_stream); }
         for (auto& s : c->staging)
             if (s.host) (void)hipHostFree(s.host);
         for (auto& e : c->half_done)
@@ -378,7 +385,7 @@ static ps_status staging_acquire(ps_ctx* c, size_t bytes, Staging** out, int* in
     return PS_OK;
 }
 
-// call after the copy out of staging buffer `index` has been enqueued
+// call after the last kernel that reads slot `index`'s device copy has been enqueued
 static ps_status staging_commit(ps_ctx* c, int index) {
     if (index % 4 != 3) return PS_OK;
     const int half = index / 4;
@@ -388,16 +395,29 @@ static ps_status staging_commit(ps_ctx* c, int index) {
     return PS_OK;
 }
 
-static ps_status ensure_dev_meta(ps_ctx* c, size_t bytes) {
-    if (c->dev_meta_bytes >= bytes) return PS_OK;
-    HIP_TRY(c, hipStreamSynchronize(c->stream));
-    if (c->dev_meta) (void)hipFree(c->dev_meta);
-    c->dev_meta = nullptr;
-    c->dev_meta_bytes = 0;
-    const size_t want = std::max(bytes + bytes / 2, (size_t)1 << 16);
-    ps_status st = dev_alloc(c, &c->dev_meta, want, "step metadata");
-    if (st != PS_OK) return st;
-    c->dev_meta_bytes = want;
+// Copy `bytes` of staging slot `index` to its device slot on the copy stream and make the main
+// stream wait for it.  *dev receives the device address.
+static ps_status upload_meta(ps_ctx* c, const Staging* sg, int index, size_t bytes, const char** dev) {
+    if (!c->copy_stream) {
+        HIP_TRY(c, hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking));
+        for (auto& e : c->meta_ready) HIP_TRY(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    }
+    if (c->dev_meta_slot < bytes) {
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        HIP_TRY(c, hipStreamSynchronize(c->copy_stream));
+        if (c->dev_meta) (void)hipFree(c->dev_meta);
+        c->dev_meta = nullptr;
+        c->dev_meta_slot = 0;
+        const size_t want = (std::max(bytes + bytes / 2, (size_t)1 << 16) + 255) & ~(size_t)255;
+        ps_status st = dev_alloc(c, &c->dev_meta, want * 8, "step metadata");
+        if (st != PS_OK) return st;
+        c->dev_meta_slot = want;
+    }
+    char* d = c->dev_meta + (size_t)index * c->dev_meta_slot;
+    HIP_TRY(c, hipMemcpyAsync(d, sg->host, bytes, hipMemcpyHostToDevice, c->copy_stream));
+    HIP_TRY(c, hipEventRecord(c->meta_ready[index], c->copy_stream));
+    HIP_TRY(c, hipStreamWaitEvent(c->stream, c->meta_ready[index], 0));
+    *dev = d;
     return PS_OK;
 }
 
@@ -418,18 +438,17 @@ static ps_status kv_copy(ps_ctx* c, bool to_pool, int32_t layer, const ps_seq* s
     int s_idx = 0;
     ps_status st = staging_acquire(c, (size_t)n * 4, &s, &s_idx);
     if (st != PS_OK) return st;
-    if ((st = ensure_dev_meta(c, (size_t)n * 4)) != PS_OK) return st;
     int32_t* slots = static_cast<int32_t*>(s->host);
     for (int i = 0; i < n; i++) {
         const int p = pos0 + i;
         slots[i] = seq->page_table[p / PS_PAGE_SIZE] * PS_PAGE_SIZE + p % PS_PAGE_SIZE;
     }
-    HIP_TRY(c, hipMemcpyAsync(c->dev_meta, s->host, (size_t)n * 4, hipMemcpyHostToDevice, c->stream));
-    if ((st = staging_commit(c, s_idx)) != PS_OK) return st;
+    const char* dslots = nullptr;
+    if ((st = upload_meta(c, s, s_idx, (size_t)n * 4, &dslots)) != PS_OK) return st;
     bf16_t* slot_base = c->pool + (size_t)(layer % c->n_kv_slots) * c->slot_elems;
-    HIP_TRY(c, launch_kv_copy(to_pool, slot_base, static_cast<const int32_t*>(c->dev_meta), n, c->desc.n_kv_heads,
+    HIP_TRY(c, launch_kv_copy(to_pool, slot_base, reinterpret_cast<const int32_t*>(dslots), n, c->desc.n_kv_heads,
                               c->desc.head_dim, static_cast<bf16_t*>(k), static_cast<bf16_t*>(v), c->stream));
-    return PS_OK;
+    return staging_commit(c, s_idx);
 }
 
 extern "C" ps_status ps_kv_write(ps_ctx* c, int32_t layer, const ps_seq* seq, int32_t pos0, int32_t n, const void* k, const void* v) {
@@ -468,7 +487,7 @@ extern "C" ps_status ps_plan_attention(ps_ctx* c, const ps_seq* seqs, int32_t n_
     const StepPlan& p = c->plan;
     *n_items = (int32_t)p.items.size();
     const int n = std::min<int>(cap, (int)p.items.size());
-    static_assert(sizeof(AttnItem) == 12 * sizeof(int32_t), "item is 12 int32, the first 8 are reported");
+    static_assert(sizeof(AttnItem) == 16 * sizeof(int32_t), "item is 16 int32, the first 8 are reported");
     for (int i = 0; i < n; i++) memcpy(items + (size_t)i * 8, &p.items[i], 8 * sizeof(int32_t));
     return PS_OK;
 }
@@ -577,7 +596,6 @@ extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, cons
     Staging* sg;
     int sg_idx = 0;
     if ((st = staging_acquire(c, ml.total, &sg, &sg_idx)) != PS_OK) return st;
-    if ((st = ensure_dev_meta(c, ml.total)) != PS_OK) return st;
     char* hb = static_cast<char*>(sg->host);
     memcpy(hb + ml.positions, p.positions.data(), p.positions.size() * 4);
     memcpy(hb + ml.slots, p.slots.data(), p.slots.size() * 4);
@@ -586,9 +604,8 @@ extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, cons
     memcpy(hb + ml.items, p.items.data(), p.items.size() * sizeof(AttnItem));
     memcpy(hb + ml.workers, p.worker_begin.data(), p.worker_begin.size() * 4);
     if (!p.groups.empty()) memcpy(hb + ml.groups, p.groups.data(), p.groups.size() * sizeof(MergeGroup));
-    HIP_TRY(c, hipMemcpyAsync(c->dev_meta, sg->host, ml.total, hipMemcpyHostToDevice, c->stream));
-    if ((st = staging_commit(c, sg_idx)) != PS_OK) return st;
-    const char* db = static_cast<const char*>(c->dev_meta);
+    const char* db = nullptr;
+    if ((st = upload_meta(c, sg, sg_idx, ml.total, &db)) != PS_OK) return st;
     const int32_t* d_pos = reinterpret_cast<const int32_t*>(db + ml.positions);
     const int32_t* d_slots = reinterpret_cast<const int32_t*>(db + ml.slots);
 
@@ -701,7 +718,7 @@ extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, cons
         stats->ms_total = total_ms;
         for (int i = 0; i < PS_N_STAGES; i++) stats->ms_stage[i] = stage_ms[i];
     }
-    return PS_OK;
+    return staging_commit(c, sg_idx);
 }
 
 extern "C" ps_status ps_attention_times(ps_ctx* c, float* ms, int32_t cap, int32_t* n) {

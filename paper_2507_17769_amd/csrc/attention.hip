@@ -177,7 +177,12 @@ __device__ __forceinline__ void attn_item(const AttnArgs& a, const AttnItem it) 
         const int n_pg = min(64, it.page_end - blk);
         const int my_pid = pages[blk + min(lane, n_pg - 1)];
         const int n_pairs = (n_pg + 1) >> 1;
-        auto pid = [&](int j) { return __builtin_amdgcn_readlane(my_pid, min(j, n_pg - 1)); };
+        const bool first_blk = blk == it.page_begin;
+        // the item carries its first two page ids, so the first pair's loads do not wait for my_pid
+        auto pid = [&](int j) {
+            if (j < 2 && first_blk) return j == 0 ? it.page0 : it.page1;
+            return __builtin_amdgcn_readlane(my_pid, min(j, n_pg - 1));
+        };
         if constexpr (PIPE) {
             // Two register sets; the steady-state body issues its loads unconditionally so that the
             // wait before each compute covers exactly the older set (a conditional load would force

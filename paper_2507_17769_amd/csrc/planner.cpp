@@ -172,7 +172,9 @@ void build_attention_plan(const PlanConfig& cfg, StepPlan& plan) {
                     take = 1;
                 }
                 plan.items.push_back(AttnItem{sg.seq, h, sg.q0, sg.qn, 2 * pair, std::min(sg.np, 2 * (pair + take)), -1,
-                                              worker, sq.tok0 + sg.q0, sq.kv_len - sq.n_new + sg.q0, sq.page_off, 0});
+                                              worker, sq.tok0 + sg.q0, sq.kv_len - sq.n_new + sg.q0, sq.page_off,
+                                              plan.pages[sq.page_off + 2 * pair],
+                                              plan.pages[sq.page_off + std::min(2 * pair + 1, sg.np - 1)], 0, 0, 0});
                 pair += take;
                 left -= (int64_t)take * sg.w;
                 done += (int64_t)take * sg.w;

@@ -54,7 +54,8 @@ struct AttnItem {
     int32_t tok_g0;      // global token index of the block's first query token
     int32_t pos0;        // cache position of that token
     int32_t page_off;    // offset of the sequence's page list in the flat page array
-    int32_t pad;
+    int32_t page0, page1;  // physical ids of the item's first two pages: the first loads need no table lookup
+    int32_t pad0, pad1, pad2;
 };
 
 // Split-KV merge group: one 16-row query tile of one (sequence, kv head).
