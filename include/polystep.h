@@ -101,9 +101,13 @@ typedef struct {
 /* Optional copies of one layer's intermediates, for numerical checks.  Any pointer may be
  * null.  Device buffers, written during ps_step: xn, xn2 [T][hidden] bf16; q [T][n_q][d]
  * bf16 after rotation; attn [T][n_q*d] bf16; x1 [T][hidden] fp32 (input + attention
- * branch); act [T][ffn] bf16 (silu(gate)*up). */
+ * branch); act [T][ffn] bf16 (silu(gate)*up); x_in, x_out [T][hidden] fp32: the residual
+ * stream entering and leaving the layer, as kept between layers (x_in is written only for
+ * layers > 0, x_out for the last layer only while option "out_f32" is set).  x_in / x_out
+ * let one layer of a deep stack be checked on its own: feed x_in and that layer's weights
+ * and KV slot to a reference and compare with x_out. */
 typedef struct {
-    void *xn, *q, *attn, *x1, *xn2, *act;
+    void *xn, *q, *attn, *x1, *xn2, *act, *x_in, *x_out;
 } ps_taps;
 
 /* ---- lifetime ------------------------------------------------------------------- */

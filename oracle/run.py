@@ -33,3 +33,11 @@ def run_step(model, layers_bits, seqs, x_bits, pool, dtype=np.float32, want_taps
     taps = {} if want_taps else None
     out = layer.stack_forward(x, ws, to_seqs(seqs), pool, sh, taps, bf16_activations)
     return out, taps
+
+
+def run_layer_from(model, weights_bits, seqs, x, pool, slot, dtype=np.float32, bf16_activations=False):
+    """One layer from a float residual-stream input x [T][hidden] (teacher forcing: x is the
+    input the layer actually received inside a deeper stack).  Appends to pool[slot]."""
+    sh = shape_from(model)
+    return layer.layer_forward(np.asarray(x, dtype=dtype), widen_weights(weights_bits, dtype), to_seqs(seqs), pool, slot, sh,
+                               None, bf16_activations)

@@ -49,7 +49,7 @@ class ps_step_stats(C.Structure):
 
 
 class ps_taps(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("xn", "q", "attn", "x1", "xn2", "act")]
+    _fields_ = [(n, C.c_void_p) for n in ("xn", "q", "attn", "x1", "xn2", "act", "x_in", "x_out")]
 
 
 class ps_grid_cell_spec(C.Structure):

@@ -632,6 +632,7 @@ extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, cons
         // 0: RMSNorm of the layer input (layers after the first get it from the previous layer's last kernel)
         if (l == 0) HIP_TRY(c, launch_rmsnorm(x_cur, x_cur_f32, L.g_attn, c->ws_xn, T, H, d.rms_eps, s));
         if (tap && c->taps.xn) HIP_TRY(c, launch_untile(c->ws_xn, static_cast<bf16_t*>(c->taps.xn), T, H, s));
+        if (tap && c->taps.x_in && l > 0) HIP_TRY(c, launch_copy_bytes(x_cur, c->taps.x_in, (size_t)T * H * 4, s));
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
         // 1: QKV projection -> fp32 partials
         GemmArgs g{};
@@ -699,6 +700,8 @@ extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, cons
         }
         HIP_TRY(c, launch_reduce_add_norm(r, s));
         void* x_next = last ? x_out : static_cast<void*>(c->ws_xmid);
+        if (tap && c->taps.x_out && (!last || c->opt_out_f32))
+            HIP_TRY(c, launch_copy_bytes(x_next, c->taps.x_out, (size_t)T * H * 4, s));
         if (stats) {
             HIP_TRY(c, hipEventRecord(c->ev[++e], s));
             HIP_TRY(c, hipEventSynchronize(c->ev[e]));

@@ -199,3 +199,54 @@ def test_profile_grid_small():
     assert abs(sum(out[2].stage_ms) - out[2].median_ms) < 5 * out[2].median_ms
     assert eng.ctx.kv_free_pages() == 400
     eng.close()
+
+
+def test_teacher_forced_layer_inside_an_aliased_stack():
+    # 4 layers on 2 KV slots (layers 0,2 share slot 0; 1,3 share slot 1).  The whole stack is checked
+    # against the oracle (which models the same aliasing), then layer 2 on its own: the x_in tap, that
+    # layer's weights and its slot's cached prefix go to the oracle, the result must match the x_out tap.
+    from oracle import run as orun
+    b = W.custom_batch("tiny", 8, 24, 40, [1, 33, 70], name="alias")
+    c = Case(b, n_layers=4, n_kv_layers=2)
+    errs = c.run(tap_layer=3)
+    _assert_errs({k: v for k, v in errs.items() if not k.startswith("x1") and "o_branch" not in k}, "aliased stack")
+    eng, T, H = c.eng, b.n_tokens, 256
+    xin = torch.zeros((T, H), dtype=torch.float32, device=eng.device)
+    xout = torch.zeros((T, H), dtype=torch.float32, device=eng.device)
+    eng.ctx.set_taps(2, x_in=xin.data_ptr(), x_out=xout.data_ptr())
+    x_dev = bits_to_dev(c.x_bits, eng.device)
+    eng.step(b.seqs, x_dev)
+    eng.ctx.sync()
+    eng.ctx.set_taps(0)
+    pool = orun.make_pool(c.model, b.n_pool_pages, 1)
+    for i, s in enumerate(b.seqs):
+        k, v = b.prefix_kv(i, 0)                      # slot 0 = layer 2's slot
+        pool.write_bits(0, [int(p) for p in s.pages], 0, k, v)
+    want = orun.run_layer_from(c.model, c.layers[2], b.seqs, xin.cpu().numpy(), pool, 0)
+    assert rel_err(xout.cpu().numpy(), want) <= TOL
+    c.close()
+
+
+def test_wide_hidden_70b_like_shape_small_ffn():
+    # hidden 8192 with 64 query / 8 KV heads (group size 8) as in the 70B-shaped layer, small FFN and batch.
+    # Weights at 1.28/sqrt(hidden) keep the attention logits at the spread they have in the 8B-shaped
+    # layer; at N(0, 0.02) the logits' standard deviation doubles, the softmax turns peaky, and rounding
+    # the stored activations to bf16 moves the definition itself by more than the bar: that input is
+    # held to the bar against the variant of the definition with bf16 activations.
+    model = dict(hidden=8192, n_q=64, n_kv=8, head_dim=128, ffn=1024, rope_base=500000.0, n_layers=1)
+    W.MODELS["_w"] = model
+    try:
+        for spec in ((70, 30, [1, 40, 300]), (0, 0, [5, 17, 64, 100] * 4)):
+            b = W.custom_batch("_w", 13, *spec, name="wide")
+            c = Case(b, weight_std=1.28 / 8192 ** 0.5)
+            errs = c.run(tight=TOL)      # 8192-term dot products: the per-row bar, as at full size
+            _assert_errs(errs, f"wide {spec}")
+            c.check_pool()
+            c.close()
+            c = Case(b)
+            errs = c.run(tight=TOL)
+            bad = {k: v for k, v in errs.items() if k.endswith("|bf16:score") and v > TOL}
+            assert not bad, f"wide {spec} at N(0, 0.02): {bad} (all: {errs})"
+            c.close()
+    finally:
+        del W.MODELS["_w"]
