@@ -51,6 +51,7 @@ struct ps_ctx {
     float *ws_x1 = nullptr, *ws_xmid = nullptr;
     float* ws_part = nullptr;  // fp32 GEMM partials [splits][T][N], shared by the three projections
     size_t part_bytes = 0;
+    size_t act_bytes = 0;
     float *part_o = nullptr, *part_ml = nullptr;
     int cap_part_slots = 0;
     // Device copies of the staging ring (same 8 slots).  The copy of step n+1's metadata runs on
@@ -71,6 +72,7 @@ struct ps_ctx {
     int opt_attn_workers = 0;
     int worker_slots = 2048;
     int opt_gemm_split_k = 0;
+    int opt_gemm_tile = 0;
     bool opt_out_f32 = false;
     int tap_layer = -1;
     ps_taps taps{};
@@ -230,6 +232,11 @@ extern "C" ps_status ps_set_option(ps_ctx* c, const char* name, int64_t value) {
     if (!strcmp(name, "attn_workers")) {
         if (value < 0 || value > (1 << 20)) return fail(c, PS_EINVAL, "attn_workers must be in [0, 2^20]");
         c->opt_attn_workers = (int)value;
+        return PS_OK;
+    }
+    if (!strcmp(name, "gemm_tile")) {
+        if (value != 0 && value != 128 && value != 256) return fail(c, PS_EINVAL, "gemm_tile must be 0, 128 or 256");
+        c->opt_gemm_tile = (int)value;
         return PS_OK;
     }
     if (!strcmp(name, "gemm_split_k")) {
@@ -517,16 +524,17 @@ static ps_status ensure_workspaces(ps_ctx* c, int T, int n_part_slots) {
         if ((st = dev_alloc(c, &c->ws_xn, (size_t)cap16 * H * 2, "xn")) != PS_OK) return st;
         if ((st = dev_alloc(c, &c->ws_q, (size_t)cap * NQ * 2, "q")) != PS_OK) return st;
         if ((st = dev_alloc(c, &c->ws_attn, (size_t)cap16 * NQ * 2, "attn")) != PS_OK) return st;
-        if ((st = dev_alloc(c, &c->ws_act, (size_t)cap16 * F * 2, "act")) != PS_OK) return st;
+        c->act_bytes = gemm_out_bytes(cap, 2 * F, H, GemmOut::SWIGLU_BF16, 0, 0);  // whole row tiles of the GEMM
+        if ((st = dev_alloc(c, &c->ws_act, c->act_bytes, "act")) != PS_OK) return st;
         if ((st = dev_alloc(c, &c->ws_x1, (size_t)cap * H * 4, "x1")) != PS_OK) return st;
         if (d.n_layers > 1 && (st = dev_alloc(c, &c->ws_xmid, (size_t)cap * H * 4, "inter-layer x")) != PS_OK) return st;
         c->cap_tokens = cap;
     }
     {   // GEMM partial buffer: sized for this step's T (the split count depends on T)
         const int H = d.hidden, F = d.ffn, NQ = d.n_q_heads * d.head_dim, NQKV = qkv_cols(d);
-        size_t need = gemm_out_bytes(T, NQKV, H, GemmOut::PARTIAL_F32, c->opt_gemm_split_k);
-        need = std::max(need, gemm_out_bytes(T, H, NQ, GemmOut::PARTIAL_F32, c->opt_gemm_split_k));
-        need = std::max(need, gemm_out_bytes(T, H, F, GemmOut::PARTIAL_F32, c->opt_gemm_split_k));
+        size_t need = gemm_out_bytes(T, NQKV, H, GemmOut::PARTIAL_F32, c->opt_gemm_split_k, c->opt_gemm_tile);
+        need = std::max(need, gemm_out_bytes(T, H, NQ, GemmOut::PARTIAL_F32, c->opt_gemm_split_k, c->opt_gemm_tile));
+        need = std::max(need, gemm_out_bytes(T, H, F, GemmOut::PARTIAL_F32, c->opt_gemm_split_k, c->opt_gemm_tile));
         if (need > c->part_bytes) {
             HIP_TRY(c, hipStreamSynchronize(c->stream));
             dev_free(c->ws_part);
@@ -637,7 +645,7 @@ extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, cons
         // 1: QKV projection -> fp32 partials
         GemmArgs g{};
         g.A = c->ws_xn; g.Wp = L.wqkv_t; g.M = T; g.N = NQKV; g.K = H; g.kind = GemmOut::PARTIAL_F32;
-        g.out = c->ws_part; g.out_bytes = c->part_bytes; g.split_k = c->opt_gemm_split_k;
+        g.out = c->ws_part; g.out_bytes = c->part_bytes; g.split_k = c->opt_gemm_split_k; g.tile = c->opt_gemm_tile;
         HIP_TRY(c, launch_gemm(g, &n_splits, s));
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
         // 2: sum the partials, rotate, round once to bf16, append k/v to the pages
@@ -680,7 +688,7 @@ extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, cons
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
         // 6: gate/up + SwiGLU
         g.A = c->ws_xn; g.Wp = L.wgu_t; g.N = 2 * F; g.K = H; g.kind = GemmOut::SWIGLU_BF16;
-        g.out = c->ws_act; g.out_bytes = 0;
+        g.out = c->ws_act; g.out_bytes = c->act_bytes;
         HIP_TRY(c, launch_gemm(g, nullptr, s));
         if (tap && c->taps.act) HIP_TRY(c, launch_untile(c->ws_act, static_cast<bf16_t*>(c->taps.act), T, F, s));
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));

@@ -14,11 +14,18 @@
 //    K slice, loads weight operands straight from HBM into registers (no LDS hop), activation
 //    operands (operand order, see act_offset) from L1/L2, two k-block groups in flight; the four wavefronts of a block split K among
 //    themselves and reduce through LDS in a fixed order.
-//  * gemm_tiled_kernel (M > 64): 128x128 block tile, bf16 MFMA 32x32x16, operands staged
-//    through LDS in BK = 64 slices with a register-held prefetch of the next slice.
+//  * gemm_dma_kernel (M > 64): 256x256 or 128x128 block tile, bf16 MFMA 32x32x16.  Activations and
+//    weights are both stored as KiB blocks that already are MFMA operands, so a k-slice of the
+//    tile is copied HBM/L2 -> LDS verbatim by global_load_lds (no register hop, no transform) into
+//    a ring of four stages, three in flight; the wavefronts read operands back with one
+//    ds_read_b128 per 32x16 operand, interleaved one-for-two with the MFMAs that consume the
+//    previous half-stage.  Block ids are mapped so that the blocks of one XCD share weight tiles.
 // Output is either fp32 partials [split][M][N] (the consumer kernel sums the splits, adds the
 // residual, normalises, rotates ...) or, for the fused gate/up matrix, silu(gate) * up in bf16.
 #include "ps_device.h"
+
+#include <algorithm>
+#include <mutex>
 
 namespace ps {
 
@@ -28,7 +35,7 @@ struct GemmParams {
     int M, N, K;
     int kind;          // GemmOut::Kind
     void* out;         // fp32 [split][M][N] row-major, or bf16 [M][N/2] in operand order
-    int kb_per_split;  // tiled: BK-slices per block split; wstream: 32-wide k-blocks per wavefront slice
+    int kb_per_split;  // 32-wide k-blocks per wavefront slice (wstream) or per block (tiled)
 };
 
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
@@ -165,53 +172,103 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 }
 
 // ------------------------------------------------------------------------------------------
-// Tiled kernel.  grid (N/128, ceil(M/128), splits), 256 threads = 2x2 wavefronts of 64x64.
+// Tiled kernel.  One block per (row tile, column tile, K split) unit, WM x WN wavefronts.
+//
+// LDS holds NS stages; a stage is one 32-wide k-block of the tile: BM/16 activation blocks, then
+// BN/16 weight blocks, each the KiB that a 16x16x32 operand occupies in memory (lane l's 16 bytes
+// at l*16).  A 32x32x16 operand (rows r = l%32, k-half h = l/32 of k-sixteenth `sub`) is two such
+// blocks side by side: lane l reads block r/16 at ((2 sub + h) * 16 + r%16) * 16.
+//
+// The LDS reads are inline assembly because the compiler, which cannot tell an LDS read from the
+// LDS writes of global_load_lds in flight, would drain the load queue before each of them.  It
+// therefore does not know that the read registers are written asynchronously: every wait below
+// names the registers it makes valid, so that their consumers cannot move above it, and no read
+// is left in flight where registers could be copied (the loop has a single straight-line body
+// whose in-flight reads sit in loop-carried registers).
 // ------------------------------------------------------------------------------------------
-constexpr int BK = 64;
-constexpr int LDS_STRIDE = BK + 8;  // +16 bytes per row: conflict-free 16-byte reads across 16 rows
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
 
-template <int BM, int BN, int WM, int WN>
-__global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmParams p) {
-    constexpr int WTM = BM / WM, WTN = BN / WN;  // wave tile
-    constexpr int TM = WTM / 32, TN = WTN / 32;  // 32x32 MFMA tiles per wave
-    static_assert(WM * WN == 4 && TM >= 1 && TN >= 1 && TN % 2 == 0, "4 waves, even column tiles");
-    constexpr int A_CHUNKS = BM * (BK / 8) / 256;  // 16-byte chunks per thread
-    constexpr int B_CHUNKS = BN * (BK / 8) / 256;
+#define PS_GLOBAL_TO_LDS(gp, lp)                                                                                     \
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gp),                            \
+                                     (__attribute__((address_space(3))) void*)(lp), 16, 0, 0)
 
-    __shared__ __attribute__((aligned(16))) bf16_t sA[BM * LDS_STRIDE];
-    __shared__ __attribute__((aligned(16))) bf16_t sB[BN * LDS_STRIDE];
+__device__ __forceinline__ u32x4_t lds_read16(uint32_t addr, int off) {
+    u32x4_t v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(off) : "memory");
+    return v;
+}
+// wait until at most CNT LDS operations are outstanding; the named registers are tied to the wait
+template <int CNT>
+__device__ __forceinline__ void lgkm_tie(u32x4_t& a) {
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a) : "n"(CNT));
+}
+template <int CNT>
+__device__ __forceinline__ void lgkm_tie(u32x4_t& a, u32x4_t& b, u32x4_t& c) {
+    asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(a), "+v"(b), "+v"(c) : "n"(CNT));
+}
+template <int CNT>
+__device__ __forceinline__ void lgkm_tie(u32x4_t& a, u32x4_t& b, u32x4_t& c, u32x4_t& d, u32x4_t& e) {
+    asm volatile("s_waitcnt lgkmcnt(%5)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d), "+v"(e) : "n"(CNT));
+}
+template <int CNT>
+__device__ __forceinline__ void vm_wait() {
+    // s_waitcnt immediate: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] at [15:14]; others left open
+    __builtin_amdgcn_s_waitcnt((CNT & 15) | ((CNT >> 4) << 14) | 0x0F70);
+}
 
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+struct TiledParams {
+    GemmParams g;
+    int tiles_m, tiles_n, splits, units_per_xcd;
+};
+
+template <int BM, int BN, int WM, int WN, int NS, int KIND>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_dma_kernel(TiledParams tp) {
+    const GemmParams& p = tp.g;
+    constexpr int NW = WM * WN;
+    constexpr int WTM = BM / WM, WTN = BN / WN;  // wavefront tile
+    constexpr int TM = WTM / 32, TN = WTN / 32;  // 32x32 MFMA tiles per wavefront
+    constexpr int NBLK = (BM + BN) / 16;         // KiB blocks per stage
+    constexpr int LPW = NBLK / NW;               // loads per wavefront per stage
+    constexpr int STAGE = NBLK * 1024;           // bytes
+    constexpr int NT = TM * TN, NR = TM + TN;
+    static_assert(NBLK % NW == 0 && NS >= 3 && NS <= 4 && NT >= 2 && (TN == 4 || TN == 2) && TM <= 4, "shape");
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave / WN, wn = wave % WN;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-    const int kb_total = p.K / BK;
-    const int kb_begin = blockIdx.z * p.kb_per_split;
-    const int kb_end = min(kb_total, kb_begin + p.kb_per_split);
-    const int KB32 = p.K >> 5;
-    const int n_tiles = p.N >> 4;
-    const bf16_t* a_src[A_CHUNKS];
-    const bf16_t* b_src[B_CHUNKS];
-    int a_dst[A_CHUNKS], b_dst[B_CHUNKS];
-    const int m_tiles = (p.M + 15) >> 4;
+
+    // Consecutive block ids go to different XCDs (each with its own L2).  XCD x works through the units
+    // [x * units_per_xcd, (x+1) * units_per_xcd) of the order (column tile, split, row tile), row tile
+    // fastest: the blocks resident on one XCD at a time share a few weight tiles.
+    const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
+    const int unit = xcd * tp.units_per_xcd + idx;
+    if (idx >= tp.units_per_xcd || unit >= tp.tiles_m * tp.tiles_n * tp.splits) return;
+    const int tm = unit % tp.tiles_m, rest = unit / tp.tiles_m;
+    const int split = rest % tp.splits, tn = rest / tp.splits;
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int KB = p.K >> 5;
+    const int kb0 = split * p.kb_per_split;
+    const int n_kb = min(KB, kb0 + p.kb_per_split) - kb0;
+    if (n_kb <= 0) return;  // (the host plans no empty split)
+
+    // this wavefront's LPW blocks of a stage (block b = wave + NW i): byte offsets from A / Wp, < 4 GiB
+    const int m_tiles = (p.M + 15) >> 4, n_tiles = p.N >> 4;
+    uint32_t off[LPW];
 #pragma unroll
-    for (int i = 0; i < A_CHUNKS; i++) {
-        // A and B slices are fetched in source (operand) order: 64 consecutive chunks = one KiB tile-block
-        const int c = tid + 256 * i, blk = c >> 6, l = c & 63;
-        const int mtl = blk >> 1, kbl = blk & 1;
-        const int mt = min(m0 / 16 + mtl, m_tiles - 1);
-        a_src[i] = p.A + (((size_t)mt * KB32 + kbl) * 64 + l) * 8;
-        a_dst[i] = (mtl * 16 + (l & 15)) * LDS_STRIDE + kbl * 32 + (l >> 4) * 8;
+    for (int i = 0; i < LPW; i++) {
+        const int b = wave + NW * i;
+        // rows / columns past the edge re-read the last tile: its products land in accumulators that are not stored
+        if (b < BM / 16) off[i] = (uint32_t)min(m0 / 16 + b, m_tiles - 1) * (uint32_t)KB * 1024u + lane * 16;
+        else off[i] = (uint32_t)min(n0 / 16 + (b - BM / 16), n_tiles - 1) * (uint32_t)KB * 1024u + lane * 16;
     }
-#pragma unroll
-    for (int i = 0; i < B_CHUNKS; i++) {
-        // chunk c of the B slice in source (tile-major) order: 64 consecutive chunks = one KiB tile-block
-        const int c = tid + 256 * i, blk = c >> 6, l = c & 63;
-        const int ntl = blk >> 1, kbl = blk & 1;  // 16-column tile and 32-wide k-block inside the slice
-        const int nt = min(n0 / 16 + ntl, n_tiles - 1);
-        b_src[i] = p.Wp + (((size_t)nt * KB32 + kbl) * 64 + l) * 8;
-        b_dst[i] = (ntl * 16 + (l & 15)) * LDS_STRIDE + kbl * 32 + (l >> 4) * 8;
-    }
+    const uint8_t* gA = reinterpret_cast<const uint8_t*>(p.A) + (size_t)kb0 * 1024;
+    const uint8_t* gW = reinterpret_cast<const uint8_t*>(p.Wp) + (size_t)kb0 * 1024;
+    auto issue_one = [&](int i, int s, int slot) {
+        const int b = wave + NW * i;
+        const uint8_t* g = (b < BM / 16 ? gA : gW) + (size_t)s * 1024;
+        PS_GLOBAL_TO_LDS(g + off[i], lds + slot * STAGE + b * 1024);
+    };
 
     f32x16_t acc[TM][TN];
 #pragma unroll
@@ -221,75 +278,156 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmParams p) {
 #pragma unroll
             for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
 
-    uint4 ra[A_CHUNKS], rb[B_CHUNKS];
-    if (kb_begin < kb_end) {
-#pragma unroll
-        for (int i = 0; i < A_CHUNKS; i++) ra[i] = ldg16(a_src[i] + (size_t)kb_begin * 2 * 512);
-#pragma unroll
-        for (int i = 0; i < B_CHUNKS; i++) rb[i] = ldg16(b_src[i] + (size_t)kb_begin * 2 * 512);
+    const int r = lane & 31, h = lane >> 5;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
+    const uint32_t a_lane = lds0 + (wm * (WTM / 16) + (r >> 4)) * 1024 + (h * 16 + (r & 15)) * 16;
+    const uint32_t b_lane = lds0 + (BM / 16 + wn * (WTN / 16) + (r >> 4)) * 1024 + (h * 16 + (r & 15)) * 16;
+
+    // Operand registers of a half-stage (one k-sixteenth): v[0..TM) = A tiles, v[TM..NR) = B tiles.  They are
+    // read in the order q = 0: A0;  q = 1..TN: B0..B(TN-1);  q = TN+i: A_i (i >= 1), one read behind every
+    // NT/NR-th MFMA of the half-stage before, and waited for row by row.
+    struct Ops { u32x4_t v[NR]; } o0, o1;
+#define PS_SLOT(q) ((q) == 0 ? 0 : (q) <= TN ? TM + (q) - 1 : (q) - TN)
+#define PS_T_OF(q) (((q) + 1) * NT / NR - 1) /* MFMA behind which read q is issued */
+#define PS_READQ(o, base_a, base_b, sub, q)                                                           \
+    {                                                                                                  \
+        if (PS_SLOT(q) < TM) o.v[PS_SLOT(q)] = lds_read16(base_a, PS_SLOT(q) * 2048 + (sub) * 512);    \
+        else o.v[PS_SLOT(q)] = lds_read16(base_b, (PS_SLOT(q) - TM) * 2048 + (sub) * 512);             \
+    }
+    // Before MFMA t = i*TN (i >= 1) operand A_i must have landed.  Outstanding then: the reads of the same
+    // half-stage behind A_i (TM - 1 - i of them) and the reads of the next half-stage issued so far.
+    auto wait_row = [&](u32x4_t& a, int t) {
+        int n_new = 0;
+        for (int q = 0; q < NR; q++) n_new += (PS_T_OF(q) < t);
+        switch ((TM - 1 - t / TN) + n_new) {  // t is a constant after unrolling: one case survives
+            case 0: lgkm_tie<0>(a); break;
+            case 1: lgkm_tie<1>(a); break;
+            case 2: lgkm_tie<2>(a); break;
+            case 3: lgkm_tie<3>(a); break;
+            case 4: lgkm_tie<4>(a); break;
+            case 5: lgkm_tie<5>(a); break;
+            case 6: lgkm_tie<6>(a); break;
+            case 7: lgkm_tie<7>(a); break;
+            default: lgkm_tie<0>(a); break;
+        }
+    };
+    // One half-stage: NT MFMAs on `o`, the reads of the next half-stage into `on`, and with WITH_LOADS the
+    // LPW loads of stage s_next.  The scheduling barriers keep the written order.
+#define PS_STEP(o, on, base_a, base_b, sub, WITH_LOADS, s_next, slot_next)                                             \
+    {                                                                                                                  \
+        _Pragma("unroll") for (int t = 0; t < NT; t++) {                                                               \
+            if (t == 0) {                                                                                              \
+                if constexpr (TN == 4) lgkm_tie<NR - 1 - TN>(o.v[0], o.v[TM], o.v[TM + 1], o.v[TM + 2], o.v[TM + 3]);  \
+                else lgkm_tie<NR - 1 - TN>(o.v[0], o.v[TM], o.v[TM + 1]);                                              \
+            } else if (t % TN == 0) {                                                                                  \
+                wait_row(o.v[t / TN], t);                                                                              \
+            }                                                                                                          \
+            acc[t / TN][t % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, o.v[t / TN]),    \
+                                                                          __builtin_bit_cast(bf16x8_t, o.v[TM + t % TN]), \
+                                                                          acc[t / TN][t % TN], 0, 0, 0);               \
+            _Pragma("unroll") for (int q_ = 0; q_ < NR; q_++)                                                          \
+                if (PS_T_OF(q_) == t) PS_READQ(on, base_a, base_b, sub, q_)                                            \
+            if (WITH_LOADS) {                                                                                          \
+                _Pragma("unroll") for (int i_ = 0; i_ < LPW; i_++)                                                     \
+                    if (i_ * NT / LPW == t) issue_one(i_, s_next, slot_next);                                          \
+            }                                                                                                          \
+            __builtin_amdgcn_sched_barrier(0);                                                                         \
+        }                                                                                                              \
     }
 
-    const int a_rd = (wm * WTM + (lane & 31)) * LDS_STRIDE + (lane >> 5) * 8;
-    const int b_rd = (wn * WTN + (lane & 31)) * LDS_STRIDE + (lane >> 5) * 8;
+    // NS slots, NS-1 stages in flight.  Loads past the last stage fetch the last stage again, into a slot
+    // that nobody reads any more: the loop body is the same every time and the wait counts are constants.
+#pragma unroll
+    for (int s = 0; s < NS - 1; s++)
+#pragma unroll
+        for (int i = 0; i < LPW; i++) issue_one(i, min(s, n_kb - 1), s);
+    vm_wait<(NS - 2) * LPW>();
+    __builtin_amdgcn_s_barrier();
+    uint32_t a_cur = a_lane, b_cur = b_lane;
+#pragma unroll
+    for (int q_ = 0; q_ < NR; q_++) PS_READQ(o0, a_cur, b_cur, 0, q_);
+    int slot = 0;
+    for (int s = 0; s < n_kb; s++) {
+        __builtin_amdgcn_sched_barrier(0);
+        PS_STEP(o0, o1, a_cur, b_cur, 1, false, 0, 0);
+        // Past this barrier stage s+1 has landed for every wavefront, and every wavefront has consumed
+        // stage s-1, whose slot the loads of stage s+NS-1 overwrite.  Reads of stage s may still be in
+        // flight: its slot is not touched before the next barrier.
+        vm_wait<(NS - 3) * LPW>();
+        __builtin_amdgcn_s_barrier();
+        const int next = slot + 1 == NS ? 0 : slot + 1;
+        const int prev = slot == 0 ? NS - 1 : slot - 1;
+        a_cur = a_lane + next * STAGE;
+        b_cur = b_lane + next * STAGE;
+        __builtin_amdgcn_sched_barrier(0);
+        PS_STEP(o1, o0, a_cur, b_cur, 0, true, min(s + NS - 1, n_kb - 1), prev);
+        slot = next;
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the reads issued for the stage past the end
+    vm_wait<0>();
+#undef PS_SLOT
+#undef PS_T_OF
+#undef PS_READQ
+#undef PS_STEP
 
-    for (int kb = kb_begin; kb < kb_end; kb++) {
-        __syncthreads();  // previous slice fully consumed
+    // lane holds column n = lane%32, rows 8*(e/4) + 4*(lane/32) + e%4 of each 32x32 tile.  The scheduling
+    // barriers keep the tiles' stores apart: hoisting all accumulator reads to the top would need a
+    // register for each of them, and the allocator would pay for that inside the main loop.
+    const int col = lane & 31, rbase = (lane >> 5) * 4;
+    if constexpr (KIND == GemmOut::SWIGLU_BF16) {
+        // silu(gate) * up through LDS, one 32-row band of the wavefront tile at a time: the accumulators go
+        // to a private [32][WTN] fp32 patch as they are, and come back as the 8 gate and 8 up values of one
+        // row that make a 16-byte piece of the operand-order output, so that a wavefront stores whole KiB
+        // blocks.  Rows past M are stored too: the buffer holds whole row tiles (gemm_out_bytes).
+        constexpr int RS = WTN + 4;  // patch row stride in floats: the 16 rows of a read fall into different banks
+        static_assert(32 * RS * 4 * NW <= NS * STAGE, "epilogue patch fits the stage ring");
+        __syncthreads();  // every wavefront is done with the stages
+        float* patch = reinterpret_cast<float*>(lds) + wave * 32 * RS;
+        const int F = p.N >> 1;
+        bf16_t* out = static_cast<bf16_t*>(p.out);
+        const int g8 = lane >> 4, r16 = lane & 15;
 #pragma unroll
-        for (int i = 0; i < A_CHUNKS; i++) *reinterpret_cast<uint4*>(&sA[a_dst[i]]) = ra[i];
-#pragma unroll
-        for (int i = 0; i < B_CHUNKS; i++) *reinterpret_cast<uint4*>(&sB[b_dst[i]]) = rb[i];
-        __syncthreads();
-        if (kb + 1 < kb_end) {
-#pragma unroll
-            for (int i = 0; i < A_CHUNKS; i++) ra[i] = ldg16(a_src[i] + (size_t)(kb + 1) * 2 * 512);
-#pragma unroll
-            for (int i = 0; i < B_CHUNKS; i++) rb[i] = ldg16(b_src[i] + (size_t)(kb + 1) * 2 * 512);
-        }
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ks++) {
-            bf16x8_t af[TM], bfr[TN];
-#pragma unroll
-            for (int i = 0; i < TM; i++)
-                af[i] = as_bf16x8(*reinterpret_cast<const uint4*>(&sA[a_rd + i * 32 * LDS_STRIDE + ks * 16]));
+        for (int i = 0; i < TM; i++) {
 #pragma unroll
             for (int j = 0; j < TN; j++)
-                bfr[j] = as_bf16x8(*reinterpret_cast<const uint4*>(&sB[b_rd + j * 32 * LDS_STRIDE + ks * 16]));
 #pragma unroll
-            for (int i = 0; i < TM; i++)
+                for (int e = 0; e < 16; e++) patch[((e >> 2) * 8 + rbase + (e & 3)) * RS + j * 32 + col] = acc[i][j][e];
+            const int mb = m0 + wm * WTM + i * 32;
 #pragma unroll
-                for (int j = 0; j < TN; j++)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+            for (int band = 0; band < 2; band++)
+#pragma unroll
+                for (int j = 0; j < TN; j += 2) {
+                    const int nb = n0 + wn * WTN + j * 32;  // multiple of 64: gate tile, then up tile of the same 32 features
+                    const float* src = patch + (band * 16 + r16) * RS + j * 32 + g8 * 8;
+                    const float4 ga = *reinterpret_cast<const float4*>(src), gb = *reinterpret_cast<const float4*>(src + 4);
+                    const float4 ua = *reinterpret_cast<const float4*>(src + 32), ub = *reinterpret_cast<const float4*>(src + 36);
+                    uint4 o;
+                    o.x = pack_bf16(silu_f(ga.x) * ua.x, silu_f(ga.y) * ua.y);
+                    o.y = pack_bf16(silu_f(ga.z) * ua.z, silu_f(ga.w) * ua.w);
+                    o.z = pack_bf16(silu_f(gb.x) * ub.x, silu_f(gb.y) * ub.y);
+                    o.w = pack_bf16(silu_f(gb.z) * ub.z, silu_f(gb.w) * ub.w);
+                    // KiB block (row band, 32-feature block): lane = 16 g + row holds features 8 g .. 8 g + 7 of its row
+                    if (nb < p.N)
+                        *reinterpret_cast<uint4*>(out + ((size_t)((mb >> 4) + band) * (F >> 5) + (nb >> 6)) * 512 + lane * 8) = o;
+                }
+            __builtin_amdgcn_sched_barrier(0);
         }
-    }
-
-    // lane holds column n = lane%32, rows 8*(e/4) + 4*(lane/32) + e%4 of each 32x32 tile
-    const int col = lane & 31, rbase = (lane >> 5) * 4;
-    if (p.kind == GemmOut::SWIGLU_BF16) {
-        bf16_t* out = static_cast<bf16_t*>(p.out);
-        const int F = p.N >> 1;
+    } else {
+        const bool interior = m0 + BM <= p.M && n0 + BN <= p.N;
+        float* out = static_cast<float*>(p.out) + (size_t)split * p.M * p.N;
 #pragma unroll
         for (int i = 0; i < TM; i++)
 #pragma unroll
-            for (int j = 0; j < TN; j += 2)
+            for (int j = 0; j < TN; j++) {
 #pragma unroll
                 for (int e = 0; e < 16; e++) {
                     const int m = m0 + wm * WTM + i * 32 + (e >> 2) * 8 + rbase + (e & 3);
-                    const int nb = n0 + wn * WTN + j * 32;  // multiple of 64: gate tile, then up tile
-                    if (m < p.M && nb < p.N) out[act_offset(m, (nb >> 1) + col, F)] = f32_to_bf16(silu_f(acc[i][j][e]) * acc[i][j + 1][e]);
+                    const int n = n0 + wn * WTN + j * 32 + col;
+                    if (interior || (m < p.M && n < p.N)) out[(size_t)m * p.N + n] = acc[i][j][e];
                 }
-        return;
-    }
-    float* out = static_cast<float*>(p.out) + (size_t)blockIdx.z * p.M * p.N;
-#pragma unroll
-    for (int i = 0; i < TM; i++)
-#pragma unroll
-        for (int j = 0; j < TN; j++)
-#pragma unroll
-            for (int e = 0; e < 16; e++) {
-                const int m = m0 + wm * WTM + i * 32 + (e >> 2) * 8 + rbase + (e & 3);
-                const int n = n0 + wn * WTN + j * 32 + col;
-                if (m < p.M && n < p.N) out[(size_t)m * p.N + n] = acc[i][j][e];
+                __builtin_amdgcn_sched_barrier(0);
             }
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -297,13 +435,30 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmParams p) {
 // ------------------------------------------------------------------------------------------
 struct GemmPlan {
     bool wstream;
-    int splits;        // partial buffers written (grid.y / grid.z)
-    int kb_per_split;
+    bool big_tile;     // tiled: 256x256 blocks (else 128x128)
+    int splits;        // partial buffers written
+    int kb_per_split;  // wstream: 32-wide k-blocks per wavefront slice; tiled: per block
 };
 
-static GemmPlan plan_gemm(int M, int N, int K, int kind, int split_opt) {
+// Tiled-kernel cost model, fitted to measured sweeps over the layer's GEMM shapes (M 144 .. 2304):
+// a 256x256 block runs alone on a CU and takes ~1.0 us per 32-wide k-stage; two 128x128 blocks share a
+// CU at ~0.62 us per stage each.  A unit costs its stages plus ~10 stages of prologue and epilogue,
+// units run in rounds of one per slot, and every split beyond the first adds partial-sum traffic.
+static double tiled_cost(int M, int N, int K, bool big, int splits, int* kb_per_split, int* eff_splits) {
+    const int B = big ? 256 : 128, slots = big ? 256 : 512;
+    const double t_stage = big ? 1.0 : 0.62;
+    const int KB = K / 32, kps = (KB + splits - 1) / splits, s_eff = (KB + kps - 1) / kps;
+    const long units = (long)((M + B - 1) / B) * ((N + B - 1) / B) * s_eff;
+    const long rounds = (units + slots - 1) / slots;
+    *kb_per_split = kps;
+    *eff_splits = s_eff;
+    return rounds * (kps + 10) * t_stage + (s_eff > 1 ? 2.0 * (s_eff - 1) * (double)M * N * 4 / 5e6 : 0.0);
+}
+
+static GemmPlan plan_gemm(int M, int N, int K, int kind, int split_opt, int tile_opt) {
     GemmPlan g;
     g.wstream = M <= 64;
+    g.big_tile = false;
     int s = 1;
     if (g.wstream) {
         const int groups = N / 64, KB = K / 32;
@@ -316,28 +471,63 @@ static GemmPlan plan_gemm(int M, int N, int K, int kind, int split_opt) {
         g.kb_per_split = (KB + 4 * s - 1) / (4 * s);
         g.splits = s;
     } else {
-        const int tiles = ((M + 127) / 128) * ((N + 127) / 128), kb = K / BK;
-        if (kind != GemmOut::SWIGLU_BF16) {
-            s = split_opt > 0 ? split_opt : (tiles < 256 ? (256 + tiles - 1) / tiles : 1);
-            s = std::max(1, std::min(std::min(s, 8), kb));
-        }
-        g.kb_per_split = (kb + s - 1) / s;
-        g.splits = (kb + g.kb_per_split - 1) / g.kb_per_split;
+        const int s_lo = kind == GemmOut::SWIGLU_BF16 ? 1 : (split_opt > 0 ? std::min(split_opt, 8) : 1);
+        const int s_hi = kind == GemmOut::SWIGLU_BF16 ? 1 : (split_opt > 0 ? s_lo : 8);
+        double best = 0;
+        bool first = true;
+        for (int big = (tile_opt == 256 ? 1 : 0); big < (tile_opt == 128 ? 1 : 2); big++)
+            for (int sp = s_lo; sp <= s_hi; sp++) {
+                int kps, eff;
+                const double c = tiled_cost(M, N, K, big != 0, sp, &kps, &eff);
+                if (first || c < best) {
+                    first = false; best = c;
+                    g.big_tile = big != 0; g.splits = eff; g.kb_per_split = kps;
+                }
+            }
     }
     return g;
 }
 
-size_t gemm_out_bytes(int M, int N, int K, int kind, int split_opt) {
-    if (kind == GemmOut::SWIGLU_BF16) return 0;  // dense output: the caller sizes it
-    return (size_t)plan_gemm(M, N, K, kind, split_opt).splits * M * N * sizeof(float);
+size_t gemm_out_bytes(int M, int N, int K, int kind, int split_opt, int tile_opt) {
+    if (kind == GemmOut::SWIGLU_BF16) {
+        // dense [rows][N/2] in operand order.  The tiled kernel stores whole row tiles without a row check
+        // (rows past M are never read back), so the buffer holds M rounded up to its largest tile.
+        const size_t rows = M <= 64 ? (size_t)((M + 15) / 16 * 16) : (size_t)((M + 255) / 256 * 256);
+        return rows * (N / 2) * sizeof(bf16_t);
+    }
+    return (size_t)plan_gemm(M, N, K, kind, split_opt, tile_opt).splits * M * N * sizeof(float);
+}
+
+template <int BM, int BN, int WM, int WN, int NS, int KIND>
+static hipError_t launch_tiled(const GemmParams& p, const GemmPlan& g, hipStream_t st) {
+    constexpr int lds_bytes = (BM + BN) / 16 * 1024 * NS;
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [] {   // more dynamic LDS than the default limit: raise it once per kernel
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BM, BN, WM, WN, NS, KIND>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    });
+    if (attr_err != hipSuccess) return attr_err;
+    TiledParams tp;
+    tp.g = p;
+    tp.tiles_m = (p.M + BM - 1) / BM;
+    tp.tiles_n = (p.N + BN - 1) / BN;
+    tp.splits = g.splits;
+    const long units = (long)tp.tiles_m * tp.tiles_n * tp.splits;
+    tp.units_per_xcd = (int)((units + 7) / 8);
+    hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WM, WN, NS, KIND>), dim3(tp.units_per_xcd * 8), dim3(64 * WM * WN), lds_bytes, st, tp);
+    return hipGetLastError();
 }
 
 hipError_t launch_gemm(const GemmArgs& a, int* n_splits, hipStream_t st) {
     if (n_splits) *n_splits = 1;
     if (a.M <= 0) return hipSuccess;
     if (a.N % 64 || a.K % 64) return hipErrorInvalidValue;
-    const GemmPlan g = plan_gemm(a.M, a.N, a.K, a.kind, a.split_k);
-    if (gemm_out_bytes(a.M, a.N, a.K, a.kind, a.split_k) > a.out_bytes) return hipErrorInvalidValue;
+    // the tiled kernel addresses A and Wp with 32-bit byte offsets
+    if (a.M > 64 && ((size_t)a.N * a.K * 2 >= (1ull << 32) || (size_t)((a.M + 15) / 16 * 16) * a.K * 2 >= (1ull << 32)))
+        return hipErrorInvalidValue;
+    const GemmPlan g = plan_gemm(a.M, a.N, a.K, a.kind, a.split_k, a.tile);
+    if (gemm_out_bytes(a.M, a.N, a.K, a.kind, a.split_k, a.tile) > a.out_bytes) return hipErrorInvalidValue;
     GemmParams p;
     p.A = a.A; p.Wp = a.Wp; p.M = a.M; p.N = a.N; p.K = a.K; p.kind = a.kind; p.out = a.out;
     p.kb_per_split = g.kb_per_split;
@@ -350,11 +540,13 @@ hipError_t launch_gemm(const GemmArgs& a, int* n_splits, hipStream_t st) {
             case 3: hipLaunchKernelGGL((gemm_wstream_kernel<3>), grid, dim3(256), 0, st, p); break;
             default: hipLaunchKernelGGL((gemm_wstream_kernel<4>), grid, dim3(256), 0, st, p); break;
         }
-    } else {
-        const dim3 grid((a.N + 127) / 128, (a.M + 127) / 128, g.splits);
-        hipLaunchKernelGGL((gemm_tiled_kernel<128, 128, 2, 2>), grid, dim3(256), 0, st, p);
+        return hipGetLastError();
     }
-    return hipGetLastError();
+    if (a.kind == GemmOut::SWIGLU_BF16)
+        return g.big_tile ? launch_tiled<256, 256, 2, 2, 4, GemmOut::SWIGLU_BF16>(p, g, st)
+                          : launch_tiled<128, 128, 2, 2, 4, GemmOut::SWIGLU_BF16>(p, g, st);
+    return g.big_tile ? launch_tiled<256, 256, 2, 2, 4, GemmOut::PARTIAL_F32>(p, g, st)
+                      : launch_tiled<128, 128, 2, 2, 4, GemmOut::PARTIAL_F32>(p, g, st);
 }
 
 // ------------------------------------------------------------------------------------------

@@ -118,12 +118,13 @@ struct GemmArgs {
     int M, N, K;
     int kind;          // GemmOut::Kind
     void* out;         // PARTIAL_F32: fp32 [splits][M][N] row-major; SWIGLU_BF16: bf16 [M][N/2] in operand order
-    size_t out_bytes;  // PARTIAL_F32: capacity of out
+    size_t out_bytes;  // capacity of out; at least gemm_out_bytes(...)
     int split_k;       // 0 = choose
+    int tile;          // M > 64: 0 = choose, 128 or 256 = block tile edge
 };
 // *n_splits receives the number of partial buffers written (1 for SWIGLU_BF16)
 hipError_t launch_gemm(const GemmArgs& a, int* n_splits, hipStream_t st);
-size_t gemm_out_bytes(int M, int N, int K, int kind, int split_k_opt);
+size_t gemm_out_bytes(int M, int N, int K, int kind, int split_k_opt, int tile_opt);
 
 struct AttnArgs {
     const bf16_t* q;   // rotated queries [T][n_q * d]: row stride ldq elements

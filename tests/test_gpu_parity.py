@@ -250,3 +250,18 @@ def test_wide_hidden_70b_like_shape_small_ffn():
             c.close()
     finally:
         del W.MODELS["_w"]
+
+
+@pytest.mark.parametrize("tile,split", [(128, 0), (128, 1), (128, 3), (256, 0), (256, 1), (256, 2), (256, 8)])
+def test_tiled_gemm_tile_sizes_and_k_splits(tile, split):
+    # more than 64 tokens take the tiled GEMM: both block tiles, automatic and forced K splits, on token
+    # counts that leave ragged row tiles (65: one row past a 64-row wavefront tile; 300: 256 + 44;
+    # 530: two full 256-row tiles + 18) and on widths that leave ragged column tiles (704-wide FFN:
+    # 1408 = 5.5 x 256 gate/up columns; 256-wide hidden = one column tile)
+    for chunk, decodes in ((65, []), (280, [7] * 20), (500, [40] * 30)):
+        b = W.custom_batch("tiny", 17, chunk, 32, decodes, name="tiles")
+        c = Case(b, options={"gemm_tile": tile, "gemm_split_k": split})
+        errs = c.run(tight=TOL)   # hundreds of rows under the max: the per-row bar, as at full size
+        _assert_errs(errs, f"tile={tile} split={split} T={b.n_tokens}")
+        c.check_pool()
+        c.close()
