@@ -35,6 +35,8 @@ def parse():
     ap.add_argument("--kv-slots", type=int, default=8, help="cfg4: physical KV layer slots (layer l uses slot l mod this)")
     ap.add_argument("--check-layers", default="", help="cfg4: comma-separated layers to check against the oracle, teacher-forced")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
+                    help="library tuning knob passed to ps_set_option (repeatable); the defaults are what is reported")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--null-stream", action="store_true", help="run on the default stream instead of a dedicated one")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -111,6 +113,8 @@ def run_grid(a):
             worst_tokens = max(worst_tokens, chunk + n_dec)
     n_pool = worst_pages + worst_pages // 8 + 64
     eng = Engine(model, n_pool, max_position=8192 + 4096 + 2048 + 16)
+    for kv in a.option:
+        eng.ctx.set_option(kv.split("=")[0], int(kv.split("=")[1]))
     eng.load_layer(0, W.layer_weights(model, a.seed, 0))
     # fill every page with N(0,1) keys and values (timing must not run on an all-zero cache)
     rng = np.random.Generator(np.random.PCG64([a.seed, 2718281]))
@@ -162,6 +166,8 @@ def run_cfg4(a):
     batch = W.config_batch(4, a.seed)
     T, total_kv = batch.n_tokens, batch.total_kv
     eng = Engine(model, batch.n_pool_pages, L, slots, max_position=max(s.kv_len for s in batch.seqs) + 16)
+    for kv in a.option:
+        eng.ctx.set_option(kv.split("=")[0], int(kv.split("=")[1]))
     gen = torch.Generator(device="cuda:0")
     gen.manual_seed(1000 + a.seed)
     shapes = {"w_qkv": (H, (nq + 2 * nkv) * d), "w_o": (nq * d, H), "w_gate": (H, F), "w_up": (H, F), "w_down": (F, H)}
@@ -294,6 +300,8 @@ def main():
     model = W.MODELS[batch.model]
     weights = W.layer_weights(batch.model, a.seed, 0)
     eng = Engine(batch.model, batch.n_pool_pages, max_position=max(s.kv_len for s in batch.seqs) + 16)
+    for kv in a.option:
+        eng.ctx.set_option(kv.split("=")[0], int(kv.split("=")[1]))
     eng.load_layer(0, weights)
     eng.load_prefixes(batch)
     x = bits_to_dev(batch.activations(), eng.device)

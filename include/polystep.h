@@ -131,6 +131,8 @@ const char* ps_last_error(const ps_ctx* ctx);
 /* Tuning knobs, mainly for tests: "attn_workers" (number of wavefront-workers the attention
  * KV streams are cut across, 0 = one per resident wavefront; different values cut the streams
  * in different places and must give the same results within rounding),
+ * "attn_prefill_weight" (cost the attention planner charges for a pair of pages of a prefill
+ * query block, where a decode token's pair costs 2; it only moves the cuts),
  * "gemm_split_k" (0 = automatic), "gemm_tile" (block tile edge of the GEMM kernel for more than
  * 64 tokens: 0 = automatic, 128 or 256), "out_f32" (1: ps_step writes x_out as fp32 [T][hidden],
  * the precision the residual stream is kept in, instead of rounding it to bf16).

@@ -70,6 +70,7 @@ struct ps_ctx {
 
     // options / debug
     int opt_attn_workers = 0;
+    int opt_attn_prefill_weight = 3;
     int worker_slots = 2048;
     int opt_gemm_split_k = 0;
     int opt_gemm_tile = 0;
@@ -131,6 +132,7 @@ static PlanConfig plan_config(const ps_ctx* c) {
     pc.max_position = c->desc.max_position;
     pc.n_pool_pages = c->n_pool_pages;
     pc.n_workers = c->opt_attn_workers;
+    pc.prefill_weight = c->opt_attn_prefill_weight;
     pc.worker_slots = c->worker_slots;
     pc.prefill_tokens = attn_prefill_tokens_per_item(pc.group);
     return pc;
@@ -229,6 +231,11 @@ extern "C" const char* ps_last_error(const ps_ctx* c) { return c ? c->err.c_str(
 
 extern "C" ps_status ps_set_option(ps_ctx* c, const char* name, int64_t value) {
     if (!c || !name) return fail(c, PS_EINVAL, "ps_set_option: null argument");
+    if (!strcmp(name, "attn_prefill_weight")) {
+        if (value < 1 || value > 64) return fail(c, PS_EINVAL, "attn_prefill_weight must be in [1, 64]");
+        c->opt_attn_prefill_weight = (int)value;
+        return PS_OK;
+    }
     if (!strcmp(name, "attn_workers")) {
         if (value < 0 || value > (1 << 20)) return fail(c, PS_EINVAL, "attn_workers must be in [0, 2^20]");
         c->opt_attn_workers = (int)value;

@@ -115,7 +115,7 @@ void build_attention_plan(const PlanConfig& cfg, StepPlan& plan) {
     plan.n_partial_items = 0;
     const int TQ = 16 / cfg.group;                 // tokens per 16-row query tile
     const int multi_nt = cfg.prefill_tokens / TQ;  // tiles a multi-tile item always reserves
-    const int W_SINGLE = 2, W_MULTI = 3;           // relative cost of a page pair: one tile (bandwidth) / several (MFMA)
+    const int W_SINGLE = 2, W_MULTI = cfg.prefill_weight;  // relative cost of a page pair: one tile (bandwidth) / several (MFMA)
 
     struct Segment { int seq, q0, qn, np, w; };
     std::vector<Segment> segs;
@@ -156,12 +156,15 @@ void build_attention_plan(const PlanConfig& cfg, StepPlan& plan) {
             left = INT64_MAX / 4;  // whatever is left belongs to the last worker
         }
     };
-    for (const Segment& sg : segs) {
-        const SeqInfo& sq = plan.seqs[sg.seq];
-        const int n_pairs = ceil_div(sg.np, 2);
-        const int nt_alloc = sg.qn <= TQ ? 1 : multi_nt;
-        const int n_tiles = ceil_div(sg.qn, TQ);
-        for (int h = 0; h < cfg.n_kv_heads; h++) {
+    // KV-head-major order: every head carries the same total weight, so with n_kv_heads a multiple of
+    // the number of L2 domains each domain's contiguous share of the workers (see attn_kernel) streams
+    // whole heads, and the query blocks of a prefill chunk that re-read one head's keys share an L2.
+    for (int h = 0; h < cfg.n_kv_heads; h++) {
+        for (const Segment& sg : segs) {
+            const SeqInfo& sq = plan.seqs[sg.seq];
+            const int n_pairs = ceil_div(sg.np, 2);
+            const int nt_alloc = sg.qn <= TQ ? 1 : multi_nt;
+            const int n_tiles = ceil_div(sg.qn, TQ);
             const size_t first = plan.items.size();
             int pair = 0;
             while (pair < n_pairs) {

@@ -32,6 +32,7 @@ struct PlanConfig {
     int n_workers = 0;         // attention workers; 0 = one per resident wavefront slot
     int worker_slots = 2048;   // wavefronts of the attention kernel resident at once
     int prefill_tokens = 8;    // query tokens per multi-tile attention item
+    int prefill_weight = 3;    // cost of a page pair of a multi-tile item; a single-tile (decode) pair costs 2
 };
 
 // Validates the batch (see ps_seq in polystep.h).  On failure returns PS_EINVAL / PS_ERANGE

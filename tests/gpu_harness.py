@@ -24,9 +24,13 @@ def rel_err(got, want):
 
 
 # Against the oracle variant that rounds activations to bf16 in the same places as the kernels,
-# what is left is fp32 summation order, exp2-vs-exp and the bf16 rounding of the softmax weights
-# (up to 2^-8 relative per weight, coherent across a row's head_dim outputs).
-TIGHT = 1e-2
+# what is left is fp32 summation order, exp2-vs-exp, the bf16 rounding of the softmax weights
+# (up to 2^-8 relative per weight, coherent across a row's head_dim outputs) and rounding flips:
+# a stored activation that lands on the other side of a bf16 rounding boundary differs by a whole
+# ulp, and a handful of such flips in the input row of a GEMM moves a small output row by about
+# 1e-2 of its RMS.  Which elements flip depends on the summation order, i.e. on the attention split
+# plan and the GEMM split, so intermediates are held to the stated factor per row, not to less.
+TIGHT = TOL
 
 
 def row_score(got, want, tol=TOL, ulps=1.0):
@@ -81,10 +85,7 @@ class Case:
         self.x_bits = batch.activations()
 
     def run(self, tap_layer=0, dtype=np.float32, tight=TIGHT):
-        """tight: per-row tolerance against the bf16-activation variant of the oracle.  The default
-        suits the small cases; at full size (thousands of terms per dot product, millions of
-        elements under the max) rounding flips of the bf16 inputs of a GEMM no longer average out
-        below it, and the callers pass TOL."""
+        """tight: per-row tolerance against the bf16-activation variant of the oracle."""
         b, eng = self.batch, self.eng
         T = b.n_tokens
         taps = eng.alloc_taps(T)
