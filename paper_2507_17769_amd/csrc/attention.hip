@@ -254,7 +254,12 @@ template <int D, int G>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_kernel(AttnArgs a) {
     // one wavefront = one worker: it runs the items the planner assigned to it, in order
     constexpr int TQ = 16 / G;
-    const int i0 = a.worker_begin[blockIdx.x], i1 = a.worker_begin[blockIdx.x + 1];
+    // consecutive block ids go to different XCDs (one L2 each): XCD x runs the contiguous workers
+    // [x * per_xcd, (x+1) * per_xcd), i.e. neighbouring parts of the work list share an L2
+    const int per_xcd = (a.n_workers + 7) >> 3;
+    const int w = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (w >= a.n_workers) return;
+    const int i0 = a.worker_begin[w], i1 = a.worker_begin[w + 1];
     for (int i = i0; i < i1; i++) {
         const AttnItem it = a.items[i];
         if (it.q_ntok <= TQ)
@@ -317,7 +322,7 @@ int attn_prefill_tokens_per_item(int G) { return PREFILL_NT * (16 / G); }
 template <int D, int G>
 static hipError_t launch_dg(const AttnArgs& a, hipStream_t st) {
     if (a.ev_begin) (void)hipEventRecord(a.ev_begin, st);
-    hipLaunchKernelGGL((attn_kernel<D, G>), dim3(a.n_workers), dim3(64), 0, st, a);
+    hipLaunchKernelGGL((attn_kernel<D, G>), dim3(((a.n_workers + 7) >> 3) * 8), dim3(64), 0, st, a);
     hipError_t e = hipGetLastError();
     if (a.ev_end) (void)hipEventRecord(a.ev_end, st);
     if (e != hipSuccess || a.n_groups == 0) return e;
