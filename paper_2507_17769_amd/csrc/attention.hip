@@ -53,6 +53,17 @@ struct TileState {
     float m[NT], lsum[NT];
 };
 
+// Maximum over the four lanes r, r+16, r+32, r+48 that share a query row, in the vector ALU:
+// v_permlane16_swap (x, x) returns {rows 0,0,2,2 | rows 1,1,3,3} of x and v_permlane32_swap the
+// {lower, lower | upper, upper} halves, so each step combines a lane with its partner in both.
+typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float row_quad_max(float v) {
+    const u32x2_t a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = fmaxf(__uint_as_float(a.x), __uint_as_float(a.y));
+    const u32x2_t b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(b.x), __uint_as_float(b.y));
+}
+
 // One pair of pages (32 keys) for all NT query tiles.  kpos0 = position of the pair's first key;
 // b_valid = the second page exists.  PV16 selects how P.V is issued: per page with 16x16x16 MFMAs
 // (bandwidth-bound decode items) or per pair with one 16x16x32 MFMA (compute-bound prefill items).
@@ -69,6 +80,7 @@ __device__ __forceinline__ void compute_pair(TileState<D, NT>& st, const PairReg
             sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(p.ka[s]), qf[nt][s], sa, 0, 0, 0);
             sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(p.kb[s]), qf[nt][s], sb, 0, 0, 0);
         }
+        // scores stay raw; the scale (> 0) goes into the running max and into the exponent's fma
         float sv[8];
         bool ok[8];
         float mx = NEG_BIG;
@@ -76,20 +88,19 @@ __device__ __forceinline__ void compute_pair(TileState<D, NT>& st, const PairReg
         for (int i = 0; i < 4; i++) {
             ok[i] = kpos_a + i <= pq[nt];
             ok[4 + i] = b_valid && (kpos_b + i <= pq[nt]);
-            sv[i] = sa[i] * scale2;
-            sv[4 + i] = sb[i] * scale2;
+            sv[i] = sa[i];
+            sv[4 + i] = sb[i];
         }
 #pragma unroll
         for (int i = 0; i < 8; i++) mx = ok[i] ? fmaxf(mx, sv[i]) : mx;
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(st.m[nt], mx);
+        mx = row_quad_max(mx);
+        const float m_new = fmaxf(st.m[nt], mx * scale2);
         const float alpha = __builtin_amdgcn_exp2f(st.m[nt] - m_new);
         st.m[nt] = m_new;
         float pv[8], ps = 0.f;
 #pragma unroll
         for (int i = 0; i < 8; i++) {
-            pv[i] = ok[i] ? __builtin_amdgcn_exp2f(sv[i] - m_new) : 0.f;
+            pv[i] = ok[i] ? __builtin_amdgcn_exp2f(fmaf(sv[i], scale2, -m_new)) : 0.f;
             ps += pv[i];
         }
         st.lsum[nt] = st.lsum[nt] * alpha + ps;
@@ -116,15 +127,20 @@ __device__ __forceinline__ void compute_pair(TileState<D, NT>& st, const PairReg
             pw.z = pack_bf16(pv[4], pv[5]);
             pw.w = pack_bf16(pv[6], pv[7]);
             const bf16x8_t pf = as_bf16x8(pw);
+            // once the running max has settled alpha is exactly 1 in every lane: skip the D/4 multiplies
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+                for (int dt = 0; dt < DT; dt++) {
+                    st.o[nt][dt][0] *= alpha; st.o[nt][dt][1] *= alpha; st.o[nt][dt][2] *= alpha; st.o[nt][dt][3] *= alpha;
+                }
+            }
 #pragma unroll
             for (int dt = 0; dt < DT; dt++) {
                 const int s = dt >> 1;
                 uint4 vw;
                 if (dt & 1) { vw.x = p.va[s].z; vw.y = p.va[s].w; vw.z = p.vb[s].z; vw.w = p.vb[s].w; }
                 else        { vw.x = p.va[s].x; vw.y = p.va[s].y; vw.z = p.vb[s].x; vw.w = p.vb[s].y; }
-                f32x4_t acc = st.o[nt][dt];
-                acc[0] *= alpha; acc[1] *= alpha; acc[2] *= alpha; acc[3] *= alpha;
-                st.o[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vw), pf, acc, 0, 0, 0);
+                st.o[nt][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vw), pf, st.o[nt][dt], 0, 0, 0);
             }
         }
     }

@@ -186,36 +186,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 // is left in flight where registers could be copied (the loop has a single straight-line body
 // whose in-flight reads sit in loop-carried registers).
 // ------------------------------------------------------------------------------------------
-typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
-
-#define PS_GLOBAL_TO_LDS(gp, lp)                                                                                     \
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gp),                            \
-                                     (__attribute__((address_space(3))) void*)(lp), 16, 0, 0)
-
-__device__ __forceinline__ u32x4_t lds_read16(uint32_t addr, int off) {
-    u32x4_t v;
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(off) : "memory");
-    return v;
-}
-// wait until at most CNT LDS operations are outstanding; the named registers are tied to the wait
-template <int CNT>
-__device__ __forceinline__ void lgkm_tie(u32x4_t& a) {
-    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(a) : "n"(CNT));
-}
-template <int CNT>
-__device__ __forceinline__ void lgkm_tie(u32x4_t& a, u32x4_t& b, u32x4_t& c) {
-    asm volatile("s_waitcnt lgkmcnt(%3)" : "+v"(a), "+v"(b), "+v"(c) : "n"(CNT));
-}
-template <int CNT>
-__device__ __forceinline__ void lgkm_tie(u32x4_t& a, u32x4_t& b, u32x4_t& c, u32x4_t& d, u32x4_t& e) {
-    asm volatile("s_waitcnt lgkmcnt(%5)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d), "+v"(e) : "n"(CNT));
-}
-template <int CNT>
-__device__ __forceinline__ void vm_wait() {
-    // s_waitcnt immediate: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] at [15:14]; others left open
-    __builtin_amdgcn_s_waitcnt((CNT & 15) | ((CNT >> 4) << 14) | 0x0F70);
-}
-
 struct TiledParams {
     GemmParams g;
     int tiles_m, tiles_n, splits, units_per_xcd;

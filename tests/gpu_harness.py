@@ -114,6 +114,7 @@ class Case:
         got = {k: f32(dev_to_bits(taps[k])) for k in ("xn", "q", "attn", "xn2", "act")}
         got["x1"] = taps["x1"].cpu().numpy()
         got["out"] = self.out32
+        self.got = got
         ot["out"], otb["out"] = want, want_b
         # final output against the definition: the stated bar, max |err| <= TOL x RMS over the whole
         # tensor, for the fp32 output; the bf16 output additionally carries its own storage rounding
@@ -175,6 +176,43 @@ class Case:
                 assert over.max() <= 0, f"{name}: appended entries differ by more than one bf16 rounding flip"
                 worst = max(worst, float(np.mean(g != wb)))
         return worst
+
+    def stagewise(self, tol=1e-2):
+        """Every stage of layer 0 on its own: the oracle's step applied to the tensors the kernels
+        actually produced as that stage's input (read back through the taps and ps_kv_read), so
+        that no deviation is carried from one stage into the next.  Needs run() first (taps on layer
+        0, one layer).  Returns name -> row_score at `tol` (<= 1 passes); bf16 tensors get one
+        rounding flip on top."""
+        from oracle import layer as ol
+        sh = orun.shape_from(self.model)
+        b, g, w = self.batch, self.got, orun.widen_weights(self.layers[0], np.float64)
+        seqs = orun.to_seqs(b.seqs)
+        nq, nkv, d = sh.n_q, sh.n_kv, sh.head_dim
+        T = b.n_tokens
+        x = f32(self.x_bits).astype(np.float64)
+        pos = np.concatenate([np.arange(s.kv_len - s.n_new, s.kv_len) for s in seqs])
+        rt = lambda a: obf.round_trip(a.astype(np.float32)).astype(np.float64)
+        out = {}
+        out["xn<-x"] = row_score(g["xn"], rt(ol.rmsnorm(x, w["g_attn"], sh.rms_eps)), tol, 2.0)
+        qkv = g["xn"].astype(np.float64) @ w["w_qkv"]
+        q = rt(ol.rope(qkv[:, :nq * d].reshape(T, nq, d), pos, sh.rope_base))
+        out["q<-xn"] = row_score(g["q"].reshape(T, -1), q.reshape(T, -1), tol, 2.0)
+        # attention over the cache as the device holds it after the step
+        pool = orun.make_pool(self.model, b.n_pool_pages, 1)
+        all_pages = np.arange(b.n_pool_pages, dtype=np.int32)
+        k, v = self.eng.read_kv(0, all_pages, 0, b.n_pool_pages * 16)
+        pool.write_bits(0, [int(p) for p in all_pages], 0, k, v)
+        attn = rt(ol.attention_paged(g["q"].astype(np.float64).reshape(T, nq, d), seqs, pool, 0, nkv))
+        out["attn<-q,cache"] = row_score(g["attn"].reshape(T, -1), attn.reshape(T, -1), tol, 2.0)
+        o = g["attn"].astype(np.float64).reshape(T, nq * d) @ w["w_o"]
+        out["o<-attn"] = row_score(g["x1"].astype(np.float64) - x, o, tol, 0.0)
+        out["xn2<-x1"] = row_score(g["xn2"], rt(ol.rmsnorm(g["x1"].astype(np.float64), w["g_ffn"], sh.rms_eps)), tol, 2.0)
+        xn2 = g["xn2"].astype(np.float64)
+        act = rt(ol.silu(xn2 @ w["w_gate"]) * (xn2 @ w["w_up"]))
+        out["act<-xn2"] = row_score(g["act"], act, tol, 2.0)
+        f = g["act"].astype(np.float64) @ w["w_down"]
+        out["ffn<-act"] = row_score(g["out"].astype(np.float64) - g["x1"].astype(np.float64), f, tol, 0.0)
+        return out
 
     def close(self):
         self.eng.close()
