@@ -4,10 +4,13 @@
 //
 //   C[M][N] = A[M][K] * W[K][N],  A = activations (bf16, K contiguous), fp32 accumulate.
 //
-// Weights are repacked once at layer init into MFMA-tile-major order (see repack_weight_kernel):
-//   Wp[n_tile = n/16][k_block = k/32][g = (k%32)/8][nn = n%16][8]        (1 KiB per tile-block)
+// Weights are repacked once at layer init into MFMA operand blocks (see repack_weight_kernel):
+//   Wp[n/64][k_block = k/32][j = (n%64)/16][g = (k%32)/8][nn = n%16][8]     (1 KiB per [g][nn][8] block)
 // so that one 16-byte load per lane fetches a contiguous KiB that already is the operand of a
-// 16x16x32 MFMA (lane = 16 g + nn holds W^T[n][k0 + 8g .. +7]).
+// 16x16x32 MFMA (lane = 16 g + nn holds W^T[n][k0 + 8g .. +7]), and the four blocks of a 64-column
+// group are adjacent: a wavefront that owns 64 columns reads one sequential stream of 4 KiB per
+// k-block (8 KiB per load batch) instead of four streams of 1 KiB, which is what keeps DRAM rows open
+// when two thousand wavefronts stream at once.
 //
 // Two kernels:
 //  * gemm_wstream_kernel (M <= 64): weight streaming.  A wavefront owns 64 output columns and a
@@ -52,7 +55,7 @@ struct WsFrags {
 template <int MT>
 __device__ __forceinline__ void ws_load(WsFrags<MT>& f, const bf16_t* w_lane, size_t w_tile_stride, const bf16_t* x_lane, int kb) {
 #pragma unroll
-    for (int j = 0; j < 4; j++) f.w[j] = ldg16(w_lane + j * w_tile_stride + (size_t)kb * 512);
+    for (int j = 0; j < 4; j++) f.w[j] = ldg16(w_lane + ((size_t)kb * 4 + j) * 512);
 #pragma unroll
     for (int mt = 0; mt < MT; mt++) f.x[mt] = ldg16(x_lane + mt * w_tile_stride + (size_t)kb * 512);
 }
@@ -76,9 +79,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int slice = blockIdx.y * 4 + wave;
     const int b0 = min(KB, slice * p.kb_per_split), b1 = min(KB, b0 + p.kb_per_split);
 
-    const size_t w_tile_stride = (size_t)KB * 512;  // elements between consecutive 16-column tiles
-    const bf16_t* w_lane = p.Wp + (size_t)ng * 4 * w_tile_stride + (size_t)lane * 8;
-    const bf16_t* x_lane = p.A + (size_t)lane * 8;  // activations are in operand order: same tile stride as the weights
+    const size_t w_tile_stride = (size_t)KB * 512;  // elements between consecutive 16-row tiles of the activations
+    const bf16_t* w_lane = p.Wp + (size_t)ng * 4 * w_tile_stride + (size_t)lane * 8;  // the group's blocks: [kb][j]
+    const bf16_t* x_lane = p.A + (size_t)lane * 8;  // activations are in operand order [m/16][kb]
 
     f32x4_t acc[MT][4];
 #pragma unroll
@@ -230,13 +233,16 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dma_kernel(TiledParams tp) 
         const int b = wave + NW * i;
         // rows / columns past the edge re-read the last tile: its products land in accumulators that are not stored
         if (b < BM / 16) off[i] = (uint32_t)min(m0 / 16 + b, m_tiles - 1) * (uint32_t)KB * 1024u + lane * 16;
-        else off[i] = (uint32_t)min(n0 / 16 + (b - BM / 16), n_tiles - 1) * (uint32_t)KB * 1024u + lane * 16;
+        else {
+            const int nt = min(n0 / 16 + (b - BM / 16), n_tiles - 1);  // weight blocks: [nt/4][kb][nt%4]
+            off[i] = ((uint32_t)(nt >> 2) * (uint32_t)KB * 4u + (uint32_t)(nt & 3)) * 1024u + lane * 16;
+        }
     }
     const uint8_t* gA = reinterpret_cast<const uint8_t*>(p.A) + (size_t)kb0 * 1024;
-    const uint8_t* gW = reinterpret_cast<const uint8_t*>(p.Wp) + (size_t)kb0 * 1024;
+    const uint8_t* gW = reinterpret_cast<const uint8_t*>(p.Wp) + (size_t)kb0 * 4096;
     auto issue_one = [&](int i, int s, int slot) {
         const int b = wave + NW * i;
-        const uint8_t* g = (b < BM / 16 ? gA : gW) + (size_t)s * 1024;
+        const uint8_t* g = b < BM / 16 ? gA + (size_t)s * 1024 : gW + (size_t)s * 4096;
         PS_GLOBAL_TO_LDS(g + off[i], lds + slot * STAGE + b * 1024);
     };
 
@@ -520,7 +526,7 @@ hipError_t launch_gemm(const GemmArgs& a, int* n_splits, hipStream_t st) {
 }
 
 // ------------------------------------------------------------------------------------------
-// One-time weight repack: W [K][N] (math layout) -> tile-major Wp (see the header comment).
+// One-time weight repack: W [K][N] (math layout) -> operand blocks Wp (see the header comment).
 // interleave = 0: row(n) = n.  interleave = 1/2 (gate / up halves of the fused matrix):
 // row(f) = (f/32)*64 + f%32 + (interleave == 2 ? 32 : 0), so that every aligned group of 64 rows
 // holds gate rows f..f+31 followed by up rows f..f+31 and SwiGLU can run in the GEMM epilogue.
@@ -549,7 +555,8 @@ __global__ __launch_bounds__(256) void repack_weight_kernel(const bf16_t* __rest
         uint32_t v[4];
 #pragma unroll
         for (int j = 0; j < 4; j++) v[j] = (uint32_t)tile[kl + 2 * j][nl] | ((uint32_t)tile[kl + 2 * j + 1][nl] << 16);
-        const size_t dst = (((size_t)(row >> 4) * KB + (k0 >> 5) + kbl) * 64 + (l >> 4) * 16 + (row & 15)) * 8;
+        const int rt = row >> 4;  // 16-row tile of the packed matrix: block [rt/4][kb][rt%4]
+        const size_t dst = ((((size_t)(rt >> 2) * KB + (k0 >> 5) + kbl) * 4 + (rt & 3)) * 64 + (l >> 4) * 16 + (row & 15)) * 8;
         *reinterpret_cast<uint4*>(wp + dst) = uint4{v[0], v[1], v[2], v[3]};
     }
 }
