@@ -136,6 +136,10 @@ const char* ps_last_error(const ps_ctx* ctx);
  * "gemm_split_k" (0 = automatic), "gemm_tile" (block tile edge of the GEMM kernel for more than
  * 64 tokens: 0 = automatic, 128 or 256), "out_f32" (1: ps_step writes x_out as fp32 [T][hidden],
  * the precision the residual stream is kept in, instead of rounding it to bf16).
+ * "only_layer" (l >= 0: ps_step runs layer l alone, x_in -> x_out, as if it were the whole model;
+ * -1 = the whole stack.  A benchmark of a single layer loads several copies of it as layers and
+ * rotates through them, so that every step streams its weights from HBM and not from a cache
+ * that a real stack of layers would have flushed).
  * "time_attention" (N >= 1: bracket the attention kernel launch of every Nth step with HIP
  * events, see ps_attention_times; the two event records cost a few microseconds of stream time).  PS_EINVAL for an unknown name or bad value. */
 ps_status ps_set_option(ps_ctx* ctx, const char* name, int64_t value);

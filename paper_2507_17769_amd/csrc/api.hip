@@ -74,6 +74,7 @@ struct ps_ctx {
     int worker_slots = 2048;
     int opt_gemm_split_k = 0;
     int opt_gemm_tile = 0;
+    int opt_only_layer = -1;
     bool opt_out_f32 = false;
     int tap_layer = -1;
     ps_taps taps{};
@@ -239,6 +240,11 @@ extern "C" ps_status ps_set_option(ps_ctx* c, const char* name, int64_t value) {
     if (!strcmp(name, "attn_workers")) {
         if (value < 0 || value > (1 << 20)) return fail(c, PS_EINVAL, "attn_workers must be in [0, 2^20]");
         c->opt_attn_workers = (int)value;
+        return PS_OK;
+    }
+    if (!strcmp(name, "only_layer")) {
+        if (value < -1 || value >= c->desc.n_layers) return fail(c, PS_ERANGE, "only_layer must be -1 or a layer index");
+        c->opt_only_layer = (int)value;
         return PS_OK;
     }
     if (!strcmp(name, "gemm_tile")) {
@@ -637,17 +643,20 @@ extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, cons
     // projection leaves fp32 partial sums; the kernel that consumes them adds them up.
     const void* x_cur = x_in;
     bool x_cur_f32 = false;
-    for (int l = 0; l < d.n_layers; l++) {
+    // only_layer: the step runs that one layer as a whole model (x_in -> x_out)
+    const int l_begin = c->opt_only_layer >= 0 ? c->opt_only_layer : 0;
+    const int l_end = c->opt_only_layer >= 0 ? c->opt_only_layer + 1 : d.n_layers;
+    for (int l = l_begin; l < l_end; l++) {
         const LayerWeights& L = c->layers[l];
         const bool tap = (l == c->tap_layer);
-        const bool last = (l == d.n_layers - 1);
+        const bool last = (l == l_end - 1);
         bf16_t* pool_slot = c->pool + (size_t)(l % c->n_kv_slots) * c->slot_elems;
         int e = 0, n_splits = 1;
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[e], s));
         // 0: RMSNorm of the layer input (layers after the first get it from the previous layer's last kernel)
-        if (l == 0) HIP_TRY(c, launch_rmsnorm(x_cur, x_cur_f32, L.g_attn, c->ws_xn, T, H, d.rms_eps, s));
+        if (l == l_begin) HIP_TRY(c, launch_rmsnorm(x_cur, x_cur_f32, L.g_attn, c->ws_xn, T, H, d.rms_eps, s));
         if (tap && c->taps.xn) HIP_TRY(c, launch_untile(c->ws_xn, static_cast<bf16_t*>(c->taps.xn), T, H, s));
-        if (tap && c->taps.x_in && l > 0) HIP_TRY(c, launch_copy_bytes(x_cur, c->taps.x_in, (size_t)T * H * 4, s));
+        if (tap && c->taps.x_in && l > l_begin) HIP_TRY(c, launch_copy_bytes(x_cur, c->taps.x_in, (size_t)T * H * 4, s));
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
         // 1: QKV projection -> fp32 partials
         GemmArgs g{};

@@ -8,6 +8,7 @@ import torch
 from paper_2507_17769_amd import binding as B
 from paper_2507_17769_amd import workloads as W
 from gpu_harness import TOL, Case, bits_to_dev, dev_to_bits, f32, rel_err
+from paper_2507_17769_amd.runner import Engine
 
 pytestmark = pytest.mark.gpu
 
@@ -275,3 +276,24 @@ def test_tiled_gemm_tile_sizes_and_k_splits(tile, split):
         _assert_errs(errs, f"tile={tile} split={split} T={b.n_tokens}")
         c.check_pool()
         c.close()
+
+
+def test_only_layer_runs_that_layer_as_the_whole_model():
+    # a 3-layer context restricted to layer 1 gives bit for bit what a 1-layer context with layer 1's weights gives
+    b = W.custom_batch("tiny", 23, 40, 20, [3, 60, 129], name="only")
+    ws = [W.layer_weights(W.MODELS["tiny"], 5, l) for l in range(3)]
+    x = bits_to_dev(b.activations(), "cuda:0")
+    outs = []
+    for layers, only in (([ws[0], ws[1], ws[2]], 1), ([ws[1]], -1)):
+        eng = Engine(W.MODELS["tiny"], b.n_pool_pages, len(layers), 1, max_position=256)
+        for l, w in enumerate(layers):
+            eng.load_layer(l, w)
+        eng.load_prefixes(b)
+        eng.ctx.set_option("only_layer", only)
+        out, _ = eng.step(b.seqs, x)
+        eng.ctx.sync()
+        outs.append(dev_to_bits(out))
+        with pytest.raises(B.PolystepError):
+            eng.ctx.set_option("only_layer", len(layers))
+        eng.close()
+    assert np.array_equal(outs[0], outs[1])
