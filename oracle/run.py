@@ -41,3 +41,20 @@ def run_layer_from(model, weights_bits, seqs, x, pool, slot, dtype=np.float32, b
     sh = shape_from(model)
     return layer.layer_forward(np.asarray(x, dtype=dtype), widen_weights(weights_bits, dtype), to_seqs(seqs), pool, slot, sh,
                                None, bf16_activations)
+
+
+def run_model(model, head_bits, layers_bits, seqs, token_ids, pool, dtype=np.float32, bf16_activations=False):
+    """Full step: token ids -> embedding -> layer stack -> final norm -> logits of every sequence's last
+    token -> greedy next token.  head_bits: {"embedding" [vocab][hidden], "g_final" [hidden],
+    "w_out" [hidden][vocab]} as bf16 bit patterns.  Returns (next tokens [n_seqs] int32,
+    logits [n_seqs][vocab], final hidden states [T][hidden])."""
+    from . import head
+    sh = shape_from(model)
+    hw = widen_weights(head_bits, dtype)
+    x = head.embed(token_ids, hw["embedding"])
+    ws = [widen_weights(w, dtype) for w in layers_bits]
+    sq = to_seqs(seqs)
+    hidden = layer.stack_forward(x, ws, sq, pool, sh, None, bf16_activations)
+    stored = (lambda a: bf16.round_trip(a.astype(np.float32)).astype(a.dtype)) if bf16_activations else None
+    lg = head.logits(hidden, sq, hw["g_final"], hw["w_out"], sh.rms_eps, stored)
+    return head.greedy(lg), lg, hidden
