@@ -197,6 +197,37 @@ ps_status ps_kv_read(ps_ctx* ctx, int32_t layer, const ps_seq* seq, int32_t pos0
  * or the pool is missing; on any error nothing has been launched. */
 ps_status ps_step(ps_ctx* ctx, const ps_seq* seqs, int32_t n_seqs, const void* x_in, void* x_out, ps_step_stats* stats);
 
+/* ---- whole model (Sec. 2.1: a request's tokens go in, the next token comes out) ----- */
+
+/* What surrounds the layer stack.  Device pointers, bf16: embedding [vocab][hidden] (row = token
+ * id), g_final [hidden] (gain of the RMS normalisation after the last layer), w_out
+ * [hidden][vocab] (output matrix, input-major like the layer weights, no bias).  vocab: a
+ * positive multiple of 64, at most 2^20, with vocab * hidden * 2 bytes below 4 GiB. */
+typedef struct {
+    const void* embedding;
+    const void* g_final;
+    const void* w_out;
+    int32_t vocab;
+} ps_head_weights;
+
+/* Copy the head's weights into the library (w_out into the GEMM's operand layout).  The caller
+ * may free its buffers once ps_sync() has returned.  May be called again.  Errors: PS_EINVAL,
+ * PS_ERANGE, PS_ENOMEM, PS_ESTATE (host-only context). */
+ps_status ps_init_head(ps_ctx* ctx, const ps_head_weights* w);
+
+/* One full-model step: token_ids (HOST, [T], concatenated like x_in of ps_step) -> embedding rows
+ * -> all layers (as ps_step) -> RMS normalisation of every sequence's LAST new token -> logits =
+ * that row times w_out -> the index of the largest logit, the lowest index among equal ones.
+ * Outputs are device buffers, any may be null: next_tokens int32 [n_seqs]; logits fp32
+ * [n_seqs][vocab]; hidden fp32 [T][hidden] (output of the last layer, before the normalisation).
+ * stats as in ps_step (layer stages only).  ms_parts: HOST float[3] or null; when given, HIP events
+ * time the embedding gather, the layer stack and the head (normalisation + output projection +
+ * greedy pick), and the call returns only after the step has finished.
+ * Errors: as ps_step; PS_ESTATE without ps_init_head or while option "only_layer" is set;
+ * PS_ERANGE for a token id outside [0, vocab). */
+ps_status ps_step_tokens(ps_ctx* ctx, const ps_seq* seqs, int32_t n_seqs, const int32_t* token_ids, int32_t* next_tokens,
+                         float* logits, float* hidden, ps_step_stats* stats, float* ms_parts);
+
 /* Integer side of a step, host only, no launch: cu_seqlens [n_seqs+1] (exclusive scan of
  * n_new), positions [T] (kv_len - n_new + i), slot_mapping [T] (page id * 16 + position
  * % 16): the cache slots the step's KV append writes.  Output arrays are host memory; any

@@ -38,6 +38,10 @@ class ps_layer_weights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("w_qkv", "w_o", "w_gate", "w_up", "w_down", "g_attn", "g_ffn")]
 
 
+class ps_head_weights(C.Structure):
+    _fields_ = [("embedding", C.c_void_p), ("g_final", C.c_void_p), ("w_out", C.c_void_p), ("vocab", C.c_int32)]
+
+
 class ps_seq(C.Structure):
     _fields_ = [("req_id", C.c_int64), ("n_new", C.c_int32), ("kv_len", C.c_int32),
                 ("page_table", C.POINTER(C.c_int32)), ("n_pages", C.c_int32)]
@@ -83,6 +87,8 @@ _SIGS = {
     "ps_kv_write": (C.c_int, [_P, C.c_int32, C.POINTER(ps_seq), C.c_int32, C.c_int32, _P, _P]),
     "ps_kv_read": (C.c_int, [_P, C.c_int32, C.POINTER(ps_seq), C.c_int32, C.c_int32, _P, _P]),
     "ps_step": (C.c_int, [_P, C.POINTER(ps_seq), C.c_int32, _P, _P, C.POINTER(ps_step_stats)]),
+    "ps_init_head": (C.c_int, [_P, C.POINTER(ps_head_weights)]),
+    "ps_step_tokens": (C.c_int, [_P, C.POINTER(ps_seq), C.c_int32, _I32P, _P, _P, _P, C.POINTER(ps_step_stats), C.POINTER(C.c_float)]),
     "ps_step_indices": (C.c_int, [_P, C.POINTER(ps_seq), C.c_int32, _I32P, _I32P, _I32P]),
     "ps_plan_attention": (C.c_int, [_P, C.POINTER(ps_seq), C.c_int32, _I32P, C.c_int32, _I32P]),
     "ps_set_taps": (C.c_int, [_P, C.c_int32, C.POINTER(ps_taps)]),
@@ -185,6 +191,22 @@ class Context:
         self._check(lib.ps_step(self.handle, sa.array, sa.n, _P(x_in_ptr), _P(x_out_ptr),
                                 C.byref(stats) if want_stats else None))
         return stats
+
+    def init_head(self, embedding, g_final, w_out, vocab):
+        w = ps_head_weights(int(embedding), int(g_final), int(w_out), int(vocab))
+        self._check(lib.ps_init_head(self.handle, C.byref(w)))
+
+    def step_tokens(self, seqs, token_ids, next_tokens_ptr=None, logits_ptr=None, hidden_ptr=None, want_stats=False, want_parts=False):
+        """token_ids: host int32 array [T].  Returns (stats or None, [ms embedding, ms layers, ms head] or None)."""
+        sa = seqs if isinstance(seqs, SeqArray) else SeqArray(seqs)
+        ids = np.ascontiguousarray(token_ids, dtype=np.int32)
+        if ids.shape != (sa.n_tokens,):
+            raise ValueError("token_ids must hold one id per new token")
+        stats = ps_step_stats() if want_stats else None
+        parts = (C.c_float * 3)() if want_parts else None
+        self._check(lib.ps_step_tokens(self.handle, sa.array, sa.n, ids.ctypes.data_as(_I32P), _P(next_tokens_ptr), _P(logits_ptr),
+                                       _P(hidden_ptr), C.byref(stats) if want_stats else None, parts))
+        return stats, ([parts[i] for i in range(3)] if want_parts else None)
 
     def step_indices(self, seqs):
         sa = seqs if isinstance(seqs, SeqArray) else SeqArray(seqs)

@@ -49,6 +49,17 @@ struct ps_ctx {
     int cap_tokens = 0;
     bf16_t *ws_xn = nullptr, *ws_q = nullptr, *ws_attn = nullptr, *ws_act = nullptr;
     float *ws_x1 = nullptr, *ws_xmid = nullptr;
+    // model head (ps_init_head): embedding table, final gain, repacked output matrix; its workspaces
+    bf16_t *embedding = nullptr, *g_final = nullptr, *wout_t = nullptr;
+    int vocab = 0;
+    bool head_ready = false;
+    bf16_t* ws_embed = nullptr;   // [cap_tokens][hidden] bf16: embedding rows of the step's tokens
+    float* ws_final = nullptr;    // [cap_tokens][hidden] fp32: output of the last layer
+    float* ws_logits = nullptr;   // fp32 partials of the output projection, [splits][n_seqs][vocab]
+    size_t logits_bytes = 0;
+    int32_t* ws_next = nullptr;   // [cap] greedy tokens when the caller passes none
+    int next_cap = 0;
+    hipEvent_t ev_head[4] = {nullptr, nullptr, nullptr, nullptr};
     float* ws_part = nullptr;  // fp32 GEMM partials [splits][T][N], shared by the three projections
     size_t part_bytes = 0;
     size_t act_bytes = 0;
@@ -199,6 +210,7 @@ extern "C" ps_status ps_sync(ps_ctx* c) {
 static void free_workspaces(ps_ctx* c) {
     dev_free(c->ws_xn); dev_free(c->ws_q); dev_free(c->ws_attn); dev_free(c->ws_act);
     dev_free(c->ws_xmid); dev_free(c->ws_x1); dev_free(c->ws_part);
+    dev_free(c->ws_embed); dev_free(c->ws_final);
     c->cap_tokens = 0;
     c->part_bytes = 0;
 }
@@ -213,6 +225,8 @@ extern "C" void ps_destroy(ps_ctx* c) {
         dev_free(c->rope_cs);
         dev_free(c->pool);
         free_workspaces(c);
+        dev_free(c->embedding); dev_free(c->g_final); dev_free(c->wout_t); dev_free(c->ws_logits); dev_free(c->ws_next);
+        for (auto& e : c->ev_head) if (e) (void)hipEventDestroy(e);
         dev_free(c->part_o); dev_free(c->part_ml);
         if (c->dev_meta) (void)hipFree(c->dev_meta);
         for (auto& e : c->meta_ready)
@@ -304,6 +318,31 @@ extern "C" ps_status ps_init_layer(ps_ctx* c, int32_t layer, const ps_layer_weig
     HIP_TRY(c, launch_copy_bytes(w->g_attn, L.g_attn, (size_t)H * 2, c->stream));
     HIP_TRY(c, launch_copy_bytes(w->g_ffn, L.g_ffn, (size_t)H * 2, c->stream));
     L.ready = true;
+    return PS_OK;
+}
+
+extern "C" ps_status ps_init_head(ps_ctx* c, const ps_head_weights* w) {
+    if (!c || !w) return fail(c, PS_EINVAL, "ps_init_head: null argument");
+    if (c->host_only) return fail(c, PS_ESTATE, "ps_init_head: host-only context");
+    if (!w->embedding || !w->g_final || !w->w_out) return fail(c, PS_EINVAL, "ps_init_head: null weight pointer");
+    if (w->vocab <= 0 || w->vocab % 64 || w->vocab > (1 << 20)) return fail(c, PS_EINVAL, "ps_init_head: vocab must be a positive multiple of 64, at most 2^20");
+    const int H = c->desc.hidden, V = w->vocab;
+    if ((size_t)V * H * 2 >= (1ull << 32)) return fail(c, PS_ERANGE, "ps_init_head: output matrix of 4 GiB or more");
+    ps_status st;
+    if (c->vocab != V) {
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        dev_free(c->embedding); dev_free(c->wout_t); dev_free(c->g_final);
+        c->vocab = 0;
+        if ((st = dev_alloc(c, &c->embedding, (size_t)V * H * 2, "embedding")) != PS_OK) return st;
+        if ((st = dev_alloc(c, &c->wout_t, (size_t)V * H * 2, "w_out")) != PS_OK) return st;
+        if ((st = dev_alloc(c, &c->g_final, (size_t)H * 2, "g_final")) != PS_OK) return st;
+        c->vocab = V;
+    }
+    c->head_ready = false;
+    HIP_TRY(c, launch_copy_bytes(w->embedding, c->embedding, (size_t)V * H * 2, c->stream));
+    HIP_TRY(c, launch_repack_weight(static_cast<const bf16_t*>(w->w_out), c->wout_t, H, V, 0, c->stream));
+    HIP_TRY(c, launch_copy_bytes(w->g_final, c->g_final, (size_t)H * 2, c->stream));
+    c->head_ready = true;
     return PS_OK;
 }
 
@@ -541,6 +580,10 @@ static ps_status ensure_workspaces(ps_ctx* c, int T, int n_part_slots) {
         if ((st = dev_alloc(c, &c->ws_act, c->act_bytes, "act")) != PS_OK) return st;
         if ((st = dev_alloc(c, &c->ws_x1, (size_t)cap * H * 4, "x1")) != PS_OK) return st;
         if (d.n_layers > 1 && (st = dev_alloc(c, &c->ws_xmid, (size_t)cap * H * 4, "inter-layer x")) != PS_OK) return st;
+        if (c->head_ready) {
+            if ((st = dev_alloc(c, &c->ws_embed, (size_t)cap * H * 2, "embedding rows")) != PS_OK) return st;
+            if ((st = dev_alloc(c, &c->ws_final, (size_t)cap * H * 4, "final hidden states")) != PS_OK) return st;
+        }
         c->cap_tokens = cap;
     }
     {   // GEMM partial buffer: sized for this step's T (the split count depends on T)
@@ -572,9 +615,9 @@ static ps_status ensure_workspaces(ps_ctx* c, int T, int n_part_slots) {
 }
 
 struct MetaLayout {
-    size_t positions, slots, seqs, pages, items, workers, groups, total;
+    size_t positions, slots, seqs, pages, items, workers, groups, tokens, last_rows, total;
 };
-static MetaLayout meta_layout(const StepPlan& p) {
+static MetaLayout meta_layout(const StepPlan& p, bool with_tokens) {
     MetaLayout m;
     size_t at = 0;
     m.positions = at; at = align16(at + p.positions.size() * 4);
@@ -584,11 +627,24 @@ static MetaLayout meta_layout(const StepPlan& p) {
     m.items = at;     at = align16(at + p.items.size() * sizeof(AttnItem));
     m.workers = at;   at = align16(at + p.worker_begin.size() * 4);
     m.groups = at;    at = align16(at + p.groups.size() * sizeof(MergeGroup));
+    m.tokens = at;    if (with_tokens) at = align16(at + (size_t)p.n_tokens * 4);
+    m.last_rows = at; if (with_tokens) at = align16(at + (size_t)p.n_seqs * 4);
     m.total = at;
     return m;
 }
 
-extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const void* x_in, void* x_out, ps_step_stats* stats) {
+// Token side of a full-model step: host token ids in, greedy tokens (and optionally logits / final hidden
+// states) out.  Null for ps_step, which takes and returns hidden states.
+struct TokenIO {
+    const int32_t* token_ids;  // host [T]
+    int32_t* next_tokens;      // device [n_seqs] or null
+    float* logits;             // device [n_seqs][vocab] or null
+    float* hidden;             // device [T][hidden] fp32 or null
+    float* ms;                 // host [3] or null: embedding, stack, head (needs stats-style synchronisation)
+};
+
+static ps_status step_impl(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const void* x_in, void* x_out, ps_step_stats* stats,
+                           const TokenIO* tio) {
     if (!c) return PS_EINVAL;
     if (c->host_only) return fail(c, PS_ESTATE, "ps_step: host-only context");
     if (!c->pool) return fail(c, PS_ESTATE, "ps_step: no KV pool (call ps_kv_alloc)");
@@ -605,7 +661,20 @@ extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, cons
         stats->n_attn_partials = p.n_partial_items;
     }
     if (n_seqs == 0) return PS_OK;
-    if (!x_in || !x_out) return fail(c, PS_EINVAL, "ps_step: null activation pointer");
+    if (!tio && (!x_in || !x_out)) return fail(c, PS_EINVAL, "ps_step: null activation pointer");
+    if (tio) {
+        if (!c->head_ready) return fail(c, PS_ESTATE, "ps_step_tokens: no model head (call ps_init_head)");
+        if (c->opt_only_layer >= 0) return fail(c, PS_ESTATE, "ps_step_tokens: option only_layer is set");
+        if (!tio->token_ids) return fail(c, PS_EINVAL, "ps_step_tokens: null token ids");
+        for (int t = 0; t < p.n_tokens; t++)
+            if (tio->token_ids[t] < 0 || tio->token_ids[t] >= c->vocab)
+                return fail(c, PS_ERANGE, "ps_step_tokens: token " + std::to_string(t) + " has id " + std::to_string(tio->token_ids[t]) +
+                                              " outside the vocabulary of " + std::to_string(c->vocab));
+        if (!c->ws_embed && c->cap_tokens > 0) {  // workspaces were sized before the head existed
+            HIP_TRY(c, hipStreamSynchronize(c->stream));
+            free_workspaces(c);
+        }
+    }
 
     c->step_counter++;
     const ps_model_desc& d = c->desc;
@@ -613,7 +682,7 @@ extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, cons
     if ((st = ensure_workspaces(c, T, p.n_partial_slots)) != PS_OK) return st;
 
     // one pinned buffer, one host-to-device copy for all of the step's integer metadata
-    const MetaLayout ml = meta_layout(p);
+    const MetaLayout ml = meta_layout(p, tio != nullptr);
     Staging* sg;
     int sg_idx = 0;
     if ((st = staging_acquire(c, ml.total, &sg, &sg_idx)) != PS_OK) return st;
@@ -625,6 +694,11 @@ extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, cons
     memcpy(hb + ml.items, p.items.data(), p.items.size() * sizeof(AttnItem));
     memcpy(hb + ml.workers, p.worker_begin.data(), p.worker_begin.size() * 4);
     if (!p.groups.empty()) memcpy(hb + ml.groups, p.groups.data(), p.groups.size() * sizeof(MergeGroup));
+    if (tio) {
+        memcpy(hb + ml.tokens, tio->token_ids, (size_t)p.n_tokens * 4);
+        int32_t* lr = reinterpret_cast<int32_t*>(hb + ml.last_rows);  // last new token of every sequence
+        for (int i = 0; i < p.n_seqs; i++) lr[i] = p.cu_seqlens[i + 1] - 1;
+    }
     const char* db = nullptr;
     if ((st = upload_meta(c, sg, sg_idx, ml.total, &db)) != PS_OK) return st;
     const int32_t* d_pos = reinterpret_cast<const int32_t*>(db + ml.positions);
@@ -639,6 +713,17 @@ extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, cons
     float total_ms = 0.f;
     hipStream_t s = c->stream;
 
+    // Full-model step: the stack's input is the embedding rows of the step's tokens, its output stays fp32
+    const bool out_f32 = tio ? true : c->opt_out_f32 != 0;
+    if (tio) {
+        if (tio->ms && !c->ev_head[0])
+            for (auto& e : c->ev_head) HIP_TRY(c, hipEventCreate(&e));
+        if (tio->ms) HIP_TRY(c, hipEventRecord(c->ev_head[0], s));
+        HIP_TRY(c, launch_embed_gather(c->embedding, reinterpret_cast<const int32_t*>(db + ml.tokens), c->ws_embed, T, H, s));
+        if (tio->ms) HIP_TRY(c, hipEventRecord(c->ev_head[1], s));
+        x_in = c->ws_embed;
+        x_out = tio->hidden ? static_cast<void*>(tio->hidden) : static_cast<void*>(c->ws_final);
+    }
     // The residual stream stays fp32 inside the stack: only x_in and x_out are bf16.  Every
     // projection leaves fp32 partial sums; the kernel that consumes them adds them up.
     const void* x_cur = x_in;
@@ -715,8 +800,8 @@ extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, cons
         HIP_TRY(c, launch_gemm(g, &n_splits, s));
         r.resid = c->ws_x1; r.resid_f32 = true; r.n_splits = n_splits;
         if (last) {
-            r.x_f32 = c->opt_out_f32 ? static_cast<float*>(x_out) : nullptr;
-            r.x_bf16 = c->opt_out_f32 ? nullptr : static_cast<bf16_t*>(x_out);
+            r.x_f32 = out_f32 ? static_cast<float*>(x_out) : nullptr;
+            r.x_bf16 = out_f32 ? nullptr : static_cast<bf16_t*>(x_out);
             r.gain = nullptr; r.xn = nullptr;
         } else {
             r.x_f32 = c->ws_xmid; r.x_bf16 = nullptr;
@@ -724,7 +809,7 @@ extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, cons
         }
         HIP_TRY(c, launch_reduce_add_norm(r, s));
         void* x_next = last ? x_out : static_cast<void*>(c->ws_xmid);
-        if (tap && c->taps.x_out && (!last || c->opt_out_f32))
+        if (tap && c->taps.x_out && (!last || out_f32))
             HIP_TRY(c, launch_copy_bytes(x_next, c->taps.x_out, (size_t)T * H * 4, s));
         if (stats) {
             HIP_TRY(c, hipEventRecord(c->ev[++e], s));
@@ -745,7 +830,60 @@ extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, cons
         stats->ms_total = total_ms;
         for (int i = 0; i < PS_N_STAGES; i++) stats->ms_stage[i] = stage_ms[i];
     }
+    if (tio) {
+        // head: RMS normalisation of every sequence's last new token, output projection, greedy token
+        if (tio->ms) HIP_TRY(c, hipEventRecord(c->ev_head[2], s));
+        const int M = p.n_seqs, V = c->vocab;
+        float* logits = tio->logits;
+        if (!logits) {
+            const size_t need = (size_t)M * V * sizeof(float);
+            if (need > c->logits_bytes) {
+                HIP_TRY(c, hipStreamSynchronize(s));
+                dev_free(c->ws_logits);
+                c->logits_bytes = 0;
+                if ((st = dev_alloc(c, &c->ws_logits, need + need / 4, "logits")) != PS_OK) return st;
+                c->logits_bytes = need + need / 4;
+            }
+            logits = c->ws_logits;
+        }
+        int32_t* next = tio->next_tokens;
+        if (!next) {
+            if (M > c->next_cap) {
+                HIP_TRY(c, hipStreamSynchronize(s));
+                dev_free(c->ws_next);
+                c->next_cap = 0;
+                if ((st = dev_alloc(c, &c->ws_next, (size_t)(M + 64) * 4, "next tokens")) != PS_OK) return st;
+                c->next_cap = M + 64;
+            }
+            next = c->ws_next;
+        }
+        HIP_TRY(c, launch_rmsnorm(x_out, true, c->g_final, c->ws_xn, M, H, d.rms_eps, s, reinterpret_cast<const int32_t*>(db + ml.last_rows)));
+        GemmArgs g{};
+        g.A = c->ws_xn; g.Wp = c->wout_t; g.M = M; g.N = V; g.K = H; g.kind = GemmOut::PARTIAL_F32;
+        g.out = logits; g.out_bytes = (size_t)M * V * sizeof(float);
+        g.split_k = 1;  // one partial buffer: it is the logits
+        g.tile = c->opt_gemm_tile;
+        int n_splits = 1;
+        HIP_TRY(c, launch_gemm(g, &n_splits, s));
+        if (n_splits != 1) return fail(c, PS_EDEVICE, "ps_step_tokens: output projection was split");
+        HIP_TRY(c, launch_argmax_rows(logits, M, V, next, s));
+        if (tio->ms) {
+            HIP_TRY(c, hipEventRecord(c->ev_head[3], s));
+            HIP_TRY(c, hipEventSynchronize(c->ev_head[3]));
+            for (int i = 0; i < 3; i++) HIP_TRY(c, hipEventElapsedTime(&tio->ms[i], c->ev_head[i], c->ev_head[i + 1]));
+        }
+    }
     return staging_commit(c, sg_idx);
+}
+
+extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const void* x_in, void* x_out, ps_step_stats* stats) {
+    return step_impl(c, seqs, n_seqs, x_in, x_out, stats, nullptr);
+}
+
+extern "C" ps_status ps_step_tokens(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const int32_t* token_ids, int32_t* next_tokens,
+                                    float* logits, float* hidden, ps_step_stats* stats, float* ms_parts) {
+    const TokenIO tio{token_ids, next_tokens, logits, hidden, ms_parts};
+    return step_impl(c, seqs, n_seqs, nullptr, nullptr, stats, &tio);
 }
 
 extern "C" ps_status ps_attention_times(ps_ctx* c, float* ms, int32_t cap, int32_t* n) {

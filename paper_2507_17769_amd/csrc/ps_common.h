@@ -85,7 +85,9 @@ struct GemmOut {
 // All take the stream explicitly and return hipGetLastError() of the launch.
 // out is written in operand order (act_offset)
 hipError_t launch_rmsnorm(const void* x, bool x_is_f32, const bf16_t* gain, bf16_t* out, int T, int H, float eps,
-                          hipStream_t st);
+                          hipStream_t st, const int32_t* src_rows = nullptr);  // src_rows: output row i normalises input row src_rows[i]
+hipError_t launch_embed_gather(const bf16_t* table, const int32_t* ids, bf16_t* out, int T, int H, hipStream_t st);
+hipError_t launch_argmax_rows(const float* x, int M, int N, int32_t* out, hipStream_t st);
 // operand-order [M][K] bf16 matrix -> row-major (for the debug taps)
 hipError_t launch_untile(const bf16_t* src, bf16_t* dst, int M, int K, hipStream_t st);
 // qkv: fp32 partials [n_splits][T][(n_q + 2 n_kv) d] of the QKV projection (summed here)

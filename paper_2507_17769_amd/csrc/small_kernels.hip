@@ -11,8 +11,10 @@ namespace ps {
 // One 256-thread block per token row: out = x * rsqrt(mean(x^2) + eps) * gain, fp32 math.
 template <bool X_F32>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const void* __restrict__ xin, const bf16_t* __restrict__ gain,
-                                                      bf16_t* __restrict__ out, int H, float eps) {
-    const int row = blockIdx.x;
+                                                      bf16_t* __restrict__ out, int H, float eps,
+                                                      const int32_t* __restrict__ src_rows) {
+    const int orow = blockIdx.x;                            // output row
+    const int row = src_rows ? src_rows[orow] : orow;       // input row (the head normalises selected rows only)
     const int tid = threadIdx.x;
     __shared__ float red[4];
     float ss = 0.f;
@@ -55,17 +57,72 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const void* __restrict__ x
         o.y = pack_bf16(v[2] * r * g[2], v[3] * r * g[3]);
         o.z = pack_bf16(v[4] * r * g[4], v[5] * r * g[5]);
         o.w = pack_bf16(v[6] * r * g[6], v[7] * r * g[7]);
-        *reinterpret_cast<uint4*>(out + act_offset(row, c, H)) = o;
+        *reinterpret_cast<uint4*>(out + act_offset(orow, c, H)) = o;
     }
 }
 
 hipError_t launch_rmsnorm(const void* x, bool x_is_f32, const bf16_t* gain, bf16_t* out, int T, int H, float eps,
-                          hipStream_t st) {
+                          hipStream_t st, const int32_t* src_rows) {
     if (T <= 0) return hipSuccess;
     if (x_is_f32)
-        hipLaunchKernelGGL(rmsnorm_kernel<true>, dim3(T), dim3(256), 0, st, x, gain, out, H, eps);
+        hipLaunchKernelGGL(rmsnorm_kernel<true>, dim3(T), dim3(256), 0, st, x, gain, out, H, eps, src_rows);
     else
-        hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3(T), dim3(256), 0, st, x, gain, out, H, eps);
+        hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3(T), dim3(256), 0, st, x, gain, out, H, eps, src_rows);
+    return hipGetLastError();
+}
+
+// --------------------------------------------------------------- embedding rows, greedy token
+// (Sec. 2.1: tokens enter the layers as embedding vectors; every step ends by generating a token.)
+// One 256-thread block per token: out[t][:] = table[ids[t]][:], 16 bytes per thread and trip.
+__global__ __launch_bounds__(256) void embed_gather_kernel(const bf16_t* __restrict__ table, const int32_t* __restrict__ ids,
+                                                           bf16_t* __restrict__ out, int H) {
+    const uint4* src = reinterpret_cast<const uint4*>(table + (size_t)ids[blockIdx.x] * H);
+    uint4* dst = reinterpret_cast<uint4*>(out + (size_t)blockIdx.x * H);
+    for (int c = threadIdx.x; c < H / 8; c += 256) dst[c] = src[c];
+}
+
+hipError_t launch_embed_gather(const bf16_t* table, const int32_t* ids, bf16_t* out, int T, int H, hipStream_t st) {
+    if (T <= 0) return hipSuccess;
+    hipLaunchKernelGGL(embed_gather_kernel, dim3(T), dim3(256), 0, st, table, ids, out, H);
+    return hipGetLastError();
+}
+
+// One 1024-thread block per row: index of the row's largest value, the lowest index among equal ones.
+// A NaN never wins a comparison, so a row of NaNs yields 0.
+__global__ __launch_bounds__(1024) void argmax_rows_kernel(const float* __restrict__ x, int N, int32_t* __restrict__ out) {
+    const float* row = x + (size_t)blockIdx.x * N;
+    float best = -INFINITY;
+    int arg = 0x7fffffff;
+    for (int c = threadIdx.x * 4; c < N; c += 4096) {   // N is a multiple of 4
+        const float4 v = *reinterpret_cast<const float4*>(row + c);
+        if (v.x > best) { best = v.x; arg = c; }
+        if (v.y > best) { best = v.y; arg = c + 1; }
+        if (v.z > best) { best = v.z; arg = c + 2; }
+        if (v.w > best) { best = v.w; arg = c + 3; }
+    }
+    // (value, index) maximum with ties to the lower index: first inside the wavefront, then across the 16 wavefronts
+    auto better = [](float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); };
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(best, o, 64);
+        const int oi = __shfl_xor(arg, o, 64);
+        if (better(ov, oi, best, arg)) { best = ov; arg = oi; }
+    }
+    __shared__ float sv[16];
+    __shared__ int si[16];
+    if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = best; si[threadIdx.x >> 6] = arg; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 16; w++)
+            if (better(sv[w], si[w], best, arg)) { best = sv[w]; arg = si[w]; }
+        out[blockIdx.x] = arg == 0x7fffffff ? 0 : arg;
+    }
+}
+
+hipError_t launch_argmax_rows(const float* x, int M, int N, int32_t* out, hipStream_t st) {
+    if (M <= 0) return hipSuccess;
+    if (N % 4) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(argmax_rows_kernel, dim3(M), dim3(1024), 0, st, x, N, out);
     return hipGetLastError();
 }
 

@@ -42,6 +42,27 @@ class Engine:
         self.ctx.init_layer(layer, **{k: t.data_ptr() for k, t in dev.items()})
         self.ctx.sync()
 
+    def load_head(self, head_bits):
+        """head_bits: {"embedding" [vocab][hidden], "g_final" [hidden], "w_out" [hidden][vocab]} as bf16 bit patterns."""
+        dev = {k: bits_to_dev(v, self.device) for k, v in head_bits.items()}
+        self.vocab = int(head_bits["embedding"].shape[0])
+        self.ctx.init_head(dev["embedding"].data_ptr(), dev["g_final"].data_ptr(), dev["w_out"].data_ptr(), self.vocab)
+        self.ctx.sync()
+
+    def step_tokens(self, seqs, token_ids, want_logits=True, want_hidden=False, want_stats=False, want_parts=False):
+        """Full-model step.  Returns dict with "next" (int32 tensor [n_seqs]), optionally "logits" (fp32
+        [n_seqs][vocab]) and "hidden" (fp32 [T][hidden]), "stats", "parts_ms"."""
+        n, T = len(seqs), sum(int(s.n_new) for s in seqs)
+        out = {"next": torch.empty(n, dtype=torch.int32, device=self.device)}
+        if want_logits:
+            out["logits"] = torch.empty((n, self.vocab), dtype=torch.float32, device=self.device)
+        if want_hidden:
+            out["hidden"] = torch.empty((T, self.model["hidden"]), dtype=torch.float32, device=self.device)
+        out["stats"], out["parts_ms"] = self.ctx.step_tokens(
+            seqs, token_ids, out["next"].data_ptr(), out["logits"].data_ptr() if want_logits else None,
+            out["hidden"].data_ptr() if want_hidden else None, want_stats, want_parts)
+        return out
+
     def write_kv(self, layer, pages, pos0, k_bits, v_bits):
         n = k_bits.shape[0]
         if n == 0:

@@ -41,6 +41,20 @@ def normal_bf16(rng, shape, std=1.0):
     return _to_bf16_bits(x)
 
 
+def head_weights(model, vocab, seed, std=WEIGHT_STD):
+    """Embedding table [vocab][hidden] ~ N(0, 1) (the scale of the configurations' input activations),
+    final gain 1, output matrix [hidden][vocab] ~ N(0, std^2); bf16 bit patterns."""
+    rng = np.random.Generator(np.random.PCG64([int(seed), 86028121, int(vocab)]))
+    H = model["hidden"]
+    return {"embedding": normal_bf16(rng, (vocab, H)), "g_final": _to_bf16_bits(np.ones(H, dtype=np.float32)),
+            "w_out": normal_bf16(rng, (H, vocab), std)}
+
+
+def token_ids(vocab, n, seed, tag=0):
+    rng = np.random.Generator(np.random.PCG64([int(seed), 49979687, int(tag)]))
+    return rng.integers(0, vocab, size=n, dtype=np.int32)
+
+
 def layer_weights(model, seed, layer=0, std=WEIGHT_STD):
     """bfloat16 N(0, std^2) weights (std 0.02 by default) in math layout [in][out]; unit gains."""
     m = MODELS[model] if isinstance(model, str) else model
