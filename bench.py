@@ -30,10 +30,11 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg2", "grid", "cfg4"])
+    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg2", "grid", "cfg4", "model8b"])
     ap.add_argument("--layers", type=int, default=80, help="cfg4: number of decoder layers")
     ap.add_argument("--kv-slots", type=int, default=8, help="cfg4: physical KV layer slots (layer l uses slot l mod this)")
     ap.add_argument("--check-layers", default="", help="cfg4: comma-separated layers to check against the oracle, teacher-forced")
+    ap.add_argument("--vocab", type=int, default=128256, help="model8b: vocabulary size")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
                     help="library tuning knob passed to ps_set_option (repeatable); the defaults are what is reported")
@@ -267,6 +268,104 @@ def run_cfg4(a):
     print(json.dumps(res))
 
 
+def run_model8b(a):
+    """8B-shaped full model on one GPU (Sec. 2.1: tokens in, next token out): embedding gather, 32 layers,
+    final norm, output projection over the whole vocabulary, greedy token.  Two batches: a single decode
+    request (the per-token latency the paper quotes for its engine, Sec. 5.1) and the 64-decode batch."""
+    import numpy as np
+    import torch
+    from paper_2507_17769_amd import workloads as W
+    from paper_2507_17769_amd.binding import STAGE_NAMES, SeqArray
+    from paper_2507_17769_amd.runner import Engine
+
+    def log(msg):
+        print(msg, file=sys.stderr, flush=True)
+
+    model, L, V = "8b", a.layers if a.layers != 80 else 32, a.vocab
+    m = W.MODELS[model]
+    H, F, nq, nkv, d = m["hidden"], m["ffn"], m["n_q"], m["n_kv"], m["head_dim"]
+    batches = {"1 decode, KV 1024": W.custom_batch(model, a.seed, 0, 0, [1024], name="b1"),
+               "64 decodes, KV U[512,4096]": W.config_batch(1, a.seed)}
+    n_pool = max(b.n_pool_pages for b in batches.values())
+    eng = Engine(model, n_pool, L, L, max_position=4096 + 16)
+    for kv in a.option:
+        eng.ctx.set_option(kv.split("=")[0], int(kv.split("=")[1]))
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(2000 + a.seed)
+    rnd = lambda shape, std: (torch.randn(shape, generator=gen, device="cuda:0", dtype=torch.float32) * std).to(torch.bfloat16)
+    ones = torch.ones(H, dtype=torch.bfloat16, device="cuda:0")
+    shapes = {"w_qkv": (H, (nq + 2 * nkv) * d), "w_o": (nq * d, H), "w_gate": (H, F), "w_up": (H, F), "w_down": (F, H)}
+    for l in range(L):
+        dev = {k: rnd(s, W.WEIGHT_STD) for k, s in shapes.items()}
+        dev["g_attn"], dev["g_ffn"] = ones, ones
+        eng.ctx.init_layer(l, **{k: t.data_ptr() for k, t in dev.items()})
+        eng.ctx.sync()
+        del dev
+    emb, w_out = rnd((V, H), 1.0), rnd((H, V), W.WEIGHT_STD)
+    eng.ctx.init_head(emb.data_ptr(), ones.data_ptr(), w_out.data_ptr(), V)
+    eng.ctx.sync()
+    eng.vocab = V
+    log(f"model8b: {L} layers + head (vocab {V}) loaded")
+    params_layer = H * (nq + 2 * nkv) * d + nq * d * H + 3 * H * F
+    weight_bytes = 2 * (L * params_layer + H * V)          # streamed per step: all layers + output matrix
+    res = {"metric": "full_model_step", "unit": "ms", "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"model8b: 8B-shaped model, {L} layers, vocabulary {V}, greedy token", "n_layers": L, "vocab": V},
+           "weight_bytes_per_step": weight_bytes, "batches": []}
+    for name, batch in batches.items():
+        # cached prefixes: one block of N(0,1) keys/values reused for every sequence and layer
+        rng = np.random.Generator(np.random.PCG64([a.seed, 27182818]))
+        from paper_2507_17769_amd.runner import bits_to_dev
+        mp = max(s.prefix for s in batch.seqs)
+        kblk = bits_to_dev(W.normal_bf16(rng, (mp, nkv, d)), eng.device)
+        vblk = bits_to_dev(W.normal_bf16(rng, (mp, nkv, d)), eng.device)
+        for slot in range(L):
+            for s in batch.seqs:
+                eng.ctx.kv_write(slot, s.pages, 0, s.prefix, kblk.data_ptr(), vblk.data_ptr())
+        eng.ctx.sync()
+        ids = W.token_ids(V, batch.n_tokens, a.seed, 1)
+        seqs = SeqArray(batch.seqs)
+        nxt = torch.empty(len(batch.seqs), dtype=torch.int32, device="cuda:0")
+        for _ in range(max(2, min(a.warmup, 5))):
+            eng.ctx.step_tokens(seqs, ids, nxt.data_ptr())
+        eng.ctx.sync()
+        steps = max(5, min(a.steps, 50))
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            eng.ctx.step_tokens(seqs, ids, nxt.data_ptr())
+        eng.ctx.sync()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        st, parts = eng.ctx.step_tokens(seqs, ids, nxt.data_ptr(), want_stats=True, want_parts=True)
+        rec = {"batch": name, "n_tokens": batch.n_tokens, "total_kv_per_layer": batch.total_kv, "ms_per_step": ms,
+               "tokens_per_s": batch.n_tokens / (ms * 1e-3),
+               "parts_ms": {"embedding": round(parts[0], 4), "layers": round(parts[1], 3), "head": round(parts[2], 4)},
+               "stage_ms_all_layers": {n: round(float(st.ms_stage[i]), 3) for i, n in enumerate(STAGE_NAMES)},
+               "hbm_GBs": (weight_bytes + 2 * nkv * d * 2 * batch.total_kv * L) / (ms * 1e-3) / 1e9}
+        # head check, teacher-forced: the oracle's head applied to the device's own final hidden states
+        if not a.no_cpu_baseline:
+            from oracle import bf16 as obf
+            from oracle import head as oh
+            from oracle import run as orun
+            out = {"logits": torch.empty((len(batch.seqs), V), dtype=torch.float32, device="cuda:0"),
+                   "hidden": torch.empty((batch.n_tokens, H), dtype=torch.float32, device="cuda:0")}
+            eng.ctx.step_tokens(seqs, ids, nxt.data_ptr(), out["logits"].data_ptr(), out["hidden"].data_ptr())
+            eng.ctx.sync()
+            hid, lg, tok = out["hidden"].cpu().numpy(), out["logits"].cpu().numpy(), nxt.cpu().numpy()
+            w_host = w_out.float().cpu().numpy()
+            want = oh.logits(hid, orun.to_seqs(batch.seqs), np.ones(H, np.float32), w_host, W.RMS_EPS)
+            rms = float(np.sqrt(np.mean(want.astype(np.float64) ** 2)))
+            err = float(np.max(np.abs(lg - want))) / rms
+            first_max = np.argmax(lg, axis=1)
+            lead_ok = all(want[i, tok[i]] >= want[i].max() - 4e-2 * rms for i in range(len(tok)))
+            rec["head_check"] = {"logits_max_err_over_rms": err, "greedy_is_first_max_of_device_logits": bool(np.array_equal(tok, first_max)),
+                                 "greedy_within_rounding_of_oracle_best": bool(lead_ok), "finite": bool(np.isfinite(hid).all()),
+                                 "pass": bool(err <= 2e-2 and np.array_equal(tok, first_max) and lead_ok)}
+            log(f"model8b: {name}: head check max|err|/rms = {err:.4f}")
+        res["batches"].append(rec)
+        log(f"model8b: {name}: {ms:.3f} ms/step")
+    eng.close()
+    print(json.dumps(res))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -294,6 +393,9 @@ def main():
         return
     if a.workload == "cfg4":
         run_cfg4(a)
+        return
+    if a.workload == "model8b":
+        run_model8b(a)
         return
     cfg = {"cfg1": 1, "cfg2": 2}[a.workload]
     batch = W.config_batch(cfg, a.seed)

@@ -3,6 +3,7 @@ and into measured_traffic.json (the HBM bytes per attention launch that bench.py
 roofline.traffic).
 
     python -m paper_2507_17769_amd.profile_summary trace  <kernel_trace.csv> <bench.json> <workload> <command> > profiles/<name>.md
+    python -m paper_2507_17769_amd.profile_summary model  <bench_model8b.json> <command> > profiles/<name>.md
     python -m paper_2507_17769_amd.profile_summary grid   <bench_grid.json> <command> > profiles/<name>.md
     python -m paper_2507_17769_amd.profile_summary counters <fetch.csv> <write.csv> <fetch_copy.csv> <write_copy.csv> \
             <workload> <seed> <md out> [--json]
@@ -144,7 +145,44 @@ def grid_summary(grid_json, command):
     return "\n".join(out) + "\n"
 
 
+def model_summary(model_json, command):
+    d = json.load(open(model_json))
+    c = d["config"]
+    out = [f"# Full-model step — 8B-shaped model, {c['n_layers']} layers, vocabulary {c['vocab']}, one MI355X", "",
+           "Tokens in, greedy next token out (Sec. 2.1): embedding gather, all layers over the paged KV cache, RMS normalisation of each "
+           "sequence's last token, output projection over the whole vocabulary, first-maximum pick; one `ps_step_tokens` call per step.",
+           "The paper's only latency remark about this path is its engine's minimal per-token latency of about 15 ms (Sec. 5.1; vLLM on an "
+           "H200, another machine and software stack: context, not a target).", "",
+           f"Command:  `{command}`", "",
+           f"Weights streamed per step: {d['weight_bytes_per_step'] / 1e9:.2f} GB (all layers + output matrix; random N(0, 0.02^2) weights drawn on the device).", "",
+           "| batch | new tokens | KV tokens per layer | ms per step | tokens/s | embedding ms | layers ms | head ms | HBM GB/s (weights + KV) |",
+           "|---|---|---|---|---|---|---|---|---|"]
+    for b in d["batches"]:
+        p = b["parts_ms"]
+        out.append(f"| {b['batch']} | {b['n_tokens']} | {b['total_kv_per_layer']} | {b['ms_per_step']:.3f} | {b['tokens_per_s']:.0f} | "
+                   f"{p['embedding']:.3f} | {p['layers']:.3f} | {p['head']:.3f} | {b['hbm_GBs']:.0f} |")
+    out += ["", "`ms per step` is the host clock over back-to-back steps; the three parts come from a separate, event-timed step "
+                "(with an event after every layer stage, which adds a few microseconds per stage).", "",
+            "Stage times summed over the layers, ms:", "", "| batch | " + " | ".join(d["batches"][0]["stage_ms_all_layers"].keys()) + " |",
+            "|---|" + "---|" * len(d["batches"][0]["stage_ms_all_layers"])]
+    for b in d["batches"]:
+        out.append(f"| {b['batch']} | " + " | ".join(f"{v:.3f}" for v in b["stage_ms_all_layers"].values()) + " |")
+    if all("head_check" in b for b in d["batches"]):
+        out += ["", "Head check (the oracle's normalisation + output projection applied to the device's own final hidden states): "
+                    "max |logit error| / RMS(logits) and the greedy pick:", "",
+                "| batch | logits max err / RMS | pick = first maximum of the device's logits | pick within rounding of the oracle's best | pass |",
+                "|---|---|---|---|---|"]
+        for b in d["batches"]:
+            h = b["head_check"]
+            out.append(f"| {b['batch']} | {h['logits_max_err_over_rms']:.4f} | {h['greedy_is_first_max_of_device_logits']} | "
+                       f"{h['greedy_within_rounding_of_oracle_best']} | {h['pass']} |")
+    return "\n".join(out) + "\n"
+
+
 def main(argv):
+    if len(argv) >= 4 and argv[1] == "model":
+        sys.stdout.write(model_summary(argv[2], argv[3]))
+        return 0
     if len(argv) >= 4 and argv[1] == "grid":
         sys.stdout.write(grid_summary(argv[2], argv[3]))
         return 0
