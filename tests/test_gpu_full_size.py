@@ -29,3 +29,24 @@ def test_8b_layer_full_size(cfg):
             g, w = f32(got).astype(np.float64), want.astype(np.float64)
             assert np.all(np.abs(g - w) <= 2.0 ** -7 * np.abs(w) + 1e-3 * np.sqrt(np.mean(w * w)))
     c.close()
+
+
+def test_70b_shaped_two_layer_stack_full_batch_teacher_forced(capsys):
+    """The 70B-shaped configuration at its real batch (1024-token chunk at prefix 4096 + 256 decodes,
+    660 k KV tokens per layer) on two layers, each checked on its own against the oracle from the
+    layer's actual input: the code path bench.py times and checks on the 80-layer stack."""
+    import argparse
+    import json
+    import bench
+    a = argparse.Namespace(layers=2, kv_slots=2, check_layers="0,1", seed=0, steps=2, warmup=1, option=[])
+    bench.run_cfg4(a)
+    res = json.loads(capsys.readouterr().out.strip().splitlines()[-1])
+    assert res["output_finite"]
+    checks = {c["layer"]: c for c in res["layer_checks"]}
+    assert set(checks) == {0, 1} and all(c["pass"] for c in checks.values()), checks
+    # layer 1 sits on a residual stream that dominates its branches: the plain bar against the definition holds
+    assert checks[1]["judged_against"] == "definition" and checks[1]["max_err_over_rms"] <= TOL
+    # layer 0 of this shape is the ill-conditioned one: the definition itself moves by more than the bar when its
+    # stored activations are rounded to bf16, and the kernels stay within the bar of that variant
+    assert checks[0]["max_err_over_rms_vs_bf16_variant"] <= TOL
+    assert checks[0]["max_err_over_rms"] <= checks[0]["oracle_gap_definition_vs_bf16_variant"] + TOL
