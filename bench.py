@@ -30,7 +30,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg2", "grid", "cfg4", "model8b"])
+    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg2", "grid", "cfg4", "model8b", "prefill"])
     ap.add_argument("--layers", type=int, default=80, help="cfg4: number of decoder layers")
     ap.add_argument("--kv-slots", type=int, default=8, help="cfg4: physical KV layer slots (layer l uses slot l mod this)")
     ap.add_argument("--check-layers", default="", help="cfg4: comma-separated layers to check against the oracle, teacher-forced")
@@ -366,6 +366,65 @@ def run_model8b(a):
     print(json.dumps(res))
 
 
+def run_prefill(a):
+    """Prefill-only steps of an 8B-shaped layer, as a prefill instance of a prefill-decode disaggregated
+    deployment runs them (Sec. 3.4: its token batch reaches 2048): one request or several sharing the step."""
+    import numpy as np
+    import torch
+    from paper_2507_17769_amd import workloads as W
+    from paper_2507_17769_amd.binding import STAGE_NAMES, SeqArray
+    from paper_2507_17769_amd.runner import Engine, bits_to_dev
+
+    model = "8b"
+    m = W.MODELS[model]
+    H, F, nq, nkv, d = m["hidden"], m["ffn"], m["n_q"], m["n_kv"], m["head_dim"]
+    params = H * (nq + 2 * nkv) * d + nq * d * H + 3 * H * F
+    specs = {"1 x 2048": [(2048, 0)], "4 x 512": [(512, 0)] * 4, "16 x 128": [(128, 0)] * 16,
+             "2 x 1024 at prefix 1024": [(1024, 1024)] * 2, "1023 + 1 + 1024 (budget boundary)": [(1023, 0), (1, 2049), (1024, 0)]}
+    batches = {k: W.multi_batch(model, a.seed, v, []) for k, v in specs.items()}
+    n_copies = 4
+    eng = Engine(model, max(b.n_pool_pages for b in batches.values()), n_copies, 1, max_position=4096 + 16)
+    for kv in a.option:
+        eng.ctx.set_option(kv.split("=")[0], int(kv.split("=")[1]))
+    weights = W.layer_weights(model, a.seed, 0)
+    for l in range(n_copies):
+        eng.load_layer(l, weights)
+    res = {"metric": "prefill_step", "unit": "ms", "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": "prefill-only steps, 8B-shaped layer, four weight copies in rotation"}, "batches": []}
+    for name, b in batches.items():
+        eng.load_prefixes(b)
+        x = bits_to_dev(b.activations(), eng.device)
+        out = torch.empty_like(x)
+        seqs = SeqArray(b.seqs)
+        for i in range(5):
+            eng.ctx.set_option("only_layer", i % n_copies)
+            eng.ctx.step(seqs, x.data_ptr(), out.data_ptr())
+        eng.ctx.sync()
+        steps = max(10, min(a.steps, 100))
+        t0 = time.perf_counter()
+        for i in range(steps):
+            eng.ctx.set_option("only_layer", i % n_copies)
+            eng.ctx.step(seqs, x.data_ptr(), out.data_ptr())
+        eng.ctx.sync()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        stage = np.zeros(len(STAGE_NAMES))
+        for i in range(5):
+            eng.ctx.set_option("only_layer", i % n_copies)
+            st = eng.ctx.step(seqs, x.data_ptr(), out.data_ptr(), want_stats=True)
+            stage += np.array(list(st.ms_stage)) / 5
+        T = b.n_tokens
+        gemm_ms = float(stage[1] + stage[4] + stage[6] + stage[7])
+        # causal (query, key) pairs of the step, 4 * d * n_q flop each
+        pairs = sum(s.n_new * s.prefix + s.n_new * (s.n_new + 1) // 2 for s in b.seqs)
+        res["batches"].append({"batch": name, "n_tokens": T, "ms_per_step": ms, "tokens_per_s": T / (ms * 1e-3),
+                               "stage_ms": {n: round(float(v), 4) for n, v in zip(STAGE_NAMES, stage)},
+                               "gemm_tflops": 2 * params * T / (gemm_ms * 1e-3) / 1e12,
+                               "gemm_frac_mfma": 2 * params * T / (gemm_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                               "attention_tflops": 4 * d * nq * pairs / (float(stage[3]) * 1e-3) / 1e12})
+    eng.close()
+    print(json.dumps(res))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -396,6 +455,9 @@ def main():
         return
     if a.workload == "model8b":
         run_model8b(a)
+        return
+    if a.workload == "prefill":
+        run_prefill(a)
         return
     cfg = {"cfg1": 1, "cfg2": 2}[a.workload]
     batch = W.config_batch(cfg, a.seed)

@@ -4,6 +4,7 @@ roofline.traffic).
 
     python -m paper_2507_17769_amd.profile_summary trace  <kernel_trace.csv> <bench.json> <workload> <command> > profiles/<name>.md
     python -m paper_2507_17769_amd.profile_summary model  <bench_model8b.json> <command> > profiles/<name>.md
+    python -m paper_2507_17769_amd.profile_summary prefill <bench_prefill.json> <command> > profiles/<name>.md
     python -m paper_2507_17769_amd.profile_summary grid   <bench_grid.json> <command> > profiles/<name>.md
     python -m paper_2507_17769_amd.profile_summary counters <fetch.csv> <write.csv> <fetch_copy.csv> <write_copy.csv> \
             <workload> <seed> <md out> [--json]
@@ -179,7 +180,28 @@ def model_summary(model_json, command):
     return "\n".join(out) + "\n"
 
 
+def prefill_summary(prefill_json, command):
+    d = json.load(open(prefill_json))
+    out = ["# Prefill-only steps — 8B-shaped layer, one MI355X", "",
+           "Steps of a prefill instance in a prefill-decode disaggregated deployment (Sec. 3.4: its token batch reaches 2048): one "
+           "request or several sharing the step, including the case where a budget already holds 1023 tokens and takes one token of "
+           "the next request (Sec. 4.6).  Four device copies of the layer in rotation, so weights come from HBM.", "",
+           f"Command:  `{command}`", "",
+           "| batch (requests x new tokens) | tokens | ms per step | tokens/s | GEMMs: TFLOP/s (% of 2.5 PFLOP/s) | attention TFLOP/s (causal pairs only) | attention ms | GEMM ms |",
+           "|---|---|---|---|---|---|---|---|"]
+    for b in d["batches"]:
+        st = b["stage_ms"]
+        gemm = st["gemm_qkv"] + st["gemm_o"] + st["gemm_gate_up"] + st["gemm_down"]
+        out.append(f"| {b['batch']} | {b['n_tokens']} | {b['ms_per_step']:.3f} | {b['tokens_per_s']:.0f} | {b['gemm_tflops']:.0f} "
+                   f"({100 * b['gemm_frac_mfma']:.1f} %) | {b['attention_tflops']:.0f} | {st['attention']:.3f} | {gemm:.3f} |")
+    out += ["", "`ms per step` is the host clock over back-to-back steps; stage times come from separate event-timed steps."]
+    return "\n".join(out) + "\n"
+
+
 def main(argv):
+    if len(argv) >= 4 and argv[1] == "prefill":
+        sys.stdout.write(prefill_summary(argv[2], argv[3]))
+        return 0
     if len(argv) >= 4 and argv[1] == "model":
         sys.stdout.write(model_summary(argv[2], argv[3]))
         return 0

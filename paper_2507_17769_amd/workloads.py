@@ -148,6 +148,17 @@ def custom_batch(model, seed, chunk, chunk_prefix, decode_kv, name="custom", tag
     return Batch(model=model, seed=int(seed), seqs=seqs, n_pool_pages=n_pool, name=name, _rng_tag=int(tag))
 
 
+def multi_batch(model, seed, chunks, decode_kv, name="multi", tag=0):
+    """Several prefill chunks in one iteration (the budget shared by more than one prefill request,
+    Sec. 4.6 of the paper's dynamic-chunking discussion) plus decodes.  chunks: (n_new, prefix) per
+    prefill request; decode_kv: KV length after the step per decode request.  The order is the one
+    given: chunks first, then decodes."""
+    rng = np.random.Generator(np.random.PCG64([int(seed), 15485863, int(tag), 1]))
+    spec = [(int(n), int(p) + int(n)) for n, p in chunks] + [(1, int(L)) for L in decode_kv]
+    seqs, n_pool = _assign_pages(rng, spec)
+    return Batch(model=model, seed=int(seed), seqs=seqs, n_pool_pages=n_pool, name=name, _rng_tag=int(tag))
+
+
 def config_batch(cfg, seed=0):
     """The benchmark configurations, by index.
 

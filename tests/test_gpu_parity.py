@@ -297,3 +297,57 @@ def test_only_layer_runs_that_layer_as_the_whole_model():
             eng.ctx.set_option("only_layer", len(layers))
         eng.close()
     assert np.array_equal(outs[0], outs[1])
+
+
+@pytest.mark.parametrize("chunks,decodes", [
+    ([(1023, 0), (1, 2049)], [5, 300]),                 # a budget already filled with 1023 tokens takes one token of the next request
+    ([(17, 3), (64, 100), (5, 0), (130, 31)], [1, 16, 17]),   # four prefill requests of ragged sizes and offsets
+    ([(512, 0)] * 4, []),                               # prefill-only step of 2048 tokens from four fresh requests
+    ([(2048, 0)], []),                                  # one 2048-token prompt in one step
+])
+def test_steps_with_several_prefill_requests(chunks, decodes):
+    b = W.multi_batch("tiny", 41, chunks, decodes)
+    c = Case(b)
+    errs = c.run()
+    _assert_errs(errs, f"chunks={chunks} decodes={decodes}")
+    c.check_pool()
+    stages = c.stagewise()
+    assert max(stages.values()) <= 1.0, stages
+    c.close()
+
+
+def test_prefill_decode_handoff_through_kv_read_and_write():
+    # Prefill on one context, decode on another: the keys and values of the prompt are the hand-off payload
+    # (ps_kv_read on the prefill side, ps_kv_write into freshly reserved pages on the decode side).  The decode
+    # step there gives bit for bit what the same step gives on the context that ran the prefill.
+    m = W.MODELS["tiny"]
+    w = W.layer_weights(m, 9, 0)
+    prompt = 100
+    pre = W.multi_batch("tiny", 43, [(prompt, 0)], [])
+    x_pre = bits_to_dev(pre.activations(), "cuda:0")
+    a = Engine(m, 64, max_position=256)
+    a.load_layer(0, w)
+    a.step(pre.seqs, x_pre)
+    a.ctx.sync()
+    pages_a = pre.seqs[0].pages
+    k, v = a.read_kv(0, pages_a, 0, prompt)
+    # decode side: its own pool and allocator
+    bctx = Engine(m, 40, max_position=256, perm_seed=77)
+    bctx.load_layer(0, w)
+    pages_b = bctx.ctx.kv_reserve(req_id=5, kv_len=prompt + 1)
+    bctx.write_kv(0, pages_b, 0, k, v)
+    x_dec = bits_to_dev(W.normal_bf16(np.random.default_rng(1), (1, m["hidden"])), "cuda:0")
+    seq_b = [W.SeqSpec(req_id=5, n_new=1, kv_len=prompt + 1, pages=pages_b)]
+    out_b, _ = bctx.step(seq_b, x_dec)
+    bctx.ctx.sync()
+    # the same decode step where the prefill ran (one more page may be needed for position `prompt`)
+    need = (prompt + 1 + 15) // 16
+    pages_a2 = np.concatenate([pages_a, np.setdiff1d(np.arange(64, dtype=np.int32), pages_a)[:need - len(pages_a)]]).astype(np.int32)
+    seq_a = [W.SeqSpec(req_id=pre.seqs[0].req_id, n_new=1, kv_len=prompt + 1, pages=pages_a2)]
+    out_a, _ = a.step(seq_a, x_dec)
+    a.ctx.sync()
+    assert np.array_equal(dev_to_bits(out_a), dev_to_bits(out_b))
+    ka, va = a.read_kv(0, pages_a2, 0, prompt + 1)
+    kb, vb = bctx.read_kv(0, pages_b, 0, prompt + 1)
+    assert np.array_equal(ka, kb) and np.array_equal(va, vb)
+    a.close(); bctx.close()
