@@ -30,7 +30,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg2", "grid", "cfg4", "model8b", "prefill"])
+    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg2", "grid", "cfg4", "model8b", "prefill", "profile"])
     ap.add_argument("--layers", type=int, default=80, help="cfg4: number of decoder layers")
     ap.add_argument("--kv-slots", type=int, default=8, help="cfg4: physical KV layer slots (layer l uses slot l mod this)")
     ap.add_argument("--check-layers", default="", help="cfg4: comma-separated layers to check against the oracle, teacher-forced")
@@ -425,6 +425,102 @@ def run_prefill(a):
     print(json.dumps(res))
 
 
+def run_profile(a):
+    """The map (batch size, KV cache size) -> iteration time of the whole 8B-shaped model (Sec. 4.4), measured on
+    decode batches, and the router's decisions taken with it through polysched (Sec. 3.4, 4.4-4.6) for the paper's
+    TPOT tiers (Sec. 5.1: 20, 30, 50, 100 ms; TTFT 300, 500, 1000 ms)."""
+    import numpy as np
+    import torch
+    from paper_2507_17769_amd import binding as B
+    from paper_2507_17769_amd import workloads as W
+    from paper_2507_17769_amd.binding import SeqArray
+    from paper_2507_17769_amd.runner import Engine, bits_to_dev
+
+    model, L, V = "8b", a.layers if a.layers != 80 else 32, a.vocab
+    m = W.MODELS[model]
+    H, F, nq, nkv, d = m["hidden"], m["ffn"], m["n_q"], m["n_kv"], m["head_dim"]
+    batch_sizes = [1, 4, 16, 64, 256]
+    kv_sizes = [4096, 32768, 131072, 524288]          # total KV tokens of the batch
+    cells = {}
+    for bs in batch_sizes:
+        for kv in kv_sizes:
+            per = kv // bs
+            if 16 <= per <= 65536:
+                cells[(bs, kv)] = W.custom_batch(model, a.seed, 0, 0, [per] * bs, name=f"b{bs}_kv{kv}", tag=bs * 7 + 1)
+    n_pool = max(b.n_pool_pages for b in cells.values())
+    eng = Engine(model, n_pool, L, L, max_position=65536 + 16)
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(3000 + a.seed)
+    rnd = lambda shape, std: (torch.randn(shape, generator=gen, device="cuda:0", dtype=torch.float32) * std).to(torch.bfloat16)
+    ones = torch.ones(H, dtype=torch.bfloat16, device="cuda:0")
+    shapes = {"w_qkv": (H, (nq + 2 * nkv) * d), "w_o": (nq * d, H), "w_gate": (H, F), "w_up": (H, F), "w_down": (F, H)}
+    for l in range(L):
+        dev = {k: rnd(s, W.WEIGHT_STD) for k, s in shapes.items()}
+        dev["g_attn"], dev["g_ffn"] = ones, ones
+        eng.ctx.init_layer(l, **{k: t.data_ptr() for k, t in dev.items()})
+        eng.ctx.sync()
+        del dev
+    emb, w_out = rnd((V, H), 1.0), rnd((H, V), W.WEIGHT_STD)
+    eng.ctx.init_head(emb.data_ptr(), ones.data_ptr(), w_out.data_ptr(), V)
+    eng.ctx.sync()
+    # the cache content does not matter for timing: the pool is filled once with N(0,1) values through one sequence-sized block
+    rng = np.random.Generator(np.random.PCG64([a.seed, 16180339]))
+    blk = bits_to_dev(W.normal_bf16(rng, (4096, nkv, d)), eng.device)
+    table = np.full((len(batch_sizes), len(kv_sizes)), np.nan, dtype=np.float32)
+    steps = max(3, min(a.steps, 10))
+    for (bs, kv), b in cells.items():
+        for s in b.seqs:          # keys and values of every cached position, block by block
+            for p0 in range(0, s.prefix, 4096):
+                n = min(4096, s.prefix - p0)
+                for slot in range(L):
+                    eng.ctx.kv_write(slot, s.pages, p0, n, blk.data_ptr(), blk.data_ptr())
+        eng.ctx.sync()
+        ids = W.token_ids(V, b.n_tokens, a.seed, 2)
+        seqs = SeqArray(b.seqs)
+        nxt = torch.empty(len(b.seqs), dtype=torch.int32, device="cuda:0")
+        for _ in range(2):
+            eng.ctx.step_tokens(seqs, ids, nxt.data_ptr())
+        eng.ctx.sync()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            eng.ctx.step_tokens(seqs, ids, nxt.data_ptr())
+        eng.ctx.sync()
+        table[batch_sizes.index(bs), kv_sizes.index(kv)] = (time.perf_counter() - t0) * 1e3 / steps
+        print(f"profile: batch {bs} kv {kv}: {table[batch_sizes.index(bs), kv_sizes.index(kv)]:.3f} ms", file=sys.stderr, flush=True)
+    eng.close()
+    # cells that cannot exist (fewer than 16 cached tokens per request) are filled from the nearest measured cell of the row
+    filled = table.copy()
+    for i in range(len(batch_sizes)):
+        for j in range(len(kv_sizes)):
+            if np.isnan(filled[i, j]):
+                js = [jj for jj in range(len(kv_sizes)) if not np.isnan(table[i, jj])]
+                filled[i, j] = table[i, min(js, key=lambda jj: abs(jj - j))]
+    prof = B.Profile(batch_sizes, kv_sizes, filled)
+    res = {"metric": "iteration_time_profile", "unit": "ms", "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"profile: 8B-shaped model, {L} layers + head, decode batches", "n_layers": L, "vocab": V},
+           "batch_sizes": batch_sizes, "kv_sizes": kv_sizes,
+           "ms": [[None if np.isnan(v) else round(float(v), 4) for v in row] for row in table], "decisions": {}}
+    dec = res["decisions"]
+    # Sec. 3.4: largest decode batch per TPOT tier for a request shape (p, d), KV capacity of what is left of 288 GB
+    weights_gb = 2 * (L * (H * (nq + 2 * nkv) * d + nq * d * H + 3 * H * F) + 2 * H * V) / 1e9
+    capacity = (288 - weights_gb - 8) * 1e9 / (2 * nkv * d * 2 * L)
+    dec["kv_capacity_tokens"] = int(capacity)
+    dec["batch_limit_pd"] = {f"p={p},d={dd},tpot={t}": prof.batch_limit_pd(p, dd, t, capacity, 4096)
+                             for (p, dd) in ((512, 512), (4096, 1024)) for t in (20, 30, 50, 100)}
+    dec["batch_limit_co"] = {f"p={p},d={dd},tpot={t},ttft={tt}": prof.batch_limit_co(p, dd, t, tt, capacity, 4096)
+                             for (p, dd) in ((512, 512), (4096, 1024)) for t in (20, 50, 100) for tt in (300, 1000)}
+    # Sec. 4.4/4.5: a server with 63 running requests (KV 2000, 100 tokens generated), average output 512
+    run = [(2000, 100)] * 63
+    dec["admit_64th_request"] = {f"tpot={t},wait={w}": list(prof.predict_admit(run, 1000, 512, t, w)) for t in (20, 30) for w in (0.0, 15.0)}
+    # Sec. 4.6: the worked example, and a co-located prefill
+    sizes = lambda plan: [sum(t for _, t in it) for it in plan]
+    dec["chunk_plan_2050_budget_1024"] = {"chunked": sizes(B.chunk_plan([2050], 1024, False)), "chunked_after_1023": sizes(B.chunk_plan([2050], 1024, False, 1023)),
+                                          "dynamic": sizes(B.chunk_plan([2050], 1024, True)), "dynamic_after_1023": sizes(B.chunk_plan([2050], 1024, True, 1023))}
+    dec["chunked_prefill_2000_tokens_beside_63_decodes"] = {f"tpot={t},ttft={tt}": list(prof.predict_chunked_prefill(run, 2000, 512, t, tt)) for t in (20, 50) for tt in (300, 1000)}
+    prof.close()
+    print(json.dumps(res))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -458,6 +554,9 @@ def main():
         return
     if a.workload == "prefill":
         run_prefill(a)
+        return
+    if a.workload == "profile":
+        run_profile(a)
         return
     cfg = {"cfg1": 1, "cfg2": 2}[a.workload]
     batch = W.config_batch(cfg, a.seed)

@@ -1,0 +1,82 @@
+/* polysched: host-side consumers of the latency profile that polystep measures.
+ *
+ * These are the decisions the paper's router takes with the (batch size, KV cache size) -> time
+ * table (Sec. 4.4 "Profile-Based Batch Formation", Sec. 4.5 "Wait-Time-Aware Scheduling",
+ * Sec. 4.6 "Handling TTFT", Sec. 3.4 batch-size limits).  Plain C, host memory only, no GPU work,
+ * no global state; a profile object is immutable after creation and may be shared by threads.
+ * All times are milliseconds.  Functions return PS_OK or PS_EINVAL (null pointer, malformed
+ * argument) and leave their outputs untouched on error. */
+#ifndef POLYSCHED_H
+#define POLYSCHED_H
+
+#include "polystep.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ps_profile ps_profile;
+
+/* Build the table: batch_sizes [n_batch] and kv_sizes [n_kv] strictly ascending, ms [n_batch][n_kv]
+ * row-major (ms[i * n_kv + j] for batch_sizes[i], kv_sizes[j]).  The arrays are copied.
+ * PS_EINVAL for empty or unsorted axes or a non-finite time; PS_ENOMEM. */
+ps_status ps_profile_create(const int32_t* batch_sizes, int32_t n_batch, const int64_t* kv_sizes, int32_t n_kv,
+                            const float* ms, ps_profile** out);
+void ps_profile_destroy(ps_profile* p);
+
+/* (batch size, KV cache size) -> time (Sec. 4.4): bilinear interpolation between profiled points;
+ * below the first point of an axis the first point's value, beyond the last point the last
+ * interval extended linearly.  Returns NaN for a null profile. */
+double ps_profile_lookup(const ps_profile* p, double batch, double kv);
+
+/* A request running on a server: its KV cache length now and the tokens it has generated. */
+typedef struct {
+    int32_t kv_len;
+    int32_t generated;
+} ps_running_req;
+
+/* Sec. 4.4: simulate future iterations with every request predicted to generate avg_decode_len
+ * tokens in total (a request at or past that is predicted to generate one more), each growing
+ * by one token per iteration until it finishes; *max_kv = the largest total KV cache size attended
+ * in one iteration, *n_iters = iterations simulated.  new_prompt_len < 0: no new request. */
+ps_status ps_max_future_kv(const ps_running_req* running, int32_t n_running, int32_t new_prompt_len, int32_t avg_decode_len,
+                           int64_t* max_kv, int32_t* n_iters);
+
+/* Sec. 4.4 + 4.5: *predicted_ms = T(n_running + 1, largest future KV size) + wait_ms (the time the
+ * request would wait for the server's current iteration); *admit = predicted < tpot_ms. */
+ps_status ps_predict_admit(const ps_profile* p, const ps_running_req* running, int32_t n_running, int32_t new_prompt_len,
+                           int32_t avg_decode_len, double tpot_ms, double wait_ms, int32_t* admit, double* predicted_ms,
+                           int64_t* max_kv);
+
+/* Sec. 4.6, prefill instance.  prompts [n]: remaining prompt lengths in arrival order; budget:
+ * token budget of an iteration; first_iteration_used: tokens of other work already in the first
+ * iteration (0..budget).  Iterations are filled first come first served; a request is finished in
+ * the current iteration if it fits the room left, or (dynamic != 0) if the iteration then stays
+ * below twice the budget, which closes the iteration to further requests; otherwise it gets the
+ * room left.  Output: chunks as triples {iteration, request, tokens} in order, at most cap triples
+ * written, *n_chunks = the number there are, *n_iterations = iterations used. */
+ps_status ps_chunk_plan(const int32_t* prompts, int32_t n, int32_t budget, int32_t dynamic, int32_t first_iteration_used,
+                        int32_t* chunks, int32_t cap, int32_t* n_chunks, int32_t* n_iterations);
+
+/* Sec. 4.6, co-location.  The chunk size predicted at scheduling time is the largest c in
+ * [1, prompt_len] with T(n_running + c, KV now + c) < tpot_ms; it is kept for ceil(prompt / c)
+ * iterations while every running decode grows by one token per iteration (and leaves when predicted
+ * finished).  *admit = every one of those iterations stays below tpot_ms and wait_ms + their sum
+ * (= *first_token_ms) stays below ttft_ms.  No chunk fits: *admit = 0, *chunk = *n_iters = 0,
+ * *first_token_ms = +inf. */
+ps_status ps_predict_chunked_prefill(const ps_profile* p, const ps_running_req* running, int32_t n_running, int32_t prompt_len,
+                                     int32_t avg_decode_len, double tpot_ms, double ttft_ms, double wait_ms, int32_t* admit,
+                                     int32_t* chunk, int32_t* n_iters, double* first_token_ms);
+
+/* Sec. 3.4.  Decode instance of a prefill-decode disaggregated deployment: the largest batch size
+ * B <= b_max with T(B, B (p + d/2)) < tpot_ms and B (p + d/2) < capacity (KV tokens); 0 if none. */
+int32_t ps_batch_limit_pd(const ps_profile* prof, double p, double d, double tpot_ms, double capacity, int32_t b_max);
+/* Co-location with chunked prefill: the largest token batch size B <= b_max with
+ * T_iter = T(B, d/(p+d) B (p + d/2) + p) < tpot_ms, (p+d)/B * T_iter < ttft_ms and that KV size
+ * below capacity; 0 if none. */
+int32_t ps_batch_limit_co(const ps_profile* prof, double p, double d, double tpot_ms, double ttft_ms, double capacity, int32_t b_max);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

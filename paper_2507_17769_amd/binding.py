@@ -42,6 +42,10 @@ class ps_head_weights(C.Structure):
     _fields_ = [("embedding", C.c_void_p), ("g_final", C.c_void_p), ("w_out", C.c_void_p), ("vocab", C.c_int32)]
 
 
+class ps_running_req(C.Structure):
+    _fields_ = [("kv_len", C.c_int32), ("generated", C.c_int32)]
+
+
 class ps_seq(C.Structure):
     _fields_ = [("req_id", C.c_int64), ("n_new", C.c_int32), ("kv_len", C.c_int32),
                 ("page_table", C.POINTER(C.c_int32)), ("n_pages", C.c_int32)]
@@ -96,7 +100,23 @@ _SIGS = {
     "ps_profile_grid": (C.c_int, [_P, C.POINTER(ps_grid_cell_spec), C.c_int32, C.POINTER(ps_grid_opts), _P, _P,
                                   C.POINTER(ps_grid_cell)]),
 }
+_D = C.c_double
+_SCHED_SIGS = {
+    "ps_profile_create": (C.c_int, [_I32P, C.c_int32, C.POINTER(C.c_int64), C.c_int32, C.POINTER(C.c_float), C.POINTER(_P)]),
+    "ps_profile_destroy": (None, [_P]),
+    "ps_profile_lookup": (_D, [_P, _D, _D]),
+    "ps_max_future_kv": (C.c_int, [_P, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int64), _I32P]),
+    "ps_predict_admit": (C.c_int, [_P, _P, C.c_int32, C.c_int32, C.c_int32, _D, _D, _I32P, C.POINTER(_D), C.POINTER(C.c_int64)]),
+    "ps_chunk_plan": (C.c_int, [_I32P, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _I32P, C.c_int32, _I32P, _I32P]),
+    "ps_predict_chunked_prefill": (C.c_int, [_P, _P, C.c_int32, C.c_int32, C.c_int32, _D, _D, _D, _I32P, _I32P, _I32P, C.POINTER(_D)]),
+    "ps_batch_limit_pd": (C.c_int32, [_P, _D, _D, _D, _D, C.c_int32]),
+    "ps_batch_limit_co": (C.c_int32, [_P, _D, _D, _D, _D, _D, C.c_int32]),
+}
 EXPORTS = sorted(_SIGS)
+SCHED_EXPORTS = sorted(_SCHED_SIGS)
+for _name, (_res, _args) in _SCHED_SIGS.items():
+    _f = getattr(lib, _name)
+    _f.restype, _f.argtypes = _res, _args
 for _name, (_res, _args) in _SIGS.items():
     _f = getattr(lib, _name)
     _f.restype, _f.argtypes = _res, _args
@@ -252,3 +272,78 @@ class Context:
         opts = ps_grid_opts(warmup, iters)
         self._check(lib.ps_profile_grid(self.handle, specs, n, C.byref(opts), _P(x_in_ptr), _P(x_out_ptr), out))
         return [out[i] for i in range(n)]
+
+
+# ---- polysched: host-side consumers of the latency profile (include/polysched.h) -------------
+def _running(reqs):
+    arr = (ps_running_req * max(1, len(reqs)))()
+    for i, (kv, g) in enumerate(reqs):
+        arr[i].kv_len, arr[i].generated = int(kv), int(g)
+    return arr
+
+
+def _sched_check(status, what):
+    if status != PS_OK:
+        raise PolystepError(status, what)
+
+
+class Profile:
+    """(batch size, KV cache size) -> time table and the decisions taken with it."""
+
+    def __init__(self, batch_sizes, kv_sizes, ms):
+        b = np.ascontiguousarray(batch_sizes, dtype=np.int32)
+        k = np.ascontiguousarray(kv_sizes, dtype=np.int64)
+        t = np.ascontiguousarray(ms, dtype=np.float32).reshape(len(b), len(k))
+        h = _P()
+        _sched_check(lib.ps_profile_create(b.ctypes.data_as(_I32P), len(b), k.ctypes.data_as(C.POINTER(C.c_int64)), len(k),
+                                           t.ctypes.data_as(C.POINTER(C.c_float)), C.byref(h)), "ps_profile_create")
+        self.handle = h
+
+    def close(self):
+        if self.handle:
+            lib.ps_profile_destroy(self.handle)
+            self.handle = None
+
+    def lookup(self, batch, kv):
+        return lib.ps_profile_lookup(self.handle, float(batch), float(kv))
+
+    def predict_admit(self, running, new_prompt, avg_decode, tpot_ms, wait_ms=0.0):
+        admit, t, kv = C.c_int32(0), _D(0), C.c_int64(0)
+        _sched_check(lib.ps_predict_admit(self.handle, _running(running), len(running), int(new_prompt), int(avg_decode), float(tpot_ms),
+                                          float(wait_ms), C.byref(admit), C.byref(t), C.byref(kv)), "ps_predict_admit")
+        return bool(admit.value), t.value, kv.value
+
+    def predict_chunked_prefill(self, running, prompt, avg_decode, tpot_ms, ttft_ms, wait_ms=0.0):
+        admit, chunk, n, t = C.c_int32(0), C.c_int32(0), C.c_int32(0), _D(0)
+        _sched_check(lib.ps_predict_chunked_prefill(self.handle, _running(running), len(running), int(prompt), int(avg_decode), float(tpot_ms),
+                                                    float(ttft_ms), float(wait_ms), C.byref(admit), C.byref(chunk), C.byref(n), C.byref(t)),
+                     "ps_predict_chunked_prefill")
+        return bool(admit.value), chunk.value, n.value, t.value
+
+    def batch_limit_pd(self, p, d, tpot_ms, capacity, b_max=4096):
+        return lib.ps_batch_limit_pd(self.handle, float(p), float(d), float(tpot_ms), float(capacity), int(b_max))
+
+    def batch_limit_co(self, p, d, tpot_ms, ttft_ms, capacity, b_max=4096):
+        return lib.ps_batch_limit_co(self.handle, float(p), float(d), float(tpot_ms), float(ttft_ms), float(capacity), int(b_max))
+
+
+def max_future_kv(running, new_prompt, avg_decode):
+    kv, n = C.c_int64(0), C.c_int32(0)
+    _sched_check(lib.ps_max_future_kv(_running(running), len(running), -1 if new_prompt is None else int(new_prompt), int(avg_decode),
+                                      C.byref(kv), C.byref(n)), "ps_max_future_kv")
+    return kv.value, n.value
+
+
+def chunk_plan(prompts, budget, dynamic, first_iteration_used=0):
+    """-> list of iterations, each a list of (request, tokens)"""
+    pr = np.ascontiguousarray(prompts, dtype=np.int32)
+    n_chunks, n_iter = C.c_int32(0), C.c_int32(0)
+    _sched_check(lib.ps_chunk_plan(pr.ctypes.data_as(_I32P), len(pr), int(budget), int(bool(dynamic)), int(first_iteration_used), None, 0,
+                                   C.byref(n_chunks), C.byref(n_iter)), "ps_chunk_plan")
+    buf = np.zeros((max(1, n_chunks.value), 3), dtype=np.int32)
+    _sched_check(lib.ps_chunk_plan(pr.ctypes.data_as(_I32P), len(pr), int(budget), int(bool(dynamic)), int(first_iteration_used),
+                                   buf.ctypes.data_as(_I32P), n_chunks.value, C.byref(n_chunks), C.byref(n_iter)), "ps_chunk_plan")
+    out = [[] for _ in range(n_iter.value)]
+    for it, r, t in buf[:n_chunks.value].tolist():
+        out[it].append((r, t))
+    return out

@@ -5,6 +5,7 @@ roofline.traffic).
     python -m paper_2507_17769_amd.profile_summary trace  <kernel_trace.csv> <bench.json> <workload> <command> > profiles/<name>.md
     python -m paper_2507_17769_amd.profile_summary model  <bench_model8b.json> <command> > profiles/<name>.md
     python -m paper_2507_17769_amd.profile_summary prefill <bench_prefill.json> <command> > profiles/<name>.md
+    python -m paper_2507_17769_amd.profile_summary profile <bench_profile.json> <command> > profiles/<name>.md
     python -m paper_2507_17769_amd.profile_summary grid   <bench_grid.json> <command> > profiles/<name>.md
     python -m paper_2507_17769_amd.profile_summary counters <fetch.csv> <write.csv> <fetch_copy.csv> <write_copy.csv> \
             <workload> <seed> <md out> [--json]
@@ -198,7 +199,41 @@ def prefill_summary(prefill_json, command):
     return "\n".join(out) + "\n"
 
 
+def profile_summary(profile_json, command):
+    d = json.load(open(profile_json))
+    c, dec = d["config"], d["decisions"]
+    out = [f"# (batch size, KV cache size) -> iteration time — 8B-shaped model, {c['n_layers']} layers + head, one MI355X", "",
+           "The map the paper's router looks iteration times up in (Sec. 4.4), measured on decode batches of the whole model "
+           "(`ps_step_tokens`: embedding, all layers, output projection, greedy token), and the decisions `polysched` takes with it.", "",
+           f"Command:  `{command}`", "",
+           "Iteration time in ms (KV cache size = total cached tokens of the batch, split evenly over its requests; `-` = fewer than 16 "
+           "cached tokens per request, not measured; such cells take the nearest measured value of their row in the table handed to polysched):", "",
+           "| batch size \\ KV size | " + " | ".join(str(k) for k in d["kv_sizes"]) + " |", "|---|" + "---|" * len(d["kv_sizes"])]
+    for b, row in zip(d["batch_sizes"], d["ms"]):
+        out.append(f"| {b} | " + " | ".join("-" if v is None else f"{v:.3f}" for v in row) + " |")
+    out += ["", "Decisions taken with this table (lookups beyond batch 256 or 524288 KV tokens extend the last interval linearly):", "",
+            f"* KV capacity assumed for the memory bounds: {dec['kv_capacity_tokens']} tokens (288 GB minus weights and 8 GB of workspace, "
+            "131072 B per token over 32 layers).",
+            "* Largest decode batch of a disaggregated decode instance, `T(B, B (p + d/2)) < TPOT` and the KV bound (Sec. 3.4): "
+            + "; ".join(f"{k} -> {v}" for k, v in dec["batch_limit_pd"].items()) + ".",
+            "* Largest token batch under co-location, `T_iter < TPOT`, `(p+d)/B T_iter < TTFT` and the KV bound (Sec. 3.4): "
+            + "; ".join(f"{k} -> {v}" for k, v in dec["batch_limit_co"].items()) + ".",
+            "* Admitting a 64th request (prompt 1000) to a server with 63 running requests (KV 2000, 100 tokens generated, average "
+            "output 512): future iterations are simulated, the largest KV size is looked up with the current batch size, the wait for "
+            "the server's current iteration is added (Sec. 4.4, 4.5): "
+            + "; ".join(f"{k} -> admit {v[0]}, predicted {v[1]:.2f} ms at {v[2]} KV tokens" for k, v in dec["admit_64th_request"].items()) + ".",
+            "* The paper's worked example of Sec. 4.6 (2050-token prompt, budget 1024): "
+            + "; ".join(f"{k}: {v}" for k, v in dec["chunk_plan_2050_budget_1024"].items()) + ".",
+            "* A 2000-token prefill co-located with those 63 decodes (admit, chunk size kept for the whole prefill, iterations, predicted "
+            "time to first token in ms): "
+            + "; ".join(f"{k} -> {v[0]}, {v[1]}, {v[2]}, {v[3]:.1f}" for k, v in dec["chunked_prefill_2000_tokens_beside_63_decodes"].items()) + "."]
+    return "\n".join(out) + "\n"
+
+
 def main(argv):
+    if len(argv) >= 4 and argv[1] == "profile":
+        sys.stdout.write(profile_summary(argv[2], argv[3]))
+        return 0
     if len(argv) >= 4 and argv[1] == "prefill":
         sys.stdout.write(prefill_summary(argv[2], argv[3]))
         return 0
