@@ -41,6 +41,31 @@ def test_ragged_shapes_tiny_model(chunk, prefix, decodes):
     c.close()
 
 
+def test_long_contexts_tiny_model():
+    """KV spans of thousands of pages: many 64-page blocks per work item, one sequence cut over hundreds of
+    workers (merge groups with far more than eight partials), rotary positions up to 1e5."""
+    b = W.custom_batch("tiny", 31, 40, 70000, [100001, 65537, 1025], name="long")
+    c = Case(b)
+    errs = c.run()
+    print("long-context errors", errs, flush=True)
+    _assert_errs(errs, "long contexts")
+    c.check_pool()
+    c.close()
+
+
+def test_many_short_decodes_tiny_model():
+    """700 one-token requests with 1..50 cached tokens: more sequences than attention workers would each get a
+    page pair of, every work item a whole sequence, and a token count that is no multiple of any tile."""
+    kv = 1 + (np.arange(700) * 37) % 50
+    b = W.custom_batch("tiny", 41, 0, 0, kv, name="many")
+    c = Case(b)
+    errs = c.run()
+    print("many-decodes errors", {k: round(v, 5) for k, v in errs.items()}, flush=True)
+    _assert_errs(errs, "many short decodes")
+    c.check_pool()
+    c.close()
+
+
 def test_unit_scale_branches():
     # weights of std 1/sqrt(hidden) make the attention and FFN branches as large as the residual
     # stream, so an error in the O or down projection cannot hide behind it in `out`
