@@ -203,3 +203,27 @@ def grid_cell_lengths(chunk, n_decode, seed):
 def grid_cell_batch(chunk, n_decode, seed, model="8b"):
     off, kv = grid_cell_lengths(chunk, n_decode, seed)
     return custom_batch(model, seed, chunk, off, kv, name=f"grid_c{chunk}_d{n_decode}", tag=chunk * 1000 + n_decode)
+
+
+SIM_TPOTS_MS = (20.0, 30.0, 50.0, 100.0)
+SIM_TTFTS_MS = (300.0, 500.0, 1000.0)
+SIM_TIER_PROBS = (0.1, 0.2, 0.3, 0.4)
+
+
+def sim_trace(seed, n, rate_per_ms, max_prompt, max_output, burst=False):
+    """Synthetic request trace of the paper's kind (Sec. 5.1, 5.3): Poisson arrivals at rate_per_ms, input lengths
+    uniform in [1, max_prompt] and output lengths uniform in [1, max_output] (`uniform_512_512` = 1024 / 1024,
+    `uniform_4096_1024` = 8192 / 2048), TTFT drawn uniformly from 300 / 500 / 1000 ms, TPOT tier 20 / 30 / 50 / 100 ms
+    with probabilities 10 / 20 / 30 / 40 %; burst: the second half of the requests draws the tiers with the
+    probabilities reversed.  Returns plain lists."""
+    rng = np.random.Generator(np.random.PCG64([int(seed), 67867967, int(n)]))
+    arrival = np.cumsum(rng.exponential(1.0 / float(rate_per_ms), n))
+    prompt = rng.integers(1, max_prompt, size=n, endpoint=True)
+    output = rng.integers(1, max_output, size=n, endpoint=True)
+    ttft = rng.choice(np.array(SIM_TTFTS_MS), size=n)
+    tier = rng.choice(len(SIM_TPOTS_MS), size=n, p=SIM_TIER_PROBS)
+    if burst:
+        late = rng.choice(len(SIM_TPOTS_MS), size=n, p=SIM_TIER_PROBS[::-1])
+        tier[n // 2:] = late[n // 2:]
+    return {"arrival": arrival.tolist(), "prompt": prompt.tolist(), "output": output.tolist(), "ttft": ttft.tolist(),
+            "tier": tier.tolist()}
