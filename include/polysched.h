@@ -76,6 +76,59 @@ int32_t ps_batch_limit_pd(const ps_profile* prof, double p, double d, double tpo
  * below capacity; 0 if none. */
 int32_t ps_batch_limit_co(const ps_profile* prof, double p, double d, double tpot_ms, double ttft_ms, double capacity, int32_t b_max);
 
+/* ---- Cluster simulation (Sec. 5.1) of the router of Sec. 4 on co-located instances --------------
+ *
+ * Instances advance in steps of 1 ms; an iteration's duration is the profile's value for (tokens in the
+ * iteration, KV tokens attended).  In every step, in this order: iterations whose end time has been
+ * reached deliver their tokens at that end time; arrived requests join the queue of their tier; every
+ * check_period_ms steps the scale-down check runs; the queues are served, tightest tier first, first come
+ * first served; instances outside an iteration that hold requests start one.
+ * An iteration holds one token per request in decode and the next chunk of the one request in prefill (an
+ * instance takes a new request only while no prefill is in progress on it); the prefill's last chunk
+ * produces token 0, a request with output_len d then takes d - 1 decode iterations.  Token i is due at
+ * arrival + TTFT + i * (the request's own TPOT) (Sec. 2.3); a request is attained if every token is.
+ * Placement (Sec. 4.2, 4.3): the request's own cluster, then the clusters of tighter tiers from the
+ * nearest one (lazy promotion), each from the instance with most requests down, then scale-up (a parked
+ * instance whose tightest request is of this tier, else an instance from the idle pool); an instance
+ * admits the request if ps_predict_chunked_prefill admits it against the instance's TPOT, the time left to
+ * the first-token deadline and the wait for the iteration in flight, ps_predict_admit keeps the largest
+ * future KV size's iteration below that TPOT, and that KV size is below kv_capacity.  A request that cannot
+ * be placed keeps its place in the queue while it could still make its first token on an empty instance
+ * and is dropped (not attained, never served) once it could not.
+ * Scale-down check, per cluster: the instance with fewest requests returns to the idle pool if empty and
+ * is parked if none of its requests is of the cluster's tier; a parked instance takes no requests and
+ * returns to the pool once empty.  cost_ms = instance time outside the idle pool (Sec. 5.4). */
+typedef struct {
+    int32_t n_servers;
+    int32_t n_tiers;
+    const double* tpot_ms;    /* [n_tiers], strictly ascending */
+    int32_t avg_decode_len;   /* the router's output-length prediction (Sec. 4.4) */
+    double kv_capacity;       /* KV tokens per instance */
+    int32_t check_period_ms;
+    int64_t max_steps;        /* the run stops after this many steps even if requests are unfinished */
+} ps_sim_config;
+
+typedef struct {
+    double arrival_ms;
+    int32_t prompt_len, output_len;
+    double ttft_ms;
+    int32_t tier;
+} ps_sim_request;
+
+typedef struct {
+    int64_t end_ms;           /* steps simulated */
+    double cost_ms;
+    int64_t scale_ups, scale_downs, promotions, dropped;
+    int64_t iterations;       /* instance iterations completed */
+    int64_t admission_tests;  /* (request, instance) pairs examined by the router */
+} ps_sim_summary;
+
+/* requests [n] sorted by arrival.  Per-request outputs (each may be null): attained (0/1), time of the
+ * first token and of the last one (-1 if never produced), the instance the request was placed on (-1 if
+ * dropped or still queued at the end).  PS_EINVAL for malformed arguments; PS_ENOMEM. */
+ps_status ps_sim_run(const ps_profile* profile, const ps_sim_config* cfg, const ps_sim_request* requests, int32_t n,
+                     uint8_t* attained, double* first_token_ms, double* finish_ms, int32_t* server, ps_sim_summary* summary);
+
 #ifdef __cplusplus
 }
 #endif

@@ -42,6 +42,21 @@ class ps_head_weights(C.Structure):
     _fields_ = [("embedding", C.c_void_p), ("g_final", C.c_void_p), ("w_out", C.c_void_p), ("vocab", C.c_int32)]
 
 
+class ps_sim_config(C.Structure):
+    _fields_ = [("n_servers", C.c_int32), ("n_tiers", C.c_int32), ("tpot_ms", C.POINTER(C.c_double)), ("avg_decode_len", C.c_int32),
+                ("kv_capacity", C.c_double), ("check_period_ms", C.c_int32), ("max_steps", C.c_int64)]
+
+
+class ps_sim_request(C.Structure):
+    _fields_ = [("arrival_ms", C.c_double), ("prompt_len", C.c_int32), ("output_len", C.c_int32), ("ttft_ms", C.c_double),
+                ("tier", C.c_int32)]
+
+
+class ps_sim_summary(C.Structure):
+    _fields_ = [("end_ms", C.c_int64), ("cost_ms", C.c_double), ("scale_ups", C.c_int64), ("scale_downs", C.c_int64),
+                ("promotions", C.c_int64), ("dropped", C.c_int64), ("iterations", C.c_int64), ("admission_tests", C.c_int64)]
+
+
 class ps_running_req(C.Structure):
     _fields_ = [("kv_len", C.c_int32), ("generated", C.c_int32)]
 
@@ -111,6 +126,7 @@ _SCHED_SIGS = {
     "ps_predict_chunked_prefill": (C.c_int, [_P, _P, C.c_int32, C.c_int32, C.c_int32, _D, _D, _D, _I32P, _I32P, _I32P, C.POINTER(_D)]),
     "ps_batch_limit_pd": (C.c_int32, [_P, _D, _D, _D, _D, C.c_int32]),
     "ps_batch_limit_co": (C.c_int32, [_P, _D, _D, _D, _D, _D, C.c_int32]),
+    "ps_sim_run": (C.c_int, [_P, _P, _P, C.c_int32, _P, _P, _P, _P, _P]),
 }
 EXPORTS = sorted(_SIGS)
 SCHED_EXPORTS = sorted(_SCHED_SIGS)
@@ -319,6 +335,24 @@ class Profile:
                                                     float(ttft_ms), float(wait_ms), C.byref(admit), C.byref(chunk), C.byref(n), C.byref(t)),
                      "ps_predict_chunked_prefill")
         return bool(admit.value), chunk.value, n.value, t.value
+
+    def simulate(self, arrival, prompt, output, ttft, tier, tpots, n_servers, avg_decode, kv_capacity, check_period=1000,
+                 max_steps=10 ** 9):
+        """ps_sim_run on parallel per-request sequences; returns a dict with the per-request arrays and the summary."""
+        n = len(arrival)
+        reqs = (ps_sim_request * max(1, n))()
+        for i in range(n):
+            reqs[i] = ps_sim_request(float(arrival[i]), int(prompt[i]), int(output[i]), float(ttft[i]), int(tier[i]))
+        tp = (C.c_double * len(tpots))(*[float(t) for t in tpots])
+        cfg = ps_sim_config(int(n_servers), len(tpots), tp, int(avg_decode), float(kv_capacity), int(check_period), int(max_steps))
+        att = np.zeros(n, dtype=np.uint8)
+        first, fin, srv = np.zeros(n), np.zeros(n), np.zeros(n, dtype=np.int32)
+        summ = ps_sim_summary()
+        _sched_check(lib.ps_sim_run(self.handle, C.byref(cfg), reqs, n, att.ctypes.data, first.ctypes.data, fin.ctypes.data,
+                                    srv.ctypes.data, C.byref(summ)), "ps_sim_run")
+        out = {name: getattr(summ, name) for name, _ in ps_sim_summary._fields_}
+        out.update(attained=att, first_token_ms=first, finish_ms=fin, server=srv)
+        return out
 
     def batch_limit_pd(self, p, d, tpot_ms, capacity, b_max=4096):
         return lib.ps_batch_limit_pd(self.handle, float(p), float(d), float(tpot_ms), float(capacity), int(b_max))

@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpolystep.so")
-SOURCES = ["api.hip", "planner.cpp", "policy.cpp", "small_kernels.hip", "gemm.hip", "attention.hip"]
+SOURCES = ["api.hip", "planner.cpp", "policy.cpp", "sim.cpp", "small_kernels.hip", "gemm.hip", "attention.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",

@@ -1,0 +1,302 @@
+// Cluster simulator for the paper's router on co-located (chunked-prefill) serving instances
+// (Sec. 5.1: instances advance in 1 ms steps with iteration times taken from the
+// (batch size, KV cache size) -> time table; Sec. 4.1-4.6: one cluster per TPOT tier, highest-load
+// instance first, lazy promotion onto tighter tiers, scaling from and to an idle pool, admission by
+// predicted future KV size and by the chunk size that can be kept for the whole prefill with the wait
+// for the iteration in flight; Sec. 2.3: token i of a request is due at arrival + TTFT + i * TPOT).
+// Host only.  The decisions themselves are the ones exported by policy.cpp.
+#include <algorithm>
+#include <cstdint>
+#include <deque>
+#include <new>
+#include <utility>
+#include <vector>
+
+#include "../../include/polysched.h"
+
+namespace {
+
+enum Phase { QUEUED = 0, PREFILL = 1, DECODE = 2, DONE = 3 };
+enum State { POOL = 0, ACTIVE = 1, PENDING = 2 };
+
+struct Request {
+    double arrival, ttft;
+    int32_t prompt, output, tier;
+    int32_t chunk = 0, prefilled = 0, generated = 0, kv_len = 0;
+    int32_t first_server = -1;
+    int phase = QUEUED;
+    bool violated = false;
+    double first_token = -1.0, finish = -1.0;
+};
+
+struct Instance {
+    int32_t id = 0;
+    int state = POOL;
+    int32_t tier = -1;
+    int64_t joined = -1;              // order of joining a cluster: the tie-break of the load order
+    std::vector<int32_t> reqs;        // in admission order
+    bool in_iteration = false;
+    double busy_until = 0.0;
+    std::vector<std::pair<int32_t, int32_t>> batch;  // (request, tokens) of the iteration in flight
+    double since = 0.0;               // when it last left the idle pool
+};
+
+struct Sim {
+    const ps_profile* prof;
+    const ps_sim_config& cfg;
+    std::vector<Request> reqs;
+    std::vector<Instance> inst;
+    std::vector<std::deque<int32_t>> queues;
+    ps_sim_summary sum{};
+    double cost = 0.0;
+    int64_t join_counter = 0;
+    std::vector<ps_running_req> run;   // scratch: the decodes of the instance under test
+    std::vector<Instance*> cand;       // scratch: candidate list
+
+    Sim(const ps_profile* p, const ps_sim_config& c) : prof(p), cfg(c) {}
+
+    // chunk size the instance would keep for the request's prefill, 0 = not admitted
+    int32_t admits(const Instance& s, const Request& r, int64_t now) {
+        run.clear();
+        for (int32_t i : s.reqs) {
+            if (reqs[i].phase == PREFILL) return 0;  // one prefill at a time
+            run.push_back(ps_running_req{reqs[i].kv_len, reqs[i].generated});
+        }
+        const double tpot = cfg.tpot_ms[s.tier];
+        const double wait = s.in_iteration ? std::max(0.0, s.busy_until - (double)now) : 0.0;
+        int32_t ok = 0, chunk = 0, n_it = 0;
+        double t_first = 0.0;
+        sum.admission_tests++;
+        if (ps_predict_chunked_prefill(prof, run.data(), (int32_t)run.size(), r.prompt, cfg.avg_decode_len, tpot,
+                                       r.arrival + r.ttft - (double)now, wait, &ok, &chunk, &n_it, &t_first) != PS_OK || !ok)
+            return 0;
+        int32_t ok2 = 0;
+        double predicted = 0.0;
+        int64_t kv = 0;
+        if (ps_predict_admit(prof, run.data(), (int32_t)run.size(), r.prompt, cfg.avg_decode_len, tpot, 0.0, &ok2, &predicted, &kv) != PS_OK ||
+            !ok2 || !((double)kv < cfg.kv_capacity))
+            return 0;
+        return chunk;
+    }
+
+    // highest load first; among equals the instance that joined its cluster first
+    static void by_load(std::vector<Instance*>& v, size_t from = 0) {
+        std::stable_sort(v.begin() + from, v.end(), [](const Instance* a, const Instance* b) {
+            if (a->reqs.size() != b->reqs.size()) return a->reqs.size() > b->reqs.size();
+            return a->joined < b->joined;
+        });
+    }
+
+    Instance* place(const Request& r, int64_t now, int32_t* chunk) {
+        for (int32_t t = r.tier; t >= 0; t--) {  // own cluster, then the tighter ones from the nearest
+            cand.clear();
+            for (Instance& s : inst)
+                if (s.state == ACTIVE && s.tier == t) cand.push_back(&s);
+            by_load(cand);
+            for (Instance* s : cand) {
+                const int32_t c = admits(*s, r, now);
+                if (c) {
+                    if (t != r.tier) sum.promotions++;
+                    *chunk = c;
+                    return s;
+                }
+            }
+        }
+        // scale up: a parked instance whose tightest request is of this tier, else one from the idle pool
+        cand.clear();
+        for (Instance& s : inst) {
+            if (s.state != PENDING) continue;
+            int32_t tightest = INT32_MAX;
+            for (int32_t i : s.reqs) tightest = std::min(tightest, reqs[i].tier);
+            if (tightest == r.tier) cand.push_back(&s);
+        }
+        by_load(cand);
+        for (Instance& s : inst)
+            if (s.state == POOL) cand.push_back(&s);
+        for (Instance* s : cand) {
+            const int was = s->state;
+            const int32_t old_tier = s->tier;
+            s->tier = r.tier;
+            s->state = ACTIVE;
+            const int32_t c = admits(*s, r, now);
+            if (c) {
+                if (was == POOL) s->since = (double)now;
+                s->joined = join_counter++;
+                sum.scale_ups++;
+                *chunk = c;
+                return s;
+            }
+            s->tier = old_tier;
+            s->state = was;
+            if (was == POOL) break;  // every idle instance gives the same answer
+        }
+        return nullptr;
+    }
+
+    void to_pool(Instance& s, int64_t now) {
+        cost += (double)now - s.since;
+        s.state = POOL;
+        s.tier = -1;
+        s.joined = -1;
+        sum.scale_downs++;
+    }
+
+    void run_all() {
+        const int32_t n = (int32_t)reqs.size();
+        int32_t next_arrival = 0, done = 0;
+        int64_t now = 0;
+        while (done < n && now < cfg.max_steps) {
+            // iterations that have ended deliver their tokens at their end time
+            for (Instance& s : inst) {
+                if (!s.in_iteration || !(s.busy_until <= (double)now)) continue;
+                const double t_end = s.busy_until;
+                for (const auto& bt : s.batch) {
+                    Request& r = reqs[bt.first];
+                    if (r.phase == PREFILL) {
+                        r.prefilled += bt.second;
+                        if (r.prefilled < r.prompt) continue;
+                        r.phase = DECODE;
+                        r.kv_len = r.prompt;
+                        r.generated = 1;
+                        r.first_token = t_end;
+                    } else {
+                        r.kv_len++;
+                        r.generated++;
+                    }
+                    if (t_end > r.arrival + r.ttft + (double)(r.generated - 1) * cfg.tpot_ms[r.tier]) r.violated = true;
+                    if (r.generated == r.output) {
+                        r.phase = DONE;
+                        r.finish = t_end;
+                        s.reqs.erase(std::find(s.reqs.begin(), s.reqs.end(), bt.first));
+                        done++;
+                    }
+                }
+                s.in_iteration = false;
+                s.batch.clear();
+                sum.iterations++;
+            }
+            for (Instance& s : inst)
+                if (s.state == PENDING && s.reqs.empty()) to_pool(s, now);
+            // arrivals
+            while (next_arrival < n && reqs[next_arrival].arrival <= (double)now) {
+                queues[reqs[next_arrival].tier].push_back(next_arrival);
+                next_arrival++;
+            }
+            // scale-down check: the lowest-load instance of every cluster
+            if (now % cfg.check_period_ms == 0) {
+                for (int32_t t = 0; t < cfg.n_tiers; t++) {
+                    Instance* last = nullptr;
+                    for (Instance& s : inst) {
+                        if (s.state != ACTIVE || s.tier != t) continue;
+                        if (!last || s.reqs.size() < last->reqs.size() || (s.reqs.size() == last->reqs.size() && s.joined > last->joined))
+                            last = &s;
+                    }
+                    if (!last) continue;
+                    if (last->reqs.empty()) {
+                        to_pool(*last, now);
+                    } else {
+                        bool own = false;
+                        for (int32_t i : last->reqs) own = own || reqs[i].tier == t;
+                        if (!own) last->state = PENDING;
+                    }
+                }
+            }
+            // routing: tightest tier first, first come first served
+            for (auto& q : queues) {
+                while (!q.empty()) {
+                    Request& r = reqs[q.front()];
+                    int32_t chunk = 0;
+                    Instance* s = place(r, now, &chunk);
+                    if (!s) {
+                        int32_t ok = 0, c = 0, n_it = 0;
+                        double t_first = 0.0;
+                        ps_predict_chunked_prefill(prof, nullptr, 0, r.prompt, cfg.avg_decode_len, cfg.tpot_ms[r.tier],
+                                                   r.arrival + r.ttft - (double)now, 0.0, &ok, &c, &n_it, &t_first);
+                        if (ok) break;  // it can still make its first token on an empty instance: keep its place
+                        q.pop_front();
+                        r.phase = DONE;
+                        r.violated = true;
+                        sum.dropped++;
+                        done++;
+                        continue;
+                    }
+                    r.first_server = s->id;
+                    r.chunk = chunk;
+                    r.phase = PREFILL;
+                    s->reqs.push_back(q.front());
+                    q.pop_front();
+                }
+            }
+            // instances outside an iteration that hold requests start one
+            for (Instance& s : inst) {
+                if (s.in_iteration || s.reqs.empty()) continue;
+                int64_t tokens = 0, kv = 0;
+                for (int32_t i : s.reqs) {
+                    const Request& r = reqs[i];
+                    if (r.phase == DECODE) {
+                        s.batch.emplace_back(i, 1);
+                        tokens += 1;
+                        kv += r.kv_len + 1;
+                    } else {
+                        const int32_t c = std::min(r.chunk, r.prompt - r.prefilled);
+                        s.batch.emplace_back(i, c);
+                        tokens += c;
+                        kv += r.prefilled + c;
+                    }
+                }
+                s.busy_until = (double)now + ps_profile_lookup(prof, (double)tokens, (double)kv);
+                s.in_iteration = true;
+            }
+            now++;
+        }
+        for (Instance& s : inst)
+            if (s.state != POOL) cost += (double)now - s.since;
+        sum.end_ms = now;
+        sum.cost_ms = cost;
+    }
+};
+
+}  // namespace
+
+extern "C" ps_status ps_sim_run(const ps_profile* profile, const ps_sim_config* cfg, const ps_sim_request* requests, int32_t n,
+                                uint8_t* attained, double* first_token_ms, double* finish_ms, int32_t* server,
+                                ps_sim_summary* summary) {
+    if (!profile || !cfg || n < 0 || (n > 0 && !requests) || !summary) return PS_EINVAL;
+    if (cfg->n_servers < 1 || cfg->n_tiers < 1 || !cfg->tpot_ms || cfg->avg_decode_len < 1 || cfg->check_period_ms < 1 || cfg->max_steps < 0)
+        return PS_EINVAL;
+    for (int32_t t = 0; t < cfg->n_tiers; t++)
+        if (!(cfg->tpot_ms[t] > 0.0) || (t > 0 && !(cfg->tpot_ms[t - 1] < cfg->tpot_ms[t]))) return PS_EINVAL;
+    for (int32_t i = 0; i < n; i++) {
+        const ps_sim_request& q = requests[i];
+        if (q.prompt_len < 1 || q.output_len < 1 || q.tier < 0 || q.tier >= cfg->n_tiers || !(q.ttft_ms > 0.0) || !(q.arrival_ms >= 0.0))
+            return PS_EINVAL;
+        if (i > 0 && q.arrival_ms < requests[i - 1].arrival_ms) return PS_EINVAL;
+    }
+    try {
+        Sim sim(profile, *cfg);
+        sim.reqs.resize(n);
+        for (int32_t i = 0; i < n; i++) {
+            Request& r = sim.reqs[i];
+            r.arrival = requests[i].arrival_ms;
+            r.ttft = requests[i].ttft_ms;
+            r.prompt = requests[i].prompt_len;
+            r.output = requests[i].output_len;
+            r.tier = requests[i].tier;
+        }
+        sim.inst.resize(cfg->n_servers);
+        for (int32_t s = 0; s < cfg->n_servers; s++) sim.inst[s].id = s;
+        sim.queues.resize(cfg->n_tiers);
+        sim.run_all();
+        for (int32_t i = 0; i < n; i++) {
+            const Request& r = sim.reqs[i];
+            if (attained) attained[i] = (r.phase == DONE && !r.violated) ? 1 : 0;
+            if (first_token_ms) first_token_ms[i] = r.first_token;
+            if (finish_ms) finish_ms[i] = r.finish;
+            if (server) server[i] = r.first_server;
+        }
+        *summary = sim.sum;
+    } catch (const std::bad_alloc&) {
+        return PS_ENOMEM;
+    }
+    return PS_OK;
+}

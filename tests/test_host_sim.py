@@ -1,0 +1,72 @@
+"""ps_sim_run (C++, through the C ABI) against the simulator oracle: every per-request output and every counter
+identical, on traces that reach queueing, drops, promotion, parking and scale-down."""
+import numpy as np
+import pytest
+
+from oracle import policy as opol
+from oracle import sim as osim
+from paper_2507_17769_amd import binding as B
+from paper_2507_17769_amd import workloads as W
+
+BS = (1, 16, 64, 256, 1024, 4096)
+KS = (16, 4096, 65536, 1048576)
+
+
+def tables(fn):
+    ms = np.array([[fn(b, k) for k in KS] for b in BS], dtype=np.float32)  # the C table stores float32
+    return B.Profile(BS, KS, ms), opol.Profile(BS, KS, ms.astype(np.float64).tolist())
+
+
+def compare(got, want, n):
+    for name in ("end_ms", "cost_ms", "scale_ups", "scale_downs", "promotions", "dropped"):
+        assert got[name] == want[name], (name, got[name], want[name])
+    assert got["attained"].tolist() == want["attained"]
+    assert got["server"].tolist() == want["server"]
+    assert got["first_token_ms"].tolist() == want["first_token_ms"]   # doubles, bit for bit
+    assert got["finish_ms"].tolist() == want["finish_ms"]
+
+
+@pytest.mark.parametrize("seed,n_servers,rate,max_prompt,max_output,avg,period,cap,burst", [
+    (0, 4, 0.03, 1024, 256, 128, 200, 2e6, False),
+    (1, 2, 0.5, 1024, 256, 128, 200, 2e6, False),       # overloaded: queues and drops
+    (2, 8, 0.06, 1024, 256, 128, 50, 2e6, True),        # frequent scale-down checks, tier mix flips half way
+    (3, 3, 0.02, 8192, 512, 256, 100, 60000.0, False),  # KV capacity binds
+    (4, 20, 0.25, 1024, 256, 128, 1000, 2e6, False),
+])
+def test_simulator_matches_the_oracle(seed, n_servers, rate, max_prompt, max_output, avg, period, cap, burst):
+    gp, op = tables(lambda b, k: 4.0 + 0.012 * b + 2e-5 * k)
+    n = 300
+    tr = W.sim_trace(seed, n, rate, max_prompt, max_output, burst=burst)
+    args = (tr["arrival"], tr["prompt"], tr["output"], tr["ttft"], tr["tier"], list(W.SIM_TPOTS_MS), n_servers, avg, cap, period)
+    want = osim.simulate(op, *args)
+    got = gp.simulate(*args)
+    print({k: v for k, v in want.items() if not isinstance(v, list)}, "attained", sum(want["attained"]))
+    compare(got, want, n)
+    gp.close()
+
+
+def test_simulator_paths_are_all_reached_by_the_comparison_cases():
+    """The cases above are only worth something if they reach the branches; checked on the oracle."""
+    _, op = tables(lambda b, k: 4.0 + 0.012 * b + 2e-5 * k)
+    seen = {"dropped": 0, "promotions": 0, "scale_downs": 0}
+    for seed, n_servers, rate, burst, period in ((1, 2, 0.5, False, 200), (2, 8, 0.06, True, 50)):
+        tr = W.sim_trace(seed, 300, rate, 1024, 256, burst=burst)
+        res = osim.simulate(op, tr["arrival"], tr["prompt"], tr["output"], tr["ttft"], tr["tier"], list(W.SIM_TPOTS_MS), n_servers, 128, 2e6, period)
+        for k in seen:
+            seen[k] += res[k]
+    assert all(v > 0 for v in seen.values()), seen
+
+
+def test_simulator_stops_at_max_steps_and_rejects_malformed_input():
+    gp, op = tables(lambda b, k: 7.0)
+    args = ([0.0, 5.0], [100, 100], [1000, 1000], [300.0, 300.0], [0, 1], [20.0, 50.0], 2, 100, 1e9, 100)
+    got, want = gp.simulate(*args, max_steps=500), osim.simulate(op, *args, max_steps=500)
+    assert got["end_ms"] == 500
+    compare(got, want, 2)
+    with pytest.raises(B.PolystepError):
+        gp.simulate([5.0, 0.0], [1, 1], [1, 1], [300.0, 300.0], [0, 0], [20.0], 1, 1, 1e9)      # arrivals not sorted
+    with pytest.raises(B.PolystepError):
+        gp.simulate([0.0], [1], [1], [300.0], [1], [20.0], 1, 1, 1e9)                            # tier out of range
+    with pytest.raises(B.PolystepError):
+        gp.simulate([0.0], [1], [1], [300.0], [0], [50.0, 20.0], 1, 1, 1e9)                      # tiers not ascending
+    gp.close()
