@@ -97,8 +97,25 @@ int32_t ps_batch_limit_co(const ps_profile* prof, double p, double d, double tpo
  * and is dropped (not attained, never served) once it could not.
  * Scale-down check, per cluster: the instance with fewest requests returns to the idle pool if empty and
  * is parked if none of its requests is of the cluster's tier; a parked instance takes no requests and
- * returns to the pool once empty.  cost_ms = instance time outside the idle pool (Sec. 5.4). */
+ * returns to the pool once empty.  cost_ms = instance time outside the idle pool (Sec. 5.4).
+ *
+ * PS_SIM_DISAGGREGATED differs as follows.  Prefill runs on a cluster of its own, shared by all tiers:
+ * queued requests are taken in order of arrival + TTFT (Sec. 4.1); a prefill instance forms its iterations
+ * with ps_chunk_plan (dynamic, prefill_budget) over its requests in admission order; a request goes to the
+ * prefill instance with most unprocessed prompt tokens whose predicted end of the request's prefill (the
+ * wait for the iteration in flight plus the planned iterations up to the request's last chunk) is before
+ * the first-token deadline, else to an instance from the idle pool.  The prefill's end delivers token 0
+ * and queues the request for decoding (the transfer takes no time); decode clusters work as above except
+ * that an instance admits the request if ps_predict_admit keeps the largest future KV size's iteration
+ * below the instance's TPOT, that KV size is below kv_capacity, and the wait for the iteration in flight
+ * plus that iteration time is before the second token's deadline, arrival + TTFT + TPOT (Sec. 4.5).  Step
+ * order: ended iterations, arrivals, scale-down check (also returning the least loaded prefill instance if
+ * it holds no request), decode queues, prefill queue, iteration starts.  A queued request is dropped once
+ * an empty instance could no longer meet its next deadline (first token before prefill, second after). */
+enum { PS_SIM_COLOCATED = 0, PS_SIM_DISAGGREGATED = 1 };
+
 typedef struct {
+    int32_t mode;             /* PS_SIM_COLOCATED or PS_SIM_DISAGGREGATED */
     int32_t n_servers;
     int32_t n_tiers;
     const double* tpot_ms;    /* [n_tiers], strictly ascending */
@@ -106,6 +123,7 @@ typedef struct {
     double kv_capacity;       /* KV tokens per instance */
     int32_t check_period_ms;
     int64_t max_steps;        /* the run stops after this many steps even if requests are unfinished */
+    int32_t prefill_budget;   /* disaggregated: token budget of a prefill iteration (Sec. 4.6) */
 } ps_sim_config;
 
 typedef struct {
@@ -124,10 +142,12 @@ typedef struct {
 } ps_sim_summary;
 
 /* requests [n] sorted by arrival.  Per-request outputs (each may be null): attained (0/1), time of the
- * first token and of the last one (-1 if never produced), the instance the request was placed on (-1 if
- * dropped or still queued at the end).  PS_EINVAL for malformed arguments; PS_ENOMEM. */
+ * first token and of the last one (-1 if never produced), the instance that ran the prefill and the one
+ * that ran the decode iterations (the same when co-located; -1 if never placed).  PS_EINVAL for malformed
+ * arguments; PS_ENOMEM. */
 ps_status ps_sim_run(const ps_profile* profile, const ps_sim_config* cfg, const ps_sim_request* requests, int32_t n,
-                     uint8_t* attained, double* first_token_ms, double* finish_ms, int32_t* server, ps_sim_summary* summary);
+                     uint8_t* attained, double* first_token_ms, double* finish_ms, int32_t* server, int32_t* decode_server,
+                     ps_sim_summary* summary);
 
 #ifdef __cplusplus
 }

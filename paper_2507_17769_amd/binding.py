@@ -43,8 +43,9 @@ class ps_head_weights(C.Structure):
 
 
 class ps_sim_config(C.Structure):
-    _fields_ = [("n_servers", C.c_int32), ("n_tiers", C.c_int32), ("tpot_ms", C.POINTER(C.c_double)), ("avg_decode_len", C.c_int32),
-                ("kv_capacity", C.c_double), ("check_period_ms", C.c_int32), ("max_steps", C.c_int64)]
+    _fields_ = [("mode", C.c_int32), ("n_servers", C.c_int32), ("n_tiers", C.c_int32), ("tpot_ms", C.POINTER(C.c_double)),
+                ("avg_decode_len", C.c_int32), ("kv_capacity", C.c_double), ("check_period_ms", C.c_int32), ("max_steps", C.c_int64),
+                ("prefill_budget", C.c_int32)]
 
 
 class ps_sim_request(C.Structure):
@@ -126,7 +127,7 @@ _SCHED_SIGS = {
     "ps_predict_chunked_prefill": (C.c_int, [_P, _P, C.c_int32, C.c_int32, C.c_int32, _D, _D, _D, _I32P, _I32P, _I32P, C.POINTER(_D)]),
     "ps_batch_limit_pd": (C.c_int32, [_P, _D, _D, _D, _D, C.c_int32]),
     "ps_batch_limit_co": (C.c_int32, [_P, _D, _D, _D, _D, _D, C.c_int32]),
-    "ps_sim_run": (C.c_int, [_P, _P, _P, C.c_int32, _P, _P, _P, _P, _P]),
+    "ps_sim_run": (C.c_int, [_P, _P, _P, C.c_int32, _P, _P, _P, _P, _P, _P]),
 }
 EXPORTS = sorted(_SIGS)
 SCHED_EXPORTS = sorted(_SCHED_SIGS)
@@ -337,21 +338,23 @@ class Profile:
         return bool(admit.value), chunk.value, n.value, t.value
 
     def simulate(self, arrival, prompt, output, ttft, tier, tpots, n_servers, avg_decode, kv_capacity, check_period=1000,
-                 max_steps=10 ** 9):
+                 max_steps=10 ** 9, disaggregated=False, prefill_budget=0):
         """ps_sim_run on parallel per-request sequences; returns a dict with the per-request arrays and the summary."""
         n = len(arrival)
         reqs = (ps_sim_request * max(1, n))()
         for i in range(n):
             reqs[i] = ps_sim_request(float(arrival[i]), int(prompt[i]), int(output[i]), float(ttft[i]), int(tier[i]))
         tp = (C.c_double * len(tpots))(*[float(t) for t in tpots])
-        cfg = ps_sim_config(int(n_servers), len(tpots), tp, int(avg_decode), float(kv_capacity), int(check_period), int(max_steps))
+        cfg = ps_sim_config(1 if disaggregated else 0, int(n_servers), len(tpots), tp, int(avg_decode), float(kv_capacity),
+                            int(check_period), int(max_steps), int(prefill_budget))
         att = np.zeros(n, dtype=np.uint8)
-        first, fin, srv = np.zeros(n), np.zeros(n), np.zeros(n, dtype=np.int32)
+        first, fin = np.zeros(n), np.zeros(n)
+        srv, dsrv = np.zeros(n, dtype=np.int32), np.zeros(n, dtype=np.int32)
         summ = ps_sim_summary()
         _sched_check(lib.ps_sim_run(self.handle, C.byref(cfg), reqs, n, att.ctypes.data, first.ctypes.data, fin.ctypes.data,
-                                    srv.ctypes.data, C.byref(summ)), "ps_sim_run")
+                                    srv.ctypes.data, dsrv.ctypes.data, C.byref(summ)), "ps_sim_run")
         out = {name: getattr(summ, name) for name, _ in ps_sim_summary._fields_}
-        out.update(attained=att, first_token_ms=first, finish_ms=fin, server=srv)
+        out.update(attained=att, first_token_ms=first, finish_ms=fin, server=srv, decode_server=dsrv)
         return out
 
     def batch_limit_pd(self, p, d, tpot_ms, capacity, b_max=4096):

@@ -5,6 +5,7 @@ import pytest
 
 from oracle import policy as opol
 from oracle import sim as osim
+from oracle import sim_pd as osim_pd
 from paper_2507_17769_amd import binding as B
 from paper_2507_17769_amd import workloads as W
 
@@ -21,7 +22,10 @@ def compare(got, want, n):
     for name in ("end_ms", "cost_ms", "scale_ups", "scale_downs", "promotions", "dropped"):
         assert got[name] == want[name], (name, got[name], want[name])
     assert got["attained"].tolist() == want["attained"]
-    assert got["server"].tolist() == want["server"]
+    if "server" in want:   # co-located: one instance does both phases
+        assert got["server"].tolist() == want["server"] and got["decode_server"].tolist() == want["server"]
+    else:
+        assert got["server"].tolist() == want["prefill_server"] and got["decode_server"].tolist() == want["decode_server"]
     assert got["first_token_ms"].tolist() == want["first_token_ms"]   # doubles, bit for bit
     assert got["finish_ms"].tolist() == want["finish_ms"]
 
@@ -43,6 +47,38 @@ def test_simulator_matches_the_oracle(seed, n_servers, rate, max_prompt, max_out
     print({k: v for k, v in want.items() if not isinstance(v, list)}, "attained", sum(want["attained"]))
     compare(got, want, n)
     gp.close()
+
+
+@pytest.mark.parametrize("seed,n_servers,rate,max_prompt,max_output,avg,period,cap,budget,burst", [
+    (0, 4, 0.03, 1024, 256, 128, 200, 2e6, 1024, False),
+    (1, 3, 0.5, 1024, 256, 128, 200, 2e6, 1024, False),       # overloaded: queues and drops on both sides
+    (2, 8, 0.06, 1024, 256, 128, 50, 2e6, 512, True),         # frequent scale-down checks, tier mix flips half way
+    (3, 4, 0.02, 8192, 512, 256, 100, 60000.0, 2048, False),  # long prompts in several chunks, KV capacity binds
+    (4, 20, 0.25, 1024, 256, 128, 1000, 2e6, 2048, False),
+])
+def test_disaggregated_simulator_matches_the_oracle(seed, n_servers, rate, max_prompt, max_output, avg, period, cap, budget, burst):
+    gp, op = tables(lambda b, k: 4.0 + 0.012 * b + 2e-5 * k)
+    n = 300
+    tr = W.sim_trace(seed, n, rate, max_prompt, max_output, burst=burst)
+    args = (tr["arrival"], tr["prompt"], tr["output"], tr["ttft"], tr["tier"], list(W.SIM_TPOTS_MS), n_servers, avg, cap)
+    want = osim_pd.simulate(op, *args, budget, period)
+    got = gp.simulate(*args, period, disaggregated=True, prefill_budget=budget)
+    print({k: v for k, v in want.items() if not isinstance(v, list)}, "attained", sum(want["attained"]))
+    compare(got, want, n)
+    gp.close()
+
+
+def test_disaggregated_paths_are_all_reached_by_the_comparison_cases():
+    _, op = tables(lambda b, k: 4.0 + 0.012 * b + 2e-5 * k)
+    seen = {"dropped": 0, "promotions": 0, "scale_downs": 0, "multi_chunk": 0}
+    for seed, n_servers, rate, mp, mo, avg, period, cap, budget, burst in ((1, 3, 0.5, 1024, 256, 128, 200, 2e6, 1024, False),
+                                                                        (3, 4, 0.02, 8192, 512, 256, 100, 60000.0, 2048, False)):
+        tr = W.sim_trace(seed, 300, rate, mp, mo, burst=burst)
+        res = osim_pd.simulate(op, tr["arrival"], tr["prompt"], tr["output"], tr["ttft"], tr["tier"], list(W.SIM_TPOTS_MS), n_servers, avg, cap, budget, period)
+        for k in ("dropped", "promotions", "scale_downs"):
+            seen[k] += res[k]
+        seen["multi_chunk"] += sum(1 for p, f in zip(tr["prompt"], res["first_token_ms"]) if p >= 2 * budget and f > 0)
+    assert all(v > 0 for v in seen.values()), seen
 
 
 def test_simulator_paths_are_all_reached_by_the_comparison_cases():
@@ -69,4 +105,6 @@ def test_simulator_stops_at_max_steps_and_rejects_malformed_input():
         gp.simulate([0.0], [1], [1], [300.0], [1], [20.0], 1, 1, 1e9)                            # tier out of range
     with pytest.raises(B.PolystepError):
         gp.simulate([0.0], [1], [1], [300.0], [0], [50.0, 20.0], 1, 1, 1e9)                      # tiers not ascending
+    with pytest.raises(B.PolystepError):
+        gp.simulate([0.0], [1], [1], [300.0], [0], [20.0], 1, 1, 1e9, disaggregated=True)        # no prefill budget
     gp.close()
