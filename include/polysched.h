@@ -58,11 +58,11 @@ ps_status ps_predict_admit(const ps_profile* p, const ps_running_req* running, i
 ps_status ps_chunk_plan(const int32_t* prompts, int32_t n, int32_t budget, int32_t dynamic, int32_t first_iteration_used,
                         int32_t* chunks, int32_t cap, int32_t* n_chunks, int32_t* n_iterations);
 
-/* Sec. 4.6, co-location.  The chunk size predicted at scheduling time is the largest c in
- * [1, prompt_len] with T(n_running + c, KV now + c) < tpot_ms; it is kept for ceil(prompt / c)
- * iterations while every running decode grows by one token per iteration (and leaves when predicted
- * finished).  *admit = every one of those iterations stays below tpot_ms and wait_ms + their sum
- * (= *first_token_ms) stays below ttft_ms.  No chunk fits: *admit = 0, *chunk = *n_iters = 0,
+/* Sec. 4.6, co-location.  The chunk size predicted at scheduling time is the largest c in [1, prompt_len]
+ * that can be kept for all ceil(prompt / c) iterations of the prefill: every one of them stays below tpot_ms
+ * while the chunks attend a growing prefix and every running decode grows by one token per iteration (and
+ * leaves when predicted finished).  *admit = such a c exists and wait_ms + the sum of those iteration times
+ * (= *first_token_ms) stays below ttft_ms.  No chunk size can be kept: *admit = 0, *chunk = *n_iters = 0,
  * *first_token_ms = +inf. */
 ps_status ps_predict_chunked_prefill(const ps_profile* p, const ps_running_req* running, int32_t n_running, int32_t prompt_len,
                                      int32_t avg_decode_len, double tpot_ms, double ttft_ms, double wait_ms, int32_t* admit,

@@ -21,10 +21,13 @@ Readings fixed where the text is loose (each is one sentence of the paper made e
   * dynamic chunking: iterations are filled first-come first-served; a request is finished in the
     current iteration if it fits the room left, or (dynamic) if the iteration then stays below
     twice the budget, in which case the iteration is closed; otherwise it gets the room left;
-  * co-location: the chunk size predicted at scheduling time is the largest c with
-    T(decodes + c, KV now + c) < TPOT; it is kept for ceil(prompt / c) iterations while the decodes
-    grow by one token per iteration (and leave when predicted finished); every one of those
-    iterations must stay below the TPOT and their sum plus the wait time below the TTFT.
+  * co-location: the chunk size predicted at scheduling time is the largest c that can be kept for
+    all ceil(prompt / c) iterations of the prefill, i.e. every one of them stays below the TPOT while
+    the chunks attend a growing prefix and the decodes grow by one token per iteration (and leave
+    when predicted finished); the request is admitted if such a c exists and the sum of those
+    iterations plus the wait time stays below the TTFT.  (Taking the largest c that fits the first
+    iteration and rejecting when a later one does not would turn away every multi-chunk prompt on a
+    table that grows with the KV size at all, even on an empty instance.)
 """
 import math
 
@@ -119,25 +122,30 @@ def predict_chunked_prefill(profile, running, prompt, avg_decode, tpot_ms, ttft_
     """Co-location.  Returns (admit?, chunk size, iterations, predicted time to first token)."""
     prompt = int(prompt)
     decs = [(int(kv), max(1, int(avg_decode) - int(g))) for kv, g in running]
-    kv_now = sum(kv + 1 for kv, _ in decs)
-    chunk = 0
-    for c in range(prompt, 0, -1):
-        if profile.lookup(len(decs) + c, kv_now + c) < tpot_ms:
-            chunk = c
-            break
-    if chunk == 0:
-        return False, 0, 0, math.inf
-    n_iter = (prompt + chunk - 1) // chunk
-    total, ok, done = float(wait_ms), True, 0
-    for j in range(n_iter):
-        c = min(chunk, prompt - done)
-        active = [(kv, rem) for kv, rem in decs if rem > j]
-        kv = sum(kv + j + 1 for kv, _ in active) + done + c
-        t = profile.lookup(len(active) + c, kv)
-        ok = ok and t < tpot_ms
-        total += t
-        done += c
-    return ok and total < ttft_ms, chunk, n_iter, total
+
+    def iteration_times(chunk):
+        """times of the ceil(prompt / chunk) iterations if this chunk size is kept, or None if one reaches the TPOT"""
+        times, done, j = [], 0, 0
+        while done < prompt:
+            c = min(chunk, prompt - done)
+            active = [(kv, rem) for kv, rem in decs if rem > j]
+            kv = sum(kv + j + 1 for kv, _ in active) + done + c
+            t = profile.lookup(len(active) + c, kv)
+            if not t < tpot_ms:
+                return None
+            times.append(t)
+            done += c
+            j += 1
+        return times
+
+    for chunk in range(prompt, 0, -1):
+        times = iteration_times(chunk)
+        if times is not None:
+            total = float(wait_ms)
+            for t in times:
+                total += t
+            return total < ttft_ms, chunk, len(times), total
+    return False, 0, 0, math.inf
 
 
 def batch_limit_pd(profile, p, d, tpot_ms, capacity, b_max=4096):

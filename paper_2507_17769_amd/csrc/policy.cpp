@@ -150,35 +150,37 @@ extern "C" ps_status ps_predict_chunked_prefill(const ps_profile* p, const ps_ru
     if (!p || !admit || !chunk || !n_iters || !first_token_ms || prompt_len < 1 || avg_decode_len < 1 || bad_running(running, n_running))
         return PS_EINVAL;
     const std::vector<Req> decs = predicted(running, n_running, avg_decode_len);
-    int64_t kv_now = 0;
-    for (const Req& r : decs) kv_now += r.kv + 1;
-    int32_t c_fit = 0;
-    for (int32_t c = prompt_len; c >= 1; c--)
-        if (ps_profile_lookup(p, (double)(n_running + c), (double)(kv_now + c)) < tpot_ms) { c_fit = c; break; }
-    if (c_fit == 0) {
-        *admit = 0; *chunk = 0; *n_iters = 0;
-        *first_token_ms = std::numeric_limits<double>::infinity();
+    // sum of the iteration times if chunk size c is kept, or a negative value as soon as one reaches the TPOT
+    auto kept = [&](int32_t c_fit, int32_t* n_out) {
+        double total = wait_ms;
+        int64_t done = 0;
+        int32_t j = 0;
+        for (; done < prompt_len; j++) {
+            const int64_t c = std::min<int64_t>(c_fit, prompt_len - done);
+            int64_t active = 0, kv = 0;
+            for (const Req& r : decs)
+                if (r.rem > j) { active++; kv += r.kv + j + 1; }
+            kv += done + c;
+            const double t = ps_profile_lookup(p, (double)(active + c), (double)kv);
+            if (!(t < tpot_ms)) return -1.0;
+            total += t;
+            done += c;
+        }
+        *n_out = j;
+        return total;
+    };
+    for (int32_t c = prompt_len; c >= 1; c--) {
+        int32_t n = 0;
+        const double total = kept(c, &n);
+        if (total < 0.0) continue;
+        *admit = total < ttft_ms ? 1 : 0;
+        *chunk = c;
+        *n_iters = n;
+        *first_token_ms = total;
         return PS_OK;
     }
-    const int32_t n = (prompt_len + c_fit - 1) / c_fit;
-    double total = wait_ms;
-    bool ok = true;
-    int64_t done = 0;
-    for (int32_t j = 0; j < n; j++) {
-        const int64_t c = std::min<int64_t>(c_fit, prompt_len - done);
-        int64_t active = 0, kv = 0;
-        for (const Req& r : decs)
-            if (r.rem > j) { active++; kv += r.kv + j + 1; }
-        kv += done + c;
-        const double t = ps_profile_lookup(p, (double)(active + c), (double)kv);
-        ok = ok && t < tpot_ms;
-        total += t;
-        done += c;
-    }
-    *admit = (ok && total < ttft_ms) ? 1 : 0;
-    *chunk = c_fit;
-    *n_iters = n;
-    *first_token_ms = total;
+    *admit = 0; *chunk = 0; *n_iters = 0;
+    *first_token_ms = std::numeric_limits<double>::infinity();
     return PS_OK;
 }
 

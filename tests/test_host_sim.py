@@ -34,12 +34,13 @@ def compare(got, want, n):
     (0, 4, 0.03, 1024, 256, 128, 200, 2e6, False),
     (1, 2, 0.5, 1024, 256, 128, 200, 2e6, False),       # overloaded: queues and drops
     (2, 8, 0.06, 1024, 256, 128, 50, 2e6, True),        # frequent scale-down checks, tier mix flips half way
-    (3, 3, 0.02, 8192, 512, 256, 100, 60000.0, False),  # KV capacity binds
+    (3, 3, 0.01, 1024, 256, 128, 100, 2500.0, False), # long prompts in several chunks, KV capacity binds
     (4, 20, 0.25, 1024, 256, 128, 1000, 2e6, False),
+    (5, 6, 0.01, 4096, 128, 64, 300, 2e6, False),       # prompts that need several chunks under the tight tiers
 ])
 def test_simulator_matches_the_oracle(seed, n_servers, rate, max_prompt, max_output, avg, period, cap, burst):
     gp, op = tables(lambda b, k: 4.0 + 0.012 * b + 2e-5 * k)
-    n = 300
+    n = 300 if cap > 1e5 else 100   # queued requests are tried again every step: the capacity-bound case is slow in the oracle
     tr = W.sim_trace(seed, n, rate, max_prompt, max_output, burst=burst)
     args = (tr["arrival"], tr["prompt"], tr["output"], tr["ttft"], tr["tier"], list(W.SIM_TPOTS_MS), n_servers, avg, cap, period)
     want = osim.simulate(op, *args)

@@ -120,17 +120,40 @@ def test_chunk_plan_invariants():
 def test_chunked_prefill_prediction_on_a_linear_profile():
     pr = op.Profile(*_profile())               # T = 2 + 0.01 B + 1e-5 KV
     run = [(4000, 0)] * 32
-    # largest c with 2 + 0.01 (32 + c) + 1e-5 (32 * 4001 + c) < 4  ->  c < (4 - 2 - 0.32 - 1.28032) / 0.01001
-    c_max = int(np.ceil((4 - 2 - 0.32 - 1.28032) / 0.01001) - 1)
+    T = lambda b, kv: 2 + 0.01 * b + 1e-5 * kv
+
+    def keeps(c, prompt, tpot):      # the definition, iteration by iteration: 32 decodes grow by one token each time
+        done, j = 0, 0
+        while done < prompt:
+            cc = min(c, prompt - done)
+            if not T(32 + cc, 32 * (4001 + j) + done + cc) < tpot:
+                return False
+            done, j = done + cc, j + 1
+        return True
+
+    want = max(c for c in range(1, 2001) if keeps(c, 2000, 4.0))
+    # the chunk that fits the first iteration alone, c < (4 - 2 - 0.32 - 1.28032) / 0.01001, cannot be kept: the prefix
+    # it attends and the decodes grow, so the prediction settles on a smaller one
+    first_only = int(np.ceil((4 - 2 - 0.32 - 1.28032) / 0.01001) - 1)
+    assert not keeps(first_only, 2000, 4.0) and want < first_only
     ok, c, n, total = op.predict_chunked_prefill(pr, run, 2000, avg_decode=500, tpot_ms=4.0, ttft_ms=1e9)
-    assert c == c_max and n == -(-2000 // c)
-    # the decodes grow while the prefill runs, so the chunk that fits now does not fit in the later iterations
-    assert not ok
+    assert ok and c == want and n == -(-2000 // c)
+    times = [pr.lookup(32 + min(c, 2000 - j * c), 32 * (4001 + j) + min((j + 1) * c, 2000)) for j in range(n)]
+    assert total == pytest.approx(sum(times)) and max(times) < 4.0
     ok2, c2, n2, total2 = op.predict_chunked_prefill(pr, run, 30, avg_decode=500, tpot_ms=4.0, ttft_ms=1e9)
     assert ok2 and c2 == 30 and n2 == 1 and total2 == pytest.approx(pr.lookup(62, 32 * 4001 + 30))
     assert not op.predict_chunked_prefill(pr, run, 30, 500, 4.0, ttft_ms=total2)[0]           # TTFT is a strict bound, wait time counts
     assert not op.predict_chunked_prefill(pr, run, 30, 500, 4.0, ttft_ms=total2 + 1.0, wait_ms=1.5)[0]
     assert op.predict_chunked_prefill(pr, run, 30, 500, 1.0, 1e9) == (False, 0, 0, float("inf"))
+    # decodes that are predicted to finish during the prefill stop counting: with 2 tokens left each, the third
+    # iteration runs without them
+    short = [(4000, 498)] * 32
+    ok3, c3, n3, total3 = op.predict_chunked_prefill(pr, short, 600, avg_decode=500, tpot_ms=4.2, ttft_ms=1e9)
+    assert ok3 and n3 >= 3
+    t_last = pr.lookup(min(c3, 600 - (n3 - 1) * c3), 600)
+    assert total3 == pytest.approx(sum(pr.lookup(32 + c3, 32 * (4001 + j) + (j + 1) * c3) for j in range(2))
+                                   + sum(pr.lookup(min(c3, 600 - j * c3), min((j + 1) * c3, 600)) for j in range(2, n3)))
+    assert t_last < 4.2
 
 
 def test_batch_limits_on_a_linear_profile():
