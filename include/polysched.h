@@ -103,8 +103,9 @@ int32_t ps_batch_limit_co(const ps_profile* prof, double p, double d, double tpo
  * queued requests are taken in order of arrival + TTFT (Sec. 4.1); a prefill instance forms its iterations
  * with ps_chunk_plan (dynamic, prefill_budget) over its requests in admission order; a request goes to the
  * prefill instance with most unprocessed prompt tokens whose predicted end of the request's prefill (the
- * wait for the iteration in flight plus the planned iterations up to the request's last chunk) is before
- * the first-token deadline, else to an instance from the idle pool.  The prefill's end delivers token 0
+ * wait for the iteration in flight plus the planned iterations up to the request's last chunk, each start
+ * counted at the whole step the instance would start it) is before the first-token deadline, else to an
+ * instance from the idle pool.  The prefill's end delivers token 0
  * and queues the request for decoding (the transfer takes no time); decode clusters work as above except
  * that an instance admits the request if ps_predict_admit keeps the largest future KV size's iteration
  * below the instance's TPOT, that KV size is below kv_capacity, and the wait for the iteration in flight

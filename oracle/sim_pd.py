@@ -22,11 +22,17 @@ Readings fixed where the text is loose (beyond those of sim.py):
     come first served), prefill queue (nearest deadline first), iteration starts;
   * a chunk attends the prompt tokens up to its own end; an iteration's duration is the table's
     value for (tokens in it, KV tokens attended);
+  * the router predicts on the simulator's clock: an instance starts its next iteration at the first
+    whole step at or after the end of the one in flight, so the wait and every planned iteration of
+    a prefill instance are counted up to whole steps (without this, prefill instances packed to the
+    deadline deliver first tokens a few milliseconds late);
   * load of a prefill instance = prompt tokens not yet processed on it; the scale-down check returns
     the prefill instance with the lowest load to the pool if it holds no request;
   * a queued request that could no longer meet its next deadline even on an empty instance is
     dropped (before prefill: the first token; between prefill and decode: the second token).
 """
+import math
+
 from . import policy
 
 POOL, ACTIVE, PENDING = 0, 1, 2
@@ -63,7 +69,8 @@ def simulate(profile, arrival, prompt, output, ttft, tier, tpots, n_servers, avg
     cost, join_counter, next_arrival, done = 0.0, 0, 0, 0
 
     def wait_of(s, now):
-        return max(0.0, s.busy_until - now) if s.busy_until is not None else 0.0
+        """steps from now until the instance can start its next iteration"""
+        return max(0, math.ceil(s.busy_until) - now) if s.busy_until is not None else 0
 
     def left(s, ri):
         """prompt tokens of request ri not yet processed or in the iteration in flight"""
@@ -88,6 +95,7 @@ def simulate(profile, arrival, prompt, output, ttft, tier, tpots, n_servers, avg
             t += profile.lookup(tokens, kv)
             if at[-1] == r.prompt:
                 return t
+            t = math.ceil(t)   # the next iteration starts at a whole step
         raise AssertionError("plan does not finish the request")
 
     def decode_admits(s, r, now):

@@ -9,6 +9,7 @@
 // (Sec. 4.1, 4.6), and decode clusters per tier with the wait-time-aware admission of Sec. 4.5.
 // Host only.  The decisions themselves are the ones exported by policy.cpp.
 #include <algorithm>
+#include <cmath>
 #include <cstdint>
 #include <deque>
 #include <new>
@@ -280,7 +281,11 @@ struct SimPD {
 
     SimPD(const ps_profile* p, const ps_sim_config& c) : prof(p), cfg(c) {}
 
-    static double wait_of(const Instance& s, int64_t now) { return s.in_iteration ? std::max(0.0, s.busy_until - (double)now) : 0.0; }
+    // whole steps from now until the instance can start its next iteration: the router predicts on the simulator's
+    // clock, on which an iteration starts at the first step at or after the end of the one before
+    static double wait_of(const Instance& s, int64_t now) {
+        return s.in_iteration ? (double)std::max<int64_t>(0, (int64_t)std::ceil(s.busy_until) - now) : 0.0;
+    }
 
     // prompt tokens of request i neither processed nor in the iteration in flight
     int32_t left(const Instance& s, int32_t i) const {
@@ -332,6 +337,7 @@ struct SimPD {
             }
             t += ps_profile_lookup(prof, (double)tokens, (double)kv);
             if (at[mine] == r.prompt) break;
+            t = std::ceil(t);
         }
         sum.admission_tests++;
         return t;

@@ -74,6 +74,18 @@ def test_prefill_goes_to_the_most_loaded_instance_that_still_meets_the_deadline(
     assert res["first_token_ms"] == [50.0, 100.0, 52.0, 150.0]
 
 
+def test_prefill_prediction_counts_whole_steps():
+    # 10.5 ms iterations start at whole steps: behind r0 (0 -> 10.5, 11 -> 21.5) a request seen at step 1 would run
+    # 22 -> 32.5, i.e. 31.5 ms from now, not 9.5 + 10.5 + 10.5 = 30.5; with 31.4 ms to its first token it takes a fresh instance
+    reqs = [(0.0, 2050, 1, 300.0, 0), (1.0, 100, 1, 31.4, 0)]
+    res = run(table(lambda b, k: 10.5), reqs, [20.0], 2, 1, 1024)
+    assert res["prefill_server"] == [0, 1] and res["first_token_ms"] == [21.5, 11.5] and res["attained"] == [1, 1]
+    # with 32 ms it waits behind r0 and is exactly as late as predicted
+    reqs = [(0.0, 2050, 1, 300.0, 0), (1.0, 100, 1, 32.0, 0)]
+    res = run(table(lambda b, k: 10.5), reqs, [20.0], 2, 1, 1024)
+    assert res["prefill_server"] == [0, 0] and res["first_token_ms"] == [21.5, 32.5] and res["attained"] == [1, 1]
+
+
 def test_decode_admission_counts_the_wait_for_the_iteration_in_flight():
     # decode iterations 18 ms, prefill iterations 25 ms, TPOT 20.  r0 decodes on instance 1 in cycles 25 -> 43 -> 61 ...
     # r1's first token comes at 55 with its second due at 30 + TTFT + 20.  With TTFT 26 there are 21 ms left: waiting
