@@ -30,7 +30,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg2", "grid", "cfg4", "model8b", "prefill", "profile"])
+    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg2", "grid", "cfg4", "model8b", "prefill", "profile", "sim"])
+    ap.add_argument("--requests", type=int, default=20000, help="sim: requests per simulated run")
+    ap.add_argument("--table", default=None, help="sim: JSON written by an earlier --workload sim run; its table is used instead of measuring")
     ap.add_argument("--layers", type=int, default=80, help="cfg4: number of decoder layers")
     ap.add_argument("--kv-slots", type=int, default=8, help="cfg4: physical KV layer slots (layer l uses slot l mod this)")
     ap.add_argument("--check-layers", default="", help="cfg4: comma-separated layers to check against the oracle, teacher-forced")
@@ -425,13 +427,15 @@ def run_prefill(a):
     print(json.dumps(res))
 
 
-def run_profile(a):
-    """The map (batch size, KV cache size) -> iteration time of the whole 8B-shaped model (Sec. 4.4), measured on
-    decode batches, and the router's decisions taken with it through polysched (Sec. 3.4, 4.4-4.6) for the paper's
-    TPOT tiers (Sec. 5.1: 20, 30, 50, 100 ms; TTFT 300, 500, 1000 ms)."""
+def measure_profile(a, batch_sizes, kv_sizes, n_decodes_in_mixed=256):
+    """Measure the map (batch size, KV cache size) -> iteration time of the whole 8B-shaped model (Sec. 4.4) with
+    ps_step_tokens.  Rows up to n_decodes_in_mixed tokens are decode batches (the KV size split evenly over the requests);
+    larger rows are the co-located kind of batch (Sec. 2.4): n_decodes_in_mixed decodes plus one prefill chunk with the
+    remaining tokens at prefix 0, the decodes sharing the KV size that the chunk does not attend.  Returns
+    (measured table with NaN where a cell cannot exist, table with those cells filled from the nearest measured cell of the
+    row, layers, vocabulary, KV capacity in tokens of one 288 GB instance)."""
     import numpy as np
     import torch
-    from paper_2507_17769_amd import binding as B
     from paper_2507_17769_amd import workloads as W
     from paper_2507_17769_amd.binding import SeqArray
     from paper_2507_17769_amd.runner import Engine, bits_to_dev
@@ -439,14 +443,18 @@ def run_profile(a):
     model, L, V = "8b", a.layers if a.layers != 80 else 32, a.vocab
     m = W.MODELS[model]
     H, F, nq, nkv, d = m["hidden"], m["ffn"], m["n_q"], m["n_kv"], m["head_dim"]
-    batch_sizes = [1, 4, 16, 64, 256]
-    kv_sizes = [4096, 32768, 131072, 524288]          # total KV tokens of the batch
     cells = {}
     for bs in batch_sizes:
         for kv in kv_sizes:
-            per = kv // bs
-            if 16 <= per <= 65536:
-                cells[(bs, kv)] = W.custom_batch(model, a.seed, 0, 0, [per] * bs, name=f"b{bs}_kv{kv}", tag=bs * 7 + 1)
+            if bs <= n_decodes_in_mixed:
+                per = kv // bs
+                if 16 <= per <= 65536:
+                    cells[(bs, kv)] = W.custom_batch(model, a.seed, 0, 0, [per] * bs, name=f"b{bs}_kv{kv}", tag=bs * 7 + 1)
+            else:
+                chunk = bs - n_decodes_in_mixed
+                per = (kv - chunk) // n_decodes_in_mixed
+                if 16 <= per <= 65536:
+                    cells[(bs, kv)] = W.custom_batch(model, a.seed, chunk, 0, [per] * n_decodes_in_mixed, name=f"b{bs}_kv{kv}", tag=bs * 7 + 1)
     n_pool = max(b.n_pool_pages for b in cells.values())
     eng = Engine(model, n_pool, L, L, max_position=65536 + 16)
     gen = torch.Generator(device="cuda:0")
@@ -488,13 +496,28 @@ def run_profile(a):
         table[batch_sizes.index(bs), kv_sizes.index(kv)] = (time.perf_counter() - t0) * 1e3 / steps
         print(f"profile: batch {bs} kv {kv}: {table[batch_sizes.index(bs), kv_sizes.index(kv)]:.3f} ms", file=sys.stderr, flush=True)
     eng.close()
-    # cells that cannot exist (fewer than 16 cached tokens per request) are filled from the nearest measured cell of the row
     filled = table.copy()
     for i in range(len(batch_sizes)):
         for j in range(len(kv_sizes)):
             if np.isnan(filled[i, j]):
                 js = [jj for jj in range(len(kv_sizes)) if not np.isnan(table[i, jj])]
                 filled[i, j] = table[i, min(js, key=lambda jj: abs(jj - j))]
+    # KV capacity of what is left of 288 GB beside the weights and 8 GB of workspace
+    weights_gb = 2 * (L * (H * (nq + 2 * nkv) * d + nq * d * H + 3 * H * F) + 2 * H * V) / 1e9
+    capacity = (288 - weights_gb - 8) * 1e9 / (2 * nkv * d * 2 * L)
+    return table, filled, L, V, capacity
+
+
+def run_profile(a):
+    """The map (batch size, KV cache size) -> iteration time of the whole 8B-shaped model (Sec. 4.4), measured on
+    decode batches, and the router's decisions taken with it through polysched (Sec. 3.4, 4.4-4.6) for the paper's
+    TPOT tiers (Sec. 5.1: 20, 30, 50, 100 ms; TTFT 300, 500, 1000 ms)."""
+    import numpy as np
+    from paper_2507_17769_amd import binding as B
+
+    batch_sizes = [1, 4, 16, 64, 256]
+    kv_sizes = [4096, 32768, 131072, 524288]          # total KV tokens of the batch
+    table, filled, L, V, capacity = measure_profile(a, batch_sizes, kv_sizes)
     prof = B.Profile(batch_sizes, kv_sizes, filled)
     res = {"metric": "iteration_time_profile", "unit": "ms", "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
            "config": {"workload": f"profile: 8B-shaped model, {L} layers + head, decode batches", "n_layers": L, "vocab": V},
@@ -502,8 +525,6 @@ def run_profile(a):
            "ms": [[None if np.isnan(v) else round(float(v), 4) for v in row] for row in table], "decisions": {}}
     dec = res["decisions"]
     # Sec. 3.4: largest decode batch per TPOT tier for a request shape (p, d), KV capacity of what is left of 288 GB
-    weights_gb = 2 * (L * (H * (nq + 2 * nkv) * d + nq * d * H + 3 * H * F) + 2 * H * V) / 1e9
-    capacity = (288 - weights_gb - 8) * 1e9 / (2 * nkv * d * 2 * L)
     dec["kv_capacity_tokens"] = int(capacity)
     dec["batch_limit_pd"] = {f"p={p},d={dd},tpot={t}": prof.batch_limit_pd(p, dd, t, capacity, 4096)
                              for (p, dd) in ((512, 512), (4096, 1024)) for t in (20, 30, 50, 100)}
@@ -518,6 +539,90 @@ def run_profile(a):
                                           "dynamic": sizes(B.chunk_plan([2050], 1024, True)), "dynamic_after_1023": sizes(B.chunk_plan([2050], 1024, True, 1023))}
     dec["chunked_prefill_2000_tokens_beside_63_decodes"] = {f"tpot={t},ttft={tt}": list(prof.predict_chunked_prefill(run, 2000, 512, t, tt)) for t in (20, 50) for tt in (300, 1000)}
     prof.close()
+    print(json.dumps(res))
+
+
+def run_sim(a):
+    """The paper's evaluation method (Sec. 5.1) on the table measured here: a cluster of 20 instances simulated in 1 ms steps
+    under the router of Sec. 4, co-located and disaggregated, on the two synthetic traces the paper fully specifies
+    (uniform_512_512, uniform_4096_1024: Sec. 5.1 / Table of trace statistics) and on the tier-flip workload of Sec. 5.3,
+    with the SLO tiers of Sec. 5.1.  Reports DSLO attainment per request rate and per TPOT tier, the goodput at 90 %
+    attainment, instance-seconds per request, and how many requests per second of wall time the C++ router places."""
+    import numpy as np
+    from paper_2507_17769_amd import binding as B
+    from paper_2507_17769_amd import workloads as W
+
+    batch_sizes = [1, 16, 64, 256, 512, 1024, 2048, 4096]
+    kv_sizes = [4096, 32768, 131072, 524288]
+    if a.table:
+        rec = json.load(open(a.table))
+        batch_sizes, kv_sizes = rec["batch_sizes"], rec["kv_sizes"]
+        table = np.array([[np.nan if v is None else v for v in row] for row in rec["ms"]], dtype=np.float32)
+        filled = np.array(rec["ms_filled"], dtype=np.float32)
+        L, V, capacity = rec["n_layers"], rec["vocab"], rec["kv_capacity_tokens"]
+    else:
+        table, filled, L, V, capacity = measure_profile(a, batch_sizes, kv_sizes)
+    prof = B.Profile(batch_sizes, kv_sizes, filled)
+    tpots = list(W.SIM_TPOTS_MS)
+    n, n_servers = a.requests, 20
+    res = {"metric": "cluster_simulation_dslo_goodput", "unit": "requests/s at >= 90 % DSLO attainment", "n_gpus": 1, "dtype": "bf16",
+           "data": "synthetic", "higher_is_better": True, "vs_baseline": None,
+           "config": {"workload": f"sim: {n_servers} simulated instances of the 8B-shaped model ({L} layers + head), iteration times from the "
+                                  f"table measured on this GPU, {n} requests per run, TPOT tiers {tpots} ms, TTFT 300/500/1000 ms"},
+           "batch_sizes": batch_sizes, "kv_sizes": kv_sizes, "n_layers": L, "vocab": V, "kv_capacity_tokens": int(capacity),
+           "ms": [[None if np.isnan(v) else round(float(v), 4) for v in row] for row in table],
+           "ms_filled": [[round(float(v), 4) for v in row] for row in filled], "runs": [], "goodput": {}}
+    # request rates: from the start value up in steps of 30 % until the attainment falls below 90 % (at most 16 steps)
+    traces = {"uniform_512_512": (1024, 1024, False, 100.0), "uniform_4096_1024": (8192, 2048, False, 20.0),
+              "tier_flip_4096_1024": (8192, 2048, True, 20.0)}
+    wall_total, placed_total, tests_total = 0.0, 0, 0
+    for name, (max_p, max_o, burst, rate0) in traces.items():
+        for mode in ("co-located", "disaggregated"):
+            best, att = 0.0, 1.0
+            for step in range(16):
+                if att < 0.9:
+                    break
+                rate = round(rate0 * 1.3 ** step, 1)
+                tr = W.sim_trace(a.seed, n, rate / 1e3, max_p, max_o, burst=burst)
+                t0 = time.perf_counter()
+                r = prof.simulate(tr["arrival"], tr["prompt"], tr["output"], tr["ttft"], tr["tier"], tpots, n_servers, (1 + max_o) // 2, capacity,
+                                  1000, disaggregated=(mode == "disaggregated"), prefill_budget=2048)
+                wall = time.perf_counter() - t0
+                wall_total, placed_total, tests_total = wall_total + wall, placed_total + n, tests_total + r["admission_tests"]
+                tier = np.array(tr["tier"])
+                att = float(r["attained"].mean())
+                if att >= 0.9:
+                    best = max(best, rate * att)
+                res["runs"].append({"trace": name, "mode": mode, "rate_per_s": rate, "attained": round(att, 4),
+                                    "attained_by_tier": [round(float(r["attained"][tier == t].mean()), 4) for t in range(len(tpots))],
+                                    "dropped": int(r["dropped"]), "promotions": int(r["promotions"]), "scale_ups": int(r["scale_ups"]),
+                                    "instance_seconds_per_request": round(r["cost_ms"] / 1e3 / n, 4),
+                                    "simulated_s": round(r["end_ms"] / 1e3, 1), "wall_s": round(wall, 3)})
+                print(f"sim: {name} {mode} {rate}/s attained {att:.3f} wall {wall:.2f}s", file=sys.stderr, flush=True)
+            res["goodput"][f"{name} {mode}"] = round(best, 1)
+    prof.close()
+    res["value"] = res["goodput"]["uniform_512_512 co-located"]
+    res["router"] = {"requests_per_wall_second": round(placed_total / wall_total, 1), "admission_tests_per_wall_second": round(tests_total / wall_total, 1),
+                     "note": "whole simulation (instances stepped in 1 ms steps included), one host thread"}
+    if not a.no_cpu_baseline:
+        # the oracle simulator on a bounded sample, on a table of the same shape that does not come from the GPU path
+        from oracle import policy as opol
+        from oracle import sim as osim
+        ms = np.array([[4.0 + 0.013 * b + 2.2e-5 * k for k in kv_sizes] for b in batch_sizes], dtype=np.float32)
+        tr = W.sim_trace(a.seed, 2000, 0.1, 1024, 1024)
+        args = (tr["arrival"], tr["prompt"], tr["output"], tr["ttft"], tr["tier"], tpots, n_servers, 512, capacity, 1000)
+        t0 = time.perf_counter()
+        want = osim.simulate(opol.Profile(batch_sizes, kv_sizes, ms.astype(np.float64).tolist()), *args)
+        t_oracle = time.perf_counter() - t0
+        gp = B.Profile(batch_sizes, kv_sizes, ms)
+        t0 = time.perf_counter()
+        got = gp.simulate(*args)
+        t_cpp = time.perf_counter() - t0
+        gp.close()
+        assert got["attained"].tolist() == want["attained"] and got["finish_ms"].tolist() == want["finish_ms"]
+        res["cpu_baseline"] = {"value": round(2000 / t_oracle, 1), "unit": "simulated requests per wall second", "cores": 1, "kind": "oracle",
+                               "sample": "uniform_512_512, 2000 requests at 100/s, co-located, analytic table 4 + 0.013 B + 2.2e-5 KV ms",
+                               "same_sample_cpp": round(2000 / t_cpp, 1), "identical_outputs": True}
     print(json.dumps(res))
 
 
@@ -541,6 +646,9 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes": n, "copies": 3}))
         return
+    if a.workload == "sim" and a.table:   # host only: the table was measured by an earlier run
+        run_sim(a)
+        return
     if not a.null_stream:   # a stream of our own (default priority); torch only allocates and copies
         torch.cuda.set_stream(torch.cuda.Stream(device="cuda:0"))
     if a.workload == "grid":
@@ -554,6 +662,9 @@ def main():
         return
     if a.workload == "prefill":
         run_prefill(a)
+        return
+    if a.workload == "sim":
+        run_sim(a)
         return
     if a.workload == "profile":
         run_profile(a)

@@ -151,15 +151,27 @@ extern "C" ps_status ps_predict_chunked_prefill(const ps_profile* p, const ps_ru
         return PS_EINVAL;
     const std::vector<Req> decs = predicted(running, n_running, avg_decode_len);
     // sum of the iteration times if chunk size c is kept, or a negative value as soon as one reaches the TPOT
+    // decodes still running in iteration j and the KV tokens they attend there, computed once per j
+    std::vector<int64_t> act_j, kv_j;
+    auto decodes_in = [&](int32_t j) {
+        while ((int32_t)act_j.size() <= j) {
+            const int64_t jj = (int64_t)act_j.size();
+            int64_t active = 0, kv = 0;
+            for (const Req& r : decs)
+                if (r.rem > jj) { active++; kv += r.kv + jj + 1; }
+            act_j.push_back(active);
+            kv_j.push_back(kv);
+        }
+    };
     auto kept = [&](int32_t c_fit, int32_t* n_out) {
         double total = wait_ms;
         int64_t done = 0;
         int32_t j = 0;
         for (; done < prompt_len; j++) {
             const int64_t c = std::min<int64_t>(c_fit, prompt_len - done);
-            int64_t active = 0, kv = 0;
-            for (const Req& r : decs)
-                if (r.rem > j) { active++; kv += r.kv + j + 1; }
+            decodes_in(j);
+            const int64_t active = act_j[j];
+            int64_t kv = kv_j[j];
             kv += done + c;
             const double t = ps_profile_lookup(p, (double)(active + c), (double)kv);
             if (!(t < tpot_ms)) return -1.0;
