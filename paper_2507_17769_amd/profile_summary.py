@@ -7,6 +7,7 @@ roofline.traffic).
     python -m paper_2507_17769_amd.profile_summary prefill <bench_prefill.json> <command> > profiles/<name>.md
     python -m paper_2507_17769_amd.profile_summary profile <bench_profile.json> <command> > profiles/<name>.md
     python -m paper_2507_17769_amd.profile_summary grid   <bench_grid.json> <command> > profiles/<name>.md
+    python -m paper_2507_17769_amd.profile_summary sim    <bench_sim.json> <command> > profiles/<name>.md
     python -m paper_2507_17769_amd.profile_summary counters <fetch.csv> <write.csv> <fetch_copy.csv> <write_copy.csv> \
             <workload> <seed> <md out> [--json]
 
@@ -230,7 +231,41 @@ def profile_summary(profile_json, command):
     return "\n".join(out) + "\n"
 
 
+def sim_summary(sim_json, command):
+    d = json.load(open(sim_json))
+    out = ["# Cluster simulation with the measured iteration-time table — 20 instances of the 8B-shaped model, one MI355X each", "",
+           "The paper's evaluation method (Sec. 5.1: instances simulated in 1 ms steps with iteration times from a measured table) under "
+           "the router of Sec. 4, through `ps_sim_run`.  The table is measured in the same run with `ps_step_tokens` (whole model); "
+           "rows up to 256 tokens are decode batches, larger rows are 256 decodes plus one prefill chunk with the remaining tokens.", "",
+           f"Command:  `{command}`", "", d["config"]["workload"] + ".", "",
+           "Iteration time in ms (`-`: the cell cannot exist, it takes the nearest measured value of its row):", "",
+           "| tokens \\ KV size | " + " | ".join(str(k) for k in d["kv_sizes"]) + " |", "|---|" + "---|" * len(d["kv_sizes"])]
+    for b, row in zip(d["batch_sizes"], d["ms"]):
+        out.append(f"| {b} | " + " | ".join("-" if v is None else f"{v:.3f}" for v in row) + " |")
+    out += ["", "Request rate swept upwards in steps of 30 % until the DSLO attainment (Sec. 2.3: every token i of a request before "
+            "arrival + TTFT + i x TPOT) falls below 90 %; input / output lengths uniform in [1, 1024] / [1, 1024] (`uniform_512_512`) and "
+            "[1, 8192] / [1, 2048] (`uniform_4096_1024`, and `tier_flip` = the same with the tier probabilities reversed for the second "
+            "half of the requests, Sec. 5.3); Poisson arrivals.", "",
+            "| trace | deployment | rate /s | attained | by tier 20 / 30 / 50 / 100 ms | dropped | promotions | instance-s per request |", "|---|---|---|---|---|---|---|---|"]
+    for r in d["runs"]:
+        out.append(f"| {r['trace']} | {r['mode']} | {r['rate_per_s']} | {r['attained']:.3f} | " + " / ".join(f"{v:.3f}" for v in r["attained_by_tier"])
+                   + f" | {r['dropped']} | {r['promotions']} | {r['instance_seconds_per_request']:.3f} |")
+    out += ["", "Goodput (attained requests per second) at the highest swept rate with at least 90 % attainment: "
+            + "; ".join(f"{k}: {v}" for k, v in d["goodput"].items()) + ".", "",
+            f"Router speed: {d['router']['requests_per_wall_second']:.0f} requests and {d['router']['admission_tests_per_wall_second']:.0f} "
+            "(request, instance) admission tests per second of wall time over all runs, one host thread, instance stepping included "
+            "(the paper reports 4825 requests per second for its scheduler, Sec. 5.6)."]
+    if "cpu_baseline" in d:
+        c = d["cpu_baseline"]
+        out += ["", f"Oracle simulator on {c['sample']}: {c['value']:.0f} requests per wall second; `ps_sim_run` on the same sample: "
+                f"{c['same_sample_cpp']:.0f}; outputs identical: {c['identical_outputs']}."]
+    return "\n".join(out) + "\n"
+
+
 def main(argv):
+    if len(argv) >= 4 and argv[1] == "sim":
+        sys.stdout.write(sim_summary(argv[2], argv[3]))
+        return 0
     if len(argv) >= 4 and argv[1] == "profile":
         sys.stdout.write(profile_summary(argv[2], argv[3]))
         return 0
