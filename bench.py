@@ -576,8 +576,20 @@ def run_sim(a):
     traces = {"uniform_512_512": (1024, 1024, False, 100.0), "uniform_4096_1024": (8192, 2048, False, 20.0),
               "tier_flip_4096_1024": (8192, 2048, True, 20.0)}
     wall_total, placed_total, tests_total = 0.0, 0, 0
+    res["optimal"] = {}
     for name, (max_p, max_o, burst, rate0) in traces.items():
         for mode in ("co-located", "disaggregated"):
+            # Sec. 3.5: the minimal cost of every request at its batch limits -> the request rate 20 instances could carry at best
+            tr = W.sim_trace(a.seed, n, 1.0, max_p, max_o, burst=burst)
+            costs = []
+            for i in range(min(n, 2000)):
+                p_, d_, tp_, tt_ = tr["prompt"][i], tr["output"][i], tpots[tr["tier"][i]], tr["ttft"][i]
+                costs.append(prof.optimal_cost_co(p_, d_, tp_, tt_, capacity, 4096) if mode == "co-located"
+                             else prof.optimal_cost_pd(p_, d_, tp_, capacity, 2048, 4096))
+            finite = [c for c in costs if np.isfinite(c)]
+            res["optimal"][f"{name} {mode}"] = {"instance_ms_per_request": round(float(np.mean(finite)), 3),
+                                                "rate_per_s": round(n_servers * 1e3 / float(np.mean(finite)), 1),
+                                                "requests_without_a_feasible_batch": len(costs) - len(finite)}
             best, att = 0.0, 1.0
             for step in range(16):
                 if att < 0.9:
@@ -600,6 +612,7 @@ def run_sim(a):
                                     "simulated_s": round(r["end_ms"] / 1e3, 1), "wall_s": round(wall, 3)})
                 print(f"sim: {name} {mode} {rate}/s attained {att:.3f} wall {wall:.2f}s", file=sys.stderr, flush=True)
             res["goodput"][f"{name} {mode}"] = round(best, 1)
+            res["optimal"][f"{name} {mode}"]["goodput_over_optimal"] = round(best / res["optimal"][f"{name} {mode}"]["rate_per_s"], 3)
     prof.close()
     res["value"] = res["goodput"]["uniform_512_512 co-located"]
     res["router"] = {"requests_per_wall_second": round(placed_total / wall_total, 1), "admission_tests_per_wall_second": round(tests_total / wall_total, 1),

@@ -76,6 +76,18 @@ int32_t ps_batch_limit_pd(const ps_profile* prof, double p, double d, double tpo
  * below capacity; 0 if none. */
 int32_t ps_batch_limit_co(const ps_profile* prof, double p, double d, double tpot_ms, double ttft_ms, double capacity, int32_t b_max);
 
+/* Sec. 3.5: cost of serving one request (prompt p, output d), in instance-milliseconds.  The table's two axes are
+ * taken apart as in the cost model of Sec. 3.4: GEMM(B) = T(B, smallest profiled KV size), DcAttn(kv) =
+ * T(smallest profiled batch, kv) - T(smallest profiled batch, smallest profiled KV size), PF(p) = DcAttn(p).
+ *   disaggregated: p GEMM(b_pf)/b_pf + PF(p) + d GEMM(b_dc)/b_dc + DcAttn(d (p + d/2))
+ *   co-located:    (p + d) GEMM(b)/b + PF(p) + DcAttn(d (p + d/2))
+ * NaN for a null profile or a non-positive batch size. */
+double ps_cost_pd(const ps_profile* prof, double p, double d, double b_pf, double b_dc);
+double ps_cost_co(const ps_profile* prof, double p, double d, double b);
+/* The same at the batch limits above (the minimal cost of Sec. 3.5); +inf if no batch size satisfies them. */
+double ps_optimal_cost_pd(const ps_profile* prof, double p, double d, double tpot_ms, double capacity, double b_pf, int32_t b_max);
+double ps_optimal_cost_co(const ps_profile* prof, double p, double d, double tpot_ms, double ttft_ms, double capacity, int32_t b_max);
+
 /* ---- Cluster simulation (Sec. 5.1) of the router of Sec. 4 on co-located instances --------------
  *
  * Instances advance in steps of 1 ms; an iteration's duration is the profile's value for (tokens in the

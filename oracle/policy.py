@@ -11,6 +11,7 @@ TTFT"): dynamic chunking for a prefill instance (a request whose remaining lengt
 the token budget is finished at once and nothing else is admitted into that enlarged iteration),
 and, for co-location, admitting a prefill only if the chunk size predicted at scheduling time can
 be kept for the whole prefill while the decodes' KV grows.  Sec. 3.4: batch-size limits.
+Sec. 3.5: the cost of serving one request at those batch sizes.
 
 Readings fixed where the text is loose (each is one sentence of the paper made executable):
   * table lookup: bilinear interpolation between profiled points; below the first point of an axis
@@ -28,6 +29,11 @@ Readings fixed where the text is loose (each is one sentence of the paper made e
     iterations plus the wait time stays below the TTFT.  (Taking the largest c that fits the first
     iteration and rejecting when a later one does not would turn away every multi-chunk prompt on a
     table that grows with the KV size at all, even on an empty instance.)
+  * cost (Sec. 3.5): the table is the only profile there is, so its two axes are taken apart as the
+    paper's cost model does (Sec. 3.4): GEMM(B) = T(B, smallest profiled KV size) and
+    DcAttn(kv) = T(smallest profiled batch, kv) - T(smallest profiled batch, smallest profiled KV
+    size); PF(p), the prefill attention of a whole prompt, is taken as DcAttn(p), the paper's own
+    simplification ("comparable to decode attention with the same existing KV length").
 """
 import math
 
@@ -170,3 +176,35 @@ def batch_limit_co(profile, p, d, tpot_ms, ttft_ms, capacity, b_max=4096):
         if kv < capacity and t < tpot_ms and (p + d) / b * t < ttft_ms:
             best = b
     return best
+
+
+def gemm_time(profile, batch):
+    """GEMM(B) of the paper's cost model: the table's time at the smallest profiled KV size."""
+    return profile.lookup(batch, profile.k[0])
+
+
+def attn_time(profile, kv):
+    """DcAttn(kv): what the table adds over its smallest profiled KV size, at the smallest profiled batch."""
+    return profile.lookup(profile.b[0], kv) - profile.lookup(profile.b[0], profile.k[0])
+
+
+def cost_pd(profile, p, d, b_pf, b_dc):
+    """Sec. 3.5, disaggregated: p GEMM(B_pf)/B_pf + PF(p) + d GEMM(B_dc)/B_dc + DcAttn(d (p + d/2)), in instance-ms."""
+    return p * gemm_time(profile, b_pf) / b_pf + attn_time(profile, p) + d * gemm_time(profile, b_dc) / b_dc + attn_time(profile, d * (p + d / 2.0))
+
+
+def cost_co(profile, p, d, b):
+    """Sec. 3.5, co-located: (p + d) GEMM(B)/B + PF(p) + DcAttn(d (p + d/2)), in instance-ms."""
+    return (p + d) * gemm_time(profile, b) / b + attn_time(profile, p) + attn_time(profile, d * (p + d / 2.0))
+
+
+def optimal_cost_pd(profile, p, d, tpot_ms, capacity, b_pf, b_max=4096):
+    """Cost at the largest decode batch the TPOT and the memory allow (Sec. 3.4, 3.5); inf if none."""
+    b = batch_limit_pd(profile, p, d, tpot_ms, capacity, b_max)
+    return cost_pd(profile, p, d, b_pf, b) if b > 0 else math.inf
+
+
+def optimal_cost_co(profile, p, d, tpot_ms, ttft_ms, capacity, b_max=4096):
+    """Cost at the largest token batch the TPOT, the TTFT and the memory allow (Sec. 3.4, 3.5); inf if none."""
+    b = batch_limit_co(profile, p, d, tpot_ms, ttft_ms, capacity, b_max)
+    return cost_co(profile, p, d, b) if b > 0 else math.inf

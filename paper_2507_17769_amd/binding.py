@@ -127,6 +127,10 @@ _SCHED_SIGS = {
     "ps_predict_chunked_prefill": (C.c_int, [_P, _P, C.c_int32, C.c_int32, C.c_int32, _D, _D, _D, _I32P, _I32P, _I32P, C.POINTER(_D)]),
     "ps_batch_limit_pd": (C.c_int32, [_P, _D, _D, _D, _D, C.c_int32]),
     "ps_batch_limit_co": (C.c_int32, [_P, _D, _D, _D, _D, _D, C.c_int32]),
+    "ps_cost_pd": (_D, [_P, _D, _D, _D, _D]),
+    "ps_cost_co": (_D, [_P, _D, _D, _D]),
+    "ps_optimal_cost_pd": (_D, [_P, _D, _D, _D, _D, _D, C.c_int32]),
+    "ps_optimal_cost_co": (_D, [_P, _D, _D, _D, _D, _D, C.c_int32]),
     "ps_sim_run": (C.c_int, [_P, _P, _P, C.c_int32, _P, _P, _P, _P, _P, _P]),
 }
 EXPORTS = sorted(_SIGS)
@@ -336,6 +340,18 @@ class Profile:
                                                     float(ttft_ms), float(wait_ms), C.byref(admit), C.byref(chunk), C.byref(n), C.byref(t)),
                      "ps_predict_chunked_prefill")
         return bool(admit.value), chunk.value, n.value, t.value
+
+    def cost_pd(self, p, d, b_pf, b_dc):
+        return lib.ps_cost_pd(self.handle, float(p), float(d), float(b_pf), float(b_dc))
+
+    def cost_co(self, p, d, b):
+        return lib.ps_cost_co(self.handle, float(p), float(d), float(b))
+
+    def optimal_cost_pd(self, p, d, tpot_ms, capacity, b_pf, b_max=4096):
+        return lib.ps_optimal_cost_pd(self.handle, float(p), float(d), float(tpot_ms), float(capacity), float(b_pf), int(b_max))
+
+    def optimal_cost_co(self, p, d, tpot_ms, ttft_ms, capacity, b_max=4096):
+        return lib.ps_optimal_cost_co(self.handle, float(p), float(d), float(tpot_ms), float(ttft_ms), float(capacity), int(b_max))
 
     def simulate(self, arrival, prompt, output, ttft, tier, tpots, n_servers, avg_decode, kv_capacity, check_period=1000,
                  max_steps=10 ** 9, disaggregated=False, prefill_budget=0):

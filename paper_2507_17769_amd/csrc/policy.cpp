@@ -217,3 +217,30 @@ extern "C" int32_t ps_batch_limit_co(const ps_profile* prof, double p, double d,
     }
     return best;
 }
+
+// Sec. 3.5.  The table's two axes taken apart as in the cost model of Sec. 3.4: GEMM(B) is the time at the smallest
+// profiled KV size, DcAttn(kv) what the KV size adds at the smallest profiled batch; PF(p) is taken as DcAttn(p).
+static double gemm_time(const ps_profile* p, double batch) { return ps_profile_lookup(p, batch, p->k[0]); }
+static double attn_time(const ps_profile* p, double kv) { return ps_profile_lookup(p, p->b[0], kv) - ps_profile_lookup(p, p->b[0], p->k[0]); }
+
+extern "C" double ps_cost_pd(const ps_profile* prof, double p, double d, double b_pf, double b_dc) {
+    if (!prof || !(b_pf > 0.0) || !(b_dc > 0.0)) return std::numeric_limits<double>::quiet_NaN();
+    return p * gemm_time(prof, b_pf) / b_pf + attn_time(prof, p) + d * gemm_time(prof, b_dc) / b_dc + attn_time(prof, d * (p + d / 2.0));
+}
+
+extern "C" double ps_cost_co(const ps_profile* prof, double p, double d, double b) {
+    if (!prof || !(b > 0.0)) return std::numeric_limits<double>::quiet_NaN();
+    return (p + d) * gemm_time(prof, b) / b + attn_time(prof, p) + attn_time(prof, d * (p + d / 2.0));
+}
+
+extern "C" double ps_optimal_cost_pd(const ps_profile* prof, double p, double d, double tpot_ms, double capacity, double b_pf, int32_t b_max) {
+    if (!prof) return std::numeric_limits<double>::quiet_NaN();
+    const int32_t b = ps_batch_limit_pd(prof, p, d, tpot_ms, capacity, b_max);
+    return b > 0 ? ps_cost_pd(prof, p, d, b_pf, (double)b) : std::numeric_limits<double>::infinity();
+}
+
+extern "C" double ps_optimal_cost_co(const ps_profile* prof, double p, double d, double tpot_ms, double ttft_ms, double capacity, int32_t b_max) {
+    if (!prof) return std::numeric_limits<double>::quiet_NaN();
+    const int32_t b = ps_batch_limit_co(prof, p, d, tpot_ms, ttft_ms, capacity, b_max);
+    return b > 0 ? ps_cost_co(prof, p, d, (double)b) : std::numeric_limits<double>::infinity();
+}

@@ -252,6 +252,12 @@ def sim_summary(sim_json, command):
                    + f" | {r['dropped']} | {r['promotions']} | {r['instance_seconds_per_request']:.3f} |")
     out += ["", "Goodput (attained requests per second) at the highest swept rate with at least 90 % attainment: "
             + "; ".join(f"{k}: {v}" for k, v in d["goodput"].items()) + ".", "",
+            "Against the optimum of Sec. 3.5 (every request served at the largest batch its TPOT, TTFT and the KV capacity allow, cost = "
+            "instance-milliseconds from the table's GEMM and attention parts; 20 instances / mean cost = the best possible rate): "
+            + "; ".join(f"{k}: {v['instance_ms_per_request']} ms per request -> {v['rate_per_s']}/s, goodput / optimum = {v['goodput_over_optimal']}"
+                        + (f" ({v['requests_without_a_feasible_batch']} of 2000 sampled requests have no feasible batch and are left out)"
+                           if v["requests_without_a_feasible_batch"] else "")
+                        for k, v in d.get("optimal", {}).items()) + ".", "",
             f"Router speed: {d['router']['requests_per_wall_second']:.0f} requests and {d['router']['admission_tests_per_wall_second']:.0f} "
             "(request, instance) admission tests per second of wall time over all runs, one host thread, instance stepping included "
             "(the paper reports 4825 requests per second for its scheduler, Sec. 5.6)."]

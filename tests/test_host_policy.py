@@ -84,6 +84,23 @@ def test_chunked_prefill_prediction_and_limits_match_oracle():
         pr.close()
 
 
+def test_costs_match_oracle():
+    rng = np.random.default_rng(5)
+    for _ in range(20):
+        b, k, ms = _tables(rng)
+        pr, want = B.Profile(b, k, ms), op.Profile(b, k, ms.tolist())
+        for _ in range(10):
+            p, d = float(rng.integers(1, 8192)), float(rng.integers(1, 2048))
+            bpf, bdc, bb = float(rng.integers(1, 4096)), float(rng.integers(1, 512)), float(rng.integers(1, 4096))
+            tpot, ttft, cap = float(rng.uniform(1, 60)), float(rng.uniform(50, 2000)), float(rng.uniform(1e4, 3e6))
+            assert pr.cost_pd(p, d, bpf, bdc) == op.cost_pd(want, p, d, bpf, bdc)      # same double arithmetic in the same order
+            assert pr.cost_co(p, d, bb) == op.cost_co(want, p, d, bb)
+            assert pr.optimal_cost_pd(p, d, tpot, cap, bpf, 600) == op.optimal_cost_pd(want, p, d, tpot, cap, bpf, 600)
+            assert pr.optimal_cost_co(p, d, tpot, ttft, cap, 600) == op.optimal_cost_co(want, p, d, tpot, ttft, cap, 600)
+        pr.close()
+    assert math.isnan(B.lib.ps_cost_co(None, 1.0, 1.0, 1.0))
+
+
 def test_argument_errors():
     with pytest.raises(B.PolystepError):
         B.Profile([4, 4], [1], [[1.0], [2.0]])            # batch sizes not strictly ascending

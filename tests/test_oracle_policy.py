@@ -170,3 +170,24 @@ def test_batch_limits_on_a_linear_profile():
     # a tight TTFT needs few iterations, i.e. a large batch: the limit is an interval's upper end or nothing
     tight = (p + d) / want * f(want)
     assert op.batch_limit_co(pr, p, d, tpot, ttft_ms=tight, capacity=1e12) == 0
+
+
+def test_cost_of_a_request_by_hand():
+    # T = 2 + 0.01 B + 1e-5 KV with KV knots from 0: GEMM(B) = 2 + 0.01 B, DcAttn(kv) = 1e-5 kv
+    pr = op.Profile([1, 4096], [0, 10 ** 7], [[2.01, 102.01], [42.96, 142.96]])
+    assert op.gemm_time(pr, 100) == pytest.approx(3.0) and op.attn_time(pr, 220000) == pytest.approx(2.2)
+    # co-located, p = 1000, d = 200, B = 100: 1200 * 3 / 100 + 0.01 + 1e-5 * 200 * 1100 = 36 + 0.01 + 2.2
+    assert op.cost_co(pr, 1000, 200, 100) == pytest.approx(38.21)
+    # disaggregated, B_pf = 2000, B_dc = 50: 1000 * 22 / 2000 + 0.01 + 200 * 2.5 / 50 + 2.2 = 11 + 0.01 + 10 + 2.2
+    assert op.cost_pd(pr, 1000, 200, 2000, 50) == pytest.approx(23.21)
+    # larger batches share the fixed 2 ms of an iteration among more tokens: the cost falls with B and tends to the
+    # per-token slope, 0.01 (p + d) + attention
+    costs = [op.cost_co(pr, 1000, 200, b) for b in (10, 100, 1000, 4000)]
+    assert all(x > y for x, y in zip(costs, costs[1:])) and costs[-1] > 0.01 * 1200 + 2.21
+    # at the batch limits: decode batch limit for TPOT 6 is ceil(4 / 0.021) - 1 = 190 (see the batch-limit test)
+    assert op.optimal_cost_pd(pr, 1000, 200, 6.0, 1e12, 2000) == pytest.approx(op.cost_pd(pr, 1000, 200, 2000, 190))
+    assert op.optimal_cost_pd(pr, 1000, 200, 2.0, 1e12, 2000) == float("inf")
+    b = op.batch_limit_co(pr, 1000, 200, 6.0, 1e12, 1e12)
+    assert op.optimal_cost_co(pr, 1000, 200, 6.0, 1e12, 1e12) == pytest.approx((1200 * (2 + 0.01 * b) / b) + 0.01 + 2.2)
+    # a looser TPOT allows a larger batch and so a lower cost (the paper's Fig. on cost vs TPOT)
+    assert op.optimal_cost_co(pr, 1000, 200, 12.0, 1e12, 1e12) < op.optimal_cost_co(pr, 1000, 200, 6.0, 1e12, 1e12)
