@@ -94,7 +94,9 @@ double ps_optimal_cost_co(const ps_profile* prof, double p, double d, double tpo
  * iteration, KV tokens attended).  In every step, in this order: iterations whose end time has been
  * reached deliver their tokens at that end time; arrived requests join the queue of their tier; every
  * check_period_ms steps the scale-down check runs; the queues are served, tightest tier first, first come
- * first served; instances outside an iteration that hold requests start one.
+ * first served; instances outside an iteration that hold requests start one, at the end time of their
+ * previous iteration if that ended within this step (iterations run back to back; only the router works on
+ * the 1 ms grid), else at the step.
  * An iteration holds one token per request in decode and the next chunk of the one request in prefill (an
  * instance takes a new request only while no prefill is in progress on it); the prefill's last chunk
  * produces token 0, a request with output_len d then takes d - 1 decode iterations.  Token i is due at
@@ -114,10 +116,10 @@ double ps_optimal_cost_co(const ps_profile* prof, double p, double d, double tpo
  * PS_SIM_DISAGGREGATED differs as follows.  Prefill runs on a cluster of its own, shared by all tiers:
  * queued requests are taken in order of arrival + TTFT (Sec. 4.1); a prefill instance forms its iterations
  * with ps_chunk_plan (dynamic, prefill_budget) over its requests in admission order; a request goes to the
- * prefill instance with most unprocessed prompt tokens whose predicted end of the request's prefill (the
- * wait for the iteration in flight plus the planned iterations up to the request's last chunk, each start
- * counted at the whole step the instance would start it) is before the first-token deadline, else to an
- * instance from the idle pool.  The prefill's end delivers token 0
+ * prefill instance with most unprocessed prompt tokens on which the plan with the request added (the wait
+ * for the iteration in flight plus the planned iterations) gives the request its first token before its
+ * deadline and still gives every request already queued there its own in time, else to an instance from
+ * the idle pool.  The prefill's end delivers token 0
  * and queues the request for decoding (the transfer takes no time); decode clusters work as above except
  * that an instance admits the request if ps_predict_admit keeps the largest future KV size's iteration
  * below the instance's TPOT, that KV size is below kv_capacity, and the wait for the iteration in flight

@@ -19,7 +19,8 @@ Readings fixed where the text is loose:
     request of a queue that cannot be placed but could still make its first-token deadline on an
     empty instance (one that no longer could is dropped: it counts as not attained and is never
     served), (E) every instance that is not inside an iteration
-    and has requests starts one;
+    and has requests starts one: at the end time of its previous iteration if that ended within this
+    step (iterations run back to back; only the router works on the 1 ms grid), else at the step;
   * an iteration holds one token of every request in decode and the next chunk of the one request
     in prefill (an instance takes a new request only while no prefill is in progress on it); its
     duration is the table's value for (tokens, sum of KV sizes attended): a decode attends its KV
@@ -65,6 +66,7 @@ class Server:
         self.sid, self.state, self.tier, self.joined = sid, POOL, -1, -1
         self.reqs = []          # request indices in admission order
         self.busy_until = None  # end time of the iteration in flight
+        self.free_at = None     # end time of an iteration that ended in the current step
         self.batch = []         # (request index, tokens) of the iteration in flight
         self.since = 0.0        # when it last left the idle pool
 
@@ -164,7 +166,7 @@ def simulate(profile, arrival, prompt, output, ttft, tier, tpots, n_servers, avg
                         r.phase, r.finish = 3, t_end
                         s.reqs.remove(ri)
                         done += 1
-                s.busy_until, s.batch = None, []
+                s.busy_until, s.batch, s.free_at = None, [], t_end
         for s in servers:
             if s.state == PENDING and not s.reqs:
                 to_pool(s, now)
@@ -217,7 +219,9 @@ def simulate(profile, arrival, prompt, output, ttft, tier, tpots, n_servers, avg
                         tokens += c
                         kv += r.prefilled + c
                 s.batch = batch
-                s.busy_until = now + profile.lookup(tokens, kv)
+                s.busy_until = (s.free_at if s.free_at is not None else now) + profile.lookup(tokens, kv)
+        for s in servers:
+            s.free_at = None
         now += 1
     for s in servers:
         if s.state != POOL:

@@ -22,17 +22,14 @@ Readings fixed where the text is loose (beyond those of sim.py):
     come first served), prefill queue (nearest deadline first), iteration starts;
   * a chunk attends the prompt tokens up to its own end; an iteration's duration is the table's
     value for (tokens in it, KV tokens attended);
-  * the router predicts on the simulator's clock: an instance starts its next iteration at the first
-    whole step at or after the end of the one in flight, so the wait and every planned iteration of
-    a prefill instance are counted up to whole steps (without this, prefill instances packed to the
-    deadline deliver first tokens a few milliseconds late);
+  * a request joins a prefill instance only if the requests already queued there still get their
+    first tokens in time with it in the plan (dynamic chunking lets a later request share the
+    iteration of an earlier one's last chunk and so lengthens it);
   * load of a prefill instance = prompt tokens not yet processed on it; the scale-down check returns
     the prefill instance with the lowest load to the pool if it holds no request;
   * a queued request that could no longer meet its next deadline even on an empty instance is
     dropped (before prefill: the first token; between prefill and decode: the second token).
 """
-import math
-
 from . import policy
 
 POOL, ACTIVE, PENDING = 0, 1, 2
@@ -51,7 +48,7 @@ class Request:
 class Server:
     def __init__(self, sid):
         self.sid, self.state, self.tier, self.joined = sid, POOL, -1, -1
-        self.reqs, self.busy_until, self.batch, self.since = [], None, [], 0.0
+        self.reqs, self.busy_until, self.batch, self.since, self.free_at = [], None, [], 0.0, None
 
 
 def simulate(profile, arrival, prompt, output, ttft, tier, tpots, n_servers, avg_decode, kv_capacity, prefill_budget,
@@ -69,8 +66,7 @@ def simulate(profile, arrival, prompt, output, ttft, tier, tpots, n_servers, avg
     cost, join_counter, next_arrival, done = 0.0, 0, 0, 0
 
     def wait_of(s, now):
-        """steps from now until the instance can start its next iteration"""
-        return max(0, math.ceil(s.busy_until) - now) if s.busy_until is not None else 0
+        return max(0.0, s.busy_until - now) if s.busy_until is not None else 0.0
 
     def left(s, ri):
         """prompt tokens of request ri not yet processed or in the iteration in flight"""
@@ -80,11 +76,13 @@ def simulate(profile, arrival, prompt, output, ttft, tier, tpots, n_servers, avg
     def prefill_load(s):
         return sum(reqs[i].prompt - reqs[i].prefilled for i in s.reqs)
 
-    def prefill_time(s, r, now):
-        """predicted time from now to the end of the iteration that finishes r's prefill on s"""
+    def prefill_admits(s, r, now):
+        """would r, queued behind the requests already on s, get its first token in time, and would they still get theirs"""
         ids = [i for i in s.reqs if left(s, i) > 0]
         rem = [left(s, i) for i in ids] + [r.prompt]
         at = [reqs[i].prompt - left(s, i) for i in ids] + [0]
+        whole = [reqs[i].prompt for i in ids] + [r.prompt]
+        due = [reqs[i].arrival + reqs[i].ttft - now for i in ids] + [r.arrival + r.ttft - now]
         t = wait_of(s, now)
         for it in policy.chunk_plan(rem, prefill_budget, True, 0):
             tokens = kv = 0
@@ -93,10 +91,10 @@ def simulate(profile, arrival, prompt, output, ttft, tier, tpots, n_servers, avg
                 tokens += tok
                 kv += at[idx]
             t += profile.lookup(tokens, kv)
-            if at[-1] == r.prompt:
-                return t
-            t = math.ceil(t)   # the next iteration starts at a whole step
-        raise AssertionError("plan does not finish the request")
+            for idx, _ in it:
+                if at[idx] == whole[idx] and not t < due[idx]:
+                    return False
+        return True
 
     def decode_admits(s, r, now):
         run = [(reqs[i].kv_len, reqs[i].generated) for i in s.reqs]
@@ -135,14 +133,13 @@ def simulate(profile, arrival, prompt, output, ttft, tier, tpots, n_servers, avg
         return None
 
     def place_prefill(r, now):
-        budget_left = r.arrival + r.ttft - now
         cl = [s for s in servers if s.state == ACTIVE and s.tier == PREFILL_CLUSTER]
         for s in sorted(cl, key=lambda s: (-prefill_load(s), s.joined)):
-            if prefill_time(s, r, now) < budget_left:
+            if prefill_admits(s, r, now):
                 return s
         for s in servers:
             if s.state == POOL:
-                if prefill_time(s, r, now) < budget_left:
+                if prefill_admits(s, r, now):
                     join(s, PREFILL_CLUSTER, now)
                     return s
                 break
@@ -187,7 +184,7 @@ def simulate(profile, arrival, prompt, output, ttft, tier, tpots, n_servers, avg
                     s.reqs.remove(ri)
                     r.phase = 4
                     decode_queues[r.tier].append(ri)
-            s.busy_until, s.batch = None, []
+            s.busy_until, s.batch, s.free_at = None, [], t_end
         for s in servers:
             if s.state == PENDING and not s.reqs:
                 to_pool(s, now)
@@ -230,7 +227,7 @@ def simulate(profile, arrival, prompt, output, ttft, tier, tpots, n_servers, avg
             r = reqs[prefill_queue[0]]
             s = place_prefill(r, now)
             if s is None:
-                if prefill_time(Server(-1), r, now) < r.arrival + r.ttft - now:
+                if prefill_admits(Server(-1), r, now):
                     break
                 prefill_queue.pop(0)
                 drop(r)
@@ -253,7 +250,9 @@ def simulate(profile, arrival, prompt, output, ttft, tier, tpots, n_servers, avg
                 for ri in s.reqs:
                     tokens += 1
                     kv += reqs[ri].kv_len + 1
-            s.busy_until = now + profile.lookup(tokens, kv)
+            s.busy_until = (s.free_at if s.free_at is not None else now) + profile.lookup(tokens, kv)
+        for s in servers:
+            s.free_at = None
         now += 1
     for s in servers:
         if s.state != POOL:

@@ -9,7 +9,6 @@
 // (Sec. 4.1, 4.6), and decode clusters per tier with the wait-time-aware admission of Sec. 4.5.
 // Host only.  The decisions themselves are the ones exported by policy.cpp.
 #include <algorithm>
-#include <cmath>
 #include <cstdint>
 #include <deque>
 #include <new>
@@ -44,6 +43,8 @@ struct Instance {
     double busy_until = 0.0;
     std::vector<std::pair<int32_t, int32_t>> batch;  // (request, tokens) of the iteration in flight
     double since = 0.0;               // when it last left the idle pool
+    bool just_ended = false;          // an iteration ended in the current step, at free_at: the next one starts there
+    double free_at = 0.0;
 };
 
 struct Sim {
@@ -178,6 +179,8 @@ struct Sim {
                 }
                 s.in_iteration = false;
                 s.batch.clear();
+                s.just_ended = true;
+                s.free_at = t_end;
                 sum.iterations++;
             }
             for (Instance& s : inst)
@@ -249,9 +252,11 @@ struct Sim {
                         kv += r.prefilled + c;
                     }
                 }
-                s.busy_until = (double)now + ps_profile_lookup(prof, (double)tokens, (double)kv);
+                // iterations run back to back: only the router works on the 1 ms grid
+                s.busy_until = (s.just_ended ? s.free_at : (double)now) + ps_profile_lookup(prof, (double)tokens, (double)kv);
                 s.in_iteration = true;
             }
+            for (Instance& s : inst) s.just_ended = false;
             now++;
         }
         for (Instance& s : inst)
@@ -277,15 +282,12 @@ struct SimPD {
     int32_t done = 0;
     std::vector<ps_running_req> run;
     std::vector<Instance*> cand;
-    std::vector<int32_t> rem, at, plan;
+    std::vector<int32_t> rem, at, whole, plan;
+    std::vector<double> due;
 
     SimPD(const ps_profile* p, const ps_sim_config& c) : prof(p), cfg(c) {}
 
-    // whole steps from now until the instance can start its next iteration: the router predicts on the simulator's
-    // clock, on which an iteration starts at the first step at or after the end of the one before
-    static double wait_of(const Instance& s, int64_t now) {
-        return s.in_iteration ? (double)std::max<int64_t>(0, (int64_t)std::ceil(s.busy_until) - now) : 0.0;
-    }
+    static double wait_of(const Instance& s, int64_t now) { return s.in_iteration ? std::max(0.0, s.busy_until - (double)now) : 0.0; }
 
     // prompt tokens of request i neither processed nor in the iteration in flight
     int32_t left(const Instance& s, int32_t i) const {
@@ -312,23 +314,32 @@ struct SimPD {
         }
     }
 
-    // predicted time from now to the end of the iteration that finishes r's prefill on s (Sec. 4.6: the iterations
-    // of the requests already there and the wait for the one in flight count)
-    double prefill_time(const Instance& s, const Request& r, int64_t now) {
+    // Would r, queued behind the requests already on s, get its first token in time, and would they still get theirs
+    // (Sec. 4.6: the iterations of the requests already there and the wait for the one in flight count; dynamic
+    // chunking lets a later request share the iteration of an earlier one's last chunk and so lengthens it)?
+    bool prefill_admits(const Instance& s, const Request& r, int64_t now) {
         rem.clear();
         at.clear();
+        whole.clear();
+        due.clear();
         for (int32_t i : s.reqs) {
             const int32_t l = left(s, i);
-            if (l > 0) { rem.push_back(l); at.push_back(reqs[i].prompt - l); }
+            if (l <= 0) continue;
+            rem.push_back(l);
+            at.push_back(reqs[i].prompt - l);
+            whole.push_back(reqs[i].prompt);
+            due.push_back(reqs[i].arrival + reqs[i].ttft - (double)now);
         }
         rem.push_back(r.prompt);
         at.push_back(0);
+        whole.push_back(r.prompt);
+        due.push_back(r.arrival + r.ttft - (double)now);
         const int32_t n_chunks = make_plan();
-        const int32_t mine = (int32_t)rem.size() - 1;
+        sum.admission_tests++;
         double t = wait_of(s, now);
         int32_t c = 0;
         while (c < n_chunks) {
-            const int32_t it = plan[3 * c];
+            const int32_t it = plan[3 * c], first = c;
             int64_t tokens = 0, kv = 0;
             for (; c < n_chunks && plan[3 * c] == it; c++) {
                 at[plan[3 * c + 1]] += plan[3 * c + 2];
@@ -336,11 +347,12 @@ struct SimPD {
                 kv += at[plan[3 * c + 1]];
             }
             t += ps_profile_lookup(prof, (double)tokens, (double)kv);
-            if (at[mine] == r.prompt) break;
-            t = std::ceil(t);
+            for (int32_t e = first; e < c; e++) {
+                const int32_t idx = plan[3 * e + 1];
+                if (at[idx] == whole[idx] && !(t < due[idx])) return false;
+            }
         }
-        sum.admission_tests++;
-        return t;
+        return true;
     }
 
     bool decode_admits(const Instance& s, int32_t tier, const Request& r, int64_t now) {
@@ -404,7 +416,6 @@ struct SimPD {
     }
 
     Instance* place_prefill(const Request& r, int64_t now) {
-        const double budget_left = r.arrival + r.ttft - (double)now;
         cand.clear();
         for (Instance& s : inst)
             if (s.state == ACTIVE && s.tier == PREFILL_CLUSTER) cand.push_back(&s);
@@ -414,10 +425,10 @@ struct SimPD {
             return a->joined < b->joined;
         });
         for (Instance* s : cand)
-            if (prefill_time(*s, r, now) < budget_left) return s;
+            if (prefill_admits(*s, r, now)) return s;
         for (Instance& s : inst) {
             if (s.state != POOL) continue;
-            if (prefill_time(s, r, now) < budget_left) {
+            if (prefill_admits(s, r, now)) {
                 join(s, PREFILL_CLUSTER, now);
                 return &s;
             }
@@ -468,6 +479,8 @@ struct SimPD {
                 }
                 s.in_iteration = false;
                 s.batch.clear();
+                s.just_ended = true;
+                s.free_at = t_end;
                 sum.iterations++;
             }
             for (Instance& s : inst)
@@ -524,7 +537,7 @@ struct SimPD {
                 Request& r = reqs[prefill_queue.front()];
                 Instance* s = place_prefill(r, now);
                 if (!s) {
-                    if (prefill_time(empty_instance, r, now) < r.arrival + r.ttft - (double)now) break;
+                    if (prefill_admits(empty_instance, r, now)) break;
                     prefill_queue.erase(prefill_queue.begin());
                     drop(r);
                     continue;
@@ -554,9 +567,11 @@ struct SimPD {
                         kv += reqs[i].kv_len + 1;
                     }
                 }
-                s.busy_until = (double)now + ps_profile_lookup(prof, (double)tokens, (double)kv);
+                // iterations run back to back: only the router works on the 1 ms grid
+                s.busy_until = (s.just_ended ? s.free_at : (double)now) + ps_profile_lookup(prof, (double)tokens, (double)kv);
                 s.in_iteration = true;
             }
+            for (Instance& s : inst) s.just_ended = false;
             now++;
         }
         for (Instance& s : inst)

@@ -4,6 +4,7 @@ of the deadline-based SLO (Sec. 2.3) on random traces."""
 import math
 
 import numpy as np
+import pytest
 
 from oracle import policy, sim
 from paper_2507_17769_amd import workloads as W
@@ -19,21 +20,26 @@ def run(prof, reqs, tpots, n_servers, avg, period=1000, cap=10 ** 12, max_steps=
 
 
 def test_single_request_timeline_by_hand():
-    # constant 7.3 ms iterations; arrival 0.4 is seen at step 1; prefill 1 -> 8.3; the instance is free at step 9:
-    # decode 9 -> 16.3, 17 -> 24.3; the run ends after step 25
+    # constant 7.3 ms iterations; arrival 0.4 is seen at step 1 and the idle instance starts the prefill there: 1 -> 8.3;
+    # iterations then run back to back: 8.3 -> 15.6 -> 22.9 (third token, done), noticed at step 23; the run ends after it
     res = run(table(lambda b, k: 7.3), [(0.4, 100, 3, 300.0, 0)], [20.0], 1, 3)
-    assert res["first_token_ms"] == [1 + 7.3] and res["finish_ms"] == [17 + 7.3]
+    assert res["first_token_ms"] == [1 + 7.3] and res["finish_ms"] == [1 + 7.3 + 7.3 + 7.3]
     assert res["attained"] == [1] and res["server"] == [0]
-    assert res["end_ms"] == 26 and res["cost_ms"] == 25.0 and res["scale_ups"] == 1 and res["scale_downs"] == 0
+    assert res["end_ms"] == 24 and res["cost_ms"] == 23.0 and res["scale_ups"] == 1 and res["scale_downs"] == 0
 
 
 def test_token_i_is_due_at_ttft_plus_i_tpot():
-    # 7.3 ms iterations on a 1 ms clock deliver a token every 8 ms: token i at 8.3 + 8 i.  With TTFT 10 and TPOT 7.5
-    # token i is due at 0.4 + 10 + 7.5 i, so tokens 0..4 are in time and token 5 is the first late one
-    for output, ok in ((5, 1), (6, 0)):
-        res = run(table(lambda b, k: 7.3), [(0.4, 100, output, 10.0, 0)], [7.5], 1, 3)
-        assert res["first_token_ms"] == [8.3] and res["finish_ms"] == [8.3 + 8 * (output - 1)]
+    # T = 1 + kv/100 ms: a 1000-token prompt (prefill 0 -> 11) decodes back to back at 11 + 0.01 i ms for token i, which
+    # the average-length prediction (10 tokens) did not foresee: token i comes at 11 + 11 i + 0.005 i (i + 1) and is due at
+    # 1000 + 20 i, so the first late one is the smallest i with 0.005 i^2 - 8.995 i - 989 > 0
+    prof = policy.Profile([1, 4096], [0, 10 ** 6], [[1.0, 1.0 + 10 ** 4]] * 2)
+    first_late = math.floor((8.995 + math.sqrt(8.995 ** 2 + 4 * 0.005 * 989)) / 0.01) + 1
+    assert first_late == 1903            # the positive root is 1902.9
+    for output, ok in ((first_late, 1), (first_late + 1, 0)):     # tokens 0 .. output - 1
+        res = run(prof, [(0.0, 1000, output, 1000.0, 0)], [20.0], 1, 10)
         assert res["attained"] == [ok]
+        i = output - 1
+        assert res["finish_ms"][0] == pytest.approx(11 + 11 * i + 0.005 * i * (i + 1), rel=1e-9)
 
 
 def test_scale_down_returns_the_empty_instance_and_cost_counts_time_outside_the_pool():
@@ -46,15 +52,14 @@ def test_scale_down_returns_the_empty_instance_and_cost_counts_time_outside_the_
 
 
 def test_deadlines_follow_the_token_index_when_the_output_outgrows_the_prediction():
-    # T = 1 + kv/100 ms: a 1000-token prompt decodes at 11 ms per token at first and slows down as its KV grows past
-    # what the average-length prediction assumed; token i is due at TTFT + 20 i
+    # the same request, checked token by token with a plain loop: iterations chained end to start
     prof = policy.Profile([1, 4096], [0, 10 ** 6], [[1.0, 1.0 + 10 ** 4]] * 2)
 
     def expect(output):
         t = 0 + prof.lookup(1000, 1000)           # prefill starts at step 0
         late = t > 1000.0
         for i in range(1, output):
-            t = math.ceil(t) + prof.lookup(1, 1000 + i)
+            t = t + prof.lookup(1, 1000 + i)
             late = late or t > 1000.0 + 20.0 * i
         return t, late
 
@@ -115,13 +120,16 @@ def test_lazy_promotion_only_when_the_own_cluster_is_full_and_before_scaling_up(
 
 
 def test_promoted_request_keeps_its_own_tpot_in_its_deadlines():
-    # tiers 7.5 / 9 ms, 7.3 ms iterations delivered every 8 ms.  r1 (tier 1) is promoted onto r0's tier-0 instance while
-    # an iteration 33 -> 40.3 is in flight; its prefill runs 41 -> 48.3 and token i comes at 48.3 + 8 i, due at
-    # 40 + 10 + 9 i: always in time with its own TPOT (it would be late from token 4 on with the instance's 7.5 ms)
-    reqs = [(0.4, 100, 2000, 300.0, 0), (40.0, 100, 8, 10.0, 1)]
-    res = run(table(lambda b, k: 7.3), reqs, [7.5, 9.0], 1, 2000, max_steps=120)
+    # tiers 20 / 50 ms, T = 1 + kv/100.  r1 (tier 1) is promoted onto r0's tier-0 instance once r0's prefill (0 -> 11) is
+    # over.  With both decoding, an iteration takes about 12 + 0.02 g ms after g tokens: slower than 20 ms from g = 400
+    # on, which makes r0 late, but r1's 2500 tokens stay ahead of 1005 + 50 i (they would not stay ahead of 1005 + 20 i)
+    prof = policy.Profile([1, 4096], [0, 10 ** 6], [[1.0, 1.0 + 10 ** 4]] * 2)
+    reqs = [(0.0, 1000, 3000, 1000.0, 0), (5.0, 100, 2500, 1000.0, 1)]
+    res = run(prof, reqs, [20.0, 50.0], 1, 10)
     assert res["server"] == [0, 0] and res["promotions"] == 1
-    assert res["first_token_ms"][1] == 48.3 and res["finish_ms"][1] == 48.3 + 8 * 7 and res["attained"][1] == 1
+    assert res["attained"] == [0, 1]
+    i = 2499
+    assert res["finish_ms"][1] > 1005 + 20 * i and res["finish_ms"][1] < 1005 + 50 * i
 
 
 def test_wait_for_the_iteration_in_flight_counts_against_the_first_token_deadline():
@@ -142,12 +150,12 @@ def test_time_already_spent_queueing_counts_against_the_first_token_deadline():
 
 
 def test_later_chunks_attend_the_prompt_prefix():
-    # T = tokens/100 + kv/10000: a 3000-token prompt on an empty instance gets the largest chunk with T < 20, 1980 tokens
-    # (19.998 ms), then 1020 tokens that attend all 3000
+    # T = tokens/100 + kv/10000: a 3000-token prompt on an empty instance keeps the largest chunk with T < 20, 1980 tokens
+    # (19.998 ms; the second iteration, 1020 tokens attending all 3000, takes 10.5 ms), back to back
     prof = policy.Profile([0, 4096], [0, 10 ** 6], [[0.0, 100.0], [40.96, 140.96]])
     res = run(prof, [(0.0, 3000, 1, 300.0, 0)], [20.0], 1, 1)
     assert prof.lookup(1980, 1980) < 20.0 <= prof.lookup(1981, 1981)
-    assert res["first_token_ms"] == [20 + prof.lookup(1020, 3000)]
+    assert res["first_token_ms"] == [prof.lookup(1980, 1980) + prof.lookup(1020, 3000)]
 
 
 def test_pending_instance_joins_the_tier_of_its_requests():

@@ -18,27 +18,27 @@ def run(prof, reqs, tpots, n_servers, avg, budget, period=1000, cap=10 ** 12, ma
 
 def test_dynamic_chunking_timeline_and_hand_over_by_hand():
     # the paper's example: 2050 tokens, budget 1024 -> iterations of 1024 and 1026 tokens (not three).  10.5 ms
-    # iterations: prefill 0 -> 10.5, 11 -> 21.5 (first token); the decode side sees the request at step 22, takes an
-    # instance from the pool, decodes 22 -> 32.5; the run ends after step 33
+    # iterations back to back: prefill 0 -> 10.5 -> 21 (first token); the decode side sees the request at step 21, takes
+    # an instance from the pool, decodes 21 -> 31.5, noticed at step 32; the run ends after it
     res = run(table(lambda b, k: 10.5), [(0.0, 2050, 2, 300.0, 0)], [20.0], 2, 2, 1024)
-    assert res["first_token_ms"] == [21.5] and res["finish_ms"] == [32.5] and res["attained"] == [1]
+    assert res["first_token_ms"] == [21.0] and res["finish_ms"] == [31.5] and res["attained"] == [1]
     assert res["prefill_server"] == [0] and res["decode_server"] == [1]
-    assert res["end_ms"] == 34 and res["cost_ms"] == 34.0 + (34 - 22) and res["scale_ups"] == 2
+    assert res["end_ms"] == 33 and res["cost_ms"] == 33.0 + (33 - 21) and res["scale_ups"] == 2
 
 
 def test_prefill_prediction_plans_with_dynamic_chunking():
     # same request with 25 ms to its first token: two iterations (21 ms) are predicted and it is admitted; three
     # iterations of plain chunking (31.5 ms) would not fit
     res = run(table(lambda b, k: 10.5), [(0.0, 2050, 1, 25.0, 0)], [20.0], 1, 1, 1024)
-    assert res["first_token_ms"] == [21.5] and res["attained"] == [1] and res["dropped"] == 0
+    assert res["first_token_ms"] == [21.0] and res["attained"] == [1] and res["dropped"] == 0
 
 
 def test_later_chunks_attend_the_prompt_prefix():
     # T = tokens/100 + kv/10000; 3000 tokens with budget 1024: 1024 tokens, then the remaining 1976 (< 2 x 1024) at once,
-    # attending all 3000
+    # attending all 3000, back to back
     prof = policy.Profile([0, 4096], [0, 10 ** 6], [[0.0, 100.0], [40.96, 140.96]])
     res = run(prof, [(0.0, 3000, 1, 300.0, 0)], [50.0], 1, 1, 1024)
-    assert res["first_token_ms"] == [11 + prof.lookup(1976, 3000)]
+    assert res["first_token_ms"] == [prof.lookup(1024, 1024) + prof.lookup(1976, 3000)]
 
 
 def test_decode_admission_respects_the_kv_capacity():
@@ -49,11 +49,22 @@ def test_decode_admission_respects_the_kv_capacity():
 
 
 def test_decode_iterations_attend_the_prompt_plus_the_generated_tokens():
-    # T = kv / 100 ms: prefill of 1000 tokens 0 -> 10; decodes attend 1001 and 1002 tokens: 10 -> 20.01, 21 -> 31.02
+    # T = kv / 100 ms: prefill of 1000 tokens 0 -> 10; the decode instance starts at step 10 and attends 1001, then 1002
+    # tokens: 10 -> 20.01 -> 30.03
     prof = policy.Profile([1, 4096], [0, 10 ** 6], [[0.0, 10.0 ** 4]] * 2)
     res = run(prof, [(0.0, 1000, 3, 300.0, 0)], [20.0], 2, 3, 2048)
-    assert res["first_token_ms"] == [10.0] and res["finish_ms"] == [21 + prof.lookup(1, 1002)]
-    assert res["finish_ms"][0] > 31.0
+    assert res["first_token_ms"] == [10.0] and res["finish_ms"] == [10 + prof.lookup(1, 1001) + prof.lookup(1, 1002)]
+    assert 30.02 < res["finish_ms"][0] < 30.04
+
+
+def test_token_i_is_due_at_ttft_plus_i_tpot():
+    # T = 1 + kv/100 ms: prefill of 1000 tokens 0 -> 11, decode from step 11 at 11 + 0.01 i ms for token i (the prediction
+    # assumed 10 tokens): token i comes at 11 + 11 i + 0.005 i (i + 1), is due at 1000 + 20 i, first late one: i = 1903
+    prof = policy.Profile([1, 4096], [0, 10 ** 6], [[1.0, 1.0 + 10 ** 4]] * 2)
+    for output, ok in ((1903, 1), (1904, 0)):     # tokens 0 .. output - 1
+        res = run(prof, [(0.0, 1000, output, 1000.0, 0)], [20.0], 2, 10, 2048)
+        i = output - 1
+        assert res["attained"] == [ok] and abs(res["finish_ms"][0] - (11 + 11 * i + 0.005 * i * (i + 1))) < 1e-6
 
 
 def test_prefill_queue_is_served_in_deadline_order():
@@ -74,16 +85,16 @@ def test_prefill_goes_to_the_most_loaded_instance_that_still_meets_the_deadline(
     assert res["first_token_ms"] == [50.0, 100.0, 52.0, 150.0]
 
 
-def test_prefill_prediction_counts_whole_steps():
-    # 10.5 ms iterations start at whole steps: behind r0 (0 -> 10.5, 11 -> 21.5) a request seen at step 1 would run
-    # 22 -> 32.5, i.e. 31.5 ms from now, not 9.5 + 10.5 + 10.5 = 30.5; with 31.4 ms to its first token it takes a fresh instance
-    reqs = [(0.0, 2050, 1, 300.0, 0), (1.0, 100, 1, 31.4, 0)]
-    res = run(table(lambda b, k: 10.5), reqs, [20.0], 2, 1, 1024)
-    assert res["prefill_server"] == [0, 1] and res["first_token_ms"] == [21.5, 11.5] and res["attained"] == [1, 1]
-    # with 32 ms it waits behind r0 and is exactly as late as predicted
-    reqs = [(0.0, 2050, 1, 300.0, 0), (1.0, 100, 1, 32.0, 0)]
-    res = run(table(lambda b, k: 10.5), reqs, [20.0], 2, 1, 1024)
-    assert res["prefill_server"] == [0, 0] and res["first_token_ms"] == [21.5, 32.5] and res["attained"] == [1, 1]
+def test_a_request_joins_only_if_those_already_queued_still_make_their_deadlines():
+    # T = tokens / 100 ms, budget 1024.  r0 (1024 tokens) runs 0 -> 10.24; ra (600 tokens, 17 ms to its first token) is
+    # queued behind it at step 1: 9.24 + 6 = 15.24 ms, in time.  rb (300 tokens) at step 2 would share ra's iteration
+    # (900 tokens, 9 ms) and push ra's first token to 19.24, past its deadline at 18: rb takes a fresh instance instead
+    prof = policy.Profile([0, 4096], [1, 10 ** 7], [[0.0, 0.0], [40.96, 40.96]])
+    reqs = [(0.0, 1024, 1, 300.0, 0), (1.0, 600, 1, 17.0, 0), (2.0, 300, 1, 300.0, 0)]
+    res = run(prof, reqs, [100.0], 2, 1, 1024)
+    assert res["prefill_server"] == [0, 0, 1]
+    assert res["first_token_ms"] == [prof.lookup(1024, 1), prof.lookup(1024, 1) + prof.lookup(600, 1), 2 + prof.lookup(300, 1)]
+    assert res["attained"] == [1, 1, 1]
 
 
 def test_decode_admission_counts_the_wait_for_the_iteration_in_flight():
