@@ -448,15 +448,15 @@ def measure_profile(a, batch_sizes, kv_sizes, n_decodes_in_mixed=256):
         for kv in kv_sizes:
             if bs <= n_decodes_in_mixed:
                 per = kv // bs
-                if 16 <= per <= 65536:
+                if 16 <= per:
                     cells[(bs, kv)] = W.custom_batch(model, a.seed, 0, 0, [per] * bs, name=f"b{bs}_kv{kv}", tag=bs * 7 + 1)
             else:
                 chunk = bs - n_decodes_in_mixed
                 per = (kv - chunk) // n_decodes_in_mixed
-                if 16 <= per <= 65536:
+                if 16 <= per:
                     cells[(bs, kv)] = W.custom_batch(model, a.seed, chunk, 0, [per] * n_decodes_in_mixed, name=f"b{bs}_kv{kv}", tag=bs * 7 + 1)
     n_pool = max(b.n_pool_pages for b in cells.values())
-    eng = Engine(model, n_pool, L, L, max_position=65536 + 16)
+    eng = Engine(model, n_pool, L, L, max_position=max(s.kv_len for b in cells.values() for s in b.seqs) + 16)
     gen = torch.Generator(device="cuda:0")
     gen.manual_seed(3000 + a.seed)
     rnd = lambda shape, std: (torch.randn(shape, generator=gen, device="cuda:0", dtype=torch.float32) * std).to(torch.bfloat16)

@@ -286,50 +286,81 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 }
 
 // Combine split partials of one query tile: out = sum_j 2^(m_j - M) O_j / sum_j 2^(m_j - M) l_j.
-// One 64-thread block per merge group; each thread owns float4 pieces of the valid rows.
+// One block per merge group.  Each lane owns float4 pieces of the valid rows, 64 pieces per pass; the block's
+// wavefronts share the splits (wavefront w takes splits w, w + NW, ...: a sequence cut over hundreds of workers would
+// otherwise be merged by one wavefront, split after split), each reduces its share to (max, sum, O) against its own
+// maximum, and wavefront 0 combines the NW results through LDS in a fixed order.
+constexpr int MERGE_MAX_WAVES = 16;
+
 template <int D, int G>
-__global__ __launch_bounds__(64) void attn_merge_kernel(AttnArgs a) {
+__global__ __launch_bounds__(64 * MERGE_MAX_WAVES) void attn_merge_kernel(AttnArgs a) {
+    __shared__ float4 s_acc[MERGE_MAX_WAVES][64];
+    __shared__ float2 s_ml[MERGE_MAX_WAVES][64];
     const MergeGroup mg = a.groups[blockIdx.x];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, NW = blockDim.x >> 6;
     const int n_rows = mg.n_tok * G;  // valid rows are the first n_tok * G of the tile
-    for (int c = threadIdx.x; c < n_rows * (D / 4); c += 64) {
-        const int r = c / (D / 4), col = (c % (D / 4)) * 4;
-        // splits are handled eight at a time with all loads of a batch issued together
+    const int n_items = n_rows * (D / 4);
+    for (int c0 = 0; c0 < n_items; c0 += 64) {
+        const int c = c0 + lane;
+        const bool live = c < n_items;
+        const int r = live ? c / (D / 4) : 0, col = live ? (c % (D / 4)) * 4 : 0;
+        // this wavefront's splits, eight at a time with all loads of a batch issued together
         float M = NEG_BIG;
-        for (int j0 = 0; j0 < mg.n_splits; j0 += 8) {
+        for (int j0 = wave; j0 < mg.n_splits; j0 += 8 * NW) {
             float mv[8];
 #pragma unroll
             for (int j = 0; j < 8; j++)
-                if (j0 + j < mg.n_splits) mv[j] = a.part_ml[((size_t)(mg.first_slot + (j0 + j) * mg.stride) * 16 + r) * 2];
+                if (j0 + j * NW < mg.n_splits) mv[j] = a.part_ml[((size_t)(mg.first_slot + (j0 + j * NW) * mg.stride) * 16 + r) * 2];
 #pragma unroll
             for (int j = 0; j < 8; j++)
-                if (j0 + j < mg.n_splits) M = fmaxf(M, mv[j]);
+                if (j0 + j * NW < mg.n_splits) M = fmaxf(M, mv[j]);
         }
         float4 acc = {0.f, 0.f, 0.f, 0.f};
         float L = 0.f;
-        for (int j0 = 0; j0 < mg.n_splits; j0 += 8) {
+        for (int j0 = wave; j0 < mg.n_splits; j0 += 8 * NW) {
             float2 ml[8];
             float4 v[8];
 #pragma unroll
             for (int j = 0; j < 8; j++)
-                if (j0 + j < mg.n_splits) {
-                    const size_t row = (size_t)(mg.first_slot + (j0 + j) * mg.stride) * 16 + r;
+                if (j0 + j * NW < mg.n_splits) {
+                    const size_t row = (size_t)(mg.first_slot + (j0 + j * NW) * mg.stride) * 16 + r;
                     ml[j] = *reinterpret_cast<const float2*>(a.part_ml + row * 2);
                     v[j] = *reinterpret_cast<const float4*>(a.part_o + row * D + col);
                 }
 #pragma unroll
             for (int j = 0; j < 8; j++)
-                if (j0 + j < mg.n_splits) {
+                if (j0 + j * NW < mg.n_splits) {
                     const float w = __builtin_amdgcn_exp2f(ml[j].x - M);
                     L += w * ml[j].y;
                     acc.x += w * v[j].x; acc.y += w * v[j].y; acc.z += w * v[j].z; acc.w += w * v[j].w;
                 }
         }
-        const float inv = 1.0f / L;
-        const int head = mg.kv_head * G + r % G;
-        uint2 w;
-        w.x = pack_bf16(acc.x * inv, acc.y * inv);
-        w.y = pack_bf16(acc.z * inv, acc.w * inv);
-        *reinterpret_cast<uint2*>(a.out + act_offset(mg.tok0 + r / G, head * D + col, a.n_q * D)) = w;
+        if (NW > 1) {
+            s_acc[wave][lane] = acc;
+            s_ml[wave][lane] = float2{M, L};
+            __syncthreads();
+            if (wave == 0) {
+                for (int w = 1; w < NW; w++) M = fmaxf(M, s_ml[w][lane].x);
+                acc = float4{0.f, 0.f, 0.f, 0.f};
+                L = 0.f;
+                for (int w = 0; w < NW; w++) {
+                    const float2 q = s_ml[w][lane];
+                    const float4 v = s_acc[w][lane];
+                    const float f = __builtin_amdgcn_exp2f(q.x - M);  // a wavefront without splits holds (NEG_BIG, 0, 0): f * 0
+                    L += f * q.y;
+                    acc.x += f * v.x; acc.y += f * v.y; acc.z += f * v.z; acc.w += f * v.w;
+                }
+            }
+        }
+        if (wave == 0 && live) {
+            const float inv = 1.0f / L;
+            const int head = mg.kv_head * G + r % G;
+            uint2 w;
+            w.x = pack_bf16(acc.x * inv, acc.y * inv);
+            w.y = pack_bf16(acc.z * inv, acc.w * inv);
+            *reinterpret_cast<uint2*>(a.out + act_offset(mg.tok0 + r / G, head * D + col, a.n_q * D)) = w;
+        }
+        if (NW > 1) __syncthreads();  // the next pass overwrites the LDS slots
     }
 }
 
@@ -342,7 +373,10 @@ static hipError_t launch_dg(const AttnArgs& a, hipStream_t st) {
     hipError_t e = hipGetLastError();
     if (a.ev_end) (void)hipEventRecord(a.ev_end, st);
     if (e != hipSuccess || a.n_groups == 0) return e;
-    hipLaunchKernelGGL((attn_merge_kernel<D, G>), dim3(a.n_groups), dim3(64), 0, st, a);
+    // wavefronts per merge block: about eight splits each (one batch of loads), a power of two up to 16
+    int nw = 1;
+    while (nw < MERGE_MAX_WAVES && nw * 8 < a.max_splits) nw *= 2;
+    hipLaunchKernelGGL((attn_merge_kernel<D, G>), dim3(a.n_groups), dim3(64 * nw), 0, st, a);
     return hipGetLastError();
 }
 

@@ -140,6 +140,7 @@ struct AttnArgs {
     int n_workers;
     const MergeGroup* groups;
     int n_groups;
+    int max_splits;    // largest n_splits of any group: sizes the merge kernel's blocks
     float* part_o;     // [slot][16][d]
     float* part_ml;    // [slot][16][2]
     bf16_t* out;       // [T][n_q * d] in operand order (act_offset)
