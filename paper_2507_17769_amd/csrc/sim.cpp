@@ -47,68 +47,74 @@ struct Instance {
     double free_at = 0.0;
 };
 
-struct Sim {
+// State and steps that both deployments share.
+struct Cluster {
     const ps_profile* prof;
     const ps_sim_config& cfg;
     std::vector<Request> reqs;
     std::vector<Instance> inst;
-    std::vector<std::deque<int32_t>> queues;
     ps_sim_summary sum{};
     double cost = 0.0;
     int64_t join_counter = 0;
+    int32_t done = 0;
     std::vector<ps_running_req> run;   // scratch: the decodes of the instance under test
     std::vector<Instance*> cand;       // scratch: candidate list
 
-    Sim(const ps_profile* p, const ps_sim_config& c) : prof(p), cfg(c) {}
+    Cluster(const ps_profile* p, const ps_sim_config& c) : prof(p), cfg(c) {}
 
-    // chunk size the instance would keep for the request's prefill, 0 = not admitted
-    int32_t admits(const Instance& s, const Request& r, int64_t now) {
-        run.clear();
-        for (int32_t i : s.reqs) {
-            if (reqs[i].phase == PREFILL) return 0;  // one prefill at a time
-            run.push_back(ps_running_req{reqs[i].kv_len, reqs[i].generated});
-        }
-        const double tpot = cfg.tpot_ms[s.tier];
-        const double wait = s.in_iteration ? std::max(0.0, s.busy_until - (double)now) : 0.0;
-        int32_t ok = 0, chunk = 0, n_it = 0;
-        double t_first = 0.0;
-        sum.admission_tests++;
-        if (ps_predict_chunked_prefill(prof, run.data(), (int32_t)run.size(), r.prompt, cfg.avg_decode_len, tpot,
-                                       r.arrival + r.ttft - (double)now, wait, &ok, &chunk, &n_it, &t_first) != PS_OK || !ok)
-            return 0;
-        int32_t ok2 = 0;
-        double predicted = 0.0;
-        int64_t kv = 0;
-        if (ps_predict_admit(prof, run.data(), (int32_t)run.size(), r.prompt, cfg.avg_decode_len, tpot, 0.0, &ok2, &predicted, &kv) != PS_OK ||
-            !ok2 || !((double)kv < cfg.kv_capacity))
-            return 0;
-        return chunk;
-    }
+    static double wait_of(const Instance& s, int64_t now) { return s.in_iteration ? std::max(0.0, s.busy_until - (double)now) : 0.0; }
 
     // highest load first; among equals the instance that joined its cluster first
-    static void by_load(std::vector<Instance*>& v, size_t from = 0) {
-        std::stable_sort(v.begin() + from, v.end(), [](const Instance* a, const Instance* b) {
+    static void by_load(std::vector<Instance*>& v) {
+        std::stable_sort(v.begin(), v.end(), [](const Instance* a, const Instance* b) {
             if (a->reqs.size() != b->reqs.size()) return a->reqs.size() > b->reqs.size();
             return a->joined < b->joined;
         });
     }
 
-    Instance* place(const Request& r, int64_t now, int32_t* chunk) {
-        for (int32_t t = r.tier; t >= 0; t--) {  // own cluster, then the tighter ones from the nearest
+    void join(Instance& s, int32_t tier, int64_t now) {
+        if (s.state == POOL) s.since = (double)now;
+        s.state = ACTIVE;
+        s.tier = tier;
+        s.joined = join_counter++;
+        sum.scale_ups++;
+    }
+
+    void to_pool(Instance& s, int64_t now) {
+        cost += (double)now - s.since;
+        s.state = POOL;
+        s.tier = -1;
+        s.joined = -1;
+        sum.scale_downs++;
+    }
+
+    void drop(Request& r) {
+        r.phase = DONE;
+        r.violated = true;
+        sum.dropped++;
+        done++;
+    }
+
+    // Sec. 4.2, 4.3: the request's own cluster, then the clusters of tighter tiers from the nearest one (lazy promotion),
+    // each from the most loaded instance down; then scale-up: a parked instance whose tightest request is of this tier,
+    // else one from the idle pool.  admit(instance, tier it would serve, request) returns 0 for "no", else a value that
+    // is handed back through *granted.
+    template <class Admit>
+    Instance* place_in_tiers(const Request& r, int64_t now, Admit admit, int32_t* granted) {
+        for (int32_t t = r.tier; t >= 0; t--) {
             cand.clear();
             for (Instance& s : inst)
                 if (s.state == ACTIVE && s.tier == t) cand.push_back(&s);
             by_load(cand);
             for (Instance* s : cand) {
-                const int32_t c = admits(*s, r, now);
-                if (c) {
+                const int32_t g = admit(*s, t, r);
+                if (g) {
                     if (t != r.tier) sum.promotions++;
-                    *chunk = c;
+                    *granted = g;
                     return s;
                 }
             }
         }
-        // scale up: a parked instance whose tightest request is of this tier, else one from the idle pool
         cand.clear();
         for (Instance& s : inst) {
             if (s.state != PENDING) continue;
@@ -120,101 +126,147 @@ struct Sim {
         for (Instance& s : inst)
             if (s.state == POOL) cand.push_back(&s);
         for (Instance* s : cand) {
-            const int was = s->state;
-            const int32_t old_tier = s->tier;
-            s->tier = r.tier;
-            s->state = ACTIVE;
-            const int32_t c = admits(*s, r, now);
-            if (c) {
-                if (was == POOL) s->since = (double)now;
-                s->joined = join_counter++;
-                sum.scale_ups++;
-                *chunk = c;
+            const int32_t g = admit(*s, r.tier, r);
+            if (g) {
+                join(*s, r.tier, now);
+                *granted = g;
                 return s;
             }
-            s->tier = old_tier;
-            s->state = was;
-            if (was == POOL) break;  // every idle instance gives the same answer
+            if (s->state == POOL) break;  // every idle instance gives the same answer
         }
         return nullptr;
     }
 
-    void to_pool(Instance& s, int64_t now) {
-        cost += (double)now - s.since;
-        s.state = POOL;
-        s.tier = -1;
-        s.joined = -1;
-        sum.scale_downs++;
+    // Iterations that have ended deliver their tokens at their end time (Sec. 2.3: token i is due at
+    // arrival + TTFT + i * TPOT).  prefill_done(instance, request index) is called for a request whose last chunk
+    // has just produced token 0 and that has more tokens to generate.
+    template <class PrefillDone>
+    void deliver_ended(int64_t now, PrefillDone prefill_done) {
+        for (Instance& s : inst) {
+            if (!s.in_iteration || !(s.busy_until <= (double)now)) continue;
+            const double t_end = s.busy_until;
+            for (const auto& bt : s.batch) {
+                Request& r = reqs[bt.first];
+                const bool was_prefill = r.phase == PREFILL;
+                if (was_prefill) {
+                    r.prefilled += bt.second;
+                    if (r.prefilled < r.prompt) continue;
+                    r.phase = DECODE;
+                    r.kv_len = r.prompt;
+                    r.generated = 1;
+                    r.first_token = t_end;
+                } else {
+                    r.kv_len++;
+                    r.generated++;
+                }
+                if (t_end > r.arrival + r.ttft + (double)(r.generated - 1) * cfg.tpot_ms[r.tier]) r.violated = true;
+                if (r.generated == r.output) {
+                    s.reqs.erase(std::find(s.reqs.begin(), s.reqs.end(), bt.first));
+                    r.phase = DONE;
+                    r.finish = t_end;
+                    done++;
+                } else if (was_prefill) {
+                    prefill_done(s, bt.first);
+                }
+            }
+            s.in_iteration = false;
+            s.batch.clear();
+            s.just_ended = true;
+            s.free_at = t_end;
+            sum.iterations++;
+        }
+        for (Instance& s : inst)
+            if (s.state == PENDING && s.reqs.empty()) to_pool(s, now);
+    }
+
+    // Scale-down check of the decode (or co-located) clusters: the least loaded instance of each returns to the idle
+    // pool if empty and is parked if none of its requests is of the cluster's tier.
+    void check_tier_clusters(int64_t now) {
+        for (int32_t t = 0; t < cfg.n_tiers; t++) {
+            Instance* last = nullptr;
+            for (Instance& s : inst) {
+                if (s.state != ACTIVE || s.tier != t) continue;
+                if (!last || s.reqs.size() < last->reqs.size() || (s.reqs.size() == last->reqs.size() && s.joined > last->joined))
+                    last = &s;
+            }
+            if (!last) continue;
+            if (last->reqs.empty()) {
+                to_pool(*last, now);
+            } else {
+                bool own = false;
+                for (int32_t i : last->reqs) own = own || reqs[i].tier == t;
+                if (!own) last->state = PENDING;
+            }
+        }
+    }
+
+    // The batch in s.batch starts: at the end of the previous iteration if that ended within this step (iterations run
+    // back to back; only the router works on the 1 ms grid), else at the step.
+    void start_iteration(Instance& s, int64_t now, int64_t tokens, int64_t kv) {
+        s.busy_until = (s.just_ended ? s.free_at : (double)now) + ps_profile_lookup(prof, (double)tokens, (double)kv);
+        s.in_iteration = true;
+    }
+
+    void end_step() {
+        for (Instance& s : inst) s.just_ended = false;
+    }
+
+    void close(int64_t now) {
+        for (Instance& s : inst)
+            if (s.state != POOL) cost += (double)now - s.since;
+        sum.end_ms = now;
+        sum.cost_ms = cost;
+    }
+};
+
+// ---------------------------------------------------------------------------------------------------
+// Co-location with chunked prefill
+// ---------------------------------------------------------------------------------------------------
+struct Sim : Cluster {
+    std::vector<std::deque<int32_t>> queues;
+    using Cluster::Cluster;
+
+    // chunk size the instance would keep for the request's prefill if it served `tier`, 0 = not admitted
+    int32_t admits(const Instance& s, int32_t tier, const Request& r, int64_t now) {
+        run.clear();
+        for (int32_t i : s.reqs) {
+            if (reqs[i].phase == PREFILL) return 0;  // one prefill at a time
+            run.push_back(ps_running_req{reqs[i].kv_len, reqs[i].generated});
+        }
+        const double tpot = cfg.tpot_ms[tier];
+        int32_t ok = 0, chunk = 0, n_it = 0;
+        double t_first = 0.0;
+        sum.admission_tests++;
+        if (ps_predict_chunked_prefill(prof, run.data(), (int32_t)run.size(), r.prompt, cfg.avg_decode_len, tpot,
+                                       r.arrival + r.ttft - (double)now, wait_of(s, now), &ok, &chunk, &n_it, &t_first) != PS_OK || !ok)
+            return 0;
+        int32_t ok2 = 0;
+        double predicted = 0.0;
+        int64_t kv = 0;
+        if (ps_predict_admit(prof, run.data(), (int32_t)run.size(), r.prompt, cfg.avg_decode_len, tpot, 0.0, &ok2, &predicted, &kv) != PS_OK ||
+            !ok2 || !((double)kv < cfg.kv_capacity))
+            return 0;
+        return chunk;
     }
 
     void run_all() {
         const int32_t n = (int32_t)reqs.size();
-        int32_t next_arrival = 0, done = 0;
+        int32_t next_arrival = 0;
         int64_t now = 0;
+        queues.resize(cfg.n_tiers);
         while (done < n && now < cfg.max_steps) {
-            // iterations that have ended deliver their tokens at their end time
-            for (Instance& s : inst) {
-                if (!s.in_iteration || !(s.busy_until <= (double)now)) continue;
-                const double t_end = s.busy_until;
-                for (const auto& bt : s.batch) {
-                    Request& r = reqs[bt.first];
-                    if (r.phase == PREFILL) {
-                        r.prefilled += bt.second;
-                        if (r.prefilled < r.prompt) continue;
-                        r.phase = DECODE;
-                        r.kv_len = r.prompt;
-                        r.generated = 1;
-                        r.first_token = t_end;
-                    } else {
-                        r.kv_len++;
-                        r.generated++;
-                    }
-                    if (t_end > r.arrival + r.ttft + (double)(r.generated - 1) * cfg.tpot_ms[r.tier]) r.violated = true;
-                    if (r.generated == r.output) {
-                        r.phase = DONE;
-                        r.finish = t_end;
-                        s.reqs.erase(std::find(s.reqs.begin(), s.reqs.end(), bt.first));
-                        done++;
-                    }
-                }
-                s.in_iteration = false;
-                s.batch.clear();
-                s.just_ended = true;
-                s.free_at = t_end;
-                sum.iterations++;
-            }
-            for (Instance& s : inst)
-                if (s.state == PENDING && s.reqs.empty()) to_pool(s, now);
-            // arrivals
+            deliver_ended(now, [](Instance&, int32_t) {});  // the request stays where it is and decodes
             while (next_arrival < n && reqs[next_arrival].arrival <= (double)now) {
                 queues[reqs[next_arrival].tier].push_back(next_arrival);
                 next_arrival++;
             }
-            // scale-down check: the lowest-load instance of every cluster
-            if (now % cfg.check_period_ms == 0) {
-                for (int32_t t = 0; t < cfg.n_tiers; t++) {
-                    Instance* last = nullptr;
-                    for (Instance& s : inst) {
-                        if (s.state != ACTIVE || s.tier != t) continue;
-                        if (!last || s.reqs.size() < last->reqs.size() || (s.reqs.size() == last->reqs.size() && s.joined > last->joined))
-                            last = &s;
-                    }
-                    if (!last) continue;
-                    if (last->reqs.empty()) {
-                        to_pool(*last, now);
-                    } else {
-                        bool own = false;
-                        for (int32_t i : last->reqs) own = own || reqs[i].tier == t;
-                        if (!own) last->state = PENDING;
-                    }
-                }
-            }
+            if (now % cfg.check_period_ms == 0) check_tier_clusters(now);
             // routing: tightest tier first, first come first served
             for (auto& q : queues) {
                 while (!q.empty()) {
                     Request& r = reqs[q.front()];
                     int32_t chunk = 0;
-                    Instance* s = place(r, now, &chunk);
+                    Instance* s = place_in_tiers(r, now, [&](const Instance& c, int32_t tier, const Request& rr) { return admits(c, tier, rr, now); }, &chunk);
                     if (!s) {
                         int32_t ok = 0, c = 0, n_it = 0;
                         double t_first = 0.0;
@@ -222,10 +274,7 @@ struct Sim {
                                                    r.arrival + r.ttft - (double)now, 0.0, &ok, &c, &n_it, &t_first);
                         if (ok) break;  // it can still make its first token on an empty instance: keep its place
                         q.pop_front();
-                        r.phase = DONE;
-                        r.violated = true;
-                        sum.dropped++;
-                        done++;
+                        drop(r);
                         continue;
                     }
                     r.first_server = r.decode_server = s->id;
@@ -235,7 +284,7 @@ struct Sim {
                     q.pop_front();
                 }
             }
-            // instances outside an iteration that hold requests start one
+            // instances outside an iteration that hold requests start one: a token of every decode, the next chunk of the prefill
             for (Instance& s : inst) {
                 if (s.in_iteration || s.reqs.empty()) continue;
                 int64_t tokens = 0, kv = 0;
@@ -252,42 +301,24 @@ struct Sim {
                         kv += r.prefilled + c;
                     }
                 }
-                // iterations run back to back: only the router works on the 1 ms grid
-                s.busy_until = (s.just_ended ? s.free_at : (double)now) + ps_profile_lookup(prof, (double)tokens, (double)kv);
-                s.in_iteration = true;
+                start_iteration(s, now, tokens, kv);
             }
-            for (Instance& s : inst) s.just_ended = false;
+            end_step();
             now++;
         }
-        for (Instance& s : inst)
-            if (s.state != POOL) cost += (double)now - s.since;
-        sum.end_ms = now;
-        sum.cost_ms = cost;
+        close(now);
     }
 };
 
 // ---------------------------------------------------------------------------------------------------
 // Prefill-decode disaggregation
 // ---------------------------------------------------------------------------------------------------
-struct SimPD {
-    const ps_profile* prof;
-    const ps_sim_config& cfg;
-    std::vector<Request> reqs;
-    std::vector<Instance> inst;
+struct SimPD : Cluster {
     std::vector<int32_t> prefill_queue;
     std::vector<std::deque<int32_t>> decode_queues;
-    ps_sim_summary sum{};
-    double cost = 0.0;
-    int64_t join_counter = 0;
-    int32_t done = 0;
-    std::vector<ps_running_req> run;
-    std::vector<Instance*> cand;
     std::vector<int32_t> rem, at, whole, plan;
     std::vector<double> due;
-
-    SimPD(const ps_profile* p, const ps_sim_config& c) : prof(p), cfg(c) {}
-
-    static double wait_of(const Instance& s, int64_t now) { return s.in_iteration ? std::max(0.0, s.busy_until - (double)now) : 0.0; }
+    using Cluster::Cluster;
 
     // prompt tokens of request i neither processed nor in the iteration in flight
     int32_t left(const Instance& s, int32_t i) const {
@@ -355,6 +386,8 @@ struct SimPD {
         return true;
     }
 
+    // Sec. 4.4, 4.5: the largest future KV size keeps the iteration below the TPOT of the tier served, fits the memory,
+    // and the wait for the iteration in flight plus that iteration still meets the request's second-token deadline
     bool decode_admits(const Instance& s, int32_t tier, const Request& r, int64_t now) {
         run.clear();
         for (int32_t i : s.reqs) run.push_back(ps_running_req{reqs[i].kv_len, reqs[i].generated});
@@ -367,54 +400,7 @@ struct SimPD {
         return ok && (double)kv < cfg.kv_capacity && wait_of(s, now) + t < r.arrival + r.ttft + cfg.tpot_ms[r.tier] - (double)now;
     }
 
-    void join(Instance& s, int32_t tier, int64_t now) {
-        if (s.state == POOL) s.since = (double)now;
-        s.state = ACTIVE;
-        s.tier = tier;
-        s.joined = join_counter++;
-        sum.scale_ups++;
-    }
-
-    void to_pool(Instance& s, int64_t now) {
-        cost += (double)now - s.since;
-        s.state = POOL;
-        s.tier = -1;
-        s.joined = -1;
-        sum.scale_downs++;
-    }
-
-    Instance* place_decode(const Request& r, int64_t now) {
-        for (int32_t t = r.tier; t >= 0; t--) {
-            cand.clear();
-            for (Instance& s : inst)
-                if (s.state == ACTIVE && s.tier == t) cand.push_back(&s);
-            Sim::by_load(cand);
-            for (Instance* s : cand)
-                if (decode_admits(*s, s->tier, r, now)) {
-                    if (t != r.tier) sum.promotions++;
-                    return s;
-                }
-        }
-        cand.clear();
-        for (Instance& s : inst) {
-            if (s.state != PENDING) continue;
-            int32_t tightest = INT32_MAX;
-            for (int32_t i : s.reqs) tightest = std::min(tightest, reqs[i].tier);
-            if (tightest == r.tier) cand.push_back(&s);
-        }
-        Sim::by_load(cand);
-        for (Instance& s : inst)
-            if (s.state == POOL) cand.push_back(&s);
-        for (Instance* s : cand) {
-            if (decode_admits(*s, r.tier, r, now)) {
-                join(*s, r.tier, now);
-                return s;
-            }
-            if (s->state == POOL) break;  // every idle instance gives the same answer
-        }
-        return nullptr;
-    }
-
+    // the prefill instance with most unprocessed prompt tokens that admits the request, else one from the idle pool
     Instance* place_prefill(const Request& r, int64_t now) {
         cand.clear();
         for (Instance& s : inst)
@@ -437,54 +423,18 @@ struct SimPD {
         return nullptr;
     }
 
-    void drop(Request& r) {
-        r.phase = DONE;
-        r.violated = true;
-        sum.dropped++;
-        done++;
-    }
-
     void run_all() {
         const int32_t n = (int32_t)reqs.size();
         int32_t next_arrival = 0;
         int64_t now = 0;
         const Instance empty_instance{};
+        decode_queues.resize(cfg.n_tiers);
         while (done < n && now < cfg.max_steps) {
-            for (Instance& s : inst) {
-                if (!s.in_iteration || !(s.busy_until <= (double)now)) continue;
-                const double t_end = s.busy_until;
-                for (const auto& bt : s.batch) {
-                    Request& r = reqs[bt.first];
-                    if (r.phase == PREFILL) {
-                        r.prefilled += bt.second;
-                        if (r.prefilled < r.prompt) continue;
-                        r.kv_len = r.prompt;
-                        r.generated = 1;
-                        r.first_token = t_end;
-                    } else {
-                        r.kv_len++;
-                        r.generated++;
-                    }
-                    if (t_end > r.arrival + r.ttft + (double)(r.generated - 1) * cfg.tpot_ms[r.tier]) r.violated = true;
-                    if (r.generated == r.output) {
-                        s.reqs.erase(std::find(s.reqs.begin(), s.reqs.end(), bt.first));
-                        r.phase = DONE;
-                        r.finish = t_end;
-                        done++;
-                    } else if (r.phase == PREFILL) {  // prefill done: hand over to the decode side
-                        s.reqs.erase(std::find(s.reqs.begin(), s.reqs.end(), bt.first));
-                        r.phase = HANDED_OVER;
-                        decode_queues[r.tier].push_back(bt.first);
-                    }
-                }
-                s.in_iteration = false;
-                s.batch.clear();
-                s.just_ended = true;
-                s.free_at = t_end;
-                sum.iterations++;
-            }
-            for (Instance& s : inst)
-                if (s.state == PENDING && s.reqs.empty()) to_pool(s, now);
+            deliver_ended(now, [this](Instance& s, int32_t i) {  // prefill done: hand over to the decode side
+                s.reqs.erase(std::find(s.reqs.begin(), s.reqs.end(), i));
+                reqs[i].phase = HANDED_OVER;
+                decode_queues[reqs[i].tier].push_back(i);
+            });
             // arrivals, kept in order of first-token deadline (Sec. 4.1)
             while (next_arrival < n && reqs[next_arrival].arrival <= (double)now) prefill_queue.push_back(next_arrival++);
             std::sort(prefill_queue.begin(), prefill_queue.end(), [this](int32_t a, int32_t b) {
@@ -492,23 +442,8 @@ struct SimPD {
                 return da != db ? da < db : a < b;
             });
             if (now % cfg.check_period_ms == 0) {
-                for (int32_t t = 0; t < cfg.n_tiers; t++) {
-                    Instance* last = nullptr;
-                    for (Instance& s : inst) {
-                        if (s.state != ACTIVE || s.tier != t) continue;
-                        if (!last || s.reqs.size() < last->reqs.size() || (s.reqs.size() == last->reqs.size() && s.joined > last->joined))
-                            last = &s;
-                    }
-                    if (!last) continue;
-                    if (last->reqs.empty()) {
-                        to_pool(*last, now);
-                    } else {
-                        bool own = false;
-                        for (int32_t i : last->reqs) own = own || reqs[i].tier == t;
-                        if (!own) last->state = PENDING;
-                    }
-                }
-                Instance* last = nullptr;
+                check_tier_clusters(now);
+                Instance* last = nullptr;  // the least loaded prefill instance goes back if it holds no request
                 int64_t last_load = 0;
                 for (Instance& s : inst) {
                     if (s.state != ACTIVE || s.tier != PREFILL_CLUSTER) continue;
@@ -520,8 +455,10 @@ struct SimPD {
             for (auto& q : decode_queues) {
                 while (!q.empty()) {
                     Request& r = reqs[q.front()];
-                    Instance* s = place_decode(r, now);
+                    int32_t yes = 0;
+                    Instance* s = place_in_tiers(r, now, [&](const Instance& c, int32_t tier, const Request& rr) { return decode_admits(c, tier, rr, now) ? 1 : 0; }, &yes);
                     if (!s) {
+                        // an empty instance could still deliver the second token in time: keep the place in the queue
                         if (ps_profile_lookup(prof, 1.0, (double)(r.kv_len + 1)) < r.arrival + r.ttft + cfg.tpot_ms[r.tier] - (double)now) break;
                         q.pop_front();
                         drop(r);
@@ -567,17 +504,12 @@ struct SimPD {
                         kv += reqs[i].kv_len + 1;
                     }
                 }
-                // iterations run back to back: only the router works on the 1 ms grid
-                s.busy_until = (s.just_ended ? s.free_at : (double)now) + ps_profile_lookup(prof, (double)tokens, (double)kv);
-                s.in_iteration = true;
+                start_iteration(s, now, tokens, kv);
             }
-            for (Instance& s : inst) s.just_ended = false;
+            end_step();
             now++;
         }
-        for (Instance& s : inst)
-            if (s.state != POOL) cost += (double)now - s.since;
-        sum.end_ms = now;
-        sum.cost_ms = cost;
+        close(now);
     }
 };
 
@@ -628,11 +560,9 @@ extern "C" ps_status ps_sim_run(const ps_profile* profile, const ps_sim_config* 
     try {
         if (cfg->mode == PS_SIM_COLOCATED) {
             Sim sim(profile, *cfg);
-            sim.queues.resize(cfg->n_tiers);
             run_and_report(sim, cfg, requests, n, attained, first_token_ms, finish_ms, server, decode_server, summary);
         } else {
             SimPD sim(profile, *cfg);
-            sim.decode_queues.resize(cfg->n_tiers);
             run_and_report(sim, cfg, requests, n, attained, first_token_ms, finish_ms, server, decode_server, summary);
         }
     } catch (const std::bad_alloc&) {
