@@ -613,6 +613,22 @@ def run_sim(a):
                 print(f"sim: {name} {mode} {rate}/s attained {att:.3f} wall {wall:.2f}s", file=sys.stderr, flush=True)
             res["goodput"][f"{name} {mode}"] = round(best, 1)
             res["optimal"][f"{name} {mode}"]["goodput_over_optimal"] = round(best / res["optimal"][f"{name} {mode}"]["rate_per_s"], 3)
+    # Sec. 5.4: an unlimited pool (200 instances), auto-scaling decides how many are used; cost = instance time per request
+    res["cost_with_unlimited_pool"] = []
+    for name, (max_p, max_o, burst, rate0) in traces.items():
+        for mode in ("co-located", "disaggregated"):
+            for frac in (0.25, 1.0):
+                rate = max(1.0, round(frac * res["goodput"][f"{name} {mode}"], 1))
+                tr = W.sim_trace(a.seed, n, rate / 1e3, max_p, max_o, burst=burst)
+                t0 = time.perf_counter()
+                r = prof.simulate(tr["arrival"], tr["prompt"], tr["output"], tr["ttft"], tr["tier"], tpots, 200, (1 + max_o) // 2, capacity,
+                                  1000, disaggregated=(mode == "disaggregated"), prefill_budget=2048)
+                wall_total, placed_total, tests_total = wall_total + time.perf_counter() - t0, placed_total + n, tests_total + r["admission_tests"]
+                res["cost_with_unlimited_pool"].append({
+                    "trace": name, "mode": mode, "rate_per_s": rate, "attained": round(float(r["attained"].mean()), 4),
+                    "instance_ms_per_request": round(r["cost_ms"] / n, 2), "mean_instances_in_use": round(r["cost_ms"] / r["end_ms"], 2),
+                    "optimal_instance_ms_per_request": res["optimal"][f"{name} {mode}"]["instance_ms_per_request"]})
+                print(f"sim: cost {name} {mode} {rate}/s: {r['cost_ms'] / n:.1f} instance-ms per request", file=sys.stderr, flush=True)
     prof.close()
     res["value"] = res["goodput"]["uniform_512_512 co-located"]
     res["router"] = {"requests_per_wall_second": round(placed_total / wall_total, 1), "admission_tests_per_wall_second": round(tests_total / wall_total, 1),

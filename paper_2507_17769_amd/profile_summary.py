@@ -261,6 +261,13 @@ def sim_summary(sim_json, command):
             f"Router speed: {d['router']['requests_per_wall_second']:.0f} requests and {d['router']['admission_tests_per_wall_second']:.0f} "
             "(request, instance) admission tests per second of wall time over all runs, one host thread, instance stepping included "
             "(the paper reports 4825 requests per second for its scheduler, Sec. 5.6)."]
+    if d.get("cost_with_unlimited_pool"):
+        out += ["", "Cost with an unlimited pool (200 instances; auto-scaling decides how many are in use; Sec. 5.4), at a quarter of and at the "
+                "goodput rate found above; the optimum is the mean minimal cost of Sec. 3.5:", "",
+                "| trace | deployment | rate /s | attained | instance-ms per request | optimum | mean instances in use |", "|---|---|---|---|---|---|---|"]
+        for r in d["cost_with_unlimited_pool"]:
+            out.append(f"| {r['trace']} | {r['mode']} | {r['rate_per_s']} | {r['attained']:.3f} | {r['instance_ms_per_request']} | "
+                       f"{r['optimal_instance_ms_per_request']} | {r['mean_instances_in_use']} |")
     if "cpu_baseline" in d:
         c = d["cpu_baseline"]
         out += ["", f"Oracle simulator on {c['sample']}: {c['value']:.0f} requests per wall second; `ps_sim_run` on the same sample: "
