@@ -2,7 +2,8 @@
  *
  * These are the decisions the paper's router takes with the (batch size, KV cache size) -> time
  * table (Sec. 4.4 "Profile-Based Batch Formation", Sec. 4.5 "Wait-Time-Aware Scheduling",
- * Sec. 4.6 "Handling TTFT", Sec. 3.4 batch-size limits).  Plain C, host memory only, no GPU work,
+ * Sec. 4.6 "Handling TTFT", Sec. 3.4 batch-size limits, Sec. 3.5 cost of a request), and the cluster
+ * simulation the paper evaluates its router with (Sec. 5.1).  Plain C, host memory only, no GPU work,
  * no global state; a profile object is immutable after creation and may be shared by threads.
  * All times are milliseconds.  Functions return PS_OK or PS_EINVAL (null pointer, malformed
  * argument) and leave their outputs untouched on error. */
