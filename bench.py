@@ -42,6 +42,7 @@ def parse():
                     help="library tuning knob passed to ps_set_option (repeatable); the defaults are what is reported")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--null-stream", action="store_true", help="run on the default stream instead of a dedicated one")
+    ap.add_argument("--device-info", action="store_true", help="only print what the runtime reports about the device")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy a few times (reference for HBM byte counters)")
     return ap.parse_args()
@@ -666,6 +667,12 @@ def main():
     from paper_2507_17769_amd.binding import STAGE_NAMES, SeqArray
     from paper_2507_17769_amd.runner import Engine, bits_to_dev
 
+    if a.device_info:
+        p = torch.cuda.get_device_properties(0)
+        info = {k: getattr(p, k) for k in dir(p) if not k.startswith("_") and isinstance(getattr(p, k), (int, float, str))}
+        info["torch"], info["hip"] = torch.__version__, torch.version.hip
+        print(json.dumps(info))
+        return
     if a.calibrate_copy:
         n = 1 << 30
         src = torch.ones(n, dtype=torch.uint8, device="cuda:0")
@@ -733,6 +740,16 @@ def main():
     eng.ctx.set_option("time_attention", 0)
     ms_per_step = (t1 - t0) * 1e3 / a.steps
 
+    # spread of the step time (not part of the timed region): 20 blocks of 10 steps, each block bracketed by a sync
+    block_ms = []
+    for b in range(20):
+        t0b = time.perf_counter()
+        for i in range(10):
+            eng.ctx.set_option("only_layer", i % n_copies)
+            eng.ctx.step(seqs, x.data_ptr(), out.data_ptr())
+        eng.ctx.sync()
+        block_ms.append((time.perf_counter() - t0b) * 1e3 / 10)
+
     # per-stage split (separate, synchronous passes; not part of the timed region)
     stage = np.zeros(len(STAGE_NAMES))
     n_stat = 10
@@ -764,6 +781,8 @@ def main():
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": measured_traffic(a.workload, a.seed), "algorithmic_bytes_per_launch": attn_bytes, "avg_launch_ms": attn_avg_ms,
                      "launches_timed": len(attn_ms)},
+        "ms_per_step_blocks_of_10": {"p10": round(float(np.percentile(block_ms, 10)), 4), "p50": round(float(np.percentile(block_ms, 50)), 4),
+                                     "p90": round(float(np.percentile(block_ms, 90)), 4), "blocks": len(block_ms)},
         "stage_ms": {n: round(float(v), 4) for n, v in zip(STAGE_NAMES, stage)},
         "gemm": {"ms": gemm_ms, "weight_GBs": 2 * params / (gemm_ms * 1e-3) / 1e9,
                  "tflops": 2 * params * T / (gemm_ms * 1e-3) / 1e12,
