@@ -8,6 +8,7 @@ roofline.traffic).
     python -m paper_2507_17769_amd.profile_summary profile <bench_profile.json> <command> > profiles/<name>.md
     python -m paper_2507_17769_amd.profile_summary grid   <bench_grid.json> <command> > profiles/<name>.md
     python -m paper_2507_17769_amd.profile_summary sim    <bench_sim.json> <command> > profiles/<name>.md
+    python -m paper_2507_17769_amd.profile_summary cfg4   <bench_cfg4.json> <command> > profiles/<name>.md
     python -m paper_2507_17769_amd.profile_summary counters <fetch.csv> <write.csv> <fetch_copy.csv> <write_copy.csv> \
             <workload> <seed> <md out> [--json]
 
@@ -231,6 +232,38 @@ def profile_summary(profile_json, command):
     return "\n".join(out) + "\n"
 
 
+def cfg4_summary(cfg4_json, command):
+    d = json.load(open(cfg4_json))
+    c, st, g, at = d["config"], d["stage_ms_all_layers"], d["gemm"], d["attention"]
+    L = c["n_layers"]
+    out = [f"# 70B-shaped stack, {L} layers on one MI355X: step time and teacher-forced layer checks", "",
+           "Command (one GPU, the bf16 weights of all layers generated on the device, KV slots aliased over the layers):", "",
+           f"    {command}", "", c["workload"] + ".", "",
+           "| figure | value |", "|---|---|",
+           f"| step ({L} layers, host clock over {d['steps']} steps) | {d['ms_per_step']:.1f} ms = {d['value']:.0f} new tokens/s |",
+           f"| per layer | {d['ms_per_step'] / L:.2f} ms |",
+           f"| weight GEMMs (QKV, O, gate/up, down), all layers | {g['ms']:.1f} ms ({st['gemm_qkv']:.1f} / {st['gemm_o']:.1f} / "
+           f"{st['gemm_gate_up']:.1f} / {st['gemm_down']:.1f}): {g['tflops']:.0f} TFLOP/s = {100 * g['frac_mfma']:.1f} % of the 2.5 PFLOP/s bf16 MFMA peak |",
+           f"| attention (one launch for the chunk and the decodes, plus merge), all layers | {at['ms']:.1f} ms: {at['kv_GBs'] / 1e3:.2f} TB/s of KV bytes "
+           "(the 1024-token chunk is compute-heavy: 5120 keys x 1024 queries x 64 heads) |",
+           f"| rmsnorm / rope+append / add+norm | {st['rmsnorm_attn']:.2f} / {st['rope_append']:.2f} / {st['rmsnorm_ffn']:.2f} ms |", "",
+           "Stage times are HIP-event brackets summed over the layers of one step (`ps_step_stats`)."]
+    if d.get("layer_checks"):
+        out += ["", "Teacher-forced checks (the layer's actual fp32 input and its KV slot's prefixes are read back from the device; the oracle "
+                "evaluates that one layer from them; compared with the layer's actual fp32 output):", "",
+                "| layer | output RMS | max err / RMS vs definition | vs definition with bf16 activations | the two oracles apart | judged against | pass |",
+                "|---|---|---|---|---|---|---|"]
+        for k in d["layer_checks"]:
+            out.append(f"| {k['layer']} | {k['out_rms']:.3g} | {k['max_err_over_rms']:.4f} | {k['max_err_over_rms_vs_bf16_variant']:.4f} | "
+                       f"{k['oracle_gap_definition_vs_bf16_variant']:.4f} | {k['judged_against']} | {k['pass']} |")
+        out += ["", "Layer 0 of this configuration is ill-conditioned as an input, not as a kernel: with N(0, 0.02) weights at hidden 8192 the branch "
+                "outputs are several times the RMS-1 input, and rounding the five stored activations (xn, q, attn, xn2, act) to bf16 moves the "
+                "definition itself by more than the bar (the two oracles apart).  No implementation that stores activations in bf16 can be closer "
+                "to the definition than that; such a layer is held to 2e-2 against the definition evaluated with those five roundings.  From layer 1 "
+                "on the residual stream dominates and the plain bar holds with a wide margin."]
+    return "\n".join(out) + "\n"
+
+
 def sim_summary(sim_json, command):
     d = json.load(open(sim_json))
     out = ["# Cluster simulation with the measured iteration-time table — 20 instances of the 8B-shaped model, one MI355X each", "",
@@ -276,6 +309,9 @@ def sim_summary(sim_json, command):
 
 
 def main(argv):
+    if len(argv) >= 4 and argv[1] == "cfg4":
+        sys.stdout.write(cfg4_summary(argv[2], argv[3]))
+        return 0
     if len(argv) >= 4 and argv[1] == "sim":
         sys.stdout.write(sim_summary(argv[2], argv[3]))
         return 0
