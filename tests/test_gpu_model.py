@@ -76,6 +76,51 @@ def test_model_step_against_oracle(spec, n_layers, vocab):
     eng.close()
 
 
+def test_generation_loop_prefill_then_decode_steps():
+    """Three requests served the way an instance serves them: one step prefills the prompts, every further step
+    feeds each request the token it generated and appends to its pages.  The oracle gets the same token ids (the
+    device's own picks), so that both sides stay on one trajectory; logits and picks are compared at every step and
+    the caches at the end."""
+    m, vocab, n_layers, n_steps = W.MODELS["tiny"], 256, 2, 7
+    prompts = [20, 7, 33]
+    rng = np.random.Generator(np.random.PCG64(77))
+    need = [(p + n_steps + 15) // 16 for p in prompts]
+    perm = rng.permutation(sum(need) + 5).astype(np.int32)
+    pages, at = [], 0
+    for k in need:
+        pages.append(perm[at:at + k].copy())
+        at += k
+    layers = [W.layer_weights(m, 13, l) for l in range(n_layers)]
+    head = W.head_weights(m, vocab, 13)
+    eng = Engine(m, len(perm), n_layers, n_layers, max_position=64)
+    for l, w in enumerate(layers):
+        eng.load_layer(l, w)
+    eng.load_head(head)
+    pool = orun.make_pool(m, len(perm), n_layers)
+    ids = W.token_ids(vocab, sum(prompts), 3)
+    kv = list(prompts)
+    for step in range(n_steps):
+        seqs = [W.SeqSpec(req_id=100 + i, n_new=(prompts[i] if step == 0 else 1), kv_len=kv[i], pages=pages[i]) for i in range(3)]
+        out = eng.step_tokens(seqs, ids)
+        eng.ctx.sync()
+        got_next, got_logits = out["next"].cpu().numpy(), out["logits"].cpu().numpy()
+        _, want_logits, _ = orun.run_model(m, head, layers, seqs, ids, pool, np.float32)
+        assert rel_err(got_logits, want_logits) <= TOL, (step, rel_err(got_logits, want_logits))
+        _check_tokens(got_next, got_logits, want_logits, f"step {step}")
+        ids = got_next.astype(np.int32)      # each request continues with the token it generated
+        kv = [k + 1 for k in kv]
+    # the caches hold the same keys and values after the loop (up to one bf16 rounding flip)
+    for i in range(3):
+        n = prompts[i] + n_steps - 1
+        for l in range(n_layers):
+            k, v = eng.read_kv(l, pages[i], 0, n)
+            wk, wv = pool.gather(l, [int(p) for p in pages[i]], n)
+            for g, w in ((k, wk), (v, wv)):
+                g64, w64 = obf.from_bits(g).astype(np.float64), np.asarray(w, dtype=np.float64)
+                assert np.all(np.abs(g64 - w64) <= 2.0 ** -7 * np.abs(w64) + 2e-2 * np.sqrt(np.mean(w64 * w64)))
+    eng.close()
+
+
 def test_equal_logits_pick_the_lowest_index():
     # an output matrix with repeated columns gives bit-identical logits in different tiles, wavefronts and blocks
     b = W.custom_batch("tiny", 3, 0, 0, [9, 40], name="ties")
