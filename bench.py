@@ -428,13 +428,14 @@ def run_prefill(a):
     print(json.dumps(res))
 
 
-def measure_profile(a, batch_sizes, kv_sizes, n_decodes_in_mixed=256):
+def measure_profile(a, batch_sizes, kv_sizes, n_decodes_in_mixed=256, extra_batches=None):
     """Measure the map (batch size, KV cache size) -> iteration time of the whole 8B-shaped model (Sec. 4.4) with
     ps_step_tokens.  Rows up to n_decodes_in_mixed tokens are decode batches (the KV size split evenly over the requests);
     larger rows are the co-located kind of batch (Sec. 2.4): n_decodes_in_mixed decodes plus one prefill chunk with the
     remaining tokens at prefix 0, the decodes sharing the KV size that the chunk does not attend.  Returns
     (measured table with NaN where a cell cannot exist, table with those cells filled from the nearest measured cell of the
-    row, layers, vocabulary, KV capacity in tokens of one 288 GB instance)."""
+    row, layers, vocabulary, KV capacity in tokens of one 288 GB instance); with extra_batches (a dict name -> batch) also
+    the measured step time of each of those, as a last element."""
     import numpy as np
     import torch
     from paper_2507_17769_amd import workloads as W
@@ -456,8 +457,10 @@ def measure_profile(a, batch_sizes, kv_sizes, n_decodes_in_mixed=256):
                 per = (kv - chunk) // n_decodes_in_mixed
                 if 16 <= per:
                     cells[(bs, kv)] = W.custom_batch(model, a.seed, chunk, 0, [per] * n_decodes_in_mixed, name=f"b{bs}_kv{kv}", tag=bs * 7 + 1)
-    n_pool = max(b.n_pool_pages for b in cells.values())
-    eng = Engine(model, n_pool, L, L, max_position=max(s.kv_len for b in cells.values() for s in b.seqs) + 16)
+    todo = dict(cells)
+    todo.update(extra_batches or {})
+    n_pool = max(b.n_pool_pages for b in todo.values())
+    eng = Engine(model, n_pool, L, L, max_position=max(s.kv_len for b in todo.values() for s in b.seqs) + 16)
     gen = torch.Generator(device="cuda:0")
     gen.manual_seed(3000 + a.seed)
     rnd = lambda shape, std: (torch.randn(shape, generator=gen, device="cuda:0", dtype=torch.float32) * std).to(torch.bfloat16)
@@ -477,7 +480,8 @@ def measure_profile(a, batch_sizes, kv_sizes, n_decodes_in_mixed=256):
     blk = bits_to_dev(W.normal_bf16(rng, (4096, nkv, d)), eng.device)
     table = np.full((len(batch_sizes), len(kv_sizes)), np.nan, dtype=np.float32)
     steps = max(3, min(a.steps, 10))
-    for (bs, kv), b in cells.items():
+    extra_ms = {}
+    for key, b in todo.items():
         for s in b.seqs:          # keys and values of every cached position, block by block
             for p0 in range(0, s.prefix, 4096):
                 n = min(4096, s.prefix - p0)
@@ -494,8 +498,13 @@ def measure_profile(a, batch_sizes, kv_sizes, n_decodes_in_mixed=256):
         for _ in range(steps):
             eng.ctx.step_tokens(seqs, ids, nxt.data_ptr())
         eng.ctx.sync()
-        table[batch_sizes.index(bs), kv_sizes.index(kv)] = (time.perf_counter() - t0) * 1e3 / steps
-        print(f"profile: batch {bs} kv {kv}: {table[batch_sizes.index(bs), kv_sizes.index(kv)]:.3f} ms", file=sys.stderr, flush=True)
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        if key in cells:
+            bs, kv = key
+            table[batch_sizes.index(bs), kv_sizes.index(kv)] = ms
+            print(f"profile: batch {bs} kv {kv}: {ms:.3f} ms", file=sys.stderr, flush=True)
+        else:
+            extra_ms[key] = ms
     eng.close()
     filled = table.copy()
     for i in range(len(batch_sizes)):
@@ -506,6 +515,8 @@ def measure_profile(a, batch_sizes, kv_sizes, n_decodes_in_mixed=256):
     # KV capacity of what is left of 288 GB beside the weights and 8 GB of workspace
     weights_gb = 2 * (L * (H * (nq + 2 * nkv) * d + nq * d * H + 3 * H * F) + 2 * H * V) / 1e9
     capacity = (288 - weights_gb - 8) * 1e9 / (2 * nkv * d * 2 * L)
+    if extra_batches is not None:
+        return table, filled, L, V, capacity, extra_ms
     return table, filled, L, V, capacity
 
 
@@ -562,7 +573,16 @@ def run_sim(a):
         filled = np.array(rec["ms_filled"], dtype=np.float32)
         L, V, capacity = rec["n_layers"], rec["vocab"], rec["kv_capacity_tokens"]
     else:
-        table, filled, L, V, capacity = measure_profile(a, batch_sizes, kv_sizes)
+        # besides the table's cells: random batches of the kind an instance runs (decodes with log-normal KV lengths, with
+        # or without a prefill chunk at some prefix), to see how well a lookup by (tokens, KV size) predicts their time
+        rng = np.random.Generator(np.random.PCG64([a.seed, 314159]))
+        check = {}
+        for i in range(24):
+            n_dec = int(np.exp(rng.uniform(0.0, np.log(512.0))))
+            chunk = 0 if rng.random() < 0.4 else int(np.exp(rng.uniform(np.log(16.0), np.log(1536.0))))
+            kvs = W.lognormal_lengths(rng, n_dec, 1024, 0.8, 16, 8192)
+            check[f"check{i}"] = W.custom_batch("8b", a.seed, chunk, int(rng.integers(0, 4096)) if chunk else 0, kvs, name=f"check{i}", tag=900 + i)
+        table, filled, L, V, capacity, check_ms = measure_profile(a, batch_sizes, kv_sizes, extra_batches=check)
     prof = B.Profile(batch_sizes, kv_sizes, filled)
     tpots = list(W.SIM_TPOTS_MS)
     n, n_servers = a.requests, 20
@@ -573,6 +593,15 @@ def run_sim(a):
            "batch_sizes": batch_sizes, "kv_sizes": kv_sizes, "n_layers": L, "vocab": V, "kv_capacity_tokens": int(capacity),
            "ms": [[None if np.isnan(v) else round(float(v), 4) for v in row] for row in table],
            "ms_filled": [[round(float(v), 4) for v in row] for row in filled], "runs": [], "goodput": {}}
+    if not a.table:
+        rows = []
+        for name, b in check.items():
+            pred = prof.lookup(b.n_tokens, b.total_kv)
+            rows.append({"decodes": sum(1 for s in b.seqs if s.n_new == 1), "chunk": max(s.n_new for s in b.seqs) if any(s.n_new > 1 for s in b.seqs) else 0,
+                         "tokens": b.n_tokens, "kv": b.total_kv, "measured_ms": round(check_ms[name], 3), "looked_up_ms": round(pred, 3),
+                         "ratio": round(pred / check_ms[name], 3)})
+        ratios = np.array([r["ratio"] for r in rows])
+        res["table_check"] = {"batches": rows, "looked_up_over_measured": {"min": float(ratios.min()), "median": float(np.median(ratios)), "max": float(ratios.max())}}
     # request rates: from the start value up in steps of 30 % until the attainment falls below 90 % (at most 16 steps)
     traces = {"uniform_512_512": (1024, 1024, False, 100.0), "uniform_4096_1024": (8192, 2048, False, 20.0),
               "tier_flip_4096_1024": (8192, 2048, True, 20.0)}

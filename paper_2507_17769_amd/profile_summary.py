@@ -275,6 +275,15 @@ def sim_summary(sim_json, command):
            "| tokens \\ KV size | " + " | ".join(str(k) for k in d["kv_sizes"]) + " |", "|---|" + "---|" * len(d["kv_sizes"])]
     for b, row in zip(d["batch_sizes"], d["ms"]):
         out.append(f"| {b} | " + " | ".join("-" if v is None else f"{v:.3f}" for v in row) + " |")
+    if d.get("table_check"):
+        tc = d["table_check"]
+        out += ["", "How well a lookup by (tokens, KV size) predicts a step (Sec. 4.4 keeps only these two parameters): 24 random batches of the kind an "
+                "instance runs (decodes with log-normal KV lengths, with or without one prefill chunk at a random prefix), measured with the same "
+                f"engine and looked up in the table above: looked-up / measured time between {tc['looked_up_over_measured']['min']:.2f} and "
+                f"{tc['looked_up_over_measured']['max']:.2f}, median {tc['looked_up_over_measured']['median']:.2f}.", "",
+                "| decodes | chunk | tokens | KV size | measured ms | looked up ms | ratio |", "|---|---|---|---|---|---|---|"]
+        for r in tc["batches"]:
+            out.append(f"| {r['decodes']} | {r['chunk']} | {r['tokens']} | {r['kv']} | {r['measured_ms']:.3f} | {r['looked_up_ms']:.3f} | {r['ratio']:.2f} |")
     out += ["", "Request rate swept upwards in steps of 30 % until the DSLO attainment (Sec. 2.3: every token i of a request before "
             "arrival + TTFT + i x TPOT) falls below 90 %; input / output lengths uniform in [1, 1024] / [1, 1024] (`uniform_512_512`) and "
             "[1, 8192] / [1, 2048] (`uniform_4096_1024`, and `tier_flip` = the same with the tier probabilities reversed for the second "
