@@ -31,6 +31,19 @@ def test_8b_layer_full_size(cfg):
     c.close()
 
 
+def test_largest_latency_grid_cell_full_size():
+    """The largest cell of the latency grid (2048-token chunk at its drawn prefix + 256 decodes, 8B-shaped layer): the
+    tiled GEMMs with 256x256 tiles, the longest prefill work items and the decode items in one attention launch."""
+    b = W.grid_cell_batch(2048, 256, seed=0)
+    print(f"grid cell: T={b.n_tokens} total_kv={b.total_kv} pool={b.n_pool_pages}", flush=True)
+    c = Case(b)
+    errs = c.run()
+    print(f"grid cell errors {errs}", flush=True)
+    bad = {k: v for k, v in errs.items() if not v <= TOL}
+    assert not bad, bad
+    c.close()
+
+
 def test_70b_shaped_two_layer_stack_full_batch_teacher_forced(capsys):
     """The 70B-shaped configuration at its real batch (1024-token chunk at prefix 4096 + 256 decodes,
     660 k KV tokens per layer) on two layers, each checked on its own against the oracle from the
