@@ -659,6 +659,29 @@ def run_sim(a):
                     "instance_ms_per_request": round(r["cost_ms"] / n, 2), "mean_instances_in_use": round(r["cost_ms"] / r["end_ms"], 2),
                     "optimal_instance_ms_per_request": res["optimal"][f"{name} {mode}"]["instance_ms_per_request"]})
                 print(f"sim: cost {name} {mode} {rate}/s: {r['cost_ms'] / n:.1f} instance-ms per request", file=sys.stderr, flush=True)
+    # Sec. 5.5: goodput per instance as the number of instances grows (uniform_4096_1024; rate from 60 % of the optimum
+    # of Sec. 3.5 upwards in steps of 15 % until the attainment falls below 90 %)
+    res["goodput_per_instance"] = []
+    n5 = min(n, 50000)
+    for mode in ("co-located", "disaggregated"):
+        opt20 = res["optimal"][f"uniform_4096_1024 {mode}"]["rate_per_s"] / n_servers
+        for servers in (8, 16, 32, 64):
+            best, att = 0.0, 1.0
+            for step in range(8):
+                if att < 0.9:
+                    break
+                rate = round(0.6 * opt20 * servers * 1.15 ** step, 1)
+                tr = W.sim_trace(a.seed, n5, rate / 1e3, 8192, 2048)
+                t0 = time.perf_counter()
+                r = prof.simulate(tr["arrival"], tr["prompt"], tr["output"], tr["ttft"], tr["tier"], tpots, servers, 1024, capacity,
+                                  1000, disaggregated=(mode == "disaggregated"), prefill_budget=2048)
+                wall_total, placed_total, tests_total = wall_total + time.perf_counter() - t0, placed_total + n5, tests_total + r["admission_tests"]
+                att = float(r["attained"].mean())
+                if att >= 0.9:
+                    best = max(best, rate * att)
+            res["goodput_per_instance"].append({"mode": mode, "instances": servers, "goodput_per_s": round(best, 1),
+                                                "per_instance": round(best / servers, 2)})
+            print(f"sim: {mode} {servers} instances: {best / servers:.2f} requests/s per instance", file=sys.stderr, flush=True)
     prof.close()
     res["value"] = res["goodput"]["uniform_512_512 co-located"]
     res["router"] = {"requests_per_wall_second": round(placed_total / wall_total, 1), "admission_tests_per_wall_second": round(tests_total / wall_total, 1),

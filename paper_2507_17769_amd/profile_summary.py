@@ -310,6 +310,9 @@ def sim_summary(sim_json, command):
         for r in d["cost_with_unlimited_pool"]:
             out.append(f"| {r['trace']} | {r['mode']} | {r['rate_per_s']} | {r['attained']:.3f} | {r['instance_ms_per_request']} | "
                        f"{r['optimal_instance_ms_per_request']} | {r['mean_instances_in_use']} |")
+    if d.get("goodput_per_instance"):
+        out += ["", "Goodput per instance as the cluster grows (uniform_4096_1024; Sec. 5.5): "
+                + "; ".join(f"{r['mode']}, {r['instances']} instances: {r['per_instance']}/s" for r in d["goodput_per_instance"]) + "."]
     if "cpu_baseline" in d:
         c = d["cpu_baseline"]
         out += ["", f"Oracle simulator on {c['sample']}: {c['value']:.0f} requests per wall second; `ps_sim_run` on the same sample: "
