@@ -8,15 +8,15 @@
 //   Wp[n/64][k_block = k/32][j = (n%64)/16][g = (k%32)/8][nn = n%16][8]     (1 KiB per [g][nn][8] block)
 // so that one 16-byte load per lane fetches a contiguous KiB that already is the operand of a
 // 16x16x32 MFMA (lane = 16 g + nn holds W^T[n][k0 + 8g .. +7]), and the four blocks of a 64-column
-// group are adjacent: a wavefront that owns 64 columns reads one sequential stream of 4 KiB per
-// k-block (8 KiB per load batch) instead of four streams of 1 KiB, which is what keeps DRAM rows open
-// when two thousand wavefronts stream at once.
+// group are adjacent: the four wavefronts of a block that owns 64 columns read one sequential stream
+// of 4 KiB per k-block between them instead of four separate streams of 1 KiB, which is what keeps
+// DRAM rows open when two thousand wavefronts stream at once.
 //
 // Two kernels:
-//  * gemm_wstream_kernel (M <= 64): weight streaming.  A wavefront owns 64 output columns and a
-//    K slice, loads weight operands straight from HBM into registers (no LDS hop), activation
-//    operands (operand order, see act_offset) from L1/L2, two k-block groups in flight; the four wavefronts of a block split K among
-//    themselves and reduce through LDS in a fixed order.
+//  * gemm_wstream_kernel (M <= 64): weight streaming.  The four computing wavefronts of a block own 16 of
+//    its 64 output columns each and load their weight operands straight from HBM into registers
+//    (no LDS hop), four stages of two k-blocks ahead; a fifth wavefront copies the activation k-blocks
+//    that all four need into an LDS ring.
 //  * gemm_dma_kernel (M > 64): 256x256 or 128x128 block tile, bf16 MFMA 32x32x16.  Activations and
 //    weights are both stored as KiB blocks that already are MFMA operands, so a k-slice of the
 //    tile is copied HBM/L2 -> LDS verbatim by global_load_lds (no register hop, no transform) into
@@ -38,139 +38,141 @@ struct GemmParams {
     int M, N, K;
     int kind;          // GemmOut::Kind
     void* out;         // fp32 [split][M][N] row-major, or bf16 [M][N/2] in operand order
-    int kb_per_split;  // 32-wide k-blocks per wavefront slice (wstream) or per block (tiled)
+    int kb_per_split;  // 32-wide k-blocks per block
 };
 
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
 
 // ------------------------------------------------------------------------------------------
-// Weight streaming kernel.  grid (N/64, splits), 256 threads.
+// Weight streaming kernel (M <= 64).  grid (N/64, splits), 320 threads.
+//
+// A block owns 64 output columns and a K range.  Its four computing wavefronts divide the columns
+// (16 each: one 16-byte load per lane and k-block fetches a KiB that already is a 16x16x32
+// operand, the four wavefronts' KiBs being adjacent), so that all four need the same activation
+// k-blocks and a fifth wavefront can copy those into an LDS ring once per block
+// (global_load_lds, verbatim KiB blocks) instead of each wavefront fetching them from L2 for
+// itself: a quarter of the activation traffic, and no reduction across wavefronts at the end.
+// The copying is a wavefront of its own because vector loads return in order: a computing
+// wavefront that also waited for activations (from L2, quickly) would wait for every weight load
+// issued before them (from HBM, slowly).  Stages of two k-blocks, one barrier per stage.
 // ------------------------------------------------------------------------------------------
-template <int MT>
-struct WsFrags {
-    uint4 w[4];   // weight operands of the 4 column tiles
-    uint4 x[MT];  // activation operands of the MT row tiles
-};
-
-template <int MT>
-__device__ __forceinline__ void ws_load(WsFrags<MT>& f, const bf16_t* w_lane, size_t w_tile_stride, const bf16_t* x_lane, int kb) {
-#pragma unroll
-    for (int j = 0; j < 4; j++) f.w[j] = ldg16(w_lane + ((size_t)kb * 4 + j) * 512);
-#pragma unroll
-    for (int mt = 0; mt < MT; mt++) f.x[mt] = ldg16(x_lane + mt * w_tile_stride + (size_t)kb * 512);
-}
-
-template <int MT>
-__device__ __forceinline__ void ws_mma(f32x4_t (&acc)[MT][4], const WsFrags<MT>& f) {
-#pragma unroll
-    for (int mt = 0; mt < MT; mt++)
-#pragma unroll
-        for (int j = 0; j < 4; j++)
-            acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(f.w[j]), as_bf16x8(f.x[mt]), acc[mt][j], 0, 0, 0);
-}
-
-template <int MT>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_wstream_kernel(GemmParams p) {
-    __shared__ __attribute__((aligned(16))) float red[4 * MT * 4 * 64 * 4];  // [wave][mt][j][lane] float4
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int r = lane & 15, g = lane >> 4;
-    const int ng = blockIdx.x;  // 64-column group
+template <int MT, int KIND>
+__global__ __launch_bounds__(320) void gemm_wstream_kernel(GemmParams p) {
+    constexpr int XS = MT * 2 * 1024;  // bytes of an activation stage: MT row tiles x 2 k-blocks
+    constexpr int WSETS = 4;           // weight stages in registers: three requested ahead of the one in work (a
+                                       // deeper ring costs registers, i.e. resident blocks, and measured slower)
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[3 * XS];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int ng = blockIdx.x;
     const int KB = p.K >> 5;
-    const int slice = blockIdx.y * 4 + wave;
-    const int b0 = min(KB, slice * p.kb_per_split), b1 = min(KB, b0 + p.kb_per_split);
+    const int kb0 = blockIdx.y * p.kb_per_split;
+    const int n_st = (min(KB, kb0 + p.kb_per_split) - kb0) >> 1;  // kb_per_split is even
+    if (n_st <= 0) return;
 
-    const size_t w_tile_stride = (size_t)KB * 512;  // elements between consecutive 16-row tiles of the activations
-    const bf16_t* w_lane = p.Wp + (size_t)ng * 4 * w_tile_stride + (size_t)lane * 8;  // the group's blocks: [kb][j]
-    const bf16_t* x_lane = p.A + (size_t)lane * 8;  // activations are in operand order [m/16][kb]
-
-    f32x4_t acc[MT][4];
+    if (wave == 4) {
+        // Producer.  KiB block b of a stage = (row tile b / 2, k-block parity b % 2).  Stages past the end repeat the
+        // last one into a slot nobody reads, so that every phase is the same.
+        const uint8_t* xa = reinterpret_cast<const uint8_t*>(p.A) + (size_t)kb0 * 1024 + lane * 16;
+        auto copy_stage = [&](int st, int slot) {
+            const uint8_t* g = xa + (size_t)min(st, n_st - 1) * 2048;
 #pragma unroll
-    for (int mt = 0; mt < MT; mt++)
-#pragma unroll
-        for (int j = 0; j < 4; j++) acc[mt][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-
-    // groups of two k-blocks, two groups in flight; loads in the steady-state body are unconditional
-    const int n_grp = (b1 - b0) >> 1;
-    if (n_grp > 0) {
-        WsFrags<MT> a0, a1, c0, c1;
-        ws_load<MT>(a0, w_lane, w_tile_stride, x_lane, b0);
-        ws_load<MT>(a1, w_lane, w_tile_stride, x_lane, b0 + 1);
-        int i = 0;
-        for (; i + 2 < n_grp; i += 2) {
-            // the scheduling barriers keep each batch of loads ahead of the MFMAs that consume the
-            // previous batch; without them the compiler sinks the loads and drains the queue
-            ws_load<MT>(c0, w_lane, w_tile_stride, x_lane, b0 + 2 * i + 2);
-            ws_load<MT>(c1, w_lane, w_tile_stride, x_lane, b0 + 2 * i + 3);
-            __builtin_amdgcn_sched_barrier(0);
-            ws_mma<MT>(acc, a0);
-            ws_mma<MT>(acc, a1);
-            __builtin_amdgcn_sched_barrier(0);
-            ws_load<MT>(a0, w_lane, w_tile_stride, x_lane, b0 + 2 * i + 4);
-            ws_load<MT>(a1, w_lane, w_tile_stride, x_lane, b0 + 2 * i + 5);
-            __builtin_amdgcn_sched_barrier(0);
-            ws_mma<MT>(acc, c0);
-            ws_mma<MT>(acc, c1);
-            __builtin_amdgcn_sched_barrier(0);
+            for (int b = 0; b < 2 * MT; b++)
+                PS_GLOBAL_TO_LDS(g + ((size_t)(b >> 1) * KB + (b & 1)) * 1024, lds + slot * XS + b * 1024);
+        };
+        copy_stage(0, 0);
+        copy_stage(1, 1);
+        vm_wait<0>();
+        __builtin_amdgcn_s_barrier();
+        int wslot = 2;
+        for (int sg = 0; sg < n_st; sg++) {
+            copy_stage(sg + 2, wslot);  // the slot stage sg - 1 has left
+            wslot = wslot == 2 ? 0 : wslot + 1;
+            vm_wait<2 * MT>();          // stage sg + 1 has landed; this phase's copies stay in flight
+            __builtin_amdgcn_s_barrier();
         }
-        if (i + 2 == n_grp) {
-            ws_load<MT>(c0, w_lane, w_tile_stride, x_lane, b0 + 2 * i + 2);
-            ws_load<MT>(c1, w_lane, w_tile_stride, x_lane, b0 + 2 * i + 3);
-            ws_mma<MT>(acc, a0);
-            ws_mma<MT>(acc, a1);
-            ws_mma<MT>(acc, c0);
-            ws_mma<MT>(acc, c1);
-        } else {
-            ws_mma<MT>(acc, a0);
-            ws_mma<MT>(acc, a1);
+        vm_wait<0>();
+        if constexpr (KIND == GemmOut::SWIGLU_BF16) {  // the epilogue's barriers: no copy is in flight any more / sums handed over
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_s_barrier();
         }
-    }
-    if ((b1 - b0) & 1) {
-        WsFrags<MT> t;
-        ws_load<MT>(t, w_lane, w_tile_stride, x_lane, b1 - 1);
-        ws_mma<MT>(acc, t);
+        return;
     }
 
-    // fixed-order reduction over the block's four K slices: wave w finishes column tile w
-    float4* red4 = reinterpret_cast<float4*>(red);
-#pragma unroll
-    for (int mt = 0; mt < MT; mt++)
-#pragma unroll
-        for (int j = 0; j < 4; j++)
-            red4[((wave * MT + mt) * 4 + j) * 64 + lane] = float4{acc[mt][j][0], acc[mt][j][1], acc[mt][j][2], acc[mt][j][3]};
-    __syncthreads();
-    auto total = [&](int mt, int j) {
-        float4 s = red4[((0 * MT + mt) * 4 + j) * 64 + lane];
-#pragma unroll
-        for (int w = 1; w < 4; w++) {
-            const float4 v = red4[((w * MT + mt) * 4 + j) * 64 + lane];
-            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
-        }
-        return s;
+    const int r = lane & 15, g = lane >> 4;
+    // this wavefront's column tile: block [ng][kb][wave] of the packed matrix
+    const uint8_t* w_src = reinterpret_cast<const uint8_t*>(p.Wp) + (((size_t)ng * KB + kb0) * 4 + wave) * 1024 + lane * 16;
+    auto load_w = [&](uint4 (&w)[2], int st) {
+        const uint8_t* gp = w_src + (size_t)min(st, n_st - 1) * 8192;
+        w[0] = ldg16(gp);
+        w[1] = ldg16(gp + 4096);
     };
-    // lane holds C[m = 16 mt + r][n = 64 ng + 16 j + 4 g + 0..3]
-    if (p.kind == GemmOut::SWIGLU_BF16) {
-        if (wave >= 2) return;  // tiles 0,1 = gate, tiles 2,3 = up of the same 32 features
+    f32x4_t acc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; mt++) acc[mt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    uint4 w[WSETS][2];
+#pragma unroll
+    for (int s = 0; s < WSETS - 1; s++) load_w(w[s], s);
+    __builtin_amdgcn_s_barrier();  // activation stages 0 and 1 are in their slots
+
+#define PS_WSHARE_PHASE(I, SG)                                                                                  \
+    {                                                                                                           \
+        load_w(w[((I) + WSETS - 1) % WSETS], (SG) + WSETS - 1);                                                 \
+        const uint8_t* xs_ = lds + slot * XS + lane * 16;                                                       \
+        uint4 x_[2][MT];                                                                                        \
+        _Pragma("unroll") for (int q = 0; q < 2; q++)                                                           \
+            _Pragma("unroll") for (int mt = 0; mt < MT; mt++) x_[q][mt] = *reinterpret_cast<const uint4*>(xs_ + (mt * 2 + q) * 1024); \
+        _Pragma("unroll") for (int q = 0; q < 2; q++)                                                           \
+            _Pragma("unroll") for (int mt = 0; mt < MT; mt++)                                                   \
+                acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(w[(I)][q]), as_bf16x8(x_[q][mt]), acc[mt], 0, 0, 0); \
+        slot = slot == 2 ? 0 : slot + 1;                                                                        \
+        __builtin_amdgcn_s_barrier();                                                                           \
+    }
+    int slot = 0, s = 0;
+    for (; s + WSETS <= n_st; s += WSETS) {
+        PS_WSHARE_PHASE(0, s)
+        PS_WSHARE_PHASE(1, s + 1)
+        PS_WSHARE_PHASE(2, s + 2)
+        PS_WSHARE_PHASE(3, s + 3)
+    }
+    if (s < n_st) PS_WSHARE_PHASE(0, s)
+    if (s + 1 < n_st) PS_WSHARE_PHASE(1, s + 1)
+    if (s + 2 < n_st) PS_WSHARE_PHASE(2, s + 2)
+#undef PS_WSHARE_PHASE
+
+    // lane holds C[m = 16 mt + r][n = 64 ng + 16 wave + 4 g + 0..3]
+    if constexpr (KIND == GemmOut::SWIGLU_BF16) {
+        // column tiles 0, 1 = gate, tiles 2, 3 = up of the same 32 features: wavefronts 2 and 3 hand their sums over
+        float4* up4 = reinterpret_cast<float4*>(lds);  // [wave - 2][mt][lane]
+        __builtin_amdgcn_s_barrier();                  // the ring is free: the producer's last copies have landed
+        if (wave >= 2) {
+#pragma unroll
+            for (int mt = 0; mt < MT; mt++) up4[((wave - 2) * MT + mt) * 64 + lane] = float4{acc[mt][0], acc[mt][1], acc[mt][2], acc[mt][3]};
+        }
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the LDS writes have been made before the barrier
+        __builtin_amdgcn_s_barrier();
+        if (wave >= 2) return;
         bf16_t* out = static_cast<bf16_t*>(p.out);
         const int F = p.N >> 1;
 #pragma unroll
         for (int mt = 0; mt < MT; mt++) {
             const int m = mt * 16 + r;
-            const float4 gt = total(mt, wave), up = total(mt, wave + 2);
+            const float4 up = up4[(wave * MT + mt) * 64 + lane];
             if (m < p.M) {
                 uint2 o;
-                o.x = pack_bf16(silu_f(gt.x) * up.x, silu_f(gt.y) * up.y);
-                o.y = pack_bf16(silu_f(gt.z) * up.z, silu_f(gt.w) * up.w);
+                o.x = pack_bf16(silu_f(acc[mt][0]) * up.x, silu_f(acc[mt][1]) * up.y);
+                o.y = pack_bf16(silu_f(acc[mt][2]) * up.z, silu_f(acc[mt][3]) * up.w);
                 *reinterpret_cast<uint2*>(out + act_offset(m, ng * 32 + wave * 16 + 4 * g, F)) = o;
             }
         }
-        return;
-    }
-    float* out = static_cast<float*>(p.out) + (size_t)blockIdx.y * p.M * p.N;
+    } else {
+        float* out = static_cast<float*>(p.out) + (size_t)blockIdx.y * p.M * p.N;
 #pragma unroll
-    for (int mt = 0; mt < MT; mt++) {
-        const int m = mt * 16 + r;
-        const float4 s = total(mt, wave);
-        if (m < p.M) *reinterpret_cast<float4*>(out + (size_t)m * p.N + ng * 64 + wave * 16 + 4 * g) = s;
+        for (int mt = 0; mt < MT; mt++) {
+            const int m = mt * 16 + r;
+            if (m < p.M)
+                *reinterpret_cast<float4*>(out + (size_t)m * p.N + ng * 64 + wave * 16 + 4 * g) = float4{acc[mt][0], acc[mt][1], acc[mt][2], acc[mt][3]};
+        }
     }
 }
 
@@ -413,7 +415,7 @@ struct GemmPlan {
     bool wstream;
     bool big_tile;     // tiled: 256x256 blocks (else 128x128)
     int splits;        // partial buffers written
-    int kb_per_split;  // wstream: 32-wide k-blocks per wavefront slice; tiled: per block
+    int kb_per_split;  // 32-wide k-blocks per block
 };
 
 // Tiled-kernel cost model, fitted to measured sweeps over the layer's GEMM shapes (M 144 .. 2304):
@@ -444,8 +446,10 @@ static GemmPlan plan_gemm(int M, int N, int K, int kind, int split_opt, int tile
             s = std::min(s, std::max(1, KB / 8));  // keep at least two k-blocks per wavefront slice
             s = std::max(s, 1);
         }
-        g.kb_per_split = (KB + 4 * s - 1) / (4 * s);
-        g.splits = s;
+        int kps = (KB + s - 1) / s;
+        kps += kps & 1;  // whole stages of two k-blocks
+        g.kb_per_split = kps;
+        g.splits = (KB + kps - 1) / kps;
     } else {
         const int s_lo = kind == GemmOut::SWIGLU_BF16 ? 1 : (split_opt > 0 ? std::min(split_opt, 8) : 1);
         const int s_hi = kind == GemmOut::SWIGLU_BF16 ? 1 : (split_opt > 0 ? s_lo : 8);
@@ -510,11 +514,17 @@ hipError_t launch_gemm(const GemmArgs& a, int* n_splits, hipStream_t st) {
     if (n_splits) *n_splits = g.splits;
     if (g.wstream) {
         const dim3 grid(a.N / 64, g.splits);
-        switch ((a.M + 15) / 16) {
-            case 1: hipLaunchKernelGGL((gemm_wstream_kernel<1>), grid, dim3(256), 0, st, p); break;
-            case 2: hipLaunchKernelGGL((gemm_wstream_kernel<2>), grid, dim3(256), 0, st, p); break;
-            case 3: hipLaunchKernelGGL((gemm_wstream_kernel<3>), grid, dim3(256), 0, st, p); break;
-            default: hipLaunchKernelGGL((gemm_wstream_kernel<4>), grid, dim3(256), 0, st, p); break;
+        const int mt = (a.M + 15) / 16;
+        if (a.kind == GemmOut::SWIGLU_BF16) {
+            if (mt == 1) hipLaunchKernelGGL((gemm_wstream_kernel<1, GemmOut::SWIGLU_BF16>), grid, dim3(320), 0, st, p);
+            else if (mt == 2) hipLaunchKernelGGL((gemm_wstream_kernel<2, GemmOut::SWIGLU_BF16>), grid, dim3(320), 0, st, p);
+            else if (mt == 3) hipLaunchKernelGGL((gemm_wstream_kernel<3, GemmOut::SWIGLU_BF16>), grid, dim3(320), 0, st, p);
+            else hipLaunchKernelGGL((gemm_wstream_kernel<4, GemmOut::SWIGLU_BF16>), grid, dim3(320), 0, st, p);
+        } else {
+            if (mt == 1) hipLaunchKernelGGL((gemm_wstream_kernel<1, GemmOut::PARTIAL_F32>), grid, dim3(320), 0, st, p);
+            else if (mt == 2) hipLaunchKernelGGL((gemm_wstream_kernel<2, GemmOut::PARTIAL_F32>), grid, dim3(320), 0, st, p);
+            else if (mt == 3) hipLaunchKernelGGL((gemm_wstream_kernel<3, GemmOut::PARTIAL_F32>), grid, dim3(320), 0, st, p);
+            else hipLaunchKernelGGL((gemm_wstream_kernel<4, GemmOut::PARTIAL_F32>), grid, dim3(320), 0, st, p);
         }
         return hipGetLastError();
     }
