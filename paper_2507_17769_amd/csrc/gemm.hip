@@ -13,11 +13,11 @@
 // DRAM rows open when two thousand wavefronts stream at once.
 //
 // Two kernels:
-//  * gemm_wstream_kernel (M <= 64): weight streaming.  The four computing wavefronts of a block own 16 of
+//  * gemm_wstream_kernel (M <= 96): weight streaming.  The four computing wavefronts of a block own 16 of
 //    its 64 output columns each and load their weight operands straight from HBM into registers
 //    (no LDS hop), four stages of two k-blocks ahead; a fifth wavefront copies the activation k-blocks
 //    that all four need into an LDS ring.
-//  * gemm_dma_kernel (M > 64): 256x256 or 128x128 block tile, bf16 MFMA 32x32x16.  Activations and
+//  * gemm_dma_kernel (M > 96, or forced by the tile option above 64): 256x256 or 128x128 block tile, bf16 MFMA 32x32x16.  Activations and
 //    weights are both stored as KiB blocks that already are MFMA operands, so a k-slice of the
 //    tile is copied HBM/L2 -> LDS verbatim by global_load_lds (no register hop, no transform) into
 //    a ring of four stages, three in flight; the wavefronts read operands back with one
@@ -44,7 +44,7 @@ struct GemmParams {
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
 
 // ------------------------------------------------------------------------------------------
-// Weight streaming kernel (M <= 64).  grid (N/64, splits), 320 threads.
+// Weight streaming kernel (M <= 96).  grid (N/64, splits), 320 threads.
 //
 // A block owns 64 output columns and a K range.  Its four computing wavefronts divide the columns
 // (16 each: one 16-byte load per lane and k-block fetches a KiB that already is a 16x16x32
@@ -435,7 +435,7 @@ static double tiled_cost(int M, int N, int K, bool big, int splits, int* kb_per_
 
 static GemmPlan plan_gemm(int M, int N, int K, int kind, int split_opt, int tile_opt) {
     GemmPlan g;
-    g.wstream = M <= 64;
+    g.wstream = M <= 64 || (M <= 96 && tile_opt == 0);  // measured: streaming wins up to ~96 tokens, the tiled kernel above
     g.big_tile = false;
     int s = 1;
     if (g.wstream) {
@@ -515,17 +515,18 @@ hipError_t launch_gemm(const GemmArgs& a, int* n_splits, hipStream_t st) {
     if (g.wstream) {
         const dim3 grid(a.N / 64, g.splits);
         const int mt = (a.M + 15) / 16;
-        if (a.kind == GemmOut::SWIGLU_BF16) {
-            if (mt == 1) hipLaunchKernelGGL((gemm_wstream_kernel<1, GemmOut::SWIGLU_BF16>), grid, dim3(320), 0, st, p);
-            else if (mt == 2) hipLaunchKernelGGL((gemm_wstream_kernel<2, GemmOut::SWIGLU_BF16>), grid, dim3(320), 0, st, p);
-            else if (mt == 3) hipLaunchKernelGGL((gemm_wstream_kernel<3, GemmOut::SWIGLU_BF16>), grid, dim3(320), 0, st, p);
-            else hipLaunchKernelGGL((gemm_wstream_kernel<4, GemmOut::SWIGLU_BF16>), grid, dim3(320), 0, st, p);
-        } else {
-            if (mt == 1) hipLaunchKernelGGL((gemm_wstream_kernel<1, GemmOut::PARTIAL_F32>), grid, dim3(320), 0, st, p);
-            else if (mt == 2) hipLaunchKernelGGL((gemm_wstream_kernel<2, GemmOut::PARTIAL_F32>), grid, dim3(320), 0, st, p);
-            else if (mt == 3) hipLaunchKernelGGL((gemm_wstream_kernel<3, GemmOut::PARTIAL_F32>), grid, dim3(320), 0, st, p);
-            else hipLaunchKernelGGL((gemm_wstream_kernel<4, GemmOut::PARTIAL_F32>), grid, dim3(320), 0, st, p);
+#define PS_WS_LAUNCH(MT_)                                                                                                  \
+    if (a.kind == GemmOut::SWIGLU_BF16) hipLaunchKernelGGL((gemm_wstream_kernel<MT_, GemmOut::SWIGLU_BF16>), grid, dim3(320), 0, st, p); \
+    else hipLaunchKernelGGL((gemm_wstream_kernel<MT_, GemmOut::PARTIAL_F32>), grid, dim3(320), 0, st, p);
+        switch (mt) {
+            case 1: PS_WS_LAUNCH(1) break;
+            case 2: PS_WS_LAUNCH(2) break;
+            case 3: PS_WS_LAUNCH(3) break;
+            case 4: PS_WS_LAUNCH(4) break;
+            case 5: PS_WS_LAUNCH(5) break;
+            default: PS_WS_LAUNCH(6) break;
         }
+#undef PS_WS_LAUNCH
         return hipGetLastError();
     }
     if (a.kind == GemmOut::SWIGLU_BF16)

@@ -122,7 +122,7 @@ struct GemmArgs {
     void* out;         // PARTIAL_F32: fp32 [splits][M][N] row-major; SWIGLU_BF16: bf16 [M][N/2] in operand order
     size_t out_bytes;  // capacity of out; at least gemm_out_bytes(...)
     int split_k;       // 0 = choose
-    int tile;          // M > 64: 0 = choose, 128 or 256 = block tile edge
+    int tile;          // M > 64: 0 = choose (streaming up to 96 tokens, then a tile), 128 or 256 = block tile edge
 };
 // *n_splits receives the number of partial buffers written (1 for SWIGLU_BF16)
 hipError_t launch_gemm(const GemmArgs& a, int* n_splits, hipStream_t st);

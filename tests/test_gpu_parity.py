@@ -31,6 +31,7 @@ def test_cfg0_tiny_mixed_batch_all_tensors():
     (1, 0, []), (1, 1, [1]), (3, 15, [2, 16]), (15, 0, [17]), (16, 16, [31, 32, 33]), (17, 100, [1, 1, 1]),
     (33, 1, [64]), (100, 37, [5, 250]), (0, 0, [1]), (0, 0, [1, 2, 3, 15, 16, 17, 18, 255, 256, 257]),
     (130, 0, []), (257, 300, [300]),
+    (70, 5, [3, 9]), (88, 0, [1, 2, 3, 4, 5, 6]),     # 72 and 94 tokens: five and six row tiles in the weight-streaming GEMM
 ])
 def test_ragged_shapes_tiny_model(chunk, prefix, decodes):
     b = W.custom_batch("tiny", 11, chunk, prefix, decodes, name="ragged")
