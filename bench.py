@@ -23,6 +23,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+NOMINAL_CLOCK_MHZ = 2400.0
 
 
 def parse():
@@ -46,6 +47,16 @@ def parse():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy a few times (reference for HBM byte counters)")
     return ap.parse_args()
+
+
+def mfma_clock(ctx, tflops):
+    """Sec. 2.2's compute-bound side priced twice: against the nominal matrix peak and against what the matrix pipes sustain at
+    the clock the device holds under dense MFMA load (read after the timed region with ps_clock_under_load)."""
+    r = ctx.clock_under_load(400000, 2)
+    peak_at_clock = MFMA_BF16_PEAK_TFLOPS * r["shader_mhz"] / NOMINAL_CLOCK_MHZ
+    return {"shader_mhz_under_mfma_load": round(r["shader_mhz"], 1), "mfma_only_loop_tflops": round(r["mfma_tflops"], 1),
+            "ticks_per_mfma": round(r["ticks_per_mfma"], 2), "nominal_clock_mhz": NOMINAL_CLOCK_MHZ,
+            "mfma_peak_at_that_clock_tflops": round(peak_at_clock, 1), "frac_mfma_at_that_clock": tflops / peak_at_clock}
 
 
 def cpu_baseline(batch, weights, n_runs=2):
@@ -229,6 +240,7 @@ def run_cfg4(a):
                     "frac_mfma": 2 * params * T * L / (gemm_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
            "attention": {"ms": stage["attention"], "kv_GBs": 2 * nkv * d * 2 * total_kv * L / (stage["attention"] * 1e-3) / 1e9},
            "output_finite": finite}
+    res["gemm"]["clock"] = mfma_clock(eng.ctx, res["gemm"]["tflops"])
     if check:
         from oracle import bf16 as obf
         from oracle import run as orun
@@ -424,6 +436,11 @@ def run_prefill(a):
                                "gemm_tflops": 2 * params * T / (gemm_ms * 1e-3) / 1e12,
                                "gemm_frac_mfma": 2 * params * T / (gemm_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
                                "attention_tflops": 4 * d * nq * pairs / (float(stage[3]) * 1e-3) / 1e12})
+    clk = mfma_clock(eng.ctx, 0.0)
+    del clk["frac_mfma_at_that_clock"]
+    res["clock"] = clk
+    for r in res["batches"]:
+        r["gemm_frac_mfma_at_measured_clock"] = r["gemm_tflops"] / clk["mfma_peak_at_that_clock_tflops"]
     eng.close()
     print(json.dumps(res))
 
@@ -841,6 +858,7 @@ def main():
                  "frac_hbm": 2 * params / (gemm_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                  "frac_mfma": 2 * params * T / (gemm_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
     }
+    res["gemm"]["clock"] = mfma_clock(eng.ctx, res["gemm"]["tflops"])
     if not a.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(batch, weights)
     eng.close()

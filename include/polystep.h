@@ -249,6 +249,24 @@ ps_status ps_plan_attention(ps_ctx* ctx, const ps_seq* seqs, int32_t n_seqs, int
  * (Sec. 2.2: decode attention does not batch; its cost follows the KV bytes read). */
 ps_status ps_attention_times(ps_ctx* ctx, float* ms, int32_t cap, int32_t* n);
 
+/* Measurement support, not a step of the path: what the device sustains while every SIMD issues
+ * back-to-back dense bf16 MFMAs with no memory traffic.  The nominal matrix peak assumes the
+ * maximum shader clock; under matrix load the power management settles lower, and the fractions
+ * of peak reported for the projections (Sec. 2.2: prefill and large batches are compute-bound)
+ * are quoted against both.  Launches blocks of four wavefronts, wavefronts_per_simd (1, 2 or 4)
+ * blocks per compute unit; each wavefront issues mfma_per_wavefront (4096 .. 2^22, rounded down to
+ * a multiple of 4) independent 32x32x16 MFMAs.  Allocates and frees a few hundred KiB of device
+ * memory, runs on the context's stream and waits for it.  *out is host memory. */
+typedef struct ps_clock_reading {
+    double shader_mhz;      /* shader-clock ticks per microsecond of the constant-rate wall clock, mean over blocks */
+    double ticks_per_mfma;  /* shader-clock ticks per MFMA as a wavefront saw them (32 = back to back, alone on its SIMD) */
+    double mfma_tflops;     /* 2*32*32*16 flop x MFMAs issued on the device / elapsed time between HIP events */
+    double elapsed_ms;
+    int32_t compute_units;
+    int32_t wavefronts_per_simd;
+} ps_clock_reading;
+ps_status ps_clock_under_load(ps_ctx* ctx, int32_t mfma_per_wavefront, int32_t wavefronts_per_simd, ps_clock_reading* out);
+
 /* Ask subsequent steps to copy layer `layer`'s intermediates; taps == NULL switches it off. */
 ps_status ps_set_taps(ps_ctx* ctx, int32_t layer, const ps_taps* taps);
 

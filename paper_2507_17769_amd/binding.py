@@ -67,6 +67,11 @@ class ps_seq(C.Structure):
                 ("page_table", C.POINTER(C.c_int32)), ("n_pages", C.c_int32)]
 
 
+class ps_clock_reading(C.Structure):
+    _fields_ = [("shader_mhz", C.c_double), ("ticks_per_mfma", C.c_double), ("mfma_tflops", C.c_double), ("elapsed_ms", C.c_double),
+                ("compute_units", C.c_int32), ("wavefronts_per_simd", C.c_int32)]
+
+
 class ps_step_stats(C.Structure):
     _fields_ = [("n_tokens", C.c_int32), ("total_kv", C.c_int64), ("n_attn_items", C.c_int32),
                 ("n_attn_partials", C.c_int32), ("ms_total", C.c_float), ("ms_stage", C.c_float * PS_N_STAGES)]
@@ -113,6 +118,7 @@ _SIGS = {
     "ps_plan_attention": (C.c_int, [_P, C.POINTER(ps_seq), C.c_int32, _I32P, C.c_int32, _I32P]),
     "ps_set_taps": (C.c_int, [_P, C.c_int32, C.POINTER(ps_taps)]),
     "ps_attention_times": (C.c_int, [_P, C.POINTER(C.c_float), C.c_int32, _I32P]),
+    "ps_clock_under_load": (C.c_int, [_P, C.c_int32, C.c_int32, C.POINTER(ps_clock_reading)]),
     "ps_profile_grid": (C.c_int, [_P, C.POINTER(ps_grid_cell_spec), C.c_int32, C.POINTER(ps_grid_opts), _P, _P,
                                   C.POINTER(ps_grid_cell)]),
 }
@@ -271,6 +277,11 @@ class Context:
         n = C.c_int32(0)
         self._check(lib.ps_attention_times(self.handle, buf, cap, C.byref(n)))
         return [buf[i] for i in range(n.value)]
+
+    def clock_under_load(self, mfma_per_wavefront=400000, wavefronts_per_simd=2):
+        r = ps_clock_reading()
+        self._check(lib.ps_clock_under_load(self.handle, mfma_per_wavefront, wavefronts_per_simd, C.byref(r)))
+        return {n: getattr(r, n) for n, _ in ps_clock_reading._fields_}
 
     def set_taps(self, layer, **ptrs):
         if not ptrs:

@@ -899,6 +899,52 @@ extern "C" ps_status ps_attention_times(ps_ctx* c, float* ms, int32_t cap, int32
     return PS_OK;
 }
 
+extern "C" ps_status ps_clock_under_load(ps_ctx* c, int32_t mfma_per_wavefront, int32_t wavefronts_per_simd, ps_clock_reading* out) {
+    if (!c || !out) return fail(c, PS_EINVAL, "ps_clock_under_load: null argument");
+    if (c->host_only) return fail(c, PS_ESTATE, "ps_clock_under_load: host-only context");
+    if (mfma_per_wavefront < 4096 || mfma_per_wavefront > (1 << 22)) return fail(c, PS_ERANGE, "ps_clock_under_load: mfma_per_wavefront outside [4096, 2^22]");
+    if (wavefronts_per_simd != 1 && wavefronts_per_simd != 2 && wavefronts_per_simd != 4)
+        return fail(c, PS_EINVAL, "ps_clock_under_load: wavefronts_per_simd must be 1, 2 or 4");
+    int dev = 0, cus = 0, wall_khz = 0;
+    HIP_TRY(c, hipGetDevice(&dev));
+    HIP_TRY(c, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    HIP_TRY(c, hipDeviceGetAttribute(&wall_khz, hipDeviceAttributeWallClockRate, dev));
+    if (cus <= 0 || wall_khz <= 0) return fail(c, PS_EDEVICE, "ps_clock_under_load: the device reports no compute units or no wall-clock rate");
+    const int blocks = cus * wavefronts_per_simd, rounds = mfma_per_wavefront / 4;
+    float* sink = nullptr;
+    long long* ticks = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    ps_status st = PS_OK;
+    hipError_t he = hipSuccess;
+    float ms = 0.f;
+    std::vector<long long> h((size_t)blocks * 2);
+    if ((st = dev_alloc(c, &sink, (size_t)blocks * 256 * sizeof(float), "clock probe output")) != PS_OK) return st;
+    if ((st = dev_alloc(c, &ticks, (size_t)blocks * 2 * sizeof(long long), "clock probe ticks")) != PS_OK) { dev_free(sink); return st; }
+    // a short launch first, so that the timed one starts with the pipes and the clock already under load
+    if ((he = hipEventCreate(&e0)) == hipSuccess && (he = hipEventCreate(&e1)) == hipSuccess &&
+        (he = launch_mfma_clock_probe(blocks, 1024, sink, ticks, c->stream)) == hipSuccess &&
+        (he = hipEventRecord(e0, c->stream)) == hipSuccess &&
+        (he = launch_mfma_clock_probe(blocks, rounds, sink, ticks, c->stream)) == hipSuccess &&
+        (he = hipEventRecord(e1, c->stream)) == hipSuccess && (he = hipStreamSynchronize(c->stream)) == hipSuccess &&
+        (he = hipEventElapsedTime(&ms, e0, e1)) == hipSuccess)
+        he = hipMemcpy(h.data(), ticks, h.size() * sizeof(long long), hipMemcpyDeviceToHost);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    dev_free(sink);
+    dev_free(ticks);
+    if (he != hipSuccess) return hip_fail(c, he, "ps_clock_under_load");
+    double shader = 0, wall = 0;
+    for (int b = 0; b < blocks; b++) { shader += (double)h[2 * b]; wall += (double)h[2 * b + 1]; }
+    if (!(wall > 0) || !(ms > 0)) return fail(c, PS_EDEVICE, "ps_clock_under_load: the clocks did not advance");
+    out->shader_mhz = shader / wall * (wall_khz / 1e3);
+    out->ticks_per_mfma = shader / blocks / (4.0 * rounds);
+    out->mfma_tflops = (double)blocks * 4 * (4.0 * rounds) * (2.0 * 32 * 32 * 16) / (ms * 1e-3) / 1e12;
+    out->elapsed_ms = ms;
+    out->compute_units = cus;
+    out->wavefronts_per_simd = wavefronts_per_simd;
+    return PS_OK;
+}
+
 // ------------------------------------------------------------------------------ latency grid
 static float median_of(std::vector<float> v) {
     std::sort(v.begin(), v.end());

@@ -113,6 +113,8 @@ hipError_t launch_kv_copy(bool to_pool, bf16_t* pool_slot, const int32_t* slots_
                           bf16_t* v, hipStream_t st);
 hipError_t launch_repack_weight(const bf16_t* w, bf16_t* wp, int K, int N, int interleave, hipStream_t st);
 hipError_t launch_copy_bytes(const void* src, void* dst, size_t n, hipStream_t st);
+// sink: blocks * 256 floats; ticks: blocks * 2 (shader-clock ticks, wall-clock ticks of wavefront 0 of each block)
+hipError_t launch_mfma_clock_probe(int blocks, int rounds, float* sink, long long* ticks, hipStream_t st);
 
 struct GemmArgs {
     const bf16_t* A;   // [M][K] activations in operand order (act_offset)

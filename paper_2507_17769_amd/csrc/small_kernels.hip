@@ -336,6 +336,49 @@ hipError_t launch_untile(const bf16_t* src, bf16_t* dst, int M, int K, hipStream
 }
 
 // Device-to-device copy of n bytes (n a multiple of 16, both pointers 16-byte aligned).
+// ------------------------------------------------------------------------------------------
+// Clock-under-load probe.  Every wavefront issues `rounds` x 4 independent 32x32x16 bf16 MFMAs on
+// operands made from a hash of its lane (finite, mixed signs and exponents) and reports how many
+// shader-clock ticks and how many ticks of the constant-rate wall clock that took.  No memory
+// traffic inside the loop: the rate is what the matrix pipes sustain at the clock the power
+// management settles on, which is the ceiling the GEMM kernels can be priced against.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void mfma_clock_probe_kernel(int rounds, float* __restrict__ sink, long long* __restrict__ ticks) {
+    uint32_t h = (blockIdx.x * 256u + threadIdx.x) * 2654435761u;
+    uint32_t w[8];
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+        h = h * 1664525u + 1013904223u;
+        // two bf16 values with exponents 2^-2 .. 2^1, random mantissa and sign
+        const uint32_t lo = 0x3e80u + ((h >> 8) & 0x1ffu) + ((h & 1u) << 15), hi = 0x3e80u + ((h >> 20) & 0x1ffu) + ((h & 2u) << 14);
+        w[i] = lo | (hi << 16);
+    }
+    const u32x4_t av = {w[0], w[1], w[2], w[3]}, bv = {w[4], w[5], w[6], w[7]};
+    const bf16x8_t a = __builtin_bit_cast(bf16x8_t, av), b = __builtin_bit_cast(bf16x8_t, bv);
+    f32x16_t c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
+    const long long t0 = clock64(), w0 = wall_clock64();
+    for (int i = 0; i < rounds; i++) {
+        c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
+        c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c1, 0, 0, 0);
+        c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c2, 0, 0, 0);
+        c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c3, 0, 0, 0);
+    }
+    const long long t1 = clock64(), w1 = wall_clock64();
+    float acc = 0.f;
+#pragma unroll
+    for (int e = 0; e < 16; e++) acc += c0[e] + c1[e] + c2[e] + c3[e];
+    sink[blockIdx.x * 256 + threadIdx.x] = acc;  // keeps the loop alive
+    if (threadIdx.x == 0) {
+        ticks[2 * blockIdx.x] = t1 - t0;
+        ticks[2 * blockIdx.x + 1] = w1 - w0;
+    }
+}
+
+hipError_t launch_mfma_clock_probe(int blocks, int rounds, float* sink, long long* ticks, hipStream_t st) {
+    hipLaunchKernelGGL(mfma_clock_probe_kernel, dim3(blocks), dim3(256), 0, st, rounds, sink, ticks);
+    return hipGetLastError();
+}
+
 hipError_t launch_copy_bytes(const void* src, void* dst, size_t n, hipStream_t st) {
     const size_t n16 = n / 16;
     if (n16 == 0) return hipSuccess;

@@ -62,6 +62,11 @@ def trace_summary(trace_csv, bench_json, workload, command):
         out += ["", f"bench.py's own line from this (profiled) run: ms_per_step {b['ms_per_step']:.4f}, attention kernel by HIP events "
                     f"{rf['avg_launch_ms'] * 1e3:.1f} µs (rocprofv3 average above: {avg:.1f} µs), algorithmic bytes "
                     f"{rf['algorithmic_bytes_per_launch']} → {rf['algorithmic_bytes_per_launch'] / avg / 1e3:.0f} GB/s by the rocprofv3 average."]
+    g = b.get("gemm", {})
+    if "clock" in g:
+        out += ["", f"The four weight GEMMs of a step (HIP-event stage times): {g['ms'] * 1e3:.0f} µs, {g['tflops']:.0f} TFLOP/s = "
+                    f"{100 * g['frac_mfma']:.1f} % of the nominal 2.5 PFLOP/s and {100 * g['clock']['frac_mfma_at_that_clock']:.1f} % of the peak at the "
+                    f"measured clock; weights streamed at {g['weight_GBs']:.0f} GB/s.  " + clock_note(g["clock"])]
     # one timed step, kernel by kernel: the steps start with the first-layer rmsnorm
     idx = [i for i, r in enumerate(rows) if "rmsnorm_kernel<false>" in r["Kernel_Name"]]
     if len(idx) > 40:
@@ -183,6 +188,13 @@ def model_summary(model_json, command):
     return "\n".join(out) + "\n"
 
 
+def clock_note(c):
+    return (f"Clock under load (`ps_clock_under_load`, read after the timed steps): a loop of nothing but dense bf16 MFMAs runs at "
+            f"{c['shader_mhz_under_mfma_load']:.0f} MHz ({c['ticks_per_mfma']:.1f} shader ticks per MFMA and wavefront, "
+            f"{c['mfma_only_loop_tflops']:.0f} TFLOP/s), not the {c['nominal_clock_mhz']:.0f} MHz behind the nominal 2.5 PFLOP/s; "
+            f"the matrix peak at that clock is {c['mfma_peak_at_that_clock_tflops']:.0f} TFLOP/s.")
+
+
 def prefill_summary(prefill_json, command):
     d = json.load(open(prefill_json))
     out = ["# Prefill-only steps — 8B-shaped layer, one MI355X", "",
@@ -190,14 +202,17 @@ def prefill_summary(prefill_json, command):
            "request or several sharing the step, including the case where a budget already holds 1023 tokens and takes one token of "
            "the next request (Sec. 4.6).  Four device copies of the layer in rotation, so weights come from HBM.", "",
            f"Command:  `{command}`", "",
-           "| batch (requests x new tokens) | tokens | ms per step | tokens/s | GEMMs: TFLOP/s (% of 2.5 PFLOP/s) | attention TFLOP/s (causal pairs only) | attention ms | GEMM ms |",
+           "| batch (requests x new tokens) | tokens | ms per step | tokens/s | GEMMs: TFLOP/s (% of 2.5 PFLOP/s; % of the peak at the measured clock) | attention TFLOP/s (causal pairs only) | attention ms | GEMM ms |",
            "|---|---|---|---|---|---|---|---|"]
     for b in d["batches"]:
         st = b["stage_ms"]
         gemm = st["gemm_qkv"] + st["gemm_o"] + st["gemm_gate_up"] + st["gemm_down"]
+        at_clock = f"; {100 * b['gemm_frac_mfma_at_measured_clock']:.1f} %" if "gemm_frac_mfma_at_measured_clock" in b else ""
         out.append(f"| {b['batch']} | {b['n_tokens']} | {b['ms_per_step']:.3f} | {b['tokens_per_s']:.0f} | {b['gemm_tflops']:.0f} "
-                   f"({100 * b['gemm_frac_mfma']:.1f} %) | {b['attention_tflops']:.0f} | {st['attention']:.3f} | {gemm:.3f} |")
+                   f"({100 * b['gemm_frac_mfma']:.1f} %{at_clock}) | {b['attention_tflops']:.0f} | {st['attention']:.3f} | {gemm:.3f} |")
     out += ["", "`ms per step` is the host clock over back-to-back steps; stage times come from separate event-timed steps."]
+    if "clock" in d:
+        out += ["", clock_note(d["clock"])]
     return "\n".join(out) + "\n"
 
 
@@ -236,6 +251,9 @@ def cfg4_summary(cfg4_json, command):
     d = json.load(open(cfg4_json))
     c, st, g, at = d["config"], d["stage_ms_all_layers"], d["gemm"], d["attention"]
     L = c["n_layers"]
+    ck = g.get("clock")
+    at_clock = (f" = {100 * ck['frac_mfma_at_that_clock']:.1f} % of the {ck['mfma_peak_at_that_clock_tflops']:.0f} TFLOP/s that the matrix pipes "
+                f"reach at the {ck['shader_mhz_under_mfma_load']:.0f} MHz measured under dense MFMA load") if ck else ""
     out = [f"# 70B-shaped stack, {L} layers on one MI355X: step time and teacher-forced layer checks", "",
            "Command (one GPU, the bf16 weights of all layers generated on the device, KV slots aliased over the layers):", "",
            f"    {command}", "", c["workload"] + ".", "",
@@ -243,7 +261,7 @@ def cfg4_summary(cfg4_json, command):
            f"| step ({L} layers, host clock over {d['steps']} steps) | {d['ms_per_step']:.1f} ms = {d['value']:.0f} new tokens/s |",
            f"| per layer | {d['ms_per_step'] / L:.2f} ms |",
            f"| weight GEMMs (QKV, O, gate/up, down), all layers | {g['ms']:.1f} ms ({st['gemm_qkv']:.1f} / {st['gemm_o']:.1f} / "
-           f"{st['gemm_gate_up']:.1f} / {st['gemm_down']:.1f}): {g['tflops']:.0f} TFLOP/s = {100 * g['frac_mfma']:.1f} % of the 2.5 PFLOP/s bf16 MFMA peak |",
+           f"{st['gemm_gate_up']:.1f} / {st['gemm_down']:.1f}): {g['tflops']:.0f} TFLOP/s = {100 * g['frac_mfma']:.1f} % of the 2.5 PFLOP/s bf16 MFMA peak{at_clock} |",
            f"| attention (one launch for the chunk and the decodes, plus merge), all layers | {at['ms']:.1f} ms: {at['kv_GBs'] / 1e3:.2f} TB/s of KV bytes "
            "(the 1024-token chunk is compute-heavy: 5120 keys x 1024 queries x 64 heads) |",
            f"| rmsnorm / rope+append / add+norm | {st['rmsnorm_attn']:.2f} / {st['rope_append']:.2f} / {st['rmsnorm_ffn']:.2f} ms |", "",

@@ -377,3 +377,29 @@ def test_prefill_decode_handoff_through_kv_read_and_write():
     kb, vb = bctx.read_kv(0, pages_b, 0, prompt + 1)
     assert np.array_equal(ka, kb) and np.array_equal(va, vb)
     a.close(); bctx.close()
+
+
+@pytest.mark.gpu
+def test_clock_under_load_reading_is_consistent():
+    """The diagnostic's three figures must agree with each other: the matrix rate is the shader clock times the
+    flop per tick that back-to-back MFMAs give, and neither exceeds the device's nominal figures."""
+    b = W.custom_batch("tiny", 0, 0, 0, [16])
+    c = Case(b)
+    try:
+        with pytest.raises(RuntimeError):
+            c.eng.ctx.clock_under_load(100, 2)
+        with pytest.raises(RuntimeError):
+            c.eng.ctx.clock_under_load(100000, 3)
+        for wps in (1, 2):
+            r = c.eng.ctx.clock_under_load(100000, wps)
+            assert r["compute_units"] == 256 and r["wavefronts_per_simd"] == wps
+            assert 500.0 < r["shader_mhz"] <= 2400.0 * 1.02
+            assert r["ticks_per_mfma"] >= 32.0 * 0.99                # a 32x32x16 bf16 MFMA occupies its SIMD for 32 ticks
+            if wps == 1:
+                assert r["ticks_per_mfma"] <= 32.0 * 1.5             # (nearly) alone on its SIMD a wavefront issues them back to back
+            assert 0.0 < r["mfma_tflops"] <= 2500.0 * 1.02
+            # 4 SIMDs x 256 CUs, one MFMA (32768 flop) per 32 ticks each
+            from_clock = r["shader_mhz"] * 1e6 * 1024 * 32768 / 32 / 1e12
+            assert r["mfma_tflops"] <= from_clock * 1.05
+    finally:
+        c.close()
