@@ -859,6 +859,10 @@ def main():
                  "frac_mfma": 2 * params * T / (gemm_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
     }
     res["gemm"]["clock"] = mfma_clock(eng.ctx, res["gemm"]["tflops"])
+    # the same fraction against what plain loads stream out of HBM on this device (2 GiB buffer, read after the timed region)
+    stream_gbs = eng.ctx.hbm_read_rate(2 << 30, 4)
+    res["roofline"]["measured_stream_read_GBs"] = round(stream_gbs, 1)
+    res["roofline"]["frac_of_measured_stream_read"] = achieved / stream_gbs
     if not a.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(batch, weights)
     eng.close()

@@ -267,6 +267,14 @@ typedef struct ps_clock_reading {
 } ps_clock_reading;
 ps_status ps_clock_under_load(ps_ctx* ctx, int32_t mfma_per_wavefront, int32_t wavefronts_per_simd, ps_clock_reading* out);
 
+/* Measurement support, not a step of the path: the rate at which plain vector loads stream a
+ * buffer of `bytes` (a multiple of 16 KiB, 1 GiB .. 8 GiB: several times the last-level cache, so
+ * that every pass comes from HBM) -- the ceiling for decode attention, whose cost is the KV bytes
+ * it reads (Sec. 2.2).  The buffer is allocated, filled once, read `passes` (1 .. 16) times
+ * between two HIP events on the context's stream, and freed; *gb_per_s (host) = bytes * passes /
+ * elapsed / 1e9. */
+ps_status ps_hbm_read_rate(ps_ctx* ctx, int64_t bytes, int32_t passes, double* gb_per_s);
+
 /* Ask subsequent steps to copy layer `layer`'s intermediates; taps == NULL switches it off. */
 ps_status ps_set_taps(ps_ctx* ctx, int32_t layer, const ps_taps* taps);
 

@@ -119,6 +119,7 @@ _SIGS = {
     "ps_set_taps": (C.c_int, [_P, C.c_int32, C.POINTER(ps_taps)]),
     "ps_attention_times": (C.c_int, [_P, C.POINTER(C.c_float), C.c_int32, _I32P]),
     "ps_clock_under_load": (C.c_int, [_P, C.c_int32, C.c_int32, C.POINTER(ps_clock_reading)]),
+    "ps_hbm_read_rate": (C.c_int, [_P, C.c_int64, C.c_int32, C.POINTER(C.c_double)]),
     "ps_profile_grid": (C.c_int, [_P, C.POINTER(ps_grid_cell_spec), C.c_int32, C.POINTER(ps_grid_opts), _P, _P,
                                   C.POINTER(ps_grid_cell)]),
 }
@@ -282,6 +283,11 @@ class Context:
         r = ps_clock_reading()
         self._check(lib.ps_clock_under_load(self.handle, mfma_per_wavefront, wavefronts_per_simd, C.byref(r)))
         return {n: getattr(r, n) for n, _ in ps_clock_reading._fields_}
+
+    def hbm_read_rate(self, n_bytes=2 << 30, passes=4):
+        g = C.c_double(0.0)
+        self._check(lib.ps_hbm_read_rate(self.handle, n_bytes, passes, C.byref(g)))
+        return g.value
 
     def set_taps(self, layer, **ptrs):
         if not ptrs:

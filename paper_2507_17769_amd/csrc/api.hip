@@ -945,6 +945,43 @@ extern "C" ps_status ps_clock_under_load(ps_ctx* c, int32_t mfma_per_wavefront, 
     return PS_OK;
 }
 
+extern "C" ps_status ps_hbm_read_rate(ps_ctx* c, int64_t bytes, int32_t passes, double* gb_per_s) {
+    if (!c || !gb_per_s) return fail(c, PS_EINVAL, "ps_hbm_read_rate: null argument");
+    if (c->host_only) return fail(c, PS_ESTATE, "ps_hbm_read_rate: host-only context");
+    if (bytes < (1ll << 30) || bytes > (8ll << 30) || (bytes & 16383)) return fail(c, PS_ERANGE, "ps_hbm_read_rate: bytes must be a multiple of 16 KiB in [1 GiB, 8 GiB]");
+    if (passes < 1 || passes > 16) return fail(c, PS_ERANGE, "ps_hbm_read_rate: passes outside [1, 16]");
+    int dev = 0, cus = 0;
+    HIP_TRY(c, hipGetDevice(&dev));
+    HIP_TRY(c, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    if (cus <= 0) return fail(c, PS_EDEVICE, "ps_hbm_read_rate: the device reports no compute units");
+    const int blocks = 2 * cus;  // eight wavefronts per compute unit
+    uint8_t* buf = nullptr;
+    uint32_t* out = nullptr;
+    ps_status st = PS_OK;
+    if ((st = dev_alloc(c, &buf, (size_t)bytes, "read-rate buffer")) != PS_OK) return st;
+    if ((st = dev_alloc(c, &out, (size_t)blocks * 4 * sizeof(uint32_t), "read-rate output")) != PS_OK) { dev_free(buf); return st; }
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipError_t he = hipSuccess;
+    float ms = 0.f;
+    if ((he = hipEventCreate(&e0)) == hipSuccess && (he = hipEventCreate(&e1)) == hipSuccess &&
+        (he = hipMemsetAsync(buf, 1, (size_t)bytes, c->stream)) == hipSuccess &&
+        (he = launch_stream_read_probe(buf, (size_t)bytes, blocks, out, c->stream)) == hipSuccess &&  // untimed first pass
+        (he = hipEventRecord(e0, c->stream)) == hipSuccess) {
+        for (int i = 0; i < passes && he == hipSuccess; i++) he = launch_stream_read_probe(buf, (size_t)bytes, blocks, out, c->stream);
+        if (he == hipSuccess && (he = hipEventRecord(e1, c->stream)) == hipSuccess && (he = hipStreamSynchronize(c->stream)) == hipSuccess)
+            he = hipEventElapsedTime(&ms, e0, e1);
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (he != hipSuccess) (void)hipDeviceSynchronize();  // nothing may still be reading the buffer when it is freed
+    dev_free(buf);
+    dev_free(out);
+    if (he != hipSuccess) return hip_fail(c, he, "ps_hbm_read_rate");
+    if (!(ms > 0)) return fail(c, PS_EDEVICE, "ps_hbm_read_rate: no time elapsed");
+    *gb_per_s = (double)bytes * passes / (ms * 1e-3) / 1e9;
+    return PS_OK;
+}
+
 // ------------------------------------------------------------------------------ latency grid
 static float median_of(std::vector<float> v) {
     std::sort(v.begin(), v.end());

@@ -115,6 +115,8 @@ hipError_t launch_repack_weight(const bf16_t* w, bf16_t* wp, int K, int N, int i
 hipError_t launch_copy_bytes(const void* src, void* dst, size_t n, hipStream_t st);
 // sink: blocks * 256 floats; ticks: blocks * 2 (shader-clock ticks, wall-clock ticks of wavefront 0 of each block)
 hipError_t launch_mfma_clock_probe(int blocks, int rounds, float* sink, long long* ticks, hipStream_t st);
+// reads the first bytes / 16 KiB whole 16 KiB chunks of buf; out: blocks * 4 words
+hipError_t launch_stream_read_probe(const void* buf, size_t bytes, int blocks, uint32_t* out, hipStream_t st);
 
 struct GemmArgs {
     const bf16_t* A;   // [M][K] activations in operand order (act_offset)

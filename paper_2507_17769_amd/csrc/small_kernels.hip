@@ -379,6 +379,36 @@ hipError_t launch_mfma_clock_probe(int blocks, int rounds, float* sink, long lon
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------
+// Streaming-read probe: every wavefront reads whole 16 KiB chunks (8 loads of 16 B per lane in
+// flight), chunk c going to wavefront c mod n_wavefronts; nothing is written unless the xor of
+// everything read hits one particular value.  The rate over a buffer several times the
+// last-level cache is what plain loads get out of HBM, the ceiling for the KV stream of decode
+// attention.  n_chunks * 16 KiB must not exceed the buffer; out holds one word per wavefront.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void stream_read_probe_kernel(const uint4* __restrict__ buf, long long n_chunks, uint32_t* __restrict__ out) {
+    const int lane = threadIdx.x & 63;
+    const long long wave = ((long long)blockIdx.x * 256 + threadIdx.x) >> 6, n_waves = ((long long)gridDim.x * 256) >> 6;
+    uint32_t acc = 0;
+    for (long long c = wave; c < n_chunks; c += n_waves) {
+        const uint4* p = buf + c * 1024 + lane;
+#pragma unroll
+        for (int j = 0; j < 16; j += 8) {
+            uint4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; u++) v[u] = p[(j + u) * 64];
+#pragma unroll
+            for (int u = 0; u < 8; u++) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+        }
+    }
+    if (acc == 0x12345678u) out[wave] = acc;
+}
+
+hipError_t launch_stream_read_probe(const void* buf, size_t bytes, int blocks, uint32_t* out, hipStream_t st) {
+    hipLaunchKernelGGL(stream_read_probe_kernel, dim3(blocks), dim3(256), 0, st, static_cast<const uint4*>(buf), (long long)(bytes >> 14), out);
+    return hipGetLastError();
+}
+
 hipError_t launch_copy_bytes(const void* src, void* dst, size_t n, hipStream_t st) {
     const size_t n16 = n / 16;
     if (n16 == 0) return hipSuccess;

@@ -62,6 +62,10 @@ def trace_summary(trace_csv, bench_json, workload, command):
         out += ["", f"bench.py's own line from this (profiled) run: ms_per_step {b['ms_per_step']:.4f}, attention kernel by HIP events "
                     f"{rf['avg_launch_ms'] * 1e3:.1f} µs (rocprofv3 average above: {avg:.1f} µs), algorithmic bytes "
                     f"{rf['algorithmic_bytes_per_launch']} → {rf['algorithmic_bytes_per_launch'] / avg / 1e3:.0f} GB/s by the rocprofv3 average."]
+    if "measured_stream_read_GBs" in rf:
+        out += ["", f"Plain loads stream a 2 GiB buffer at {rf['measured_stream_read_GBs']:.0f} GB/s on this device (`ps_hbm_read_rate`, read after the "
+                    f"timed steps): the attention kernel's {rf['achieved']:.0f} GB/s (HIP events) is {100 * rf['frac']:.1f} % of the nominal 8 TB/s and "
+                    f"{100 * rf['frac_of_measured_stream_read']:.1f} % of that rate."]
     g = b.get("gemm", {})
     if "clock" in g:
         out += ["", f"The four weight GEMMs of a step (HIP-event stage times): {g['ms'] * 1e3:.0f} µs, {g['tflops']:.0f} TFLOP/s = "

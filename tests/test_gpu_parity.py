@@ -403,3 +403,17 @@ def test_clock_under_load_reading_is_consistent():
             assert r["mfma_tflops"] <= from_clock * 1.05
     finally:
         c.close()
+
+
+@pytest.mark.gpu
+def test_hbm_read_rate_reading_is_plausible():
+    b = W.custom_batch("tiny", 0, 0, 0, [16])
+    c = Case(b)
+    try:
+        for bad in ((1 << 29, 2), ((1 << 30) + 4096, 2), (1 << 30, 0), (1 << 30, 17)):
+            with pytest.raises(B.PolystepError):
+                c.eng.ctx.hbm_read_rate(*bad)
+        r = c.eng.ctx.hbm_read_rate(1 << 30, 2)
+        assert 1000.0 < r <= 8000.0 * 1.02      # between a fraction of and the nominal HBM rate, GB/s
+    finally:
+        c.close()
