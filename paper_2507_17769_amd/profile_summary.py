@@ -9,6 +9,7 @@ roofline.traffic).
     python -m paper_2507_17769_amd.profile_summary grid   <bench_grid.json> <command> > profiles/<name>.md
     python -m paper_2507_17769_amd.profile_summary sim    <bench_sim.json> <command> > profiles/<name>.md
     python -m paper_2507_17769_amd.profile_summary cfg4   <bench_cfg4.json> <command> > profiles/<name>.md
+    python -m paper_2507_17769_amd.profile_summary mfma   <counter_collection.csv> <workload> <command> > profiles/<name>.md
     python -m paper_2507_17769_amd.profile_summary counters <fetch.csv> <write.csv> <fetch_copy.csv> <write_copy.csv> \
             <workload> <seed> <md out> [--json]
 
@@ -122,6 +123,36 @@ def counters_summary(fetch_csv, write_csv, fetch_copy_csv, write_copy_csv, workl
            "note": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by the plain-copy calibration; written by "
                    "paper_2507_17769_amd/profile_summary.py, see profiles/"}
     return "\n".join(md) + "\n", rec
+
+
+def mfma_summary(counter_csv, workload, command):
+    """Matrix-pipe counters of the projection kernels: MFMA-busy cycles against the cycles of the dispatch."""
+    per = collections.defaultdict(lambda: collections.defaultdict(list))
+    dur = collections.defaultdict(dict)
+    for r in csv.DictReader(open(counter_csv)):
+        k = short(r["Kernel_Name"])
+        if not k.startswith("gemm_"):
+            continue
+        key = (k, int(r["Grid_Size"]) // max(1, int(r["Workgroup_Size"])))
+        per[key][r["Counter_Name"]].append(float(r["Counter_Value"]))
+        dur[key][r["Dispatch_Id"]] = (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3
+    out = [f"# rocprofv3 matrix-pipe counters of the projection GEMMs — bench.py --workload {workload}", "",
+           "Command (`export TMPDIR=/tmp` first):", "", f"    {command}", "",
+           "Per kernel and grid size, averaged over its dispatches (kernels run one at a time under counter collection).  "
+           "`SQ_VALU_MFMA_BUSY_CYCLES` is summed over the 1024 SIMDs, `GRBM_GUI_ACTIVE` over the 8 XCDs; the latter runs from the "
+           "moment the dispatch is taken up to its end, so for a kernel of tens of microseconds it is more than duration x clock and "
+           "busy / active understates the pipes.  Busy cycles per SIMD against duration x 2400 MHz is the fraction of the nominal "
+           "peak, and agrees with the flop the counter saw (`SQ_INSTS_VALU_MFMA_MOPS_BF16` x 512) over the duration.", "",
+           "| kernel | blocks | dispatches | µs | MFMA busy cycles per SIMD | active cycles per XCD | busy / active % | busy / (µs x 2400 MHz) % | counted GFLOP | TFLOP/s | % of 2.5 PFLOP/s |",
+           "|---|---|---|---|---|---|---|---|---|---|---|"]
+    for key in sorted(per, key=lambda k: -sum(dur[k].values())):
+        c = {n: sum(v) / len(v) for n, v in per[key].items()}
+        us = sum(dur[key].values()) / len(dur[key])
+        busy, active = c["SQ_VALU_MFMA_BUSY_CYCLES"] / 1024, c["GRBM_GUI_ACTIVE"] / 8
+        flop = c["SQ_INSTS_VALU_MFMA_MOPS_BF16"] * 512
+        out.append(f"| {key[0]} | {key[1]} | {len(dur[key])} | {us:.1f} | {busy:.0f} | {active:.0f} | {100 * busy / active:.1f} | "
+                   f"{100 * busy / (us * 2400):.1f} | {flop / 1e9:.1f} | {flop / us / 1e6:.0f} | {100 * flop / us / 1e6 / 2500:.1f} |")
+    return "\n".join(out) + "\n"
 
 
 def grid_summary(grid_json, command):
@@ -343,6 +374,9 @@ def sim_summary(sim_json, command):
 
 
 def main(argv):
+    if len(argv) >= 5 and argv[1] == "mfma":
+        sys.stdout.write(mfma_summary(argv[2], argv[3], argv[4]))
+        return 0
     if len(argv) >= 4 and argv[1] == "cfg4":
         sys.stdout.write(cfg4_summary(argv[2], argv[3]))
         return 0
