@@ -8,19 +8,29 @@
 namespace ps {
 
 // ---------------------------------------------------------------------------- RMSNorm
-// One 256-thread block per token row: out = x * rsqrt(mean(x^2) + eps) * gain, fp32 math.
+// One block per token row, one thread per 8 consecutive elements (H <= 8192): out = x * rsqrt(mean(x^2) + eps) * gain,
+// fp32 math, the row held in registers between the sum and the scaling.
+// sum over the block of one value per thread; red: one float per wavefront
+__device__ __forceinline__ float block_sum(float v, float* red) {
+    v = wave_sum(v);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float tot = 0.f;
+    for (int w = 0; w < (int)(blockDim.x >> 6); w++) tot += red[w];
+    return tot;
+}
+
 template <bool X_F32>
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const void* __restrict__ xin, const bf16_t* __restrict__ gain,
-                                                      bf16_t* __restrict__ out, int H, float eps,
-                                                      const int32_t* __restrict__ src_rows) {
+__global__ __launch_bounds__(1024) void rmsnorm_kernel(const void* __restrict__ xin, const bf16_t* __restrict__ gain,
+                                                       bf16_t* __restrict__ out, int H, float eps,
+                                                       const int32_t* __restrict__ src_rows) {
     const int orow = blockIdx.x;                            // output row
     const int row = src_rows ? src_rows[orow] : orow;       // input row (the head normalises selected rows only)
-    const int tid = threadIdx.x;
-    __shared__ float red[4];
-    float ss = 0.f;
-    // every thread owns groups of 8 consecutive elements: tid*8 + k*2048
-    for (int c = tid * 8; c < H; c += 2048) {
-        float v[8];
+    const int c = threadIdx.x * 8;
+    __shared__ float red[16];
+    float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    uint4 gw = uint4{0u, 0u, 0u, 0u};
+    if (c < H) {
         if (X_F32) {
             const float4* p = reinterpret_cast<const float4*>(static_cast<const float*>(xin) + (size_t)row * H + c);
             float4 a = p[0], b = p[1];
@@ -30,26 +40,13 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const void* __restrict__ x
             v[0] = bf16_lo(w.x); v[1] = bf16_hi(w.x); v[2] = bf16_lo(w.y); v[3] = bf16_hi(w.y);
             v[4] = bf16_lo(w.z); v[5] = bf16_hi(w.z); v[6] = bf16_lo(w.w); v[7] = bf16_hi(w.w);
         }
-#pragma unroll
-        for (int i = 0; i < 8; i++) ss += v[i] * v[i];
+        gw = ldg16(gain + c);
     }
-    ss = wave_sum(ss);
-    if ((tid & 63) == 0) red[tid >> 6] = ss;
-    __syncthreads();
-    const float tot = red[0] + red[1] + red[2] + red[3];
-    const float r = 1.0f / sqrtf(tot / (float)H + eps);
-    for (int c = tid * 8; c < H; c += 2048) {
-        float v[8];
-        if (X_F32) {
-            const float4* p = reinterpret_cast<const float4*>(static_cast<const float*>(xin) + (size_t)row * H + c);
-            float4 a = p[0], b = p[1];
-            v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-        } else {
-            uint4 w = ldg16(static_cast<const bf16_t*>(xin) + (size_t)row * H + c);
-            v[0] = bf16_lo(w.x); v[1] = bf16_hi(w.x); v[2] = bf16_lo(w.y); v[3] = bf16_hi(w.y);
-            v[4] = bf16_lo(w.z); v[5] = bf16_hi(w.z); v[6] = bf16_lo(w.w); v[7] = bf16_hi(w.w);
-        }
-        uint4 gw = ldg16(gain + c);
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; i++) ss += v[i] * v[i];
+    const float r = 1.0f / sqrtf(block_sum(ss, red) / (float)H + eps);
+    if (c < H) {
         float g[8] = {bf16_lo(gw.x), bf16_hi(gw.x), bf16_lo(gw.y), bf16_hi(gw.y),
                       bf16_lo(gw.z), bf16_hi(gw.z), bf16_lo(gw.w), bf16_hi(gw.w)};
         uint4 o;
@@ -64,10 +61,12 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const void* __restrict__ x
 hipError_t launch_rmsnorm(const void* x, bool x_is_f32, const bf16_t* gain, bf16_t* out, int T, int H, float eps,
                           hipStream_t st, const int32_t* src_rows) {
     if (T <= 0) return hipSuccess;
+    if (H > 8192 || H % 8) return hipErrorInvalidValue;
+    const int nt = ((H / 8 + 63) / 64) * 64;
     if (x_is_f32)
-        hipLaunchKernelGGL(rmsnorm_kernel<true>, dim3(T), dim3(256), 0, st, x, gain, out, H, eps, src_rows);
+        hipLaunchKernelGGL(rmsnorm_kernel<true>, dim3(T), dim3(nt), 0, st, x, gain, out, H, eps, src_rows);
     else
-        hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3(T), dim3(256), 0, st, x, gain, out, H, eps, src_rows);
+        hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3(T), dim3(nt), 0, st, x, gain, out, H, eps, src_rows);
     return hipGetLastError();
 }
 
@@ -229,91 +228,83 @@ hipError_t launch_kv_copy(bool to_pool, bf16_t* pool_slot, const int32_t* slots_
 }
 
 // ------------------------------------------------- split reduce + residual + RMSNorm
-// One 256-thread block per token row.  x = resid + sum_s partials[s]; optionally stored as fp32
-// and/or bf16; optionally followed by RMSNorm (x * rsqrt(mean(x^2) + eps) * gain) stored as bf16.
-// The row stays in registers between the two phases (H <= 8192).
+// One block per token row, one thread per 8 consecutive elements (H <= 8192).  x = resid + sum_s partials[s];
+// optionally stored as fp32 and/or bf16; optionally followed by RMSNorm (x * rsqrt(mean(x^2) + eps) * gain) stored
+// as bf16.  The row stays in registers between the two phases.
 template <bool RESID_F32>
-__global__ __launch_bounds__(256) void reduce_add_norm_kernel(ReduceAddNormArgs a) {
-    const int row = blockIdx.x, tid = threadIdx.x;
-    const int H = a.H;
+__global__ __launch_bounds__(1024) void reduce_add_norm_kernel(ReduceAddNormArgs a) {
+    const int row = blockIdx.x;
+    const int H = a.H, c = threadIdx.x * 8;
     const size_t split_stride = (size_t)a.T * H;
-    __shared__ float red[4];
-    float v[4][8];
-    float ss = 0.f;
+    __shared__ float red[16];
+    float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    uint4 gw = uint4{0u, 0u, 0u, 0u};
+    if (c < H) {
+        // all loads are issued before the first add (n_splits <= 8)
+        float4 q0[8], q1[8];
 #pragma unroll
-    for (int k = 0; k < 4; k++) {
-        const int c = tid * 8 + k * 2048;
-        if (c < H) {
-            if (RESID_F32) {
-                const float4* p = reinterpret_cast<const float4*>(static_cast<const float*>(a.resid) + (size_t)row * H + c);
-                const float4 x0 = p[0], x1 = p[1];
-                v[k][0] = x0.x; v[k][1] = x0.y; v[k][2] = x0.z; v[k][3] = x0.w;
-                v[k][4] = x1.x; v[k][5] = x1.y; v[k][6] = x1.z; v[k][7] = x1.w;
-            } else {
-                const uint4 w = ldg16(static_cast<const bf16_t*>(a.resid) + (size_t)row * H + c);
-                v[k][0] = bf16_lo(w.x); v[k][1] = bf16_hi(w.x); v[k][2] = bf16_lo(w.y); v[k][3] = bf16_hi(w.y);
-                v[k][4] = bf16_lo(w.z); v[k][5] = bf16_hi(w.z); v[k][6] = bf16_lo(w.w); v[k][7] = bf16_hi(w.w);
+        for (int s = 0; s < 8; s++)
+            if (s < a.n_splits) {
+                const float4* p = reinterpret_cast<const float4*>(a.partials + s * split_stride + (size_t)row * H + c);
+                q0[s] = p[0];
+                q1[s] = p[1];
             }
-            // all split loads are issued before the first add (n_splits <= 8)
-            float4 q0[8], q1[8];
+        if (a.gain) gw = ldg16(a.gain + c);
+        if (RESID_F32) {
+            const float4* p = reinterpret_cast<const float4*>(static_cast<const float*>(a.resid) + (size_t)row * H + c);
+            const float4 x0 = p[0], x1 = p[1];
+            v[0] = x0.x; v[1] = x0.y; v[2] = x0.z; v[3] = x0.w;
+            v[4] = x1.x; v[5] = x1.y; v[6] = x1.z; v[7] = x1.w;
+        } else {
+            const uint4 w = ldg16(static_cast<const bf16_t*>(a.resid) + (size_t)row * H + c);
+            v[0] = bf16_lo(w.x); v[1] = bf16_hi(w.x); v[2] = bf16_lo(w.y); v[3] = bf16_hi(w.y);
+            v[4] = bf16_lo(w.z); v[5] = bf16_hi(w.z); v[6] = bf16_lo(w.w); v[7] = bf16_hi(w.w);
+        }
 #pragma unroll
-            for (int s = 0; s < 8; s++)
-                if (s < a.n_splits) {
-                    const float4* p = reinterpret_cast<const float4*>(a.partials + s * split_stride + (size_t)row * H + c);
-                    q0[s] = p[0];
-                    q1[s] = p[1];
-                }
-#pragma unroll
-            for (int s = 0; s < 8; s++)
-                if (s < a.n_splits) {
-                    v[k][0] += q0[s].x; v[k][1] += q0[s].y; v[k][2] += q0[s].z; v[k][3] += q0[s].w;
-                    v[k][4] += q1[s].x; v[k][5] += q1[s].y; v[k][6] += q1[s].z; v[k][7] += q1[s].w;
-                }
-            if (a.x_f32) {
-                float4* o = reinterpret_cast<float4*>(a.x_f32 + (size_t)row * H + c);
-                o[0] = float4{v[k][0], v[k][1], v[k][2], v[k][3]};
-                o[1] = float4{v[k][4], v[k][5], v[k][6], v[k][7]};
+        for (int s = 0; s < 8; s++)
+            if (s < a.n_splits) {
+                v[0] += q0[s].x; v[1] += q0[s].y; v[2] += q0[s].z; v[3] += q0[s].w;
+                v[4] += q1[s].x; v[5] += q1[s].y; v[6] += q1[s].z; v[7] += q1[s].w;
             }
-            if (a.x_bf16) {
-                uint4 o;
-                o.x = pack_bf16(v[k][0], v[k][1]); o.y = pack_bf16(v[k][2], v[k][3]);
-                o.z = pack_bf16(v[k][4], v[k][5]); o.w = pack_bf16(v[k][6], v[k][7]);
-                *reinterpret_cast<uint4*>(a.x_bf16 + (size_t)row * H + c) = o;
-            }
-#pragma unroll
-            for (int i = 0; i < 8; i++) ss += v[k][i] * v[k][i];
+        if (a.x_f32) {
+            float4* o = reinterpret_cast<float4*>(a.x_f32 + (size_t)row * H + c);
+            o[0] = float4{v[0], v[1], v[2], v[3]};
+            o[1] = float4{v[4], v[5], v[6], v[7]};
+        }
+        if (a.x_bf16) {
+            uint4 o;
+            o.x = pack_bf16(v[0], v[1]); o.y = pack_bf16(v[2], v[3]);
+            o.z = pack_bf16(v[4], v[5]); o.w = pack_bf16(v[6], v[7]);
+            *reinterpret_cast<uint4*>(a.x_bf16 + (size_t)row * H + c) = o;
         }
     }
     if (!a.gain) return;
-    ss = wave_sum(ss);
-    if ((tid & 63) == 0) red[tid >> 6] = ss;
-    __syncthreads();
-    const float r = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)H + a.eps);
+    float ss = 0.f;
 #pragma unroll
-    for (int k = 0; k < 4; k++) {
-        const int c = tid * 8 + k * 2048;
-        if (c < H) {
-            const uint4 gw = ldg16(a.gain + c);
-            uint4 o;
-            o.x = pack_bf16(v[k][0] * r * bf16_lo(gw.x), v[k][1] * r * bf16_hi(gw.x));
-            o.y = pack_bf16(v[k][2] * r * bf16_lo(gw.y), v[k][3] * r * bf16_hi(gw.y));
-            o.z = pack_bf16(v[k][4] * r * bf16_lo(gw.z), v[k][5] * r * bf16_hi(gw.z));
-            o.w = pack_bf16(v[k][6] * r * bf16_lo(gw.w), v[k][7] * r * bf16_hi(gw.w));
-            *reinterpret_cast<uint4*>(a.xn + act_offset(row, c, H)) = o;
-        }
+    for (int i = 0; i < 8; i++) ss += v[i] * v[i];
+    const float r = 1.0f / sqrtf(block_sum(ss, red) / (float)H + a.eps);
+    if (c < H) {
+        uint4 o;
+        o.x = pack_bf16(v[0] * r * bf16_lo(gw.x), v[1] * r * bf16_hi(gw.x));
+        o.y = pack_bf16(v[2] * r * bf16_lo(gw.y), v[3] * r * bf16_hi(gw.y));
+        o.z = pack_bf16(v[4] * r * bf16_lo(gw.z), v[5] * r * bf16_hi(gw.z));
+        o.w = pack_bf16(v[6] * r * bf16_lo(gw.w), v[7] * r * bf16_hi(gw.w));
+        *reinterpret_cast<uint4*>(a.xn + act_offset(row, c, H)) = o;
     }
 }
 
 hipError_t launch_reduce_add_norm(const ReduceAddNormArgs& a, hipStream_t st) {
     if (a.T <= 0) return hipSuccess;
     if (a.H > 8192 || a.H % 8 || a.n_splits > 8) return hipErrorInvalidValue;
+    const int nt = ((a.H / 8 + 63) / 64) * 64;
     if (a.resid_f32)
-        hipLaunchKernelGGL(reduce_add_norm_kernel<true>, dim3(a.T), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(reduce_add_norm_kernel<true>, dim3(a.T), dim3(nt), 0, st, a);
     else
-        hipLaunchKernelGGL(reduce_add_norm_kernel<false>, dim3(a.T), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(reduce_add_norm_kernel<false>, dim3(a.T), dim3(nt), 0, st, a);
     return hipGetLastError();
 }
 
+// Device-to-device copy of n bytes (n a multiple of 16, both pointers 16-byte aligned).
 __global__ __launch_bounds__(256) void copy_bytes_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
     for (size_t i = blockIdx.x * (size_t)256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
 }
@@ -335,7 +326,6 @@ hipError_t launch_untile(const bf16_t* src, bf16_t* dst, int M, int K, hipStream
     return hipGetLastError();
 }
 
-// Device-to-device copy of n bytes (n a multiple of 16, both pointers 16-byte aligned).
 // ------------------------------------------------------------------------------------------
 // Clock-under-load probe.  Every wavefront issues `rounds` x 4 independent 32x32x16 bf16 MFMAs on
 // operands made from a hash of its lane (finite, mixed signs and exponents) and reports how many
