@@ -126,59 +126,79 @@ hipError_t launch_argmax_rows(const float* x, int M, int N, int32_t* out, hipStr
 }
 
 // --------------------------------------------------------------- rotary + KV append
-// grid (T, n_q + 2 n_kv), 64 threads.  Thread j < d/2 owns the pair (j, j + d/2).
+// grid (T, ceil((n_q + 2 n_kv) / heads per block)), 256 threads.  A head takes d/8 threads; a thread owns the four
+// rotation pairs (j, j + d/2), j = 4 * (its index in the head) .. + 3, and moves them as 16-byte pieces.
 // Input is the fp32 QKV projection as n_splits partial sums [n_splits][T][(n_q + 2 n_kv) d],
 // added up here; every value is rounded to bf16 exactly once, after the rotation: query heads
 // go to q_out [T][n_q][d], key heads (rotated) and value heads to their cache slot.  cs is the
 // fp64-built table [position][d/2] of (cos, sin).
-__global__ __launch_bounds__(64) void rope_append_kernel(const float* __restrict__ qkv, int n_splits, size_t split_stride,
-                                                         bf16_t* __restrict__ q_out, int n_q, int n_kv, int d,
-                                                         const int32_t* __restrict__ positions,
-                                                         const int32_t* __restrict__ slots,
-                                                         const float2* __restrict__ cs, bf16_t* __restrict__ pool) {
+__global__ __launch_bounds__(256) void rope_append_kernel(const float* __restrict__ qkv, int n_splits, size_t split_stride,
+                                                          bf16_t* __restrict__ q_out, int n_q, int n_kv, int d,
+                                                          const int32_t* __restrict__ positions,
+                                                          const int32_t* __restrict__ slots,
+                                                          const float2* __restrict__ cs, bf16_t* __restrict__ pool) {
     const int t = blockIdx.x;
-    const int hh = blockIdx.y;
-    const int j = threadIdx.x;
+    const int tph = d >> 3;                       // threads per head
+    const int hh = blockIdx.y * (256 / tph) + threadIdx.x / tph;
+    if (hh >= n_q + 2 * n_kv) return;
+    const int j = 4 * (threadIdx.x % tph);
     const int half = d >> 1;
-    if (j >= half) return;
     const int ld = (n_q + 2 * n_kv) * d;
     const float* row = qkv + (size_t)t * ld + (size_t)hh * d;
     // all split loads are issued before the first add (n_splits <= 8)
-    float plo[8], phi[8];
+    float4 plo[8], phi[8];
 #pragma unroll
     for (int s = 0; s < 8; s++)
         if (s < n_splits) {
-            plo[s] = row[s * split_stride + j];
-            phi[s] = row[s * split_stride + j + half];
+            plo[s] = *reinterpret_cast<const float4*>(row + s * split_stride + j);
+            phi[s] = *reinterpret_cast<const float4*>(row + s * split_stride + j + half);
         }
-    float lo = 0.f, hi = 0.f;
+    float lo[4] = {0.f, 0.f, 0.f, 0.f}, hi[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s = 0; s < 8; s++)
         if (s < n_splits) {
-            lo += plo[s];
-            hi += phi[s];
+            lo[0] += plo[s].x; lo[1] += plo[s].y; lo[2] += plo[s].z; lo[3] += plo[s].w;
+            hi[0] += phi[s].x; hi[1] += phi[s].y; hi[2] += phi[s].z; hi[3] += phi[s].w;
         }
+    bf16_t blo[4], bhi[4];
     if (hh < n_q + n_kv) {
-        const float2 c = cs[(size_t)positions[t] * half + j];
-        const bf16_t blo = f32_to_bf16(lo * c.x - hi * c.y);
-        const bf16_t bhi = f32_to_bf16(hi * c.x + lo * c.y);
-        if (hh < n_q) {
-            bf16_t* qr = q_out + ((size_t)t * n_q + hh) * d;
-            qr[j] = blo;
-            qr[j + half] = bhi;
-        } else {
-            const int h = hh - n_q;
-            const int slot = slots[t];
-            bf16_t* kc = pool + (((size_t)(slot >> 4) * n_kv + h) * 2 + 0) * (size_t)(16 * d);
-            kc[k_elem_offset(slot & 15, j)] = blo;
-            kc[k_elem_offset(slot & 15, j + half)] = bhi;
+        const float4* cp = reinterpret_cast<const float4*>(cs + (size_t)positions[t] * half + j);
+        const float4 c01 = cp[0], c23 = cp[1];    // (cos, sin) of pairs j, j+1 and j+2, j+3
+        const float co[4] = {c01.x, c01.z, c23.x, c23.z}, si[4] = {c01.y, c01.w, c23.y, c23.w};
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            blo[e] = f32_to_bf16(lo[e] * co[e] - hi[e] * si[e]);
+            bhi[e] = f32_to_bf16(hi[e] * co[e] + lo[e] * si[e]);
         }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            blo[e] = f32_to_bf16(lo[e]);
+            bhi[e] = f32_to_bf16(hi[e]);
+        }
+    }
+    const uint2 plo4 = uint2{(uint32_t)blo[0] | ((uint32_t)blo[1] << 16), (uint32_t)blo[2] | ((uint32_t)blo[3] << 16)};
+    const uint2 phi4 = uint2{(uint32_t)bhi[0] | ((uint32_t)bhi[1] << 16), (uint32_t)bhi[2] | ((uint32_t)bhi[3] << 16)};
+    if (hh < n_q) {
+        bf16_t* qr = q_out + ((size_t)t * n_q + hh) * d;
+        *reinterpret_cast<uint2*>(qr + j) = plo4;
+        *reinterpret_cast<uint2*>(qr + j + half) = phi4;
+    } else if (hh < n_q + n_kv) {
+        const int h = hh - n_q;
+        const int slot = slots[t];
+        bf16_t* kc = pool + (((size_t)(slot >> 4) * n_kv + h) * 2 + 0) * (size_t)(16 * d);
+        // j is a multiple of 4: the four elements sit in one 8-element group of the key chunk
+        *reinterpret_cast<uint2*>(kc + k_elem_offset(slot & 15, j)) = plo4;
+        *reinterpret_cast<uint2*>(kc + k_elem_offset(slot & 15, j + half)) = phi4;
     } else {
         const int h = hh - n_q - n_kv;
         const int slot = slots[t];
         bf16_t* vc = pool + (((size_t)(slot >> 4) * n_kv + h) * 2 + 1) * (size_t)(16 * d);
-        vc[v_elem_offset(slot & 15, j)] = f32_to_bf16(lo);
-        vc[v_elem_offset(slot & 15, j + half)] = f32_to_bf16(hi);
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+            vc[v_elem_offset(slot & 15, j + e)] = blo[e];
+            vc[v_elem_offset(slot & 15, j + half + e)] = bhi[e];
+        }
     }
 }
 
@@ -186,10 +206,11 @@ hipError_t launch_rope_append(const float* qkv, int n_splits, bf16_t* q_out, int
                               const int32_t* positions, const int32_t* slots, const float* rope_cs, bf16_t* pool_slot,
                               hipStream_t st) {
     if (T <= 0) return hipSuccess;
-    if (n_splits > 8) return hipErrorInvalidValue;
+    if (n_splits > 8 || d % 8 || d > 2048) return hipErrorInvalidValue;
     const size_t split_stride = (size_t)T * (n_q + 2 * n_kv) * d;
-    hipLaunchKernelGGL(rope_append_kernel, dim3(T, n_q + 2 * n_kv), dim3(64), 0, st, qkv, n_splits, split_stride, q_out,
-                       n_q, n_kv, d,
+    const int heads_per_block = 256 / (d / 8);
+    hipLaunchKernelGGL(rope_append_kernel, dim3(T, (n_q + 2 * n_kv + heads_per_block - 1) / heads_per_block), dim3(256), 0, st, qkv,
+                       n_splits, split_stride, q_out, n_q, n_kv, d,
                        positions, slots, reinterpret_cast<const float2*>(rope_cs), pool_slot);
     return hipGetLastError();
 }
