@@ -766,7 +766,11 @@ static ps_status step_impl(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const 
         a.groups = reinterpret_cast<const MergeGroup*>(db + ml.groups);
         a.n_groups = (int)p.groups.size();
         a.max_splits = 0;
-        for (const MergeGroup& mg : p.groups) a.max_splits = std::max(a.max_splits, (int)mg.n_splits);
+        a.max_merge_rows = 0;
+        for (const MergeGroup& mg : p.groups) {
+            a.max_splits = std::max(a.max_splits, (int)mg.n_splits);
+            a.max_merge_rows = std::max(a.max_merge_rows, (int)mg.n_tok * (d.n_q_heads / d.n_kv_heads));
+        }
         a.part_o = c->part_o; a.part_ml = c->part_ml; a.out = c->ws_attn;
         a.n_q = d.n_q_heads; a.n_kv = d.n_kv_heads; a.d = d.head_dim;
         const bool time_attn = c->opt_time_attention > 0 && c->attn_ev_count < ATTN_EV_PAIRS &&

@@ -19,6 +19,8 @@
 // kernel combines them.
 #include "ps_device.h"
 
+#include <algorithm>
+
 namespace ps {
 
 constexpr float NEG_BIG = -1.0e30f;
@@ -286,73 +288,76 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 }
 
 // Combine split partials of one query tile: out = sum_j 2^(m_j - M) O_j / sum_j 2^(m_j - M) l_j.
-// One block per merge group.  Each lane owns float4 pieces of the valid rows, 64 pieces per pass; the block's
-// wavefronts share the splits (wavefront w takes splits w, w + NW, ...: a sequence cut over hundreds of workers would
-// otherwise be merged by one wavefront, split after split), each reduces its share to (max, sum, O) against its own
-// maximum, and wavefront 0 combines the NW results through LDS in a fixed order.
+// One block per merge group.  A tile is n_rows x D/4 float4 pieces, 64 pieces per pass and wavefront.  The block's
+// wavefronts form a (pass, split) grid: wavefront (wp, ws) takes the passes wp, wp + NWP, ... and of each the splits
+// ws, ws + NWS, ...  Passes are independent, so a 16-row prefill tile (eight passes) costs the latency of one;
+// the NWS wavefronts of a pass (a sequence cut over hundreds of workers would otherwise be merged split after split)
+// each reduce their share to (max, sum, O) against their own maximum, and the first of them combines the NWS results
+// through LDS in a fixed order.
 constexpr int MERGE_MAX_WAVES = 16;
 
 template <int D, int G>
-__global__ __launch_bounds__(64 * MERGE_MAX_WAVES) void attn_merge_kernel(AttnArgs a) {
+__global__ __launch_bounds__(64 * MERGE_MAX_WAVES) void attn_merge_kernel(AttnArgs a, int NWS) {
     __shared__ float4 s_acc[MERGE_MAX_WAVES][64];
     __shared__ float2 s_ml[MERGE_MAX_WAVES][64];
     const MergeGroup mg = a.groups[blockIdx.x];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, NW = blockDim.x >> 6;
+    const int NWP = NW / NWS, ws = wave % NWS, wp = wave / NWS;
     const int n_rows = mg.n_tok * G;  // valid rows are the first n_tok * G of the tile
     const int n_items = n_rows * (D / 4);
-    for (int c0 = 0; c0 < n_items; c0 += 64) {
-        const int c = c0 + lane;
+    for (int c0 = 0; c0 < n_items; c0 += 64 * NWP) {   // the same trip count for every wavefront: the barriers below
+        const int c = c0 + wp * 64 + lane;
         const bool live = c < n_items;
         const int r = live ? c / (D / 4) : 0, col = live ? (c % (D / 4)) * 4 : 0;
         // this wavefront's splits, eight at a time with all loads of a batch issued together
         float M = NEG_BIG;
-        for (int j0 = wave; j0 < mg.n_splits; j0 += 8 * NW) {
+        for (int j0 = ws; j0 < mg.n_splits; j0 += 8 * NWS) {
             float mv[8];
 #pragma unroll
             for (int j = 0; j < 8; j++)
-                if (j0 + j * NW < mg.n_splits) mv[j] = a.part_ml[((size_t)(mg.first_slot + (j0 + j * NW) * mg.stride) * 16 + r) * 2];
+                if (j0 + j * NWS < mg.n_splits) mv[j] = a.part_ml[((size_t)(mg.first_slot + (j0 + j * NWS) * mg.stride) * 16 + r) * 2];
 #pragma unroll
             for (int j = 0; j < 8; j++)
-                if (j0 + j * NW < mg.n_splits) M = fmaxf(M, mv[j]);
+                if (j0 + j * NWS < mg.n_splits) M = fmaxf(M, mv[j]);
         }
         float4 acc = {0.f, 0.f, 0.f, 0.f};
         float L = 0.f;
-        for (int j0 = wave; j0 < mg.n_splits; j0 += 8 * NW) {
+        for (int j0 = ws; j0 < mg.n_splits; j0 += 8 * NWS) {
             float2 ml[8];
             float4 v[8];
 #pragma unroll
             for (int j = 0; j < 8; j++)
-                if (j0 + j * NW < mg.n_splits) {
-                    const size_t row = (size_t)(mg.first_slot + (j0 + j * NW) * mg.stride) * 16 + r;
+                if (j0 + j * NWS < mg.n_splits) {
+                    const size_t row = (size_t)(mg.first_slot + (j0 + j * NWS) * mg.stride) * 16 + r;
                     ml[j] = *reinterpret_cast<const float2*>(a.part_ml + row * 2);
                     v[j] = *reinterpret_cast<const float4*>(a.part_o + row * D + col);
                 }
 #pragma unroll
             for (int j = 0; j < 8; j++)
-                if (j0 + j * NW < mg.n_splits) {
+                if (j0 + j * NWS < mg.n_splits) {
                     const float w = __builtin_amdgcn_exp2f(ml[j].x - M);
                     L += w * ml[j].y;
                     acc.x += w * v[j].x; acc.y += w * v[j].y; acc.z += w * v[j].z; acc.w += w * v[j].w;
                 }
         }
-        if (NW > 1) {
+        if (NWS > 1) {
             s_acc[wave][lane] = acc;
             s_ml[wave][lane] = float2{M, L};
             __syncthreads();
-            if (wave == 0) {
-                for (int w = 1; w < NW; w++) M = fmaxf(M, s_ml[w][lane].x);
+            if (ws == 0) {
+                for (int w = 1; w < NWS; w++) M = fmaxf(M, s_ml[wave + w][lane].x);
                 acc = float4{0.f, 0.f, 0.f, 0.f};
                 L = 0.f;
-                for (int w = 0; w < NW; w++) {
-                    const float2 q = s_ml[w][lane];
-                    const float4 v = s_acc[w][lane];
+                for (int w = 0; w < NWS; w++) {
+                    const float2 q = s_ml[wave + w][lane];
+                    const float4 v = s_acc[wave + w][lane];
                     const float f = __builtin_amdgcn_exp2f(q.x - M);  // a wavefront without splits holds (NEG_BIG, 0, 0): f * 0
                     L += f * q.y;
                     acc.x += f * v.x; acc.y += f * v.y; acc.z += f * v.z; acc.w += f * v.w;
                 }
             }
         }
-        if (wave == 0 && live) {
+        if (ws == 0 && live) {
             const float inv = 1.0f / L;
             const int head = mg.kv_head * G + r % G;
             uint2 w;
@@ -360,7 +365,7 @@ __global__ __launch_bounds__(64 * MERGE_MAX_WAVES) void attn_merge_kernel(AttnAr
             w.y = pack_bf16(acc.z * inv, acc.w * inv);
             *reinterpret_cast<uint2*>(a.out + act_offset(mg.tok0 + r / G, head * D + col, a.n_q * D)) = w;
         }
-        if (NW > 1) __syncthreads();  // the next pass overwrites the LDS slots
+        if (NWS > 1) __syncthreads();  // the next pass overwrites the LDS slots
     }
 }
 
@@ -373,10 +378,14 @@ static hipError_t launch_dg(const AttnArgs& a, hipStream_t st) {
     hipError_t e = hipGetLastError();
     if (a.ev_end) (void)hipEventRecord(a.ev_end, st);
     if (e != hipSuccess || a.n_groups == 0) return e;
-    // wavefronts per merge block: about eight splits each (one batch of loads), a power of two up to 16
-    int nw = 1;
-    while (nw < MERGE_MAX_WAVES && nw * 8 < a.max_splits) nw *= 2;
-    hipLaunchKernelGGL((attn_merge_kernel<D, G>), dim3(a.n_groups), dim3(64 * nw), 0, st, a);
+    // wavefronts that share a pass's splits: about eight splits each (one batch of loads), a power of two up to 16;
+    // the rest of the block's 16 wavefronts take different passes, as many as the largest tile has
+    int nws = 1;
+    while (nws < MERGE_MAX_WAVES && nws * 8 < a.max_splits) nws *= 2;
+    const int passes = (std::max(1, a.max_merge_rows) * (D / 4) + 63) / 64;
+    int nwp = 1;
+    while (nwp * 2 * nws <= MERGE_MAX_WAVES && nwp < passes) nwp *= 2;
+    hipLaunchKernelGGL((attn_merge_kernel<D, G>), dim3(a.n_groups), dim3(64 * nws * nwp), 0, st, a, nws);
     return hipGetLastError();
 }
 

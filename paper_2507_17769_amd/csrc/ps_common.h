@@ -145,6 +145,7 @@ struct AttnArgs {
     const MergeGroup* groups;
     int n_groups;
     int max_splits;    // largest n_splits of any group: sizes the merge kernel's blocks
+    int max_merge_rows;   // largest n_tok * G over the merge groups (rows of a tile that are merged)
     float* part_o;     // [slot][16][d]
     float* part_ml;    // [slot][16][2]
     bf16_t* out;       // [T][n_q * d] in operand order (act_offset)
