@@ -174,7 +174,7 @@ ps_status ps_kv_release(ps_ctx* ctx, int64_t req_id);
 int32_t ps_kv_free_pages(const ps_ctx* ctx);
 
 /* Store / fetch keys and values of logical positions pos0 .. pos0+n-1 of `seq` in KV layer
- * slot `layer mod n_kv_layers`.  k and v are device bf16 [n][n_kv_heads][head_dim]; keys
+ * slot `layer mod n_kv_layers`.  k and v are device bf16 [n][n_kv_heads][head_dim], 16-byte aligned; keys
  * are stored as given (the cache holds keys after rotation).  Only seq->page_table and
  * n_pages are used.  Used to load a cached prefix, to snapshot, and as the payload of a
  * prefill->decode hand-off (Sec. 2.4).  Errors: PS_ERANGE (position or page id). */

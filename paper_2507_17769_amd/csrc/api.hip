@@ -488,6 +488,7 @@ static ps_status kv_copy(ps_ctx* c, bool to_pool, int32_t layer, const ps_seq* s
     if (layer < 0 || layer >= c->desc.n_layers) return fail(c, PS_ERANGE, std::string(name) + ": layer index out of range");
     if (n == 0) return PS_OK;
     if (!k || !v) return fail(c, PS_EINVAL, std::string(name) + ": null k or v");
+    if ((reinterpret_cast<uintptr_t>(k) | reinterpret_cast<uintptr_t>(v)) & 15) return fail(c, PS_EINVAL, std::string(name) + ": k and v must be 16-byte aligned");
     if (n < 0 || pos0 < 0 || (int64_t)pos0 + n > (int64_t)seq->n_pages * PS_PAGE_SIZE)
         return fail(c, PS_ERANGE, std::string(name) + ": positions outside the sequence's pages");
     for (int p = pos0 / PS_PAGE_SIZE; p <= (pos0 + n - 1) / PS_PAGE_SIZE; p++)
@@ -505,7 +506,7 @@ static ps_status kv_copy(ps_ctx* c, bool to_pool, int32_t layer, const ps_seq* s
     const char* dslots = nullptr;
     if ((st = upload_meta(c, s, s_idx, (size_t)n * 4, &dslots)) != PS_OK) return st;
     bf16_t* slot_base = c->pool + (size_t)(layer % c->n_kv_slots) * c->slot_elems;
-    HIP_TRY(c, launch_kv_copy(to_pool, slot_base, reinterpret_cast<const int32_t*>(dslots), n, c->desc.n_kv_heads,
+    HIP_TRY(c, launch_kv_copy(to_pool, slot_base, reinterpret_cast<const int32_t*>(dslots), n, pos0 & 3, c->desc.n_kv_heads,
                               c->desc.head_dim, static_cast<bf16_t*>(k), static_cast<bf16_t*>(v), c->stream));
     return staging_commit(c, s_idx);
 }

@@ -109,7 +109,7 @@ struct ReduceAddNormArgs {
     float eps;
 };
 hipError_t launch_reduce_add_norm(const ReduceAddNormArgs& a, hipStream_t st);
-hipError_t launch_kv_copy(bool to_pool, bf16_t* pool_slot, const int32_t* slots_dev, int n, int n_kv, int d, bf16_t* k,
+hipError_t launch_kv_copy(bool to_pool, bf16_t* pool_slot, const int32_t* slots_dev, int n, int phase, int n_kv, int d, bf16_t* k,
                           bf16_t* v, hipStream_t st);
 hipError_t launch_repack_weight(const bf16_t* w, bf16_t* wp, int K, int N, int interleave, hipStream_t st);
 hipError_t launch_copy_bytes(const void* src, void* dst, size_t n, hipStream_t st);

@@ -216,35 +216,85 @@ hipError_t launch_rope_append(const float* qkv, int n_splits, bf16_t* q_out, int
 }
 
 // ------------------------------------------------------- logical KV write / read
-// grid (n, n_kv), 64 threads; k, v are [n][n_kv][d] in logical order.
+// k, v are [n][n_kv][d] in logical order; slots[i] = page * 16 + position in the page of token i, the tokens being
+// consecutive positions starting at a position whose remainder mod 4 is `phase`.  One thread per (group of four
+// positions aligned to 4, kv head, 8 consecutive dd): in the cache a key keeps 8 consecutive dd of one token together
+// (16 bytes) and a value keeps the four tokens of such a group together for one dd (8 bytes), so the thread moves
+// whole 16-byte rows on the logical side and 16- or 8-byte pieces on the cache side, transposing the 4 x 8 value
+// tile in registers.  Tokens of a group outside [0, n) are left alone (the first and last group may be partial).
 template <bool TO_POOL>
-__global__ __launch_bounds__(64) void kv_copy_kernel(bf16_t* __restrict__ pool, const int32_t* __restrict__ slots,
-                                                     int n_kv, int d, bf16_t* __restrict__ k, bf16_t* __restrict__ v) {
-    const int i = blockIdx.x, h = blockIdx.y;
-    const int slot = slots[i];
+__global__ __launch_bounds__(256) void kv_copy_kernel(bf16_t* __restrict__ pool, const int32_t* __restrict__ slots, int n,
+                                                      int phase, int n_kv, int d, bf16_t* __restrict__ k, bf16_t* __restrict__ v) {
+    const int gpd = d >> 3;  // 8-element groups per head
+    const int n_quads = (phase + n + 3) >> 2;
+    const long long id = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (id >= (long long)n_quads * n_kv * gpd) return;
+    const int g = (int)(id % gpd), h = (int)((id / gpd) % n_kv), qi = (int)(id / ((long long)gpd * n_kv));
+    const int dd0 = g * 8;
+    const int i0 = 4 * qi - phase;                    // token index of the group's first position
+    const int t_lo = max(0, -i0), t_hi = min(4, n - i0);   // valid positions of the group: t_lo <= t < t_hi
+    const int slot = slots[i0 + t_lo] - t_lo;         // slot of the group's first position (same page: groups are aligned)
     bf16_t* kc = pool + (((size_t)(slot >> 4) * n_kv + h) * 2 + 0) * (size_t)(16 * d);
     bf16_t* vc = kc + 16 * d;
-    bf16_t* kr = k + ((size_t)i * n_kv + h) * d;
-    bf16_t* vr = v + ((size_t)i * n_kv + h) * d;
-    const int tok = slot & 15;
-    for (int dd = threadIdx.x; dd < d; dd += 64) {
+    const int tok0 = slot & 15;                       // a multiple of 4
+    for (int t = t_lo; t < t_hi; t++) {
+        uint4* kr = reinterpret_cast<uint4*>(k + ((size_t)(i0 + t) * n_kv + h) * d + dd0);
+        uint4* kp = reinterpret_cast<uint4*>(kc + k_elem_offset(tok0 + t, dd0));
+        if (TO_POOL) *kp = *kr;
+        else *kr = *kp;
+    }
+    if (t_lo == 0 && t_hi == 4) {
+        uint16_t tile[4][8];
         if (TO_POOL) {
-            kc[k_elem_offset(tok, dd)] = kr[dd];
-            vc[v_elem_offset(tok, dd)] = vr[dd];
+#pragma unroll
+            for (int t = 0; t < 4; t++) {
+                const uint4 r = *reinterpret_cast<const uint4*>(v + ((size_t)(i0 + t) * n_kv + h) * d + dd0);
+                const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+                for (int e = 0; e < 8; e++) tile[t][e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+            }
+#pragma unroll
+            for (int e = 0; e < 8; e++)
+                *reinterpret_cast<uint2*>(vc + v_elem_offset(tok0, dd0 + e)) =
+                    uint2{(uint32_t)tile[0][e] | ((uint32_t)tile[1][e] << 16), (uint32_t)tile[2][e] | ((uint32_t)tile[3][e] << 16)};
         } else {
-            kr[dd] = kc[k_elem_offset(tok, dd)];
-            vr[dd] = vc[v_elem_offset(tok, dd)];
+#pragma unroll
+            for (int e = 0; e < 8; e++) {
+                const uint2 r = *reinterpret_cast<const uint2*>(vc + v_elem_offset(tok0, dd0 + e));
+                tile[0][e] = (uint16_t)r.x; tile[1][e] = (uint16_t)(r.x >> 16);
+                tile[2][e] = (uint16_t)r.y; tile[3][e] = (uint16_t)(r.y >> 16);
+            }
+#pragma unroll
+            for (int t = 0; t < 4; t++) {
+                uint4 o;
+                o.x = (uint32_t)tile[t][0] | ((uint32_t)tile[t][1] << 16);
+                o.y = (uint32_t)tile[t][2] | ((uint32_t)tile[t][3] << 16);
+                o.z = (uint32_t)tile[t][4] | ((uint32_t)tile[t][5] << 16);
+                o.w = (uint32_t)tile[t][6] | ((uint32_t)tile[t][7] << 16);
+                *reinterpret_cast<uint4*>(v + ((size_t)(i0 + t) * n_kv + h) * d + dd0) = o;
+            }
         }
+    } else {
+        for (int t = t_lo; t < t_hi; t++)
+            for (int e = 0; e < 8; e++) {
+                bf16_t* vr = v + ((size_t)(i0 + t) * n_kv + h) * d + dd0 + e;
+                bf16_t* vp = vc + v_elem_offset(tok0 + t, dd0 + e);
+                if (TO_POOL) *vp = *vr;
+                else *vr = *vp;
+            }
     }
 }
 
-hipError_t launch_kv_copy(bool to_pool, bf16_t* pool_slot, const int32_t* slots_dev, int n, int n_kv, int d, bf16_t* k,
+hipError_t launch_kv_copy(bool to_pool, bf16_t* pool_slot, const int32_t* slots_dev, int n, int phase, int n_kv, int d, bf16_t* k,
                           bf16_t* v, hipStream_t st) {
     if (n <= 0) return hipSuccess;
+    if (d % 8 || phase < 0 || phase > 3) return hipErrorInvalidValue;
+    const long long threads = (long long)((phase + n + 3) >> 2) * n_kv * (d >> 3);
+    const int blocks = (int)((threads + 255) / 256);
     if (to_pool)
-        hipLaunchKernelGGL(kv_copy_kernel<true>, dim3(n, n_kv), dim3(64), 0, st, pool_slot, slots_dev, n_kv, d, k, v);
+        hipLaunchKernelGGL(kv_copy_kernel<true>, dim3(blocks), dim3(256), 0, st, pool_slot, slots_dev, n, phase, n_kv, d, k, v);
     else
-        hipLaunchKernelGGL(kv_copy_kernel<false>, dim3(n, n_kv), dim3(64), 0, st, pool_slot, slots_dev, n_kv, d, k, v);
+        hipLaunchKernelGGL(kv_copy_kernel<false>, dim3(blocks), dim3(256), 0, st, pool_slot, slots_dev, n, phase, n_kv, d, k, v);
     return hipGetLastError();
 }
 
