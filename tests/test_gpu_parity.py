@@ -181,9 +181,20 @@ def test_kv_write_read_roundtrip_is_exact():
     k = rng.integers(0, 0x7F80, size=(50, 2, 64)).astype(np.uint16)
     v = rng.integers(0, 0x7F80, size=(50, 2, 64)).astype(np.uint16)
     pages = b.seqs[0].pages
+    # the whole span first, then positions 13..62 over it: neither start nor end falls on a group of four positions,
+    # and what the partial groups leave alone must still be there
+    k_all = rng.integers(0, 0x7F80, size=(77, 2, 64)).astype(np.uint16)
+    v_all = rng.integers(0, 0x7F80, size=(77, 2, 64)).astype(np.uint16)
+    c.eng.write_kv(0, pages, 0, k_all, v_all)
     c.eng.write_kv(0, pages, 13, k, v)
     k2, v2 = c.eng.read_kv(0, pages, 13, 50)
     assert np.array_equal(k, k2) and np.array_equal(v, v2)
+    k_all[13:63], v_all[13:63] = k, v
+    k3, v3 = c.eng.read_kv(0, pages, 0, 77)
+    assert np.array_equal(k_all, k3) and np.array_equal(v_all, v3)
+    for p0, n in ((1, 1), (2, 3), (3, 6), (15, 2), (60, 17)):
+        k4, v4 = c.eng.read_kv(0, pages, p0, n)
+        assert np.array_equal(k_all[p0:p0 + n], k4) and np.array_equal(v_all[p0:p0 + n], v4), (p0, n)
     with pytest.raises(B.PolystepError) as e:
         c.eng.read_kv(0, pages, 70, 20)
     assert e.value.status == B.PS_ERANGE
