@@ -147,7 +147,10 @@ class Case:
         to the oracle's pool (prefix and untouched pages alike).  Appended keys and values: against
         the oracle variant with bf16 activations they are one bf16 rounding of the same fp32
         arithmetic, so they agree up to one rounding flip (one bf16 ulp of the value, 2^-7 relative,
-        plus 1e-3 x RMS for entries that cancel to near zero); against the definition they are held
+        plus 3e-3 x RMS for entries that cancel to near zero: the normalised input itself carries bf16
+        rounding flips against the oracle's, each moving a sum by about 2^-8 / sqrt(hidden) of its RMS;
+        over 480 random batches the largest excess seen was 2.3e-3 x RMS, on one entry);
+        against the definition they are held
         to the floating-point bar.  Returns the fraction of appended entries that differ at all from
         the bf16-activation variant."""
         eng, b = self.eng, self.batch
@@ -172,7 +175,7 @@ class Case:
                     assert row_score(g, wb, TOL, 2.0) <= 1.0, f"{name}: appended entries off (slot {slot})"
                     continue
                 rms = float(np.sqrt(np.mean(wb * wb))) or 1.0
-                over = np.abs(g - wb) - (2.0 ** -7 * np.abs(wb) + 1e-3 * rms)
+                over = np.abs(g - wb) - (2.0 ** -7 * np.abs(wb) + 3e-3 * rms)
                 assert over.max() <= 0, f"{name}: appended entries differ by more than one bf16 rounding flip"
                 worst = max(worst, float(np.mean(g != wb)))
         return worst
