@@ -429,3 +429,41 @@ def test_hbm_read_rate_reading_is_plausible():
         assert 1000.0 < r <= 8000.0 * 1.02      # between a fraction of and the nominal HBM rate, GB/s
     finally:
         c.close()
+
+
+def _random_shape(rng):
+    kind = int(rng.integers(0, 4))
+    if kind == 0:    # decode-only, up to 100 tokens: every row-tile count of the streaming GEMM and the first tiled sizes
+        return 0, 0, [int(x) for x in rng.integers(1, 400, size=rng.integers(1, 101))]
+    if kind == 1:    # mixed
+        return int(rng.integers(1, 150)), int(rng.integers(0, 300)), [int(x) for x in rng.integers(1, 600, size=rng.integers(0, 30))]
+    if kind == 2:    # prefill only
+        return int(rng.integers(1, 300)), int(rng.integers(0, 500)), []
+    return int(rng.integers(1, 20)), int(rng.integers(0, 2000)), [int(x) for x in rng.integers(500, 3000, size=rng.integers(1, 4))]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("seed,random_heads", [(7, False), (8, True)])
+def test_random_batches_tiny_models(seed, random_heads):
+    """Seeded random batch shapes (and, in the second run, head layouts and FFN widths): all tensors of the step and the
+    cache against the oracle, as in the ragged cases above."""
+    rng = np.random.default_rng(seed)
+    layouts = [(4, 4, 64), (8, 4, 128), (8, 2, 64), (8, 1, 128), (16, 1, 64), (16, 1, 128), (4, 2, 128), (2, 2, 64)]
+    try:
+        for it in range(30):
+            chunk, prefix, decodes = _random_shape(rng)
+            name = "tiny"
+            if random_heads:
+                n_q, n_kv, d = layouts[int(rng.integers(0, len(layouts)))]
+                W.MODELS["_r"] = dict(hidden=256, n_q=n_q, n_kv=n_kv, head_dim=d, ffn=int(rng.choice([192, 320, 448])),
+                                      rope_base=10000.0, n_layers=1)
+                name = "_r"
+            b = W.custom_batch(name, int(rng.integers(0, 1000)), chunk, prefix, decodes, name="random")
+            c = Case(b)
+            try:
+                _assert_errs(c.run(), f"seed={seed} case={it} chunk={chunk} prefix={prefix} decodes={decodes} model={W.MODELS[name]}")
+                c.check_pool()
+            finally:
+                c.close()
+    finally:
+        W.MODELS.pop("_r", None)
