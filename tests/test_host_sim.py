@@ -109,3 +109,25 @@ def test_simulator_stops_at_max_steps_and_rejects_malformed_input():
     with pytest.raises(B.PolystepError):
         gp.simulate([0.0], [1], [1], [300.0], [0], [20.0], 1, 1, 1e9, disaggregated=True)        # no prefill budget
     gp.close()
+
+
+def test_random_configurations_match_the_oracle():
+    """Seeded random tables, cluster sizes, rates, length mixes, check periods, capacities and budgets, either deployment."""
+    rng = np.random.default_rng(1)
+    for it in range(12):
+        a, bb, cc = float(rng.uniform(2, 8)), float(rng.uniform(0.004, 0.03)), float(rng.uniform(5e-6, 5e-5))
+        gp, op = tables(lambda b, k: a + bb * b + cc * k)
+        n_servers, rate = int(rng.integers(1, 12)), float(rng.choice([0.005, 0.02, 0.05, 0.15, 0.4]))
+        max_prompt, max_output, avg = int(rng.choice([256, 1024, 4096])), int(rng.choice([64, 256])), int(rng.choice([32, 128]))
+        period, cap, burst = int(rng.choice([50, 200, 1000])), float(rng.choice([3000.0, 30000.0, 2e6])), bool(rng.integers(0, 2))
+        budget = int(rng.choice([256, 1024, 2048]))
+        tr = W.sim_trace(int(rng.integers(0, 10000)), 120, rate, max_prompt, max_output, burst=burst)
+        args = (tr["arrival"], tr["prompt"], tr["output"], tr["ttft"], tr["tier"], list(W.SIM_TPOTS_MS), n_servers, avg, cap)
+        if rng.integers(0, 2):
+            want = osim_pd.simulate(op, *args, budget, period)
+            got = gp.simulate(*args, period, disaggregated=True, prefill_budget=budget)
+        else:
+            want = osim.simulate(op, *args, period)
+            got = gp.simulate(*args, period)
+        compare(got, want, 120)
+        gp.close()
