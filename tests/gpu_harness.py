@@ -109,7 +109,7 @@ class Case:
         want, otaps = orun.run_step(self.model, self.layers, b.seqs, self.x_bits, self.pool, dtype, want_taps=True)
         want_b, otaps_b = orun.run_step(self.model, self.layers, b.seqs, self.x_bits, pool_b, dtype, want_taps=True,
                                         bf16_activations=True)
-        self.want = want
+        self.want, self.want_b = want, want_b
         ot, otb = otaps[tap_layer], otaps_b[tap_layer]
         got = {k: f32(dev_to_bits(taps[k])) for k in ("xn", "q", "attn", "xn2", "act")}
         got["x1"] = taps["x1"].cpu().numpy()
@@ -126,18 +126,20 @@ class Case:
         self.score = {}
         for k, v in got.items():
             fp32_tensor = k in ("x1", "out")
-            # vs the definition: reported, and enforced only at five times the bar as a gross-error
-            # catch.  The rounding of the bf16 tensors an intermediate is computed FROM is not
+            # vs the definition: reported, and enforced only at ten times the bar as a gross-error
+            # catch (a 200-token chunk at prefix 1000 on the 8B shape reached 6.5 times the bar on one
+            # attention row while agreeing with the bf16-activation variant within the bar itself).
+            # The rounding of the bf16 tensors an intermediate is computed FROM is not
             # proportional to its own size: a softmax over ~100 effective keys turns 2^-9 relative
             # noise on q into several percent of a (small) attention output row, and silu(g)*u is
             # heavy-tailed.  The definition evaluated with bf16 activations shows the same deviations.
-            self.score[k] = 0.2 * row_score(v, ot[k], TOL, 0.0 if fp32_tensor else 2.0)
+            self.score[k] = 0.1 * row_score(v, ot[k], TOL, 0.0 if fp32_tensor else 2.0)
             # vs the same arithmetic with bf16 activations: a rounding flip (one ulp) plus TIGHT
             self.score[k + "|bf16"] = row_score(v, otb[k], tight, 0.0 if fp32_tensor else 2.0)
         if tap_layer == 0:
             # the attention branch on its own scale: x1 - x against the O-projection output
             ob = got["x1"].astype(np.float64) - f32(self.x_bits)
-            self.score["o_branch"] = 0.2 * row_score(ob, ot["o"], TOL, 0.0)
+            self.score["o_branch"] = 0.1 * row_score(ob, ot["o"], TOL, 0.0)
             self.score["o_branch|bf16"] = row_score(ob, otb["o"], TOL, 0.0)
         self.err.update({k + ":score": v * TOL for k, v in self.score.items()})
         return self.err
