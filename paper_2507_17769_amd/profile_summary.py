@@ -51,7 +51,8 @@ def trace_summary(trace_csv, bench_json, workload, command):
     b = json.load(open(bench_json))
     out = [f"# rocprofv3 kernel trace — bench.py --workload {workload}", "", b["config"]["workload"], "",
            "Command (run on the MI355X box from the repository root, `export TMPDIR=/tmp` first):", "", f"    {command}", "",
-           "The run covers library set-up (weight repack, KV prefix load), the warm-up steps, the timed steps and 10 steps with "
+           "The run covers library set-up (weight repack, KV prefix load), the warm-up steps, the timed steps, the two probes read after them "
+           "(`mfma_clock_probe_kernel`, `stream_read_probe_kernel`: not part of a step) and 10 steps with "
            "per-stage events.", "",
            "| kernel | calls | avg µs | min µs | max µs | % of GPU time |", "|---|---|---|---|---|---|"]
     for k, v in sorted(dur.items(), key=lambda kv: -sum(kv[1])):
