@@ -44,33 +44,34 @@ struct GemmParams {
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
 
 // ------------------------------------------------------------------------------------------
-// Weight streaming kernel (M <= 96).  grid (N/64, splits), 320 threads.
+// Weight streaming kernel (M <= 96).  grid (N/64/NG, splits), 64 (4 NG + 1) threads, NG = 1 or 2 column groups per block.
 //
 // A block owns 64 output columns and a K range.  Its four computing wavefronts divide the columns
 // (16 each: one 16-byte load per lane and k-block fetches a KiB that already is a 16x16x32
 // operand, the four wavefronts' KiBs being adjacent), so that all four need the same activation
 // k-blocks and a fifth wavefront can copy those into an LDS ring once per block
 // (global_load_lds, verbatim KiB blocks) instead of each wavefront fetching them from L2 for
-// itself: a quarter of the activation traffic, and no reduction across wavefronts at the end.
+// itself: a quarter of the activation traffic (an eighth with two column groups, eight computing wavefronts, per
+// block), and no reduction across wavefronts at the end.
 // The copying is a wavefront of its own because vector loads return in order: a computing
 // wavefront that also waited for activations (from L2, quickly) would wait for every weight load
 // issued before them (from HBM, slowly).  Stages of two k-blocks, one barrier per stage.
 // ------------------------------------------------------------------------------------------
-template <int MT, int KIND>
-__global__ __launch_bounds__(320) void gemm_wstream_kernel(GemmParams p) {
+template <int MT, int KIND, int NG>
+__global__ __launch_bounds__(64 * (4 * NG + 1)) void gemm_wstream_kernel(GemmParams p) {
+    constexpr int NCW = 4 * NG;        // computing wavefronts: four per group of 64 columns, NG groups share the activation ring
     constexpr int XS = MT * 2 * 1024;  // bytes of an activation stage: MT row tiles x 2 k-blocks
     constexpr int WSETS = 4;           // weight stages in registers: three requested ahead of the one in work (a
                                        // deeper ring costs registers, i.e. resident blocks, and measured slower)
     __shared__ __attribute__((aligned(1024))) uint8_t lds[3 * XS];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int ng = blockIdx.x;
     const int KB = p.K >> 5;
     const int kb0 = blockIdx.y * p.kb_per_split;
     const int n_st = (min(KB, kb0 + p.kb_per_split) - kb0) >> 1;  // kb_per_split is even
     if (n_st <= 0) return;
 
-    if (wave == 4) {
+    if (wave == NCW) {
         // Producer.  KiB block b of a stage = (row tile b / 2, k-block parity b % 2).  Stages past the end repeat the
         // last one into a slot nobody reads, so that every phase is the same.
         const uint8_t* xa = reinterpret_cast<const uint8_t*>(p.A) + (size_t)kb0 * 1024 + lane * 16;
@@ -100,8 +101,13 @@ __global__ __launch_bounds__(320) void gemm_wstream_kernel(GemmParams p) {
     }
 
     const int r = lane & 15, g = lane >> 4;
-    // this wavefront's column tile: block [ng][kb][wave] of the packed matrix
-    const uint8_t* w_src = reinterpret_cast<const uint8_t*>(p.Wp) + (((size_t)ng * KB + kb0) * 4 + wave) * 1024 + lane * 16;
+    // this wavefront's column tile: block [ng][kb][cw] of the packed matrix.  A group past the last one (odd group
+    // count with NG = 2) streams the last group again and stores nothing: it still takes part in every barrier.
+    const int n_groups = p.N >> 6;
+    const int ng_own = blockIdx.x * NG + wave / 4, cw = wave & 3;
+    const bool have_group = ng_own < n_groups;
+    const int ng = have_group ? ng_own : n_groups - 1;
+    const uint8_t* w_src = reinterpret_cast<const uint8_t*>(p.Wp) + (((size_t)ng * KB + kb0) * 4 + cw) * 1024 + lane * 16;
     auto load_w = [&](uint4 (&w)[2], int st) {
         const uint8_t* gp = w_src + (size_t)min(st, n_st - 1) * 8192;
         w[0] = ldg16(gp);
@@ -140,38 +146,40 @@ __global__ __launch_bounds__(320) void gemm_wstream_kernel(GemmParams p) {
     if (s + 2 < n_st) PS_WSHARE_PHASE(2, s + 2)
 #undef PS_WSHARE_PHASE
 
-    // lane holds C[m = 16 mt + r][n = 64 ng + 16 wave + 4 g + 0..3]
+    // lane holds C[m = 16 mt + r][n = 64 ng + 16 cw + 4 g + 0..3]
     if constexpr (KIND == GemmOut::SWIGLU_BF16) {
-        // column tiles 0, 1 = gate, tiles 2, 3 = up of the same 32 features: wavefronts 2 and 3 hand their sums over
-        float4* up4 = reinterpret_cast<float4*>(lds);  // [wave - 2][mt][lane]
+        // column tiles 0, 1 = gate, tiles 2, 3 = up of the same 32 features: wavefronts 2 and 3 of a group hand their sums over
+        float4* up4 = reinterpret_cast<float4*>(lds);  // [group in block][cw - 2][mt][lane]
+        const int gi = wave / 4;
         __builtin_amdgcn_s_barrier();                  // the ring is free: the producer's last copies have landed
-        if (wave >= 2) {
+        if (cw >= 2) {
 #pragma unroll
-            for (int mt = 0; mt < MT; mt++) up4[((wave - 2) * MT + mt) * 64 + lane] = float4{acc[mt][0], acc[mt][1], acc[mt][2], acc[mt][3]};
+            for (int mt = 0; mt < MT; mt++) up4[((gi * 2 + cw - 2) * MT + mt) * 64 + lane] = float4{acc[mt][0], acc[mt][1], acc[mt][2], acc[mt][3]};
         }
         __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the LDS writes have been made before the barrier
         __builtin_amdgcn_s_barrier();
-        if (wave >= 2) return;
+        if (cw >= 2 || !have_group) return;
         bf16_t* out = static_cast<bf16_t*>(p.out);
         const int F = p.N >> 1;
 #pragma unroll
         for (int mt = 0; mt < MT; mt++) {
             const int m = mt * 16 + r;
-            const float4 up = up4[(wave * MT + mt) * 64 + lane];
+            const float4 up = up4[((gi * 2 + cw) * MT + mt) * 64 + lane];
             if (m < p.M) {
                 uint2 o;
                 o.x = pack_bf16(silu_f(acc[mt][0]) * up.x, silu_f(acc[mt][1]) * up.y);
                 o.y = pack_bf16(silu_f(acc[mt][2]) * up.z, silu_f(acc[mt][3]) * up.w);
-                *reinterpret_cast<uint2*>(out + act_offset(m, ng * 32 + wave * 16 + 4 * g, F)) = o;
+                *reinterpret_cast<uint2*>(out + act_offset(m, ng * 32 + cw * 16 + 4 * g, F)) = o;
             }
         }
     } else {
+        if (!have_group) return;
         float* out = static_cast<float*>(p.out) + (size_t)blockIdx.y * p.M * p.N;
 #pragma unroll
         for (int mt = 0; mt < MT; mt++) {
             const int m = mt * 16 + r;
             if (m < p.M)
-                *reinterpret_cast<float4*>(out + (size_t)m * p.N + ng * 64 + wave * 16 + 4 * g) = float4{acc[mt][0], acc[mt][1], acc[mt][2], acc[mt][3]};
+                *reinterpret_cast<float4*>(out + (size_t)m * p.N + ng * 64 + cw * 16 + 4 * g) = float4{acc[mt][0], acc[mt][1], acc[mt][2], acc[mt][3]};
         }
     }
 }
@@ -513,11 +521,16 @@ hipError_t launch_gemm(const GemmArgs& a, int* n_splits, hipStream_t st) {
     p.kb_per_split = g.kb_per_split;
     if (n_splits) *n_splits = g.splits;
     if (g.wstream) {
-        const dim3 grid(a.N / 64, g.splits);
         const int mt = (a.M + 15) / 16;
+        // Two column groups per block halve the activation copies (as many bytes as the weights at 64 tokens) at the
+        // price of half as many blocks.  Measured: always a gain for the gate/up matrix (448 groups, no K split; 64
+        // tokens: 54 -> 49 us), a gain for the split projections from four row tiles on, a loss below.
+        const bool two = a.kind == GemmOut::SWIGLU_BF16 || mt >= 4;
+        const dim3 grid(two ? (a.N / 64 + 1) / 2 : a.N / 64, g.splits);
 #define PS_WS_LAUNCH(MT_)                                                                                                  \
-    if (a.kind == GemmOut::SWIGLU_BF16) hipLaunchKernelGGL((gemm_wstream_kernel<MT_, GemmOut::SWIGLU_BF16>), grid, dim3(320), 0, st, p); \
-    else hipLaunchKernelGGL((gemm_wstream_kernel<MT_, GemmOut::PARTIAL_F32>), grid, dim3(320), 0, st, p);
+    if (a.kind == GemmOut::SWIGLU_BF16) hipLaunchKernelGGL((gemm_wstream_kernel<MT_, GemmOut::SWIGLU_BF16, 2>), grid, dim3(576), 0, st, p); \
+    else if (two) hipLaunchKernelGGL((gemm_wstream_kernel<MT_, GemmOut::PARTIAL_F32, 2>), grid, dim3(576), 0, st, p);             \
+    else hipLaunchKernelGGL((gemm_wstream_kernel<MT_, GemmOut::PARTIAL_F32, 1>), grid, dim3(320), 0, st, p);
         switch (mt) {
             case 1: PS_WS_LAUNCH(1) break;
             case 2: PS_WS_LAUNCH(2) break;
