@@ -135,7 +135,7 @@ const char* ps_last_error(const ps_ctx* ctx);
  * query block, where a decode token's pair costs 2; it only moves the cuts),
  * "gemm_split_k" (0 = automatic), "gemm_tile" (block tile edge of the tiled GEMM kernel, which
  * serves more than 64 tokens: 0 = automatic (the weight-streaming kernel stays in charge up to 96
- * tokens), 128 or 256), "out_f32" (1: ps_step writes x_out as fp32 [T][hidden],
+ * tokens, up to 160 for all projections but the QKV one), 128 or 256), "out_f32" (1: ps_step writes x_out as fp32 [T][hidden],
  * the precision the residual stream is kept in, instead of rounding it to bf16).
  * "only_layer" (l >= 0: ps_step runs layer l alone, x_in -> x_out, as if it were the whole model;
  * -1 = the whole stack.  A benchmark of a single layer loads several copies of it as layers and

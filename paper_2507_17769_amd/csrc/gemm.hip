@@ -13,11 +13,11 @@
 // DRAM rows open when two thousand wavefronts stream at once.
 //
 // Two kernels:
-//  * gemm_wstream_kernel (M <= 96): weight streaming.  The four computing wavefronts of a block own 16 of
+//  * gemm_wstream_kernel (M <= 96, and up to 160 for all but the QKV-shaped projection): weight streaming.  The four computing wavefronts of a block own 16 of
 //    its 64 output columns each and load their weight operands straight from HBM into registers
 //    (no LDS hop), four stages of two k-blocks ahead; a fifth wavefront copies the activation k-blocks
 //    that all four need into an LDS ring.
-//  * gemm_dma_kernel (M > 96, or forced by the tile option above 64): 256x256 or 128x128 block tile, bf16 MFMA 32x32x16.  Activations and
+//  * gemm_dma_kernel (above that, or forced by the tile option above 64): 256x256 or 128x128 block tile, bf16 MFMA 32x32x16.  Activations and
 //    weights are both stored as KiB blocks that already are MFMA operands, so a k-slice of the
 //    tile is copied HBM/L2 -> LDS verbatim by global_load_lds (no register hop, no transform) into
 //    a ring of four stages, three in flight; the wavefronts read operands back with one
@@ -44,7 +44,7 @@ struct GemmParams {
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
 
 // ------------------------------------------------------------------------------------------
-// Weight streaming kernel (M <= 96).  grid (N/64/NG, splits), 64 (4 NG + 1) threads, NG = 1 or 2 column groups per block.
+// Weight streaming kernel (M <= 160: up to ten row tiles of 16).  grid (N/64/NG, splits), 64 (4 NG + 1) threads, NG = 1 or 2 column groups per block.
 //
 // A block owns 64 output columns and a K range.  Its four computing wavefronts divide the columns
 // (16 each: one 16-byte load per lane and k-block fetches a KiB that already is a 16x16x32
@@ -443,7 +443,10 @@ static double tiled_cost(int M, int N, int K, bool big, int splits, int* kb_per_
 
 static GemmPlan plan_gemm(int M, int N, int K, int kind, int split_opt, int tile_opt) {
     GemmPlan g;
-    g.wstream = M <= 64 || (M <= 96 && tile_opt == 0);  // measured: streaming wins up to ~96 tokens, the tiled kernel above
+    // measured: streaming wins up to 96 tokens for every projection, and up to 160 (ten row tiles) for all but the QKV-shaped
+    // one (more columns than rows of weights: 48 blocks per split and six splits of partial sums; 129 tokens: 29 vs 24 us),
+    // above all for the gate/up matrix (129 tokens: 61 vs 75 us) and the down projection (42 vs 46)
+    g.wstream = M <= 64 || (tile_opt == 0 && (M <= 96 || (M <= 160 && (kind == GemmOut::SWIGLU_BF16 || N <= K))));
     g.big_tile = false;
     int s = 1;
     if (g.wstream) {
@@ -537,7 +540,11 @@ hipError_t launch_gemm(const GemmArgs& a, int* n_splits, hipStream_t st) {
             case 3: PS_WS_LAUNCH(3) break;
             case 4: PS_WS_LAUNCH(4) break;
             case 5: PS_WS_LAUNCH(5) break;
-            default: PS_WS_LAUNCH(6) break;
+            case 6: PS_WS_LAUNCH(6) break;
+            case 7: PS_WS_LAUNCH(7) break;
+            case 8: PS_WS_LAUNCH(8) break;
+            case 9: PS_WS_LAUNCH(9) break;
+            default: PS_WS_LAUNCH(10) break;
         }
 #undef PS_WS_LAUNCH
         return hipGetLastError();

@@ -32,6 +32,7 @@ def test_cfg0_tiny_mixed_batch_all_tensors():
     (33, 1, [64]), (100, 37, [5, 250]), (0, 0, [1]), (0, 0, [1, 2, 3, 15, 16, 17, 18, 255, 256, 257]),
     (130, 0, []), (257, 300, [300]),
     (70, 5, [3, 9]), (88, 0, [1, 2, 3, 4, 5, 6]),     # 72 and 94 tokens: five and six row tiles in the weight-streaming GEMM
+    (112, 9, []), (120, 0, [3] * 8), (140, 1, [2, 2, 2, 2]), (150, 0, [7] * 10), (151, 0, [7] * 10),   # 112, 128, 144, 160 | 161 tokens: seven to ten row tiles | tiled again
     (64, 0, []), (65, 0, []), (90, 2, [4] * 6), (91, 2, [4] * 6),   # 64 | 65 and 96 | 97 tokens: a full fourth row tile | the first of a fifth, the last batch of the streaming GEMM | the first of the tiled one
 ])
 def test_ragged_shapes_tiny_model(chunk, prefix, decodes):
