@@ -446,7 +446,7 @@ def run_prefill(a):
 
 
 def measure_profile(a, batch_sizes, kv_sizes, n_decodes_in_mixed=256, extra_batches=None):
-    """Measure the map (batch size, KV cache size) -> iteration time of the whole 8B-shaped model (Sec. 4.4) with
+    """Measure the map (batch size, KV cache size) -> iteration time of the whole 8B-shaped model (Sec. 4.5) with
     ps_step_tokens.  Rows up to n_decodes_in_mixed tokens are decode batches (the KV size split evenly over the requests);
     larger rows are the co-located kind of batch (Sec. 2.4): n_decodes_in_mixed decodes plus one prefill chunk with the
     remaining tokens at prefix 0, the decodes sharing the KV size that the chunk does not attend.  Returns
@@ -538,8 +538,8 @@ def measure_profile(a, batch_sizes, kv_sizes, n_decodes_in_mixed=256, extra_batc
 
 
 def run_profile(a):
-    """The map (batch size, KV cache size) -> iteration time of the whole 8B-shaped model (Sec. 4.4), measured on
-    decode batches, and the router's decisions taken with it through polysched (Sec. 3.4, 4.4-4.6) for the paper's
+    """The map (batch size, KV cache size) -> iteration time of the whole 8B-shaped model (Sec. 4.5), measured on
+    decode batches, and the router's decisions taken with it through polysched (Sec. 3.4, 4.5-4.7) for the paper's
     TPOT tiers (Sec. 5.1: 20, 30, 50, 100 ms; TTFT 300, 500, 1000 ms)."""
     import numpy as np
     from paper_2507_17769_amd import binding as B
@@ -559,10 +559,10 @@ def run_profile(a):
                              for (p, dd) in ((512, 512), (4096, 1024)) for t in (20, 30, 50, 100)}
     dec["batch_limit_co"] = {f"p={p},d={dd},tpot={t},ttft={tt}": prof.batch_limit_co(p, dd, t, tt, capacity, 4096)
                              for (p, dd) in ((512, 512), (4096, 1024)) for t in (20, 50, 100) for tt in (300, 1000)}
-    # Sec. 4.4/4.5: a server with 63 running requests (KV 2000, 100 tokens generated), average output 512
+    # Sec. 4.5/4.6: a server with 63 running requests (KV 2000, 100 tokens generated), average output 512
     run = [(2000, 100)] * 63
     dec["admit_64th_request"] = {f"tpot={t},wait={w}": list(prof.predict_admit(run, 1000, 512, t, w)) for t in (20, 30) for w in (0.0, 15.0)}
-    # Sec. 4.6: the worked example, and a co-located prefill
+    # Sec. 4.7: the worked example, and a co-located prefill
     sizes = lambda plan: [sum(t for _, t in it) for it in plan]
     dec["chunk_plan_2050_budget_1024"] = {"chunked": sizes(B.chunk_plan([2050], 1024, False)), "chunked_after_1023": sizes(B.chunk_plan([2050], 1024, False, 1023)),
                                           "dynamic": sizes(B.chunk_plan([2050], 1024, True)), "dynamic_after_1023": sizes(B.chunk_plan([2050], 1024, True, 1023))}

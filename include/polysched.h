@@ -1,8 +1,8 @@
 /* polysched: host-side consumers of the latency profile that polystep measures.
  *
  * These are the decisions the paper's router takes with the (batch size, KV cache size) -> time
- * table (Sec. 4.4 "Profile-Based Batch Formation", Sec. 4.5 "Wait-Time-Aware Scheduling",
- * Sec. 4.6 "Handling TTFT", Sec. 3.4 batch-size limits, Sec. 3.5 cost of a request), and the cluster
+ * table (Sec. 4.5 "Profile-Based Batch Formation", Sec. 4.6 "Wait-Time-Aware Scheduling",
+ * Sec. 4.7 "Handling TTFT", Sec. 3.4 batch-size limits, Sec. 3.5 cost of a request), and the cluster
  * simulation the paper evaluates its router with (Sec. 5.1).  Plain C, host memory only, no GPU work,
  * no global state; a profile object is immutable after creation and may be shared by threads.
  * All times are milliseconds.  Functions return PS_OK or PS_EINVAL (null pointer, malformed
@@ -25,7 +25,7 @@ ps_status ps_profile_create(const int32_t* batch_sizes, int32_t n_batch, const i
                             const float* ms, ps_profile** out);
 void ps_profile_destroy(ps_profile* p);
 
-/* (batch size, KV cache size) -> time (Sec. 4.4): bilinear interpolation between profiled points;
+/* (batch size, KV cache size) -> time (Sec. 4.5): bilinear interpolation between profiled points;
  * below the first point of an axis the first point's value, beyond the last point the last
  * interval extended linearly.  Returns NaN for a null profile. */
 double ps_profile_lookup(const ps_profile* p, double batch, double kv);
@@ -36,20 +36,20 @@ typedef struct {
     int32_t generated;
 } ps_running_req;
 
-/* Sec. 4.4: simulate future iterations with every request predicted to generate avg_decode_len
+/* Sec. 4.5: simulate future iterations with every request predicted to generate avg_decode_len
  * tokens in total (a request at or past that is predicted to generate one more), each growing
  * by one token per iteration until it finishes; *max_kv = the largest total KV cache size attended
  * in one iteration, *n_iters = iterations simulated.  new_prompt_len < 0: no new request. */
 ps_status ps_max_future_kv(const ps_running_req* running, int32_t n_running, int32_t new_prompt_len, int32_t avg_decode_len,
                            int64_t* max_kv, int32_t* n_iters);
 
-/* Sec. 4.4 + 4.5: *predicted_ms = T(n_running + 1, largest future KV size) + wait_ms (the time the
+/* Sec. 4.5 + 4.6: *predicted_ms = T(n_running + 1, largest future KV size) + wait_ms (the time the
  * request would wait for the server's current iteration); *admit = predicted < tpot_ms. */
 ps_status ps_predict_admit(const ps_profile* p, const ps_running_req* running, int32_t n_running, int32_t new_prompt_len,
                            int32_t avg_decode_len, double tpot_ms, double wait_ms, int32_t* admit, double* predicted_ms,
                            int64_t* max_kv);
 
-/* Sec. 4.6, prefill instance.  prompts [n]: remaining prompt lengths in arrival order; budget:
+/* Sec. 4.7, prefill instance.  prompts [n]: remaining prompt lengths in arrival order; budget:
  * token budget of an iteration; first_iteration_used: tokens of other work already in the first
  * iteration (0..budget).  Iterations are filled first come first served; a request is finished in
  * the current iteration if it fits the room left, or (dynamic != 0) if the iteration then stays
@@ -59,7 +59,7 @@ ps_status ps_predict_admit(const ps_profile* p, const ps_running_req* running, i
 ps_status ps_chunk_plan(const int32_t* prompts, int32_t n, int32_t budget, int32_t dynamic, int32_t first_iteration_used,
                         int32_t* chunks, int32_t cap, int32_t* n_chunks, int32_t* n_iterations);
 
-/* Sec. 4.6, co-location.  The chunk size predicted at scheduling time is the largest c in [1, prompt_len]
+/* Sec. 4.7, co-location.  The chunk size predicted at scheduling time is the largest c in [1, prompt_len]
  * that can be kept for all ceil(prompt / c) iterations of the prefill: every one of them stays below tpot_ms
  * while the chunks attend a growing prefix and every running decode grows by one token per iteration (and
  * leaves when predicted finished).  *admit = such a c exists and wait_ms + the sum of those iteration times
@@ -102,7 +102,7 @@ double ps_optimal_cost_co(const ps_profile* prof, double p, double d, double tpo
  * instance takes a new request only while no prefill is in progress on it); the prefill's last chunk
  * produces token 0, a request with output_len d then takes d - 1 decode iterations.  Token i is due at
  * arrival + TTFT + i * (the request's own TPOT) (Sec. 2.3); a request is attained if every token is.
- * Placement (Sec. 4.2, 4.3): the request's own cluster, then the clusters of tighter tiers from the
+ * Placement (Sec. 4.3, 4.4): the request's own cluster, then the clusters of tighter tiers from the
  * nearest one (lazy promotion), each from the instance with most requests down, then scale-up (a parked
  * instance whose tightest request is of this tier, else an instance from the idle pool); an instance
  * admits the request if ps_predict_chunked_prefill admits it against the instance's TPOT, the time left to
@@ -115,7 +115,7 @@ double ps_optimal_cost_co(const ps_profile* prof, double p, double d, double tpo
  * returns to the pool once empty.  cost_ms = instance time outside the idle pool (Sec. 5.4).
  *
  * PS_SIM_DISAGGREGATED differs as follows.  Prefill runs on a cluster of its own, shared by all tiers:
- * queued requests are taken in order of arrival + TTFT (Sec. 4.1); a prefill instance forms its iterations
+ * queued requests are taken in order of arrival + TTFT (Sec. 4.2); a prefill instance forms its iterations
  * with ps_chunk_plan (dynamic, prefill_budget) over its requests in admission order; a request goes to the
  * prefill instance with most unprocessed prompt tokens on which the plan with the request added (the wait
  * for the iteration in flight plus the planned iterations) gives the request its first token before its
@@ -124,7 +124,7 @@ double ps_optimal_cost_co(const ps_profile* prof, double p, double d, double tpo
  * and queues the request for decoding (the transfer takes no time); decode clusters work as above except
  * that an instance admits the request if ps_predict_admit keeps the largest future KV size's iteration
  * below the instance's TPOT, that KV size is below kv_capacity, and the wait for the iteration in flight
- * plus that iteration time is before the second token's deadline, arrival + TTFT + TPOT (Sec. 4.5).  Step
+ * plus that iteration time is before the second token's deadline, arrival + TTFT + TPOT (Sec. 4.6).  Step
  * order: ended iterations, arrivals, scale-down check (also returning the least loaded prefill instance if
  * it holds no request), decode queues, prefill queue, iteration starts.  A queued request is dropped once
  * an empty instance could no longer meet its next deadline (first token before prefill, second after). */
@@ -135,11 +135,11 @@ typedef struct {
     int32_t n_servers;
     int32_t n_tiers;
     const double* tpot_ms;    /* [n_tiers], strictly ascending */
-    int32_t avg_decode_len;   /* the router's output-length prediction (Sec. 4.4) */
+    int32_t avg_decode_len;   /* the router's output-length prediction (Sec. 4.5) */
     double kv_capacity;       /* KV tokens per instance */
     int32_t check_period_ms;
     int64_t max_steps;        /* the run stops after this many steps even if requests are unfinished */
-    int32_t prefill_budget;   /* disaggregated: token budget of a prefill iteration (Sec. 4.6) */
+    int32_t prefill_budget;   /* disaggregated: token budget of a prefill iteration (Sec. 4.7) */
 } ps_sim_config;
 
 typedef struct {

@@ -1,12 +1,12 @@
 """Consumers of the latency profile: what the paper's router does with the table this repository
 measures (test infrastructure; plain and slow on purpose).
 
-Sec. 4.4 ("Profile-Based Batch Formation"): iteration time is looked up in a map
+Sec. 4.5 ("Profile-Based Batch Formation"): iteration time is looked up in a map
 (batch size, KV cache size) -> time; when routing, future iterations are simulated with every
 request's output predicted as the average decode length, the largest KV cache size reached is
 taken, and the request is admitted when the time looked up for (current token batch size, that KV
-size) is below the TPOT.  Sec. 4.5 ("Wait-Time-Aware Scheduling"): the time the request waits for
-the server's current iteration is added to the predicted iteration time.  Sec. 4.6 ("Handling
+size) is below the TPOT.  Sec. 4.6 ("Wait-Time-Aware Scheduling"): the time the request waits for
+the server's current iteration is added to the predicted iteration time.  Sec. 4.7 ("Handling
 TTFT"): dynamic chunking for a prefill instance (a request whose remaining length is below twice
 the token budget is finished at once and nothing else is admitted into that enlarged iteration),
 and, for co-location, admitting a prefill only if the chunk size predicted at scheduling time can

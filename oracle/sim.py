@@ -3,12 +3,12 @@
 
 What is simulated (Sec. 5.1): serving instances whose iteration times come from the
 (batch size, KV cache size) -> time table, advanced in 1 ms steps, under the router of Sec. 4:
-one cluster of instances per TPOT tier (4.1 request binning), requests sent to the highest-load
-instance that still meets the SLO so that a load gradient forms (4.2), looser-tier requests
-allowed onto tighter-tier instances only when their own cluster is full (4.3 lazy promotion),
-instances taken from and returned to a shared idle pool (4.2), the admission test by simulated
-future KV size (4.4) and by the chunk size that can be kept for the whole prefill with the wait
-for the instance's current iteration included (4.5, 4.6), and the deadline-based SLO of Sec. 2.3:
+one cluster of instances per TPOT tier (4.2 request binning), requests sent to the highest-load
+instance that still meets the SLO so that a load gradient forms (4.3), looser-tier requests
+allowed onto tighter-tier instances only when their own cluster is full (4.4 lazy promotion),
+instances taken from and returned to a shared idle pool (4.3), the admission test by simulated
+future KV size (4.5) and by the chunk size that can be kept for the whole prefill with the wait
+for the instance's current iteration included (4.6, 4.7), and the deadline-based SLO of Sec. 2.3:
 token i of a request (i = 0 the first token) is due at arrival + TTFT + i * TPOT.
 
 Readings fixed where the text is loose:

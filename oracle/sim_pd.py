@@ -1,21 +1,21 @@
 """Cluster simulator for the paper's policy on prefill-decode disaggregated instances
 (test infrastructure; plain and slow on purpose).  The co-located variant is in sim.py; the clock,
 the deadline-based SLO (Sec. 2.3), the decode clusters per TPOT tier with highest-load-first
-placement, lazy promotion, idle pool and parking (Sec. 4.1-4.3) are the same here.  What differs:
+placement, lazy promotion, idle pool and parking (Sec. 4.2-4.4) are the same here.  What differs:
 
   * prefill runs on a cluster of its own that serves all tiers; queued requests are taken in order
-    of their first-token deadline, arrival + TTFT (Sec. 4.1); a prefill instance forms its
-    iterations by dynamic chunking with a token budget (Sec. 4.6: a request whose remaining length
+    of their first-token deadline, arrival + TTFT (Sec. 4.2); a prefill instance forms its
+    iterations by dynamic chunking with a token budget (Sec. 4.7: a request whose remaining length
     is below twice the budget is finished at once and closes the iteration); a request goes to the
     prefill instance with most queued prompt tokens that is still predicted to deliver its first
     token in time, counting the iterations of the requests already there and the wait for the one
-    in flight (Sec. 4.6), else to a new instance from the idle pool;
+    in flight (Sec. 4.7), else to a new instance from the idle pool;
   * when its prefill ends the request has its first token and its KV cache and queues for a decode
     instance of its tier (the transfer itself takes no time here: the paper gives none);
   * a decode instance admits it if the iteration time predicted for the largest future KV size
-    stays below the instance's TPOT, that KV size is below the capacity (Sec. 4.4), and the wait for
+    stays below the instance's TPOT, that KV size is below the capacity (Sec. 4.5), and the wait for
     the iteration in flight plus that iteration time still meets the deadline of the request's
-    second token, arrival + TTFT + TPOT (Sec. 4.5).
+    second token, arrival + TTFT + TPOT (Sec. 4.6).
 
 Readings fixed where the text is loose (beyond those of sim.py):
   * step order: ended iterations, arrivals, scale-down check, decode queues (tightest first, first

@@ -57,6 +57,15 @@ __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)
 // wavefront that also waited for activations (from L2, quickly) would wait for every weight load
 // issued before them (from HBM, slowly).  Stages of two k-blocks, one barrier per stage.
 // ------------------------------------------------------------------------------------------
+// The consumers' plain LDS reads are ordered against the producer wavefront's global_load_lds copies by the
+// hardware barrier alone.  The builtin is no memory fence for the compiler, which could move an LDS read across
+// it: the empty asm statements with a memory clobber pin the reads to their side without emitting any wait.
+__device__ __forceinline__ void ws_barrier() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 template <int MT, int KIND, int NG>
 __global__ __launch_bounds__(64 * (4 * NG + 1)) void gemm_wstream_kernel(GemmParams p) {
     constexpr int NCW = 4 * NG;        // computing wavefronts: four per group of 64 columns, NG groups share the activation ring
@@ -119,7 +128,7 @@ __global__ __launch_bounds__(64 * (4 * NG + 1)) void gemm_wstream_kernel(GemmPar
     uint4 w[WSETS][2];
 #pragma unroll
     for (int s = 0; s < WSETS - 1; s++) load_w(w[s], s);
-    __builtin_amdgcn_s_barrier();  // activation stages 0 and 1 are in their slots
+    ws_barrier();  // activation stages 0 and 1 are in their slots
 
 #define PS_WSHARE_PHASE(I, SG)                                                                                  \
     {                                                                                                           \
@@ -132,7 +141,7 @@ __global__ __launch_bounds__(64 * (4 * NG + 1)) void gemm_wstream_kernel(GemmPar
             _Pragma("unroll") for (int mt = 0; mt < MT; mt++)                                                   \
                 acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(w[(I)][q]), as_bf16x8(x_[q][mt]), acc[mt], 0, 0, 0); \
         slot = slot == 2 ? 0 : slot + 1;                                                                        \
-        __builtin_amdgcn_s_barrier();                                                                           \
+        ws_barrier();                                                                                           \
     }
     int slot = 0, s = 0;
     for (; s + WSETS <= n_st; s += WSETS) {
@@ -151,13 +160,13 @@ __global__ __launch_bounds__(64 * (4 * NG + 1)) void gemm_wstream_kernel(GemmPar
         // column tiles 0, 1 = gate, tiles 2, 3 = up of the same 32 features: wavefronts 2 and 3 of a group hand their sums over
         float4* up4 = reinterpret_cast<float4*>(lds);  // [group in block][cw - 2][mt][lane]
         const int gi = wave / 4;
-        __builtin_amdgcn_s_barrier();                  // the ring is free: the producer's last copies have landed
+        ws_barrier();                                  // the ring is free: the producer's last copies have landed
         if (cw >= 2) {
 #pragma unroll
             for (int mt = 0; mt < MT; mt++) up4[((gi * 2 + cw - 2) * MT + mt) * 64 + lane] = float4{acc[mt][0], acc[mt][1], acc[mt][2], acc[mt][3]};
         }
         __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the LDS writes have been made before the barrier
-        __builtin_amdgcn_s_barrier();
+        ws_barrier();
         if (cw >= 2 || !have_group) return;
         bf16_t* out = static_cast<bf16_t*>(p.out);
         const int F = p.N >> 1;

@@ -1,12 +1,12 @@
 // Cluster simulator for the paper's router on co-located (chunked-prefill) serving instances
 // (Sec. 5.1: instances advance in 1 ms steps with iteration times taken from the
-// (batch size, KV cache size) -> time table; Sec. 4.1-4.6: one cluster per TPOT tier, highest-load
+// (batch size, KV cache size) -> time table; Sec. 4.2-4.7: one cluster per TPOT tier, highest-load
 // instance first, lazy promotion onto tighter tiers, scaling from and to an idle pool, admission by
 // predicted future KV size and by the chunk size that can be kept for the whole prefill with the wait
 // for the iteration in flight; Sec. 2.3: token i of a request is due at arrival + TTFT + i * TPOT).
 // A second simulator does the same for prefill-decode disaggregated instances: a prefill cluster shared by
 // all tiers that takes requests in first-token-deadline order and forms iterations by dynamic chunking
-// (Sec. 4.1, 4.6), and decode clusters per tier with the wait-time-aware admission of Sec. 4.5.
+// (Sec. 4.2, 4.7), and decode clusters per tier with the wait-time-aware admission of Sec. 4.6.
 // Host only.  The decisions themselves are the ones exported by policy.cpp.
 #include <algorithm>
 #include <cstdint>
@@ -95,7 +95,7 @@ struct Cluster {
         done++;
     }
 
-    // Sec. 4.2, 4.3: the request's own cluster, then the clusters of tighter tiers from the nearest one (lazy promotion),
+    // Sec. 4.3, 4.4: the request's own cluster, then the clusters of tighter tiers from the nearest one (lazy promotion),
     // each from the most loaded instance down; then scale-up: a parked instance whose tightest request is of this tier,
     // else one from the idle pool.  admit(instance, tier it would serve, request) returns 0 for "no", else a value that
     // is handed back through *granted.
@@ -346,7 +346,7 @@ struct SimPD : Cluster {
     }
 
     // Would r, queued behind the requests already on s, get its first token in time, and would they still get theirs
-    // (Sec. 4.6: the iterations of the requests already there and the wait for the one in flight count; dynamic
+    // (Sec. 4.7: the iterations of the requests already there and the wait for the one in flight count; dynamic
     // chunking lets a later request share the iteration of an earlier one's last chunk and so lengthens it)?
     bool prefill_admits(const Instance& s, const Request& r, int64_t now) {
         rem.clear();
@@ -386,7 +386,7 @@ struct SimPD : Cluster {
         return true;
     }
 
-    // Sec. 4.4, 4.5: the largest future KV size keeps the iteration below the TPOT of the tier served, fits the memory,
+    // Sec. 4.5, 4.6: the largest future KV size keeps the iteration below the TPOT of the tier served, fits the memory,
     // and the wait for the iteration in flight plus that iteration still meets the request's second-token deadline
     bool decode_admits(const Instance& s, int32_t tier, const Request& r, int64_t now) {
         run.clear();
@@ -435,7 +435,7 @@ struct SimPD : Cluster {
                 reqs[i].phase = HANDED_OVER;
                 decode_queues[reqs[i].tier].push_back(i);
             });
-            // arrivals, kept in order of first-token deadline (Sec. 4.1)
+            // arrivals, kept in order of first-token deadline (Sec. 4.2)
             while (next_arrival < n && reqs[next_arrival].arrival <= (double)now) prefill_queue.push_back(next_arrival++);
             std::sort(prefill_queue.begin(), prefill_queue.end(), [this](int32_t a, int32_t b) {
                 const double da = reqs[a].arrival + reqs[a].ttft, db = reqs[b].arrival + reqs[b].ttft;

@@ -150,7 +150,7 @@ def custom_batch(model, seed, chunk, chunk_prefix, decode_kv, name="custom", tag
 
 def multi_batch(model, seed, chunks, decode_kv, name="multi", tag=0):
     """Several prefill chunks in one iteration (the budget shared by more than one prefill request,
-    Sec. 4.6 of the paper's dynamic-chunking discussion) plus decodes.  chunks: (n_new, prefix) per
+    Sec. 4.7 of the paper's dynamic-chunking discussion) plus decodes.  chunks: (n_new, prefix) per
     prefill request; decode_kv: KV length after the step per decode request.  The order is the one
     given: chunks first, then decodes."""
     rng = np.random.Generator(np.random.PCG64([int(seed), 15485863, int(tag), 1]))

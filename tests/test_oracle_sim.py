@@ -1,5 +1,5 @@
 """Pins of the cluster simulator's oracle: hand-computed timelines, capacity bounds that follow from
-the admission formulas, the placement order of Sec. 4.2/4.3 on constructed clusters, and invariants
+the admission formulas, the placement order of Sec. 4.3/4.4 on constructed clusters, and invariants
 of the deadline-based SLO (Sec. 2.3) on random traces."""
 import math
 

@@ -1,6 +1,6 @@
 """Pins of the prefill-decode disaggregated simulator's oracle: hand-computed timelines for dynamic chunking
-(Sec. 4.6), deadline order of the prefill queue (Sec. 4.1), load-based choice of the prefill instance, the
-wait-time-aware decode admission (Sec. 4.5), the hand-over, and invariants on random traces."""
+(Sec. 4.7), deadline order of the prefill queue (Sec. 4.2), load-based choice of the prefill instance, the
+wait-time-aware decode admission (Sec. 4.6), the hand-over, and invariants on random traces."""
 import numpy as np
 
 from oracle import policy, sim_pd
