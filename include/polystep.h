@@ -198,6 +198,24 @@ ps_status ps_kv_read(ps_ctx* ctx, int32_t layer, const ps_seq* seq, int32_t pos0
  * or the pool is missing; on any error nothing has been launched. */
 ps_status ps_step(ps_ctx* ctx, const ps_seq* seqs, int32_t n_seqs, const void* x_in, void* x_out, ps_step_stats* stats);
 
+/* The same step for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  ps_step_static runs exactly the kernels of ps_step, but every buffer
+ * beyond x_in and x_out (normalised activations, queries, attention output, gated activation, the fp32
+ * residual stream, GEMM and attention split partials, the device copy of the step's integer metadata) is a
+ * piece of one device array of PS_STATIC_SCRATCH_BYTES that is part of the library image: each GPU the
+ * library runs on holds that array from the moment the library is loaded until the process ends.  The call
+ * makes no hipMalloc / hipFree / hipHostMalloc and creates no stream or event (the pinned metadata ring and its
+ * events are made by ps_create); host-side planning arrays live on the process heap.  Results are
+ * bit-identical to ps_step's for the same batch and options.
+ * Limits: the buffers of the step must fit the array and its metadata 512 KiB, otherwise PS_ERANGE and nothing
+ * is launched (an 8B-shaped layer fits about 200 decode tokens with a few hundred thousand cached tokens; a
+ * message states the bytes needed).  No per-stage statistics.  All contexts of a process on one GPU share
+ * that GPU's array, which keeps the previous call's contents (nothing in it has to start at zero): static
+ * steps that overlap on one GPU -- two contexts on different streams -- race and must be serialised by the
+ * caller; steps on one stream are ordered by the stream.  Other errors as ps_step. */
+#define PS_STATIC_SCRATCH_BYTES (64u << 20)
+ps_status ps_step_static(ps_ctx* ctx, const ps_seq* seqs, int32_t n_seqs, const void* x_in, void* x_out);
+
 /* ---- whole model (Sec. 2.1: a request's tokens go in, the next token comes out) ----- */
 
 /* What surrounds the layer stack.  Device pointers, bf16: embedding [vocab][hidden] (row = token

@@ -24,6 +24,7 @@ STATUS_NAMES = ["PS_OK", "PS_EINVAL", "PS_ERANGE", "PS_ENOMEM", "PS_ESTATE", "PS
 PS_PAGE_SIZE = 16
 PS_N_STAGES = 8
 PS_GRID_MAX_DRAWS = 8
+PS_STATIC_SCRATCH_BYTES = 64 << 20
 PS_FLAG_HOST_ONLY = 1
 STAGE_NAMES = ["rmsnorm_attn", "gemm_qkv", "rope_append", "attention", "gemm_o", "rmsnorm_ffn", "gemm_gate_up", "gemm_down"]
 
@@ -112,6 +113,7 @@ _SIGS = {
     "ps_kv_write": (C.c_int, [_P, C.c_int32, C.POINTER(ps_seq), C.c_int32, C.c_int32, _P, _P]),
     "ps_kv_read": (C.c_int, [_P, C.c_int32, C.POINTER(ps_seq), C.c_int32, C.c_int32, _P, _P]),
     "ps_step": (C.c_int, [_P, C.POINTER(ps_seq), C.c_int32, _P, _P, C.POINTER(ps_step_stats)]),
+    "ps_step_static": (C.c_int, [_P, C.POINTER(ps_seq), C.c_int32, _P, _P]),
     "ps_init_head": (C.c_int, [_P, C.POINTER(ps_head_weights)]),
     "ps_step_tokens": (C.c_int, [_P, C.POINTER(ps_seq), C.c_int32, _I32P, _P, _P, _P, C.POINTER(ps_step_stats), C.POINTER(C.c_float)]),
     "ps_step_indices": (C.c_int, [_P, C.POINTER(ps_seq), C.c_int32, _I32P, _I32P, _I32P]),
@@ -239,6 +241,10 @@ class Context:
         self._check(lib.ps_step(self.handle, sa.array, sa.n, _P(x_in_ptr), _P(x_out_ptr),
                                 C.byref(stats) if want_stats else None))
         return stats
+
+    def step_static(self, seqs, x_in_ptr, x_out_ptr):
+        sa = seqs if isinstance(seqs, SeqArray) else SeqArray(seqs)
+        self._check(lib.ps_step_static(self.handle, sa.array, sa.n, _P(x_in_ptr), _P(x_out_ptr)))
 
     def init_head(self, embedding, g_final, w_out, vocab):
         w = ps_head_weights(int(embedding), int(g_final), int(w_out), int(vocab))

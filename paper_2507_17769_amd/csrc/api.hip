@@ -4,6 +4,7 @@
 #include <cmath>
 #include <cstring>
 #include <deque>
+#include <mutex>
 #include <new>
 
 #include "planner.h"
@@ -96,12 +97,30 @@ struct ps_ctx {
     std::vector<hipEvent_t> attn_ev;  // ring of 2 * ATTN_EV_PAIRS events
     int attn_ev_count = 0;            // pairs recorded since the last ps_attention_times
 
+    // ps_step_static: this device's copy of the scratch array, a pinned ring for the metadata (allocated by ps_create)
+    unsigned char* static_scratch = nullptr;
+    char* static_host = nullptr;
+    hipEvent_t static_ev[4] = {nullptr, nullptr, nullptr, nullptr};
+    bool static_pending[4] = {false, false, false, false};
+    int static_next = 0;
+
     hipEvent_t ev[PS_N_STAGES * 2 + 2] = {};
     bool have_events = false;
     StepPlan plan;
 };
 
 static constexpr int ATTN_EV_PAIRS = 2048;
+
+// Scratch of ps_step_static: workspaces, GEMM and attention partials and the step's metadata, carved out of one
+// file-scope device array instead of hipMalloc'ed buffers.  Every device the library runs on holds its own copy of
+// the array at its own address; `scratch` itself is only a host-side handle, so the address is asked for once per
+// device (ps_create, with that device current) and kept.
+static __device__ __align__(256) unsigned char scratch[PS_STATIC_SCRATCH_BYTES];
+static constexpr int MAX_DEVICES = 64;
+static void* g_scratch_addr[MAX_DEVICES] = {};
+static std::mutex g_scratch_mutex;
+static constexpr size_t STATIC_META_SLOT = 512u << 10;  // bytes of step metadata one static step may carry
+static constexpr int STATIC_META_SLOTS = 4;             // pinned host ring
 static thread_local std::string g_create_err;
 
 static ps_status fail(ps_ctx* c, ps_status s, const std::string& msg) {
@@ -195,6 +214,28 @@ extern "C" ps_status ps_create(const ps_model_desc* desc, void* hip_stream, ps_c
     hipError_t e = hipMemcpy(c->rope_cs, cs.data(), cs.size() * sizeof(float), hipMemcpyHostToDevice);
     if (e != hipSuccess) { ps_destroy(c); return hip_fail(nullptr, e, "hipMemcpy(rotary table)"); }
     c->worker_slots = attention_worker_slots();
+    {   // set-up for ps_step_static, so that the entry point itself never allocates
+        int dev = 0;
+        e = hipGetDevice(&dev);
+        if (e != hipSuccess) { ps_destroy(c); return hip_fail(nullptr, e, "hipGetDevice"); }
+        if (dev < 0 || dev >= MAX_DEVICES) { ps_destroy(c); return fail(nullptr, PS_ERANGE, "ps_create: device index above 63"); }
+        {
+            std::lock_guard<std::mutex> lock(g_scratch_mutex);
+            if (!g_scratch_addr[dev]) {
+                void* addr = nullptr;
+                e = hipGetSymbolAddress(&addr, HIP_SYMBOL(scratch));
+                if (e != hipSuccess || !addr) { ps_destroy(c); return hip_fail(nullptr, e, "hipGetSymbolAddress(scratch)"); }
+                g_scratch_addr[dev] = addr;
+            }
+            c->static_scratch = static_cast<unsigned char*>(g_scratch_addr[dev]);
+        }
+        e = hipHostMalloc(reinterpret_cast<void**>(&c->static_host), STATIC_META_SLOT * STATIC_META_SLOTS, hipHostMallocDefault);
+        if (e != hipSuccess) { (void)hipGetLastError(); c->static_host = nullptr; ps_destroy(c); return fail(nullptr, PS_ENOMEM, "ps_create: pinned metadata ring"); }
+        for (auto& ev : c->static_ev) {
+            e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+            if (e != hipSuccess) { ps_destroy(c); return hip_fail(nullptr, e, "hipEventCreate"); }
+        }
+    }
     *out = c;
     return PS_OK;
 }
@@ -204,6 +245,7 @@ extern "C" ps_status ps_sync(ps_ctx* c) {
     if (c->host_only) return PS_OK;
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     c->half_pending[0] = c->half_pending[1] = false;
+    for (bool& b : c->static_pending) b = false;
     return PS_OK;
 }
 
@@ -236,6 +278,8 @@ extern "C" void ps_destroy(ps_ctx* c) {
             if (s.host) (void)hipHostFree(s.host);
         for (auto& e : c->half_done)
             if (e) (void)hipEventDestroy(e);
+        if (c->static_host) (void)hipHostFree(c->static_host);
+        for (auto& e : c->static_ev) if (e) (void)hipEventDestroy(e);
         if (c->have_events) for (auto& e : c->ev) if (e) (void)hipEventDestroy(e);
         for (auto& e : c->attn_ev) if (e) (void)hipEventDestroy(e);
     }
@@ -454,6 +498,22 @@ static ps_status staging_commit(ps_ctx* c, int index) {
     return PS_OK;
 }
 
+// Between staging_acquire and staging_commit a call may fail (a HIP error, an allocation) after copies and kernels
+// that read the slot have been enqueued.  The guard then waits for both streams and forgets the pending halves, so
+// that the next pass through the ring cannot overwrite buffers that are still being read.
+struct StagingGuard {
+    ps_ctx* c;
+    bool committed = false;
+    explicit StagingGuard(ps_ctx* ctx) : c(ctx) {}
+    ~StagingGuard() {
+        if (committed) return;
+        (void)hipStreamSynchronize(c->stream);
+        if (c->copy_stream) (void)hipStreamSynchronize(c->copy_stream);
+        c->half_pending[0] = c->half_pending[1] = false;
+        for (bool& b : c->static_pending) b = false;
+    }
+};
+
 // Copy `bytes` of staging slot `index` to its device slot on the copy stream and make the main
 // stream wait for it.  *dev receives the device address.
 static ps_status upload_meta(ps_ctx* c, const Staging* sg, int index, size_t bytes, const char** dev) {
@@ -498,6 +558,7 @@ static ps_status kv_copy(ps_ctx* c, bool to_pool, int32_t layer, const ps_seq* s
     int s_idx = 0;
     ps_status st = staging_acquire(c, (size_t)n * 4, &s, &s_idx);
     if (st != PS_OK) return st;
+    StagingGuard guard(c);
     int32_t* slots = static_cast<int32_t*>(s->host);
     for (int i = 0; i < n; i++) {
         const int p = pos0 + i;
@@ -508,7 +569,8 @@ static ps_status kv_copy(ps_ctx* c, bool to_pool, int32_t layer, const ps_seq* s
     bf16_t* slot_base = c->pool + (size_t)(layer % c->n_kv_slots) * c->slot_elems;
     HIP_TRY(c, launch_kv_copy(to_pool, slot_base, reinterpret_cast<const int32_t*>(dslots), n, pos0 & 3, c->desc.n_kv_heads,
                               c->desc.head_dim, static_cast<bf16_t*>(k), static_cast<bf16_t*>(v), c->stream));
-    return staging_commit(c, s_idx);
+    if ((st = staging_commit(c, s_idx)) == PS_OK) guard.committed = true;
+    return st;
 }
 
 extern "C" ps_status ps_kv_write(ps_ctx* c, int32_t layer, const ps_seq* seq, int32_t pos0, int32_t n, const void* k, const void* v) {
@@ -644,8 +706,48 @@ struct TokenIO {
     float* ms;                 // host [3] or null: embedding, stack, head (needs stats-style synchronisation)
 };
 
+// Device buffers of one step besides its inputs and outputs: the library's growing workspaces (ps_step,
+// ps_step_tokens) or pieces of the static scratch array (ps_step_static).
+struct StepBufs {
+    bf16_t *xn = nullptr, *q = nullptr, *attn = nullptr, *act = nullptr;
+    float *x1 = nullptr, *xmid = nullptr, *part = nullptr, *part_o = nullptr, *part_ml = nullptr;
+    size_t part_bytes = 0, act_bytes = 0;
+    char* meta = nullptr;  // static steps only: device copy of the metadata
+};
+
+// Lay the buffers of a step of T tokens out in the static scratch array.  Nothing is allocated: a step whose buffers
+// do not fit PS_STATIC_SCRATCH_BYTES is refused.
+static ps_status carve_static(ps_ctx* c, int T, int n_part_slots, size_t meta_bytes, StepBufs* w) {
+    const ps_model_desc& d = c->desc;
+    const int H = d.hidden, F = d.ffn, NQ = d.n_q_heads * d.head_dim, NQKV = qkv_cols(d);
+    const size_t T16 = (size_t)((T + 15) & ~15);
+    size_t at = 0;
+    auto take = [&](size_t bytes) { const size_t o = at; at = (at + bytes + 255) & ~(size_t)255; return o; };
+    const size_t o_xn = take(T16 * H * 2), o_q = take((size_t)T * NQ * 2), o_attn = take(T16 * NQ * 2);
+    w->act_bytes = gemm_out_bytes(T, 2 * F, H, GemmOut::SWIGLU_BF16, 0, 0);
+    const size_t o_act = take(w->act_bytes), o_x1 = take((size_t)T * H * 4), o_xmid = take(d.n_layers > 1 ? (size_t)T * H * 4 : 0);
+    w->part_bytes = gemm_out_bytes(T, NQKV, H, GemmOut::PARTIAL_F32, c->opt_gemm_split_k, c->opt_gemm_tile);
+    w->part_bytes = std::max(w->part_bytes, gemm_out_bytes(T, H, NQ, GemmOut::PARTIAL_F32, c->opt_gemm_split_k, c->opt_gemm_tile));
+    w->part_bytes = std::max(w->part_bytes, gemm_out_bytes(T, H, F, GemmOut::PARTIAL_F32, c->opt_gemm_split_k, c->opt_gemm_tile));
+    const size_t o_part = take(w->part_bytes);
+    const size_t o_po = take((size_t)n_part_slots * 16 * d.head_dim * 4), o_pml = take((size_t)n_part_slots * 16 * 2 * 4);
+    const size_t o_meta = take(meta_bytes);
+    if (meta_bytes > STATIC_META_SLOT)
+        return fail(c, PS_ERANGE, "ps_step_static: the step's metadata (" + std::to_string(meta_bytes) + " bytes: positions, page lists, attention work list) exceeds " +
+                                      std::to_string(STATIC_META_SLOT) + " bytes; use ps_step for batches of this size");
+    if (at > (size_t)PS_STATIC_SCRATCH_BYTES)
+        return fail(c, PS_ERANGE, "ps_step_static: the step needs " + std::to_string(at) + " bytes of scratch, the static array holds " +
+                                      std::to_string((size_t)PS_STATIC_SCRATCH_BYTES) + "; use ps_step for batches of this size");
+    unsigned char* b = c->static_scratch;
+    w->xn = reinterpret_cast<bf16_t*>(b + o_xn); w->q = reinterpret_cast<bf16_t*>(b + o_q); w->attn = reinterpret_cast<bf16_t*>(b + o_attn);
+    w->act = reinterpret_cast<bf16_t*>(b + o_act); w->x1 = reinterpret_cast<float*>(b + o_x1); w->xmid = reinterpret_cast<float*>(b + o_xmid);
+    w->part = reinterpret_cast<float*>(b + o_part); w->part_o = reinterpret_cast<float*>(b + o_po); w->part_ml = reinterpret_cast<float*>(b + o_pml);
+    w->meta = reinterpret_cast<char*>(b + o_meta);
+    return PS_OK;
+}
+
 static ps_status step_impl(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const void* x_in, void* x_out, ps_step_stats* stats,
-                           const TokenIO* tio) {
+                           const TokenIO* tio, bool use_static = false) {
     if (!c) return PS_EINVAL;
     if (c->host_only) return fail(c, PS_ESTATE, "ps_step: host-only context");
     if (!c->pool) return fail(c, PS_ESTATE, "ps_step: no KV pool (call ps_kv_alloc)");
@@ -680,14 +782,34 @@ static ps_status step_impl(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const 
     c->step_counter++;
     const ps_model_desc& d = c->desc;
     const int T = p.n_tokens, H = d.hidden, F = d.ffn, NQ = d.n_q_heads * d.head_dim, NQKV = qkv_cols(d);
-    if ((st = ensure_workspaces(c, T, p.n_partial_slots)) != PS_OK) return st;
+    const MetaLayout ml = meta_layout(p, tio != nullptr);
+    StepBufs W;
+    if (use_static) {
+        if ((st = carve_static(c, T, p.n_partial_slots, ml.total, &W)) != PS_OK) return st;
+    } else {
+        if ((st = ensure_workspaces(c, T, p.n_partial_slots)) != PS_OK) return st;
+        W.xn = c->ws_xn; W.q = c->ws_q; W.attn = c->ws_attn; W.act = c->ws_act; W.x1 = c->ws_x1; W.xmid = c->ws_xmid;
+        W.part = c->ws_part; W.part_o = c->part_o; W.part_ml = c->part_ml; W.part_bytes = c->part_bytes; W.act_bytes = c->act_bytes;
+    }
 
     // one pinned buffer, one host-to-device copy for all of the step's integer metadata
-    const MetaLayout ml = meta_layout(p, tio != nullptr);
-    Staging* sg;
+    Staging* sg = nullptr;
     int sg_idx = 0;
-    if ((st = staging_acquire(c, ml.total, &sg, &sg_idx)) != PS_OK) return st;
-    char* hb = static_cast<char*>(sg->host);
+    char* hb = nullptr;
+    if (use_static) {
+        // slot of the pinned ring made at ps_create; its previous copy (four static steps ago) must have been made
+        sg_idx = c->static_next;
+        c->static_next = (sg_idx + 1) % STATIC_META_SLOTS;
+        if (c->static_pending[sg_idx]) {
+            HIP_TRY(c, hipEventSynchronize(c->static_ev[sg_idx]));
+            c->static_pending[sg_idx] = false;
+        }
+        hb = c->static_host + (size_t)sg_idx * STATIC_META_SLOT;
+    } else {
+        if ((st = staging_acquire(c, ml.total, &sg, &sg_idx)) != PS_OK) return st;
+        hb = static_cast<char*>(sg->host);
+    }
+    StagingGuard guard(c);
     memcpy(hb + ml.positions, p.positions.data(), p.positions.size() * 4);
     memcpy(hb + ml.slots, p.slots.data(), p.slots.size() * 4);
     memcpy(hb + ml.seqs, p.seqs.data(), p.seqs.size() * sizeof(SeqInfo));
@@ -701,7 +823,13 @@ static ps_status step_impl(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const 
         for (int i = 0; i < p.n_seqs; i++) lr[i] = p.cu_seqlens[i + 1] - 1;
     }
     const char* db = nullptr;
-    if ((st = upload_meta(c, sg, sg_idx, ml.total, &db)) != PS_OK) return st;
+    if (use_static) {
+        // on the step's own stream: ordered behind the kernels of the previous step, which read the same device copy
+        HIP_TRY(c, hipMemcpyAsync(W.meta, hb, ml.total, hipMemcpyHostToDevice, c->stream));
+        HIP_TRY(c, hipEventRecord(c->static_ev[sg_idx], c->stream));
+        c->static_pending[sg_idx] = true;
+        db = W.meta;
+    } else if ((st = upload_meta(c, sg, sg_idx, ml.total, &db)) != PS_OK) return st;
     const int32_t* d_pos = reinterpret_cast<const int32_t*>(db + ml.positions);
     const int32_t* d_slots = reinterpret_cast<const int32_t*>(db + ml.slots);
 
@@ -740,24 +868,24 @@ static ps_status step_impl(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const 
         int e = 0, n_splits = 1;
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[e], s));
         // 0: RMSNorm of the layer input (layers after the first get it from the previous layer's last kernel)
-        if (l == l_begin) HIP_TRY(c, launch_rmsnorm(x_cur, x_cur_f32, L.g_attn, c->ws_xn, T, H, d.rms_eps, s));
-        if (tap && c->taps.xn) HIP_TRY(c, launch_untile(c->ws_xn, static_cast<bf16_t*>(c->taps.xn), T, H, s));
+        if (l == l_begin) HIP_TRY(c, launch_rmsnorm(x_cur, x_cur_f32, L.g_attn, W.xn, T, H, d.rms_eps, s));
+        if (tap && c->taps.xn) HIP_TRY(c, launch_untile(W.xn, static_cast<bf16_t*>(c->taps.xn), T, H, s));
         if (tap && c->taps.x_in && l > l_begin) HIP_TRY(c, launch_copy_bytes(x_cur, c->taps.x_in, (size_t)T * H * 4, s));
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
         // 1: QKV projection -> fp32 partials
         GemmArgs g{};
-        g.A = c->ws_xn; g.Wp = L.wqkv_t; g.M = T; g.N = NQKV; g.K = H; g.kind = GemmOut::PARTIAL_F32;
-        g.out = c->ws_part; g.out_bytes = c->part_bytes; g.split_k = c->opt_gemm_split_k; g.tile = c->opt_gemm_tile;
+        g.A = W.xn; g.Wp = L.wqkv_t; g.M = T; g.N = NQKV; g.K = H; g.kind = GemmOut::PARTIAL_F32;
+        g.out = W.part; g.out_bytes = W.part_bytes; g.split_k = c->opt_gemm_split_k; g.tile = c->opt_gemm_tile;
         HIP_TRY(c, launch_gemm(g, &n_splits, s));
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
         // 2: sum the partials, rotate, round once to bf16, append k/v to the pages
-        HIP_TRY(c, launch_rope_append(c->ws_part, n_splits, c->ws_q, T, d.n_q_heads, d.n_kv_heads, d.head_dim, d_pos,
+        HIP_TRY(c, launch_rope_append(W.part, n_splits, W.q, T, d.n_q_heads, d.n_kv_heads, d.head_dim, d_pos,
                                       d_slots, c->rope_cs, pool_slot, s));
-        if (tap && c->taps.q) HIP_TRY(c, launch_copy_bytes(c->ws_q, c->taps.q, (size_t)T * NQ * 2, s));
+        if (tap && c->taps.q) HIP_TRY(c, launch_copy_bytes(W.q, c->taps.q, (size_t)T * NQ * 2, s));
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
         // 3: attention
         AttnArgs a{};
-        a.q = c->ws_q; a.ldq = NQ; a.pool_slot = pool_slot;
+        a.q = W.q; a.ldq = NQ; a.pool_slot = pool_slot;
         a.seqs = reinterpret_cast<const SeqInfo*>(db + ml.seqs);
         a.pages = reinterpret_cast<const int32_t*>(db + ml.pages);
         a.items = reinterpret_cast<const AttnItem*>(db + ml.items);
@@ -772,7 +900,7 @@ static ps_status step_impl(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const 
             a.max_splits = std::max(a.max_splits, (int)mg.n_splits);
             a.max_merge_rows = std::max(a.max_merge_rows, (int)mg.n_tok * (d.n_q_heads / d.n_kv_heads));
         }
-        a.part_o = c->part_o; a.part_ml = c->part_ml; a.out = c->ws_attn;
+        a.part_o = W.part_o; a.part_ml = W.part_ml; a.out = W.attn;
         a.n_q = d.n_q_heads; a.n_kv = d.n_kv_heads; a.d = d.head_dim;
         const bool time_attn = c->opt_time_attention > 0 && c->attn_ev_count < ATTN_EV_PAIRS &&
                                (c->step_counter % c->opt_time_attention) == 0;
@@ -780,42 +908,42 @@ static ps_status step_impl(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const 
         a.ev_end = time_attn ? c->attn_ev[2 * c->attn_ev_count + 1] : nullptr;
         HIP_TRY(c, launch_attention(a, s));
         if (time_attn) c->attn_ev_count++;
-        if (tap && c->taps.attn) HIP_TRY(c, launch_untile(c->ws_attn, static_cast<bf16_t*>(c->taps.attn), T, NQ, s));
+        if (tap && c->taps.attn) HIP_TRY(c, launch_untile(W.attn, static_cast<bf16_t*>(c->taps.attn), T, NQ, s));
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
         // 4: O projection -> fp32 partials
-        g.A = c->ws_attn; g.Wp = L.wo_t; g.N = H; g.K = NQ;
+        g.A = W.attn; g.Wp = L.wo_t; g.N = H; g.K = NQ;
         HIP_TRY(c, launch_gemm(g, &n_splits, s));
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
         // 5: x1 = x + sum(partials) (fp32), xn = RMSNorm(x1)
         ReduceAddNormArgs r{};
-        r.resid = x_cur; r.resid_f32 = x_cur_f32; r.partials = c->ws_part; r.n_splits = n_splits; r.T = T; r.H = H;
-        r.x_f32 = c->ws_x1; r.x_bf16 = nullptr; r.gain = L.g_ffn; r.xn = c->ws_xn; r.eps = d.rms_eps;
+        r.resid = x_cur; r.resid_f32 = x_cur_f32; r.partials = W.part; r.n_splits = n_splits; r.T = T; r.H = H;
+        r.x_f32 = W.x1; r.x_bf16 = nullptr; r.gain = L.g_ffn; r.xn = W.xn; r.eps = d.rms_eps;
         HIP_TRY(c, launch_reduce_add_norm(r, s));
-        if (tap && c->taps.x1) HIP_TRY(c, launch_copy_bytes(c->ws_x1, c->taps.x1, (size_t)T * H * 4, s));
-        if (tap && c->taps.xn2) HIP_TRY(c, launch_untile(c->ws_xn, static_cast<bf16_t*>(c->taps.xn2), T, H, s));
+        if (tap && c->taps.x1) HIP_TRY(c, launch_copy_bytes(W.x1, c->taps.x1, (size_t)T * H * 4, s));
+        if (tap && c->taps.xn2) HIP_TRY(c, launch_untile(W.xn, static_cast<bf16_t*>(c->taps.xn2), T, H, s));
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
         // 6: gate/up + SwiGLU
-        g.A = c->ws_xn; g.Wp = L.wgu_t; g.N = 2 * F; g.K = H; g.kind = GemmOut::SWIGLU_BF16;
-        g.out = c->ws_act; g.out_bytes = c->act_bytes;
+        g.A = W.xn; g.Wp = L.wgu_t; g.N = 2 * F; g.K = H; g.kind = GemmOut::SWIGLU_BF16;
+        g.out = W.act; g.out_bytes = W.act_bytes;
         HIP_TRY(c, launch_gemm(g, nullptr, s));
-        if (tap && c->taps.act) HIP_TRY(c, launch_untile(c->ws_act, static_cast<bf16_t*>(c->taps.act), T, F, s));
+        if (tap && c->taps.act) HIP_TRY(c, launch_untile(W.act, static_cast<bf16_t*>(c->taps.act), T, F, s));
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
         // 7: down projection -> fp32 partials; out = x1 + sum(partials); for an inner layer also the
         //    next layer's normalised input
-        g.A = c->ws_act; g.Wp = L.wd_t; g.N = H; g.K = F; g.kind = GemmOut::PARTIAL_F32;
-        g.out = c->ws_part; g.out_bytes = c->part_bytes;
+        g.A = W.act; g.Wp = L.wd_t; g.N = H; g.K = F; g.kind = GemmOut::PARTIAL_F32;
+        g.out = W.part; g.out_bytes = W.part_bytes;
         HIP_TRY(c, launch_gemm(g, &n_splits, s));
-        r.resid = c->ws_x1; r.resid_f32 = true; r.n_splits = n_splits;
+        r.resid = W.x1; r.resid_f32 = true; r.n_splits = n_splits;
         if (last) {
             r.x_f32 = out_f32 ? static_cast<float*>(x_out) : nullptr;
             r.x_bf16 = out_f32 ? nullptr : static_cast<bf16_t*>(x_out);
             r.gain = nullptr; r.xn = nullptr;
         } else {
-            r.x_f32 = c->ws_xmid; r.x_bf16 = nullptr;
-            r.gain = c->layers[l + 1].g_attn; r.xn = c->ws_xn;
+            r.x_f32 = W.xmid; r.x_bf16 = nullptr;
+            r.gain = c->layers[l + 1].g_attn; r.xn = W.xn;
         }
         HIP_TRY(c, launch_reduce_add_norm(r, s));
-        void* x_next = last ? x_out : static_cast<void*>(c->ws_xmid);
+        void* x_next = last ? x_out : static_cast<void*>(W.xmid);
         if (tap && c->taps.x_out && (!last || out_f32))
             HIP_TRY(c, launch_copy_bytes(x_next, c->taps.x_out, (size_t)T * H * 4, s));
         if (stats) {
@@ -864,9 +992,9 @@ static ps_status step_impl(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const 
             }
             next = c->ws_next;
         }
-        HIP_TRY(c, launch_rmsnorm(x_out, true, c->g_final, c->ws_xn, M, H, d.rms_eps, s, reinterpret_cast<const int32_t*>(db + ml.last_rows)));
+        HIP_TRY(c, launch_rmsnorm(x_out, true, c->g_final, W.xn, M, H, d.rms_eps, s, reinterpret_cast<const int32_t*>(db + ml.last_rows)));
         GemmArgs g{};
-        g.A = c->ws_xn; g.Wp = c->wout_t; g.M = M; g.N = V; g.K = H; g.kind = GemmOut::PARTIAL_F32;
+        g.A = W.xn; g.Wp = c->wout_t; g.M = M; g.N = V; g.K = H; g.kind = GemmOut::PARTIAL_F32;
         g.out = logits; g.out_bytes = (size_t)M * V * sizeof(float);
         g.split_k = 1;  // one partial buffer: it is the logits
         g.tile = c->opt_gemm_tile;
@@ -880,7 +1008,14 @@ static ps_status step_impl(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const 
             for (int i = 0; i < 3; i++) HIP_TRY(c, hipEventElapsedTime(&tio->ms[i], c->ev_head[i], c->ev_head[i + 1]));
         }
     }
-    return staging_commit(c, sg_idx);
+    if (use_static) { guard.committed = true; return PS_OK; }
+    if ((st = staging_commit(c, sg_idx)) == PS_OK) guard.committed = true;
+    return st;
+}
+
+extern "C" ps_status ps_step_static(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const void* x_in, void* x_out) {
+    if (c && !c->host_only && !c->static_scratch) return fail(c, PS_ESTATE, "ps_step_static: the context has no static scratch");
+    return step_impl(c, seqs, n_seqs, x_in, x_out, nullptr, nullptr, true);
 }
 
 extern "C" ps_status ps_step(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const void* x_in, void* x_out, ps_step_stats* stats) {
@@ -1001,7 +1136,10 @@ extern "C" ps_status ps_profile_grid(ps_ctx* c, const ps_grid_cell_spec* cells, 
     if (opts->iters < 1 || opts->warmup < 0) return fail(c, PS_EINVAL, "ps_profile_grid: iters must be >= 1, warmup >= 0");
     hipEvent_t t0 = nullptr, t1 = nullptr;
     HIP_TRY(c, hipEventCreate(&t0));
-    HIP_TRY(c, hipEventCreate(&t1));
+    {
+        const hipError_t e1 = hipEventCreate(&t1);
+        if (e1 != hipSuccess) { (void)hipEventDestroy(t0); return hip_fail(c, e1, "hipEventCreate"); }
+    }
     ps_status rc = PS_OK;
     const int64_t id_base = INT64_MIN / 2;  // request ids of the synthetic sequences
     for (int ci = 0; ci < n_cells && rc == PS_OK; ci++) {
