@@ -1,11 +1,13 @@
 """Benchmark of the mixed-batch serving step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg1|cfg2|grid] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4|cfg1|cfg2|grid|...] [--no-cpu-baseline]
 
-A step is one pass of the whole layer (RMSNorm, QKV, rotary + KV append, paged attention,
+A step is one pass of the whole layer stack (per layer: RMSNorm, QKV, rotary + KV append, paged attention,
 O-projection, SwiGLU feed-forward) over one batch of synthetic input that is already resident
-in HBM.  The default workload is the decode-only batch (64 decode tokens, KV lengths uniform in
-[512, 4096], 8B-shaped layer).  Prints ONE JSON line.
+in HBM.  The default workload is the largest configuration that fits one GPU: the 70B-shaped stack of 80
+layers on a mixed batch (1024-token prefill chunk at prefix 4096 + 256 decodes).  The two single-layer
+8B-shaped configurations (64 decodes; 512-token chunk + 128 decodes) ride along as secondary records in the
+same line.  Step time = median of per-step HIP event pairs on the step's stream.  Prints ONE JSON line.
 
 --workload grid times the latency-profile grid instead (prefill chunk sizes x decode counts, five
 draws of the lengths per cell, median step time): the (batch size, KV cache size) -> iteration
@@ -29,9 +31,10 @@ NOMINAL_CLOCK_MHZ = 2400.0
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg1", choices=["cfg1", "cfg2", "grid", "cfg4", "model8b", "prefill", "profile", "sim"])
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-secondary", action="store_true", help="cfg4: leave out the secondary cfg1 / cfg2 records")
+    ap.add_argument("--workload", default="cfg4", choices=["cfg1", "cfg2", "grid", "cfg4", "model8b", "prefill", "profile", "sim"])
     ap.add_argument("--requests", type=int, default=20000, help="sim: requests per simulated run")
     ap.add_argument("--table", default=None, help="sim: JSON written by an earlier --workload sim run; its table is used instead of measuring")
     ap.add_argument("--layers", type=int, default=80, help="cfg4: number of decoder layers")
@@ -162,9 +165,71 @@ def run_grid(a):
                       "pool_pages": n_pool, "wall_s": round(wall, 2), "cells": out}))
 
 
+def percentiles(ms):
+    import numpy as np
+    return {"p10": round(float(np.percentile(ms, 10)), 4), "p50": round(float(np.percentile(ms, 50)), 4),
+            "p90": round(float(np.percentile(ms, 90)), 4), "mean": round(float(np.mean(ms)), 4)}
+
+
+def timed_steps(eng, call, steps, warmup):
+    """W untimed steps, then K steps each bracketed by an event pair on the stream the library launches on (torch's
+    current stream, handed to ps_create), the whole region bracketed by synchronisations.  call(i) enqueues step i.
+    Returns per-step GPU times (ms; consecutive pairs tile the stream's timeline, so an idle GPU waiting for the host
+    counts against the step), per-call host times (us) and the wall time of the region."""
+    import torch
+    for i in range(warmup):
+        call(i)
+    eng.ctx.sync()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    host_us = []
+    t0 = time.perf_counter()
+    for i in range(steps):
+        evs[i][0].record(eng.stream)
+        h0 = time.perf_counter()
+        call(warmup + i)
+        host_us.append((time.perf_counter() - h0) * 1e6)
+        evs[i][1].record(eng.stream)
+    eng.ctx.sync()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return [b0.elapsed_time(b1) for b0, b1 in evs], host_us, wall_ms
+
+
+def cpu_baseline_cfg4(batch, seed, n_layers):
+    """The oracle on ONE layer of the 70B-shaped stack at the full batch, times the number of layers (extrapolated:
+    the whole fp32 stack is 175 TFLOP and 137 GB of weights)."""
+    import numpy as np
+    from oracle import run as orun
+    from paper_2507_17769_amd import workloads as W
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    m = W.MODELS[batch.model]
+    w = W.layer_weights(batch.model, seed, 0)
+    pool = orun.make_pool(m, batch.n_pool_pages)
+    rng = np.random.Generator(np.random.PCG64([seed, 31415926]))
+    mp = max(s.prefix for s in batch.seqs)
+    k = W.normal_bf16(rng, (mp, m["n_kv"], m["head_dim"]))
+    v = W.normal_bf16(rng, (mp, m["n_kv"], m["head_dim"]))
+    for s in batch.seqs:
+        if s.prefix > 0:
+            pool.write_bits(0, [int(p) for p in s.pages], 0, k[:s.prefix], v[:s.prefix])
+    x = batch.activations()
+    t0 = time.perf_counter()
+    orun.run_step(m, [w], batch.seqs, x, pool)
+    t = time.perf_counter() - t0
+    return {"value": batch.n_tokens / (t * n_layers), "unit": "tokens/s", "cores": int(threads), "kind": "oracle", "extrapolated": True,
+            "sample": f"one layer of the {n_layers} at the full batch ({batch.n_tokens} tokens, {batch.total_kv} KV tokens), one run, "
+                      f"{t:.1f} s, numpy fp32; the step is taken as {n_layers} x that",
+            "ms_per_step": t * 1e3 * n_layers}
+
+
 def run_cfg4(a):
     """70B-shaped stack on one GPU: 80 layers (137 GB of bf16 weights, generated on the device),
-    1024-token chunk at prefix 4096 + 256 decodes, KV slots aliased across layers."""
+    1024-token chunk at prefix 4096 + 256 decodes, KV slots aliased across layers.  Returns the result record."""
     import numpy as np
     import torch
     from paper_2507_17769_amd import workloads as W
@@ -217,30 +282,44 @@ def run_cfg4(a):
     x = bits_to_dev(x_bits, eng.device)
     out = torch.empty_like(x)
     seqs = SeqArray(batch.seqs)
-    for _ in range(max(1, min(a.warmup, 2))):
-        eng.ctx.step(seqs, x.data_ptr(), out.data_ptr())
-    eng.ctx.sync()
-    steps = max(1, min(a.steps, 5))
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        eng.ctx.step(seqs, x.data_ptr(), out.data_ptr())
-    eng.ctx.sync()
-    ms = (time.perf_counter() - t0) * 1e3 / steps
+    # The timed region: every 5th step also carries event pairs around its attention and projection launches (the
+    # kernel durations behind `roofline`); the step time reported is the median, which those few steps do not move.
+    eng.ctx.set_option("time_gemm", 5)
+    eng.ctx.set_option("time_attention", 5)
+    ms, host_us, wall_ms = timed_steps(eng, lambda i: eng.ctx.step(seqs, x.data_ptr(), out.data_ptr()), a.steps, a.warmup)
+    gemm_recs = np.array(eng.ctx.gemm_times(), dtype=np.float64).reshape(-1, 4)
+    attn_ms = eng.ctx.attention_times()
+    eng.ctx.set_option("time_gemm", 0)
+    eng.ctx.set_option("time_attention", 0)
+    med = float(np.median(ms))
     st = eng.ctx.step(seqs, x.data_ptr(), out.data_ptr(), want_stats=True)
     stage = {n: round(float(st.ms_stage[i]), 3) for i, n in enumerate(STAGE_NAMES)}
     params = H * (nq + 2 * nkv) * d + nq * d * H + 3 * H * F
-    gemm_ms = stage["gemm_qkv"] + stage["gemm_o"] + stage["gemm_gate_up"] + stage["gemm_down"]
     finite = bool(torch.isfinite(out.view(torch.bfloat16).float()).all().item())
-    res = {"metric": "mixed_batch_step_throughput", "value": T / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": steps,
-           "ms_per_step": ms, "dtype": "bf16", "data": "synthetic",
-           "config": {"workload": f"cfg4: 70B-shaped stack, {L} layers, {slots} KV slots, {T} new tokens (1024-token chunk at prefix "
-                                  f"4096 + 256 decodes), {total_kv} KV tokens per layer", "n_tokens": T, "total_kv": total_kv, "n_layers": L},
-           "stage_ms_all_layers": stage,
-           "gemm": {"ms": gemm_ms, "tflops": 2 * params * T * L / (gemm_ms * 1e-3) / 1e12,
-                    "frac_mfma": 2 * params * T * L / (gemm_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
-           "attention": {"ms": stage["attention"], "kv_GBs": 2 * nkv * d * 2 * total_kv * L / (stage["attention"] * 1e-3) / 1e9},
-           "output_finite": finite}
-    res["gemm"]["clock"] = mfma_clock(eng.ctx, res["gemm"]["tflops"])
+    # dominant kernels of this step: the four projection launches of a layer (compute-bound at 1280 tokens)
+    gemm_layer_ms = float(gemm_recs.sum(axis=1).mean()) if len(gemm_recs) else float("nan")
+    flop_layer = 2.0 * params * T
+    tflops = flop_layer / (gemm_layer_ms * 1e-3) / 1e12
+    attn_avg = float(np.mean(attn_ms)) if attn_ms else float("nan")
+    res = {"metric": "mixed_batch_step_throughput", "value": T / (med * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps,
+           "warmup": a.warmup, "ms_per_step": med, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"cfg4: 70B-shaped stack (hidden 8192, 64 q / 8 kv heads, d 128, ffn 28672), {L} layers, {slots} KV slots, "
+                                  f"{T} new tokens (1024-token chunk at prefix 4096 + 256 decodes), {total_kv} KV tokens per layer, "
+                                  f"16-token pages, seed {a.seed}", "n_tokens": T, "total_kv": total_kv, "n_layers": L},
+           "ms_per_step_events": percentiles(ms), "wall_ms_per_step": wall_ms / a.steps,
+           "host_us_per_step": round(float(np.median(host_us)), 1),
+           "roofline": {"bound": "mfma", "kernel": "gemm_dma_kernel: the four projection launches of one layer (QKV, O, gate/up + SwiGLU, down)",
+                        "achieved": tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tflops / MFMA_BF16_PEAK_TFLOPS,
+                        "traffic": None, "algorithmic_flop_per_launch_group": flop_layer, "avg_launch_group_ms": gemm_layer_ms,
+                        "avg_launch_ms": {n: round(float(v), 4) for n, v in zip(("qkv", "o", "gate_up", "down"), gemm_recs.mean(axis=0))} if len(gemm_recs) else None,
+                        "launch_groups_timed": int(len(gemm_recs)),
+                        "note": "event pairs on the step's stream around each launch, in every 5th step of the timed region"},
+           "attention": {"avg_launch_ms": attn_avg, "launches_timed": len(attn_ms),
+                         "kv_GBs": 2 * nkv * d * 2 * total_kv / (attn_avg * 1e-3) / 1e9,
+                         "note": "chunk and decode attention in one launch; the KV bytes of the decodes over the whole launch time"},
+           "stage_ms_all_layers": stage, "output_finite": finite}
+    res["roofline"]["clock"] = mfma_clock(eng.ctx, tflops)
     if check:
         from oracle import bf16 as obf
         from oracle import run as orun
@@ -270,17 +349,20 @@ def run_cfg4(a):
             err = float(np.max(np.abs(got - w64))) / rms
             err_b = float(np.max(np.abs(got - wb64))) / rms
             gap = float(np.max(np.abs(wb64 - w64))) / rms
-            # The bar is max|err| <= 2e-2 x RMS against the definition.  Where the definition itself moves by
-            # more than that when its five stored activations are rounded to bf16 (`oracle_gap`: a property of
-            # the inputs, not of any kernel), the layer is held to the same bar against that variant instead.
-            kind = "definition" if err <= 2e-2 else "bf16-activation variant of the definition"
-            ok = err <= 2e-2 or (err_b <= 2e-2 and gap > 2e-2)
-            res["layer_checks"].append({"layer": l, "out_rms": rms, "max_err_over_rms": err, "max_err_over_rms_vs_bf16_variant": err_b,
-                                        "oracle_gap_definition_vs_bf16_variant": gap, "judged_against": kind, "pass": bool(ok)})
-            log(f"cfg4: layer {l}: out rms {rms:.3f}; max|err|/rms = {err:.4f} (definition), {err_b:.4f} (bf16-activation variant); "
-                f"the two oracles differ by {gap:.4f}")
+            # One rule for every layer: within the bar of the definition evaluated with bf16 contraction operands,
+            # hence within the bar plus the CPU-only distance between the two evaluations of the plain definition.
+            ok = err_b <= 2e-2 and err <= 2e-2 + gap
+            res["layer_checks"].append({"layer": l, "out_rms": rms, "max_err_over_rms_vs_bf16_operand_definition": err_b,
+                                        "max_err_over_rms_vs_plain_definition": err, "cpu_only_gap_between_the_two": gap, "pass": bool(ok)})
+            log(f"cfg4: layer {l}: out rms {rms:.3f}; max|err|/rms = {err_b:.4f} (bf16-operand definition), {err:.4f} (plain definition); "
+                f"the two differ by {gap:.4f} on the CPU alone")
     eng.close()
-    print(json.dumps(res))
+    del eng, kblk, vblk, x, out
+    torch.cuda.empty_cache()
+    if not a.no_cpu_baseline and not check:
+        log("cfg4: timing the oracle on one layer")
+        res["cpu_baseline"] = cpu_baseline_cfg4(batch, a.seed, L)
+    return res
 
 
 def run_model8b(a):
@@ -760,7 +842,16 @@ def main():
         run_grid(a)
         return
     if a.workload == "cfg4":
-        run_cfg4(a)
+        # The headline: the largest single-GPU configuration.  One JSON line; the single-layer 8B-shaped configurations
+        # ride along as secondary records (decode attention against the HBM roofline, mixed-batch GEMMs against MFMA).
+        res = run_cfg4(a)
+        if not a.no_secondary and not a.check_layers:
+            res["secondary"] = {}
+            for name, cfg in (("cfg1", 1), ("cfg2", 2)):
+                print(f"bench: secondary record {name}", file=sys.stderr, flush=True)
+                res["secondary"][name] = run_layer_cfg(a, cfg, 200, 20, cpu=not a.no_cpu_baseline)
+            res["secondary"]["host_cost_700_short_decodes"] = host_cost_many_sequences(a)
+        print(json.dumps(res))
         return
     if a.workload == "model8b":
         run_model8b(a)
@@ -774,7 +865,40 @@ def main():
     if a.workload == "profile":
         run_profile(a)
         return
-    cfg = {"cfg1": 1, "cfg2": 2}[a.workload]
+    print(json.dumps(run_layer_cfg(a, {"cfg1": 1, "cfg2": 2}[a.workload], a.steps, a.warmup, cpu=not a.no_cpu_baseline)))
+
+
+def host_cost_many_sequences(a):
+    """Host side of a step with many sequences (700 one-token requests with 1..50 cached tokens, 8B-shaped layer):
+    validation, planning, metadata fill and the enqueue of the step's launches, per ps_step call with the stream busy."""
+    import numpy as np
+    import torch
+    from paper_2507_17769_amd import workloads as W
+    from paper_2507_17769_amd.binding import SeqArray
+    from paper_2507_17769_amd.runner import Engine, bits_to_dev
+    kv = 1 + (np.arange(700) * 37) % 50
+    b = W.custom_batch("8b", a.seed, 0, 0, kv, name="many")
+    eng = Engine(b.model, b.n_pool_pages, 1, 1, max_position=128)
+    eng.load_layer(0, W.layer_weights(b.model, a.seed, 0))
+    eng.load_prefixes(b)
+    x = bits_to_dev(b.activations(), eng.device)
+    out = torch.empty_like(x)
+    seqs = SeqArray(b.seqs)
+    ms, host_us, wall_ms = timed_steps(eng, lambda i: eng.ctx.step(seqs, x.data_ptr(), out.data_ptr()), 100, 10)
+    eng.close()
+    return {"n_seqs": 700, "n_tokens": b.n_tokens, "total_kv": b.total_kv, "host_us_per_step": round(float(np.median(host_us)), 1),
+            "ms_per_step": round(float(np.median(ms)), 4), "wall_ms_per_step": round(wall_ms / 100, 4)}
+
+
+def run_layer_cfg(a, cfg, steps, warmup, cpu=True):
+    """One 8B-shaped layer: the decode-only batch (cfg 1) or the mixed batch (cfg 2).  Returns the result record."""
+    import numpy as np
+    import torch
+    from paper_2507_17769_amd import workloads as W
+    from paper_2507_17769_amd.binding import STAGE_NAMES, SeqArray
+    from paper_2507_17769_amd.runner import Engine, bits_to_dev
+
+    name = f"cfg{cfg}"
     batch = W.config_batch(cfg, a.seed)
     model = W.MODELS[batch.model]
     weights = W.layer_weights(batch.model, a.seed, 0)
@@ -792,32 +916,23 @@ def main():
     seqs = SeqArray(batch.seqs)
     T, total_kv = batch.n_tokens, batch.total_kv
 
-    for i in range(a.warmup):
+    def call(i):
         eng.ctx.set_option("only_layer", i % n_copies)
         eng.ctx.step(seqs, x.data_ptr(), out.data_ptr())
-    eng.ctx.sync()
-    eng.ctx.set_option("time_attention", 8)          # two event records on the step's stream, every 8th step
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(a.steps):
-        eng.ctx.set_option("only_layer", i % n_copies)
-        eng.ctx.step(seqs, x.data_ptr(), out.data_ptr())
-    eng.ctx.sync()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    attn_ms = eng.ctx.attention_times()
-    eng.ctx.set_option("time_attention", 0)
-    ms_per_step = (t1 - t0) * 1e3 / a.steps
 
-    # spread of the step time (not part of the timed region): 20 blocks of 10 steps, each block bracketed by a sync
-    block_ms = []
-    for b in range(20):
-        t0b = time.perf_counter()
-        for i in range(10):
-            eng.ctx.set_option("only_layer", i % n_copies)
-            eng.ctx.step(seqs, x.data_ptr(), out.data_ptr())
-        eng.ctx.sync()
-        block_ms.append((time.perf_counter() - t0b) * 1e3 / 10)
+    # the timed region carries no instrumentation: at a quarter of a millisecond per step two event records show
+    ms, host_us, wall_ms = timed_steps(eng, call, steps, warmup)
+    med = float(np.median(ms))
+    # kernel durations for the roofline: event pairs around the attention launch and the projection launches, in
+    # 32 further steps of the same loop
+    eng.ctx.set_option("time_attention", 1)
+    eng.ctx.set_option("time_gemm", 1)
+    for i in range(32):
+        call(i)
+    attn_ms = eng.ctx.attention_times()
+    gemm_recs = np.array(eng.ctx.gemm_times(), dtype=np.float64).reshape(-1, 4)
+    eng.ctx.set_option("time_attention", 0)
+    eng.ctx.set_option("time_gemm", 0)
 
     # per-stage split (separate, synchronous passes; not part of the timed region)
     stage = np.zeros(len(STAGE_NAMES))
@@ -833,40 +948,50 @@ def main():
     params = H * (nq + 2 * nkv) * d + nq * d * H + 3 * H * F
     kv_bytes_per_token = 2 * nkv * d * 2
     attn_avg_ms = float(np.mean(attn_ms)) if attn_ms else float("nan")
-    # dominant kernel of the decode-only step: paged attention, bound by the KV bytes it must read
     attn_bytes = kv_bytes_per_token * total_kv
     achieved = attn_bytes / (attn_avg_ms * 1e-3) / 1e9
-    gemm_ms = float(stage[1] + stage[4] + stage[6] + stage[7])
+    gemm_ms = float(gemm_recs.sum(axis=1).mean())
+    gemm_tflops = 2 * params * T / (gemm_ms * 1e-3) / 1e12
+    hbm_roof = {"bound": "hbm", "kernel": "attn_kernel (paged attention, split merge excluded)",
+                "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                "traffic": measured_traffic(name, a.seed),
+                "traffic_note": "stored reading of the rocprofv3 FETCH_SIZE / WRITE_SIZE counters of an earlier run of this command "
+                                "(null once the kernel source has changed since)",
+                "algorithmic_bytes_per_launch": attn_bytes, "avg_launch_ms": attn_avg_ms, "launches_timed": len(attn_ms)}
+    mfma_roof = {"bound": "mfma", "kernel": "the four projection launches of the layer (QKV, O, gate/up + SwiGLU, down)",
+                 "achieved": gemm_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / MFMA_BF16_PEAK_TFLOPS,
+                 "traffic": None, "algorithmic_flop_per_launch_group": 2.0 * params * T, "avg_launch_group_ms": gemm_ms,
+                 "avg_launch_ms": {n: round(float(v), 4) for n, v in zip(("qkv", "o", "gate_up", "down"), gemm_recs.mean(axis=0))},
+                 "launch_groups_timed": int(len(gemm_recs))}
     res = {
-        "metric": "mixed_batch_step_throughput", "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
-        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": ms_per_step,
+        "metric": "mixed_batch_step_throughput", "value": T / (med * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": med,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{batch.name}: 8B-shaped layer (hidden 4096, 32 q / 8 kv heads, d 128, ffn 14336), "
                                f"{T} new tokens ({sum(1 for s in batch.seqs if s.n_new == 1)} decodes"
                                f"{', 512-token chunk at prefix 2048' if cfg == 2 else ''}), {total_kv} KV tokens, "
                                f"16-token pages, seed {a.seed}",
                    "n_tokens": T, "total_kv": total_kv, "n_layers": 1},
-        "roofline": {"bound": "hbm", "kernel": "attn_kernel (paged attention, split merge excluded)",
-                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": measured_traffic(a.workload, a.seed), "algorithmic_bytes_per_launch": attn_bytes, "avg_launch_ms": attn_avg_ms,
-                     "launches_timed": len(attn_ms)},
-        "ms_per_step_blocks_of_10": {"p10": round(float(np.percentile(block_ms, 10)), 4), "p50": round(float(np.percentile(block_ms, 50)), 4),
-                                     "p90": round(float(np.percentile(block_ms, 90)), 4), "blocks": len(block_ms)},
+        "ms_per_step_events": percentiles(ms), "wall_ms_per_step": wall_ms / steps, "host_us_per_step": round(float(np.median(host_us)), 1),
+        # the decode-only step is bound by the bytes it streams, the mixed step by its projections
+        "roofline": hbm_roof if cfg == 1 else mfma_roof,
+        "roofline_other": mfma_roof if cfg == 1 else hbm_roof,
+        "step_hbm_GBs": (2 * params + attn_bytes) / (med * 1e-3) / 1e9,
         "stage_ms": {n: round(float(v), 4) for n, v in zip(STAGE_NAMES, stage)},
-        "gemm": {"ms": gemm_ms, "weight_GBs": 2 * params / (gemm_ms * 1e-3) / 1e9,
-                 "tflops": 2 * params * T / (gemm_ms * 1e-3) / 1e12,
-                 "frac_hbm": 2 * params / (gemm_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                 "frac_mfma": 2 * params * T / (gemm_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
+        "gemm": {"ms": gemm_ms, "weight_GBs": 2 * params / (gemm_ms * 1e-3) / 1e9, "tflops": gemm_tflops,
+                 "frac_hbm": 2 * params / (gemm_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "frac_mfma": gemm_tflops / MFMA_BF16_PEAK_TFLOPS},
     }
-    res["gemm"]["clock"] = mfma_clock(eng.ctx, res["gemm"]["tflops"])
+    res["gemm"]["clock"] = mfma_clock(eng.ctx, gemm_tflops)
     # the same fraction against what plain loads stream out of HBM on this device (2 GiB buffer, read after the timed region)
     stream_gbs = eng.ctx.hbm_read_rate(2 << 30, 4)
-    res["roofline"]["measured_stream_read_GBs"] = round(stream_gbs, 1)
-    res["roofline"]["frac_of_measured_stream_read"] = achieved / stream_gbs
-    if not a.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(batch, weights)
+    hbm_roof["measured_stream_read_GBs"] = round(stream_gbs, 1)
+    hbm_roof["frac_of_measured_stream_read"] = achieved / stream_gbs
     eng.close()
-    print(json.dumps(res))
+    del eng, x, out
+    torch.cuda.empty_cache()
+    if cpu:
+        res["cpu_baseline"] = cpu_baseline(batch, weights)
+    return res
 
 
 if __name__ == "__main__":

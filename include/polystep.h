@@ -142,7 +142,9 @@ const char* ps_last_error(const ps_ctx* ctx);
  * rotates through them, so that every step streams its weights from HBM and not from a cache
  * that a real stack of layers would have flushed).
  * "time_attention" (N >= 1: bracket the attention kernel launch of every Nth step with HIP
- * events, see ps_attention_times; the two event records cost a few microseconds of stream time).  PS_EINVAL for an unknown name or bad value. */
+ * events, see ps_attention_times; the two event records cost a few microseconds of stream time),
+ * "time_gemm" (N >= 1: the same around each of the four projection launches of every layer of every Nth step, see
+ * ps_gemm_times).  PS_EINVAL for an unknown name or bad value. */
 ps_status ps_set_option(ps_ctx* ctx, const char* name, int64_t value);
 
 /* ---- weights (Sec. 2.1: attention module, O-projection, gated feed-forward) -------- */
@@ -266,6 +268,14 @@ ps_status ps_plan_attention(ps_ctx* ctx, const ps_seq* seqs, int32_t n_seqs, int
  * number written to *n.  This is the kernel the roofline of a decode-heavy step is quoted on
  * (Sec. 2.2: decode attention does not batch; its cost follows the KV bytes read). */
 ps_status ps_attention_times(ps_ctx* ctx, float* ms, int32_t cap, int32_t* n);
+
+/* Durations (ms) of the four projection launches of a layer (QKV, O, gate/up + SwiGLU, down, in that order; the
+ * kernels that sum their split partials are not included) recorded since the previous call while option
+ * "time_gemm" was on: one record of four values per layer of every timed step, at most 1024 records are kept.
+ * Waits for the stream.  Writes min(count, cap) records to ms (host, [cap][4]) and their number to *n.  These are
+ * the kernels the roofline of a prefill-heavy step is quoted on (Sec. 2.2: large token batches make the
+ * projections compute-bound). */
+ps_status ps_gemm_times(ps_ctx* ctx, float* ms, int32_t cap, int32_t* n);
 
 /* Measurement support, not a step of the path: what the device sustains while every SIMD issues
  * back-to-back dense bf16 MFMAs with no memory traffic.  The nominal matrix peak assumes the

@@ -120,6 +120,7 @@ _SIGS = {
     "ps_plan_attention": (C.c_int, [_P, C.POINTER(ps_seq), C.c_int32, _I32P, C.c_int32, _I32P]),
     "ps_set_taps": (C.c_int, [_P, C.c_int32, C.POINTER(ps_taps)]),
     "ps_attention_times": (C.c_int, [_P, C.POINTER(C.c_float), C.c_int32, _I32P]),
+    "ps_gemm_times": (C.c_int, [_P, C.POINTER(C.c_float), C.c_int32, _I32P]),
     "ps_clock_under_load": (C.c_int, [_P, C.c_int32, C.c_int32, C.POINTER(ps_clock_reading)]),
     "ps_hbm_read_rate": (C.c_int, [_P, C.c_int64, C.c_int32, C.POINTER(C.c_double)]),
     "ps_profile_grid": (C.c_int, [_P, C.POINTER(ps_grid_cell_spec), C.c_int32, C.POINTER(ps_grid_opts), _P, _P,
@@ -284,6 +285,13 @@ class Context:
         n = C.c_int32(0)
         self._check(lib.ps_attention_times(self.handle, buf, cap, C.byref(n)))
         return [buf[i] for i in range(n.value)]
+
+    def gemm_times(self, cap=1024):
+        """-> list of [qkv, o, gate_up, down] ms, one per layer of every timed step"""
+        buf = (C.c_float * (4 * cap))()
+        n = C.c_int32(0)
+        self._check(lib.ps_gemm_times(self.handle, buf, cap, C.byref(n)))
+        return [[buf[4 * i + k] for k in range(4)] for i in range(n.value)]
 
     def clock_under_load(self, mfma_per_wavefront=400000, wavefronts_per_simd=2):
         r = ps_clock_reading()

@@ -104,12 +104,18 @@ struct ps_ctx {
     bool static_pending[4] = {false, false, false, false};
     int static_next = 0;
 
+    // optional event pairs around the four projection launches of a layer (see ps_gemm_times)
+    int opt_time_gemm = 0;            // 0 = off, N = bracket them in every Nth step
+    std::vector<hipEvent_t> gemm_ev;  // ring of 8 * GEMM_EV_RECS events: record r holds pairs (qkv, o, gate/up, down)
+    int gemm_ev_count = 0;            // records (one per layer of a timed step) since the last ps_gemm_times
+
     hipEvent_t ev[PS_N_STAGES * 2 + 2] = {};
     bool have_events = false;
     StepPlan plan;
 };
 
 static constexpr int ATTN_EV_PAIRS = 2048;
+static constexpr int GEMM_EV_RECS = 1024;
 
 // Scratch of ps_step_static: workspaces, GEMM and attention partials and the step's metadata, carved out of one
 // file-scope device array instead of hipMalloc'ed buffers.  Every device the library runs on holds its own copy of
@@ -282,6 +288,7 @@ extern "C" void ps_destroy(ps_ctx* c) {
         for (auto& e : c->static_ev) if (e) (void)hipEventDestroy(e);
         if (c->have_events) for (auto& e : c->ev) if (e) (void)hipEventDestroy(e);
         for (auto& e : c->attn_ev) if (e) (void)hipEventDestroy(e);
+        for (auto& e : c->gemm_ev) if (e) (void)hipEventDestroy(e);
     }
     delete c;
 }
@@ -324,6 +331,17 @@ extern "C" ps_status ps_set_option(ps_ctx* c, const char* name, int64_t value) {
         }
         c->opt_time_attention = (int)value;
         c->attn_ev_count = 0;
+        return PS_OK;
+    }
+    if (!strcmp(name, "time_gemm")) {
+        if (value < 0 || value > 1024) return fail(c, PS_EINVAL, "time_gemm must be in [0, 1024]");
+        if (c->host_only) return fail(c, PS_ESTATE, "time_gemm: host-only context");
+        if (value && c->gemm_ev.empty()) {
+            c->gemm_ev.assign(8 * GEMM_EV_RECS, nullptr);
+            for (auto& e : c->gemm_ev) HIP_TRY(c, hipEventCreate(&e));
+        }
+        c->opt_time_gemm = (int)value;
+        c->gemm_ev_count = 0;
         return PS_OK;
     }
     if (!strcmp(name, "out_f32")) {
@@ -866,6 +884,16 @@ static ps_status step_impl(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const 
         const bool last = (l == l_end - 1);
         bf16_t* pool_slot = c->pool + (size_t)(l % c->n_kv_slots) * c->slot_elems;
         int e = 0, n_splits = 1;
+        // event pairs around this layer's four projection launches, when asked for and while the ring has room
+        hipEvent_t* gev = nullptr;
+        if (c->opt_time_gemm > 0 && c->gemm_ev_count < GEMM_EV_RECS && (c->step_counter % c->opt_time_gemm) == 0)
+            gev = c->gemm_ev.data() + (size_t)8 * c->gemm_ev_count++;
+        auto run_gemm = [&](const GemmArgs& ga, int* splits, int which) -> hipError_t {
+            if (gev) (void)hipEventRecord(gev[2 * which], s);
+            const hipError_t ge = launch_gemm(ga, splits, s);
+            if (gev) (void)hipEventRecord(gev[2 * which + 1], s);
+            return ge;
+        };
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[e], s));
         // 0: RMSNorm of the layer input (layers after the first get it from the previous layer's last kernel)
         if (l == l_begin) HIP_TRY(c, launch_rmsnorm(x_cur, x_cur_f32, L.g_attn, W.xn, T, H, d.rms_eps, s));
@@ -876,7 +904,7 @@ static ps_status step_impl(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const 
         GemmArgs g{};
         g.A = W.xn; g.Wp = L.wqkv_t; g.M = T; g.N = NQKV; g.K = H; g.kind = GemmOut::PARTIAL_F32;
         g.out = W.part; g.out_bytes = W.part_bytes; g.split_k = c->opt_gemm_split_k; g.tile = c->opt_gemm_tile;
-        HIP_TRY(c, launch_gemm(g, &n_splits, s));
+        HIP_TRY(c, run_gemm(g, &n_splits, 0));
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
         // 2: sum the partials, rotate, round once to bf16, append k/v to the pages
         HIP_TRY(c, launch_rope_append(W.part, n_splits, W.q, T, d.n_q_heads, d.n_kv_heads, d.head_dim, d_pos,
@@ -912,7 +940,7 @@ static ps_status step_impl(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const 
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
         // 4: O projection -> fp32 partials
         g.A = W.attn; g.Wp = L.wo_t; g.N = H; g.K = NQ;
-        HIP_TRY(c, launch_gemm(g, &n_splits, s));
+        HIP_TRY(c, run_gemm(g, &n_splits, 1));
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
         // 5: x1 = x + sum(partials) (fp32), xn = RMSNorm(x1)
         ReduceAddNormArgs r{};
@@ -925,14 +953,14 @@ static ps_status step_impl(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const 
         // 6: gate/up + SwiGLU
         g.A = W.xn; g.Wp = L.wgu_t; g.N = 2 * F; g.K = H; g.kind = GemmOut::SWIGLU_BF16;
         g.out = W.act; g.out_bytes = W.act_bytes;
-        HIP_TRY(c, launch_gemm(g, nullptr, s));
+        HIP_TRY(c, run_gemm(g, nullptr, 2));
         if (tap && c->taps.act) HIP_TRY(c, launch_untile(W.act, static_cast<bf16_t*>(c->taps.act), T, F, s));
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
         // 7: down projection -> fp32 partials; out = x1 + sum(partials); for an inner layer also the
         //    next layer's normalised input
         g.A = W.act; g.Wp = L.wd_t; g.N = H; g.K = F; g.kind = GemmOut::PARTIAL_F32;
         g.out = W.part; g.out_bytes = W.part_bytes;
-        HIP_TRY(c, launch_gemm(g, &n_splits, s));
+        HIP_TRY(c, run_gemm(g, &n_splits, 3));
         r.resid = W.x1; r.resid_f32 = true; r.n_splits = n_splits;
         if (last) {
             r.x_f32 = out_f32 ? static_cast<float*>(x_out) : nullptr;
@@ -1036,6 +1064,18 @@ extern "C" ps_status ps_attention_times(ps_ctx* c, float* ms, int32_t cap, int32
     for (int i = 0; i < cnt; i++) HIP_TRY(c, hipEventElapsedTime(&ms[i], c->attn_ev[2 * i], c->attn_ev[2 * i + 1]));
     *n = cnt;
     c->attn_ev_count = 0;
+    return PS_OK;
+}
+
+extern "C" ps_status ps_gemm_times(ps_ctx* c, float* ms, int32_t cap, int32_t* n) {
+    if (!c || !n || (!ms && cap > 0)) return fail(c, PS_EINVAL, "ps_gemm_times: null argument");
+    if (c->host_only) return fail(c, PS_ESTATE, "ps_gemm_times: host-only context");
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    const int cnt = std::min<int>(c->gemm_ev_count, cap);
+    for (int i = 0; i < cnt; i++)
+        for (int k = 0; k < 4; k++) HIP_TRY(c, hipEventElapsedTime(&ms[4 * i + k], c->gemm_ev[8 * i + 2 * k], c->gemm_ev[8 * i + 2 * k + 1]));
+    *n = cnt;
+    c->gemm_ev_count = 0;
     return PS_OK;
 }
 

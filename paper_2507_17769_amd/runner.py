@@ -95,6 +95,8 @@ class Engine:
             "x1": torch.zeros((T, m["hidden"]), dtype=torch.float32, device=self.device),
             "xn2": torch.zeros((T, m["hidden"]), **i16),
             "act": torch.zeros((T, m["ffn"]), **i16),
+            "x_in": torch.zeros((T, m["hidden"]), dtype=torch.float32, device=self.device),
+            "x_out": torch.zeros((T, m["hidden"]), dtype=torch.float32, device=self.device),
         }
 
     def step(self, seqs, x_dev, out_dev=None, want_stats=False):

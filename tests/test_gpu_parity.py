@@ -1,6 +1,8 @@
 """GPU parity: libpolystep (through its C ABI) against the CPU oracle, element by element, on
-the same seeded inputs.  Bar: max |err| <= 2e-2 x RMS of the oracle tensor for every
-floating-point tensor checked; integer results (slots written, untouched cache) bit-exact."""
+the same seeded inputs.  Bar: max |err| <= 2e-2 x RMS, applied by one rule to every case (final output
+against the definition with bf16 contraction operands and, less the CPU-only gap, against the plain one;
+every stage on its own per token row; see gpu_harness.py); integer results (slots written, untouched
+cache) bit-exact."""
 import numpy as np
 import pytest
 import torch
@@ -141,10 +143,11 @@ def test_chunked_prefill_on_gpu_matches_one_shot_and_oracle():
         assert np.all(np.abs(got - ref) <= TOL * rms + 2 * hb * np.abs(ref))
         k1, v1 = one.eng.read_kv(0, base.seqs[0].pages, 0, L)
         k2, v2 = c.eng.read_kv(0, base.seqs[0].pages, 0, L)
-        from gpu_harness import bf16_ulp_distance
-        for a_, b_ in ((k1, k2), (v1, v2)):
+        # both caches hold bf16 roundings of fp32 sums of the same products (the normalised input does not depend on
+        # the chunking): one rounding flip plus twice the rounding-error bound of such a sum
+        for a_, b_, bound in zip((k1, v1), (k2, v2), one.kv_sum_bounds()):
             fa, fb = f32(a_).astype(np.float64), f32(b_).astype(np.float64)
-            assert np.all(np.abs(fa - fb) <= 2.0 ** -7 * np.abs(fa) + 1e-3 * np.sqrt(np.mean(fa * fa)))
+            assert np.all(np.abs(fa - fb) <= 2.0 ** -7 * np.abs(fa) + 2 * bound)
         c.close()
     one.close()
 
@@ -249,7 +252,7 @@ def test_teacher_forced_layer_inside_an_aliased_stack():
     b = W.custom_batch("tiny", 8, 24, 40, [1, 33, 70], name="alias")
     c = Case(b, n_layers=4, n_kv_layers=2)
     errs = c.run(tap_layer=3)
-    _assert_errs({k: v for k, v in errs.items() if not k.startswith("x1") and "o_branch" not in k}, "aliased stack")
+    _assert_errs(errs, "aliased stack")
     eng, T, H = c.eng, b.n_tokens, 256
     xin = torch.zeros((T, H), dtype=torch.float32, device=eng.device)
     xout = torch.zeros((T, H), dtype=torch.float32, device=eng.device)
@@ -270,10 +273,9 @@ def test_teacher_forced_layer_inside_an_aliased_stack():
 def test_wide_hidden_70b_like_shape_small_ffn():
     # hidden 8192 with 64 query / 8 KV heads (group size 8) as in the 70B-shaped layer, small FFN and batch.
     # With N(0, 0.02) weights at this width the attention logits have twice the spread of the 8B-shaped
-    # layer, the softmax turns peaky, and rounding the stored activations to bf16 moves the definition
-    # itself by more than the bar.  So: (1) weights at 1.28/sqrt(hidden), which keep the logits' spread
-    # of the 8B shape: final output against the definition at the bar; (2) both weight scales: every stage
-    # on its own against the oracle applied to the stage's actual input, at half the bar per row.
+    # layer, the softmax turns peaky, and rounding the contraction operands to bf16 moves the definition
+    # itself by more than the bar (printed: the CPU-only gap).  Two weight scales, N(0, 0.02) and
+    # 1.28/sqrt(hidden), which keeps the logits' spread of the 8B shape; the same rule for both.
     model = dict(hidden=8192, n_q=64, n_kv=8, head_dim=128, ffn=1024, rope_base=500000.0, n_layers=1)
     W.MODELS["_w"] = model
     try:
@@ -282,11 +284,9 @@ def test_wide_hidden_70b_like_shape_small_ffn():
             for std in (1.28 / 8192 ** 0.5, W.WEIGHT_STD):
                 c = Case(b, weight_std=std)
                 errs = c.run()
-                if std != W.WEIGHT_STD:
-                    assert errs["out"] <= TOL and errs["out_bf16"] <= TOL, (spec, errs)
-                    c.check_pool()
-                stages = c.stagewise()
-                assert max(stages.values()) <= 1.0, (spec, std, stages)
+                print(f"wide spec={spec} std={std:.4f}: {c.report}", flush=True)
+                _assert_errs(errs, f"wide spec={spec} std={std}")
+                c.check_pool()
                 c.close()
     finally:
         del W.MODELS["_w"]
@@ -296,9 +296,9 @@ def test_every_stage_on_its_own_tiny_and_mixed():
     # the same stage-by-stage check on the tiny model: prefill chunk with ragged tiles + decodes
     for spec in ((100, 37, [5, 250]), (257, 300, [300, 1, 17])):
         c = Case(W.custom_batch("tiny", 19, *spec, name="stages"))
-        c.run()
-        stages = c.stagewise()
-        assert max(stages.values()) <= 1.0, (spec, stages)
+        errs = c.run()
+        assert sum(k.startswith("stage ") for k in errs) == 8, errs      # seven stages and the appended cache entries
+        _assert_errs(errs, f"stages spec={spec}")
         c.close()
 
 
@@ -350,8 +350,6 @@ def test_steps_with_several_prefill_requests(chunks, decodes):
     errs = c.run()
     _assert_errs(errs, f"chunks={chunks} decodes={decodes}")
     c.check_pool()
-    stages = c.stagewise()
-    assert max(stages.values()) <= 1.0, stages
     c.close()
 
 
