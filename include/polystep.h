@@ -133,7 +133,9 @@ const char* ps_last_error(const ps_ctx* ctx);
  * in different places and must give the same results within rounding),
  * "attn_prefill_weight" (cost the attention planner charges for a pair of pages of a prefill
  * query block, where a decode token's pair costs 2; it only moves the cuts),
- * "gemm_split_k" (0 = automatic), "gemm_tile" (block tile edge of the tiled GEMM kernel, which
+ * "gemm_split_k" (0 = automatic; the weight-streaming kernel's K splits), "gemm_whole_tiles" (1: the tiled GEMM kernel gives
+ * every tile to one block instead of cutting the K loops of a last, partial wave of tiles over all blocks; same results up
+ * to fp32 summation order), "gemm_tile" (block tile edge of the tiled GEMM kernel, which
  * serves more than 64 tokens: 0 = automatic (the weight-streaming kernel stays in charge up to 96
  * tokens, up to 160 for all projections but the QKV one), 128 or 256), "out_f32" (1: ps_step writes x_out as fp32 [T][hidden],
  * the precision the residual stream is kept in, instead of rounding it to bf16).

@@ -66,6 +66,11 @@ struct ps_ctx {
     size_t act_bytes = 0;
     float *part_o = nullptr, *part_ml = nullptr;
     int cap_part_slots = 0;
+    // tiled GEMM: parked accumulators of partial K runs and one counter per tile (zero between launches)
+    float* ws_skfrag = nullptr;
+    size_t skfrag_bytes = 0;
+    int* ws_skcnt = nullptr;
+    int skcnt_n = 0;
     // Device copies of the staging ring (same 8 slots).  The copy of step n+1's metadata runs on
     // copy_stream while step n's kernels execute; the main stream only waits for the slot's event.
     char* dev_meta = nullptr;
@@ -86,6 +91,7 @@ struct ps_ctx {
     int worker_slots = 2048;
     int opt_gemm_split_k = 0;
     int opt_gemm_tile = 0;
+    int opt_gemm_whole_tiles = 0;
     int opt_only_layer = -1;
     bool opt_out_f32 = false;
     int tap_layer = -1;
@@ -276,6 +282,7 @@ extern "C" void ps_destroy(ps_ctx* c) {
         dev_free(c->embedding); dev_free(c->g_final); dev_free(c->wout_t); dev_free(c->ws_logits); dev_free(c->ws_next);
         for (auto& e : c->ev_head) if (e) (void)hipEventDestroy(e);
         dev_free(c->part_o); dev_free(c->part_ml);
+        dev_free(c->ws_skfrag); dev_free(c->ws_skcnt);
         if (c->dev_meta) (void)hipFree(c->dev_meta);
         for (auto& e : c->meta_ready)
             if (e) (void)hipEventDestroy(e);
@@ -315,6 +322,11 @@ extern "C" ps_status ps_set_option(ps_ctx* c, const char* name, int64_t value) {
     if (!strcmp(name, "gemm_tile")) {
         if (value != 0 && value != 128 && value != 256) return fail(c, PS_EINVAL, "gemm_tile must be 0, 128 or 256");
         c->opt_gemm_tile = (int)value;
+        return PS_OK;
+    }
+    if (!strcmp(name, "gemm_whole_tiles")) {
+        if (value != 0 && value != 1) return fail(c, PS_EINVAL, "gemm_whole_tiles must be 0 or 1");
+        c->opt_gemm_whole_tiles = (int)value;
         return PS_OK;
     }
     if (!strcmp(name, "gemm_split_k")) {
@@ -644,7 +656,30 @@ extern "C" ps_status ps_set_taps(ps_ctx* c, int32_t layer, const ps_taps* taps) 
 // ------------------------------------------------------------------------------ the step
 static size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
 
-static ps_status ensure_workspaces(ps_ctx* c, int T, int n_part_slots) {
+// What the tiled GEMM needs beside its output for a step of T tokens: the largest over the layer's four projections.
+static void sk_need(const ps_ctx* c, int T, int head_rows, size_t* frag_bytes, int* n_counters) {
+    const ps_model_desc& d = c->desc;
+    const int H = d.hidden, F = d.ffn, NQ = d.n_q_heads * d.head_dim, NQKV = qkv_cols(d);
+    const int shapes[4][3] = {{NQKV, H, GemmOut::PARTIAL_F32}, {H, NQ, GemmOut::PARTIAL_F32}, {2 * F, H, GemmOut::SWIGLU_BF16}, {H, F, GemmOut::PARTIAL_F32}};
+    *frag_bytes = 0;
+    *n_counters = 0;
+    for (const auto& sh : shapes) {
+        size_t fb = 0;
+        int nc = 0;
+        gemm_workspace(T, sh[0], sh[1], sh[2], c->opt_gemm_split_k, c->opt_gemm_tile, &fb, &nc);
+        *frag_bytes = std::max(*frag_bytes, fb);
+        *n_counters = std::max(*n_counters, nc);
+    }
+    if (head_rows > 0) {   // the output projection: one row per sequence
+        size_t fb = 0;
+        int nc = 0;
+        gemm_workspace(head_rows, c->vocab, H, GemmOut::PARTIAL_F32, 1, c->opt_gemm_tile, &fb, &nc);
+        *frag_bytes = std::max(*frag_bytes, fb);
+        *n_counters = std::max(*n_counters, nc);
+    }
+}
+
+static ps_status ensure_workspaces(ps_ctx* c, int T, int n_part_slots, int head_rows) {
     const ps_model_desc& d = c->desc;
     if (T > c->cap_tokens) {
         HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -680,6 +715,29 @@ static ps_status ensure_workspaces(ps_ctx* c, int T, int n_part_slots) {
             ps_status st = dev_alloc(c, &c->ws_part, want, "GEMM partials");
             if (st != PS_OK) return st;
             c->part_bytes = want;
+        }
+    }
+    {   // tiled GEMM workspace
+        size_t fb = 0;
+        int nc = 0;
+        sk_need(c, T, head_rows, &fb, &nc);
+        if (fb > c->skfrag_bytes) {
+            HIP_TRY(c, hipStreamSynchronize(c->stream));
+            dev_free(c->ws_skfrag);
+            c->skfrag_bytes = 0;
+            ps_status st = dev_alloc(c, &c->ws_skfrag, fb, "GEMM parked accumulators");
+            if (st != PS_OK) return st;
+            c->skfrag_bytes = fb;
+        }
+        if (nc > c->skcnt_n) {
+            HIP_TRY(c, hipStreamSynchronize(c->stream));
+            dev_free(c->ws_skcnt);
+            c->skcnt_n = 0;
+            const int want = (nc + nc / 2 + 255) & ~3;
+            ps_status st = dev_alloc(c, &c->ws_skcnt, (size_t)want * sizeof(int), "GEMM tile counters");
+            if (st != PS_OK) return st;
+            HIP_TRY(c, launch_fill_zero(c->ws_skcnt, (size_t)want * sizeof(int), c->stream));   // the kernels leave them zero
+            c->skcnt_n = want;
         }
     }
     if (n_part_slots > c->cap_part_slots) {
@@ -730,6 +788,10 @@ struct StepBufs {
     bf16_t *xn = nullptr, *q = nullptr, *attn = nullptr, *act = nullptr;
     float *x1 = nullptr, *xmid = nullptr, *part = nullptr, *part_o = nullptr, *part_ml = nullptr;
     size_t part_bytes = 0, act_bytes = 0;
+    float* skfrag = nullptr;
+    size_t skfrag_bytes = 0;
+    int* skcnt = nullptr;
+    int skcnt_n = 0;
     char* meta = nullptr;  // static steps only: device copy of the metadata
 };
 
@@ -750,6 +812,10 @@ static ps_status carve_static(ps_ctx* c, int T, int n_part_slots, size_t meta_by
     const size_t o_part = take(w->part_bytes);
     const size_t o_po = take((size_t)n_part_slots * 16 * d.head_dim * 4), o_pml = take((size_t)n_part_slots * 16 * 2 * 4);
     const size_t o_meta = take(meta_bytes);
+    int n_cnt = 0;
+    sk_need(c, T, 0, &w->skfrag_bytes, &n_cnt);
+    w->skcnt_n = (n_cnt + 3) & ~3;
+    const size_t o_skfrag = take(w->skfrag_bytes), o_skcnt = take((size_t)w->skcnt_n * sizeof(int));
     if (meta_bytes > STATIC_META_SLOT)
         return fail(c, PS_ERANGE, "ps_step_static: the step's metadata (" + std::to_string(meta_bytes) + " bytes: positions, page lists, attention work list) exceeds " +
                                       std::to_string(STATIC_META_SLOT) + " bytes; use ps_step for batches of this size");
@@ -761,6 +827,8 @@ static ps_status carve_static(ps_ctx* c, int T, int n_part_slots, size_t meta_by
     w->act = reinterpret_cast<bf16_t*>(b + o_act); w->x1 = reinterpret_cast<float*>(b + o_x1); w->xmid = reinterpret_cast<float*>(b + o_xmid);
     w->part = reinterpret_cast<float*>(b + o_part); w->part_o = reinterpret_cast<float*>(b + o_po); w->part_ml = reinterpret_cast<float*>(b + o_pml);
     w->meta = reinterpret_cast<char*>(b + o_meta);
+    w->skfrag = reinterpret_cast<float*>(b + o_skfrag);
+    w->skcnt = reinterpret_cast<int*>(b + o_skcnt);
     return PS_OK;
 }
 
@@ -805,10 +873,13 @@ static ps_status step_impl(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const 
     if (use_static) {
         if ((st = carve_static(c, T, p.n_partial_slots, ml.total, &W)) != PS_OK) return st;
     } else {
-        if ((st = ensure_workspaces(c, T, p.n_partial_slots)) != PS_OK) return st;
+        if ((st = ensure_workspaces(c, T, p.n_partial_slots, tio ? p.n_seqs : 0)) != PS_OK) return st;
         W.xn = c->ws_xn; W.q = c->ws_q; W.attn = c->ws_attn; W.act = c->ws_act; W.x1 = c->ws_x1; W.xmid = c->ws_xmid;
         W.part = c->ws_part; W.part_o = c->part_o; W.part_ml = c->part_ml; W.part_bytes = c->part_bytes; W.act_bytes = c->act_bytes;
+        W.skfrag = c->ws_skfrag; W.skfrag_bytes = c->skfrag_bytes; W.skcnt = c->ws_skcnt; W.skcnt_n = c->skcnt_n;
     }
+    // the array of a static step keeps whatever the previous call left where this call's tile counters lie
+    if (use_static && W.skcnt_n > 0) HIP_TRY(c, launch_fill_zero(W.skcnt, (size_t)W.skcnt_n * sizeof(int), c->stream));
 
     // one pinned buffer, one host-to-device copy for all of the step's integer metadata
     Staging* sg = nullptr;
@@ -904,6 +975,8 @@ static ps_status step_impl(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const 
         GemmArgs g{};
         g.A = W.xn; g.Wp = L.wqkv_t; g.M = T; g.N = NQKV; g.K = H; g.kind = GemmOut::PARTIAL_F32;
         g.out = W.part; g.out_bytes = W.part_bytes; g.split_k = c->opt_gemm_split_k; g.tile = c->opt_gemm_tile;
+        g.sk_frag = W.skfrag; g.sk_frag_bytes = W.skfrag_bytes; g.sk_counters = W.skcnt; g.sk_n_counters = W.skcnt_n;
+        g.sk_mode = c->opt_gemm_whole_tiles;
         HIP_TRY(c, run_gemm(g, &n_splits, 0));
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
         // 2: sum the partials, rotate, round once to bf16, append k/v to the pages
@@ -1026,6 +1099,7 @@ static ps_status step_impl(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const 
         g.out = logits; g.out_bytes = (size_t)M * V * sizeof(float);
         g.split_k = 1;  // one partial buffer: it is the logits
         g.tile = c->opt_gemm_tile;
+        g.sk_frag = W.skfrag; g.sk_frag_bytes = W.skfrag_bytes; g.sk_counters = W.skcnt; g.sk_n_counters = W.skcnt_n;
         int n_splits = 1;
         HIP_TRY(c, launch_gemm(g, &n_splits, s));
         if (n_splits != 1) return fail(c, PS_EDEVICE, "ps_step_tokens: output projection was split");

@@ -17,15 +17,17 @@
 //    its 64 output columns each and load their weight operands straight from HBM into registers
 //    (no LDS hop), four stages of two k-blocks ahead; a fifth wavefront copies the activation k-blocks
 //    that all four need into an LDS ring.
-//  * gemm_dma_kernel (above that, or forced by the tile option above 64): 256x256 or 128x128 block tile, bf16 MFMA 32x32x16.  Activations and
+//  * gemm_sk_kernel (above that, or forced by the tile option above 64): 256x256 or 128x128 block tile, bf16 MFMA 16x16x32.  Activations and
 //    weights are both stored as KiB blocks that already are MFMA operands, so a k-slice of the
 //    tile is copied HBM/L2 -> LDS verbatim by global_load_lds (no register hop, no transform) into
 //    a ring of four stages, three in flight; the wavefronts read operands back with one
-//    ds_read_b128 per 32x16 operand, interleaved one-for-two with the MFMAs that consume the
-//    previous half-stage.  Block ids are mapped so that the blocks of one XCD share weight tiles.
-// Output is either fp32 partials [split][M][N] (the consumer kernel sums the splits, adds the
+//    ds_read_b128 per 16x32 operand, interleaved with the MFMAs that consume the previous stage.
+//    Blocks are resident once per compute unit and take whole tiles in waves; the K loops of the tiles
+//    that do not fill a wave are cut evenly over the blocks ("stream-K"), see SkParams.
+// Output is either fp32 partials [split][M][N] (one per K split of the streaming kernel; the consumer kernel sums the splits, adds the
 // residual, normalises, rotates ...) or, for the fused gate/up matrix, silu(gate) * up in bf16.
 #include "ps_device.h"
+#include "sk_decomp.h"
 
 #include <algorithm>
 #include <mutex>
@@ -194,234 +196,387 @@ __global__ __launch_bounds__(64 * (4 * NG + 1)) void gemm_wstream_kernel(GemmPar
 }
 
 // ------------------------------------------------------------------------------------------
-// Tiled kernel.  One block per (row tile, column tile, K split) unit, WM x WN wavefronts.
+// Tiled kernel.  LDS holds NS stages; a stage is one 32-wide k-block of the tile: BM/16 activation blocks, then
+// BN/16 weight blocks, each the KiB that a 16x16x32 operand occupies in memory.
 //
-// LDS holds NS stages; a stage is one 32-wide k-block of the tile: BM/16 activation blocks, then
-// BN/16 weight blocks, each the KiB that a 16x16x32 operand occupies in memory (lane l's 16 bytes
-// at l*16).  A 32x32x16 operand (rows r = l%32, k-half h = l/32 of k-sixteenth `sub`) is two such
-// blocks side by side: lane l reads block r/16 at ((2 sub + h) * 16 + r%16) * 16.
+// The LDS reads are inline assembly because the compiler, which cannot tell an LDS read from the LDS writes of
+// global_load_lds in flight, would drain the load queue before each of them.  It therefore does not know that
+// the read registers are written asynchronously: every wait names the registers it makes valid, so that their
+// consumers cannot move above it.
 //
-// The LDS reads are inline assembly because the compiler, which cannot tell an LDS read from the
-// LDS writes of global_load_lds in flight, would drain the load queue before each of them.  It
-// therefore does not know that the read registers are written asynchronously: every wait below
-// names the registers it makes valid, so that their consumers cannot move above it, and no read
-// is left in flight where registers could be copied (the loop has a single straight-line body
-// whose in-flight reads sit in loop-carried registers).
+// Why the 16x16x32 MFMA: under the power limit it sustains more than the 32x32x16 form.  A loop of nothing
+// but independent MFMAs on N(0,1) x N(0,0.02) operands (128x128 per wavefront, one wavefront per SIMD)
+// runs at 2.06 PFLOP/s against 1.79-1.83 with the 32x32x16 form, while both reach the nominal 2.45 on
+// all-zero operands: the small form reads and writes a quarter of the accumulator values per instruction
+// for half the flops, and the clock the power management holds follows the energy per flop.
+//
+// A stage's KiB blocks ARE 16x16x32 operands (lane l's 16 bytes at l*16: row l%16, k 8*(l/16)..+7), so an
+// operand is one ds_read_b128 at a constant offset.  The weight tile is the A operand and the activation
+// tile the B operand: a lane then holds four consecutive output columns of one row (float4 stores of the
+// partial sums), and for the gate/up matrix the gate and up values of the same four features sit in the same
+// lane of two accumulators, so silu(gate) * up is formed in registers and stored as 8-byte pieces of the
+// operand-order activation without a pass through LDS.
+//
+// Per stage and wavefront (256x256 block, 128x128 per wavefront): 64 MFMAs on the operand set read during the
+// previous stage, the 16 reads of the next stage's operands (one behind every third MFMA, all waited for at
+// the end of the stage, the last one having had more than 250 cycles), the wavefront's 8 copies of the stage
+// three ahead, one barrier.  Two operand sets alternate, so the loop is unrolled by two stages and the
+// registers of in-flight reads never cross a copy.
 // ------------------------------------------------------------------------------------------
-struct TiledParams {
+template <int N>
+struct OpSet { u32x4_t v[N]; };
+
+// acc += A . B, the accumulator pinned to the accumulation registers and the operands to the vector registers.
+// Written as assembly because the register allocator, left to choose per instruction between the two register files
+// for 256 accumulator registers plus 128 operand registers, shuffles them between the files inside the main loop.
+// The compiler inserts no hazard waits around assembly: every accumulator is used again 64 (16) instructions later,
+// far beyond the instruction's passes, and the epilogue waits before it reads the results.
+__device__ __forceinline__ void mfma16_acc(f32x4_t& c, const u32x4_t& a, const u32x4_t& b) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+}
+
+__device__ __forceinline__ void lgkm0_tie(OpSet<4>& o) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(o.v[0]), "+v"(o.v[1]), "+v"(o.v[2]), "+v"(o.v[3]));
+}
+__device__ __forceinline__ void vm0_tie(OpSet<4>& o) {
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(o.v[0]), "+v"(o.v[1]), "+v"(o.v[2]), "+v"(o.v[3]));
+}
+__device__ __forceinline__ void vm0_tie(OpSet<8>& o) {
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(o.v[0]), "+v"(o.v[1]), "+v"(o.v[2]), "+v"(o.v[3]), "+v"(o.v[4]), "+v"(o.v[5]), "+v"(o.v[6]), "+v"(o.v[7]));
+}
+__device__ __forceinline__ void lgkm0_tie(OpSet<8>& o) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(o.v[0]), "+v"(o.v[1]), "+v"(o.v[2]), "+v"(o.v[3]), "+v"(o.v[4]), "+v"(o.v[5]), "+v"(o.v[6]), "+v"(o.v[7]));
+}
+__device__ __forceinline__ void lgkm0_tie(OpSet<12>& o) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(o.v[0]), "+v"(o.v[1]), "+v"(o.v[2]), "+v"(o.v[3]), "+v"(o.v[4]), "+v"(o.v[5]), "+v"(o.v[6]), "+v"(o.v[7]),
+                                          "+v"(o.v[8]), "+v"(o.v[9]), "+v"(o.v[10]), "+v"(o.v[11]));
+}
+__device__ __forceinline__ void lgkm0_tie(OpSet<16>& o) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(o.v[0]), "+v"(o.v[1]), "+v"(o.v[2]), "+v"(o.v[3]), "+v"(o.v[4]), "+v"(o.v[5]), "+v"(o.v[6]), "+v"(o.v[7]),
+                                          "+v"(o.v[8]), "+v"(o.v[9]), "+v"(o.v[10]), "+v"(o.v[11]), "+v"(o.v[12]), "+v"(o.v[13]), "+v"(o.v[14]), "+v"(o.v[15]));
+}
+
+// Work decomposition ("stream-K" tail).  The tiles, in the order (column tile, row tile) with the row tile fastest,
+// are dealt in contiguous ranges to the eight XCDs (one L2 each); block ids are handed out round-robin over the XCDs,
+// so block id % 8 is the XCD and id / 8 = lb its index there, 0 .. B-1, B blocks per XCD being resident at once.
+// An XCD with T tiles runs T / B waves of whole tiles (block lb takes tiles lb, lb + B, ...: the B tiles in flight
+// are a few columns x all rows, so weight and activation panels are shared through the L2), and then the T % B
+// tiles that are left, whose K loops it cuts into B equal runs, one per block: no partial last wave.  A run that
+// covers part of a tile's K range parks its accumulators in a workspace slot and counts itself in on the tile;
+// whichever block counts in last adds the parked pieces up, always in the order of their K ranges, and runs the
+// epilogue.  Nobody waits for anybody: the blocks exchange nothing but the parked pieces and the counter, each
+// side of which is fenced at device scope.
+struct SkParams {
     GemmParams g;
-    int tiles_m, tiles_n, splits, units_per_xcd;
+    int tiles_m, tiles_n, splits, kp_per_split;   // K splits of every tile (1 for the gate/up matrix) and their length in pairs of k-blocks
+    int tiles_per_xcd, blocks_per_xcd;            // units (tile, split) per XCD, resident blocks per XCD
+    int cut_tail;       // 1: the tail's K loops are cut evenly over the blocks; 0: every tail tile is one block's
+    int slots_per_xcd;  // parked pieces an XCD may hold (sk_decomp.h)
+    float* frag;        // [xcd][slots_per_xcd][BM * BN] parked accumulators, in the lanes' own order
+    int* counters;      // [tiles], zero on entry and again on exit
 };
 
-template <int BM, int BN, int WM, int WN, int NS, int KIND>
-__global__ __launch_bounds__(64 * WM * WN) void gemm_dma_kernel(TiledParams tp) {
-    const GemmParams& p = tp.g;
-    constexpr int NW = WM * WN;
-    constexpr int WTM = BM / WM, WTN = BN / WN;  // wavefront tile
-    constexpr int TM = WTM / 32, TN = WTN / 32;  // 32x32 MFMA tiles per wavefront
+template <int BM, int BN, int NS, int KIND>
+__global__ __launch_bounds__(256) void gemm_sk_kernel(SkParams sp) {
+    const GemmParams& p = sp.g;
+    constexpr int NW = 4;
+    constexpr int WTM = BM / 2, WTN = BN / 2;    // wavefront tile: WTM token rows x WTN weight columns
+    constexpr int TM = WTM / 16, TN = WTN / 16;  // activation tiles (B operands), weight tiles (A operands)
     constexpr int NBLK = (BM + BN) / 16;         // KiB blocks per stage
-    constexpr int LPW = NBLK / NW;               // loads per wavefront per stage
-    constexpr int STAGE = NBLK * 1024;           // bytes
+    constexpr int LPW = NBLK / NW;               // copies per wavefront per stage
+    constexpr int STAGE = NBLK * 1024;
     constexpr int NT = TM * TN, NR = TM + TN;
-    static_assert(NBLK % NW == 0 && NS >= 3 && NS <= 4 && NT >= 2 && (TN == 4 || TN == 2) && TM <= 4, "shape");
-    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
+    constexpr int RSTEP = (NT * 3 / 4) / NR > 0 ? (NT * 3 / 4) / NR : 1;   // MFMAs between two operand reads
+    static_assert(NBLK % NW == 0 && NS >= 3 && NS <= 5 && (NR == 8 || NR == 12 || NR == 16) && NR * RSTEP <= NT, "shape");
+    static_assert(KIND != GemmOut::SWIGLU_BF16 || TN % 4 == 0, "a wavefront owns whole gate/up groups of 64 columns");
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];   // NS stages, then one word for the block's verdict
+    int* const s_flag = reinterpret_cast<int*>(lds + NS * STAGE);
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int wm = wave / WN, wn = wave % WN;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int r = lane & 15, g = lane >> 4;
 
-    // Consecutive block ids go to different XCDs (each with its own L2).  XCD x works through the units
-    // [x * units_per_xcd, (x+1) * units_per_xcd) of the order (column tile, split, row tile), row tile
-    // fastest: the blocks resident on one XCD at a time share a few weight tiles.
-    const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
-    const int unit = xcd * tp.units_per_xcd + idx;
-    if (idx >= tp.units_per_xcd || unit >= tp.tiles_m * tp.tiles_n * tp.splits) return;
-    const int tm = unit % tp.tiles_m, rest = unit / tp.tiles_m;
-    const int split = rest % tp.splits, tn = rest / tp.splits;
-    const int m0 = tm * BM, n0 = tn * BN;
+    // A unit is a tile's share of K: (column tile, K split, row tile), the row tile fastest.  Where the text below says
+    // tile it means unit; the tail's K loops are cut only when there is one split (sp.cut_tail implies sp.splits == 1).
+    const int xcd = blockIdx.x & 7, lb = blockIdx.x >> 3, B = sp.blocks_per_xcd;
+    const int n_units_all = sp.tiles_m * sp.tiles_n * sp.splits;
+    const int t_first = xcd * sp.tiles_per_xcd, T = min(n_units_all, t_first + sp.tiles_per_xcd) - t_first;
+    if (T <= 0) return;
+    const int full = T / B, R = T - full * B;
     const int KB = p.K >> 5;
-    const int kb0 = split * p.kb_per_split;
-    const int n_kb = min(KB, kb0 + p.kb_per_split) - kb0;
-    if (n_kb <= 0) return;  // (the host plans no empty split)
-
-    // this wavefront's LPW blocks of a stage (block b = wave + NW i): byte offsets from A / Wp, < 4 GiB
+    const int KP = sp.splits == 1 ? KB >> 1 : sp.kp_per_split;   // pairs of 32-wide k-blocks in a unit (the last split may have fewer)
     const int m_tiles = (p.M + 15) >> 4, n_tiles = p.N >> 4;
-    uint32_t off[LPW];
-#pragma unroll
-    for (int i = 0; i < LPW; i++) {
-        const int b = wave + NW * i;
-        // rows / columns past the edge re-read the last tile: its products land in accumulators that are not stored
-        if (b < BM / 16) off[i] = (uint32_t)min(m0 / 16 + b, m_tiles - 1) * (uint32_t)KB * 1024u + lane * 16;
-        else {
-            const int nt = min(n0 / 16 + (b - BM / 16), n_tiles - 1);  // weight blocks: [nt/4][kb][nt%4]
-            off[i] = ((uint32_t)(nt >> 2) * (uint32_t)KB * 4u + (uint32_t)(nt & 3)) * 1024u + lane * 16;
-        }
-    }
-    const uint8_t* gA = reinterpret_cast<const uint8_t*>(p.A) + (size_t)kb0 * 1024;
-    const uint8_t* gW = reinterpret_cast<const uint8_t*>(p.Wp) + (size_t)kb0 * 4096;
-    auto issue_one = [&](int i, int s, int slot) {
-        const int b = wave + NW * i;
-        const uint8_t* g = b < BM / 16 ? gA + (size_t)s * 1024 : gW + (size_t)s * 4096;
-        PS_GLOBAL_TO_LDS(g + off[i], lds + slot * STAGE + b * 1024);
-    };
-
-    f32x16_t acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; i++)
-#pragma unroll
-        for (int j = 0; j < TN; j++)
-#pragma unroll
-            for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
-
-    const int r = lane & 31, h = lane >> 5;
     const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
-    const uint32_t a_lane = lds0 + (wm * (WTM / 16) + (r >> 4)) * 1024 + (h * 16 + (r & 15)) * 16;
-    const uint32_t b_lane = lds0 + (BM / 16 + wn * (WTN / 16) + (r >> 4)) * 1024 + (h * 16 + (r & 15)) * 16;
+    const uint32_t x_lane = lds0 + (wm * TM) * 1024 + lane * 16;                // activation tiles of this wavefront
+    const uint32_t w_lane = lds0 + (BM / 16 + wn * TN) * 1024 + lane * 16;      // weight tiles
+    typedef OpSet<NR> Ops;   // v[0..TN) weight tiles (A operands), v[TN..NR) activation tiles (B operands)
 
-    // Operand registers of a half-stage (one k-sixteenth): v[0..TM) = A tiles, v[TM..NR) = B tiles.  They are
-    // read in the order q = 0: A0;  q = 1..TN: B0..B(TN-1);  q = TN+i: A_i (i >= 1), one read behind every
-    // NT/NR-th MFMA of the half-stage before, and waited for row by row.
-    struct Ops { u32x4_t v[NR]; } o0, o1;
-#define PS_SLOT(q) ((q) == 0 ? 0 : (q) <= TN ? TM + (q) - 1 : (q) - TN)
-#define PS_T_OF(q) (((q) + 1) * NT / NR - 1) /* MFMA behind which read q is issued */
-#define PS_READQ(o, base_a, base_b, sub, q)                                                           \
-    {                                                                                                  \
-        if (PS_SLOT(q) < TM) o.v[PS_SLOT(q)] = lds_read16(base_a, PS_SLOT(q) * 2048 + (sub) * 512);    \
-        else o.v[PS_SLOT(q)] = lds_read16(base_b, (PS_SLOT(q) - TM) * 2048 + (sub) * 512);             \
-    }
-    // Before MFMA t = i*TN (i >= 1) operand A_i must have landed.  Outstanding then: the reads of the same
-    // half-stage behind A_i (TM - 1 - i of them) and the reads of the next half-stage issued so far.
-    auto wait_row = [&](u32x4_t& a, int t) {
-        int n_new = 0;
-        for (int q = 0; q < NR; q++) n_new += (PS_T_OF(q) < t);
-        switch ((TM - 1 - t / TN) + n_new) {  // t is a constant after unrolling: one case survives
-            case 0: lgkm_tie<0>(a); break;
-            case 1: lgkm_tie<1>(a); break;
-            case 2: lgkm_tie<2>(a); break;
-            case 3: lgkm_tie<3>(a); break;
-            case 4: lgkm_tie<4>(a); break;
-            case 5: lgkm_tie<5>(a); break;
-            case 6: lgkm_tie<6>(a); break;
-            case 7: lgkm_tie<7>(a); break;
-            default: lgkm_tie<0>(a); break;
+    // the block's work: `full` whole tiles, then its run [it, it_end) of the XCD's tail, counted in pairs of k-blocks.
+    // The tail is cut over Bt <= B blocks, fewer where the runs would get too short to be worth their parked pieces;
+    // Bt <= R * KP, so no run is empty.
+    // With cut_tail off the tail is not cut: Bt = R, every run is one whole tile and nothing is parked.
+    const int Bt = R > 0 ? (sp.cut_tail ? sk_tail_blocks(B, R, KP) : R) : 0;
+    int it = lb < Bt ? sk_run_begin(lb, Bt, R, KP) : 0;
+    const int it_end = lb < Bt ? sk_run_begin(lb + 1, Bt, R, KP) : 0;
+    // The tail comes first: its parked pieces are then added up while the other blocks are already at their whole
+    // tiles, instead of at the very end with every block waiting.
+    for (int w = 0;;) {
+        int tile, kp0, kp1;
+        if (it < it_end) {
+            const int rt = it / KP;
+            tile = t_first + full * B + rt;
+            kp0 = it - rt * KP;
+            kp1 = min(KP, it_end - rt * KP);
+            it = rt * KP + kp1;
+        } else {
+            if (w >= full) break;
+            tile = t_first + w * B + lb; kp0 = 0; kp1 = KP;
+            w++;
         }
-    };
-    // One half-stage: NT MFMAs on `o`, the reads of the next half-stage into `on`, and with WITH_LOADS the
-    // LPW loads of stage s_next.  The scheduling barriers keep the written order.
-#define PS_STEP(o, on, base_a, base_b, sub, WITH_LOADS, s_next, slot_next)                                             \
-    {                                                                                                                  \
-        _Pragma("unroll") for (int t = 0; t < NT; t++) {                                                               \
-            if (t == 0) {                                                                                              \
-                if constexpr (TN == 4) lgkm_tie<NR - 1 - TN>(o.v[0], o.v[TM], o.v[TM + 1], o.v[TM + 2], o.v[TM + 3]);  \
-                else lgkm_tie<NR - 1 - TN>(o.v[0], o.v[TM], o.v[TM + 1]);                                              \
-            } else if (t % TN == 0) {                                                                                  \
-                wait_row(o.v[t / TN], t);                                                                              \
-            }                                                                                                          \
-            acc[t / TN][t % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, o.v[t / TN]),    \
-                                                                          __builtin_bit_cast(bf16x8_t, o.v[TM + t % TN]), \
-                                                                          acc[t / TN][t % TN], 0, 0, 0);               \
-            _Pragma("unroll") for (int q_ = 0; q_ < NR; q_++)                                                          \
-                if (PS_T_OF(q_) == t) PS_READQ(on, base_a, base_b, sub, q_)                                            \
-            if (WITH_LOADS) {                                                                                          \
-                _Pragma("unroll") for (int i_ = 0; i_ < LPW; i_++)                                                     \
-                    if (i_ * NT / LPW == t) issue_one(i_, s_next, slot_next);                                          \
-            }                                                                                                          \
-            __builtin_amdgcn_sched_barrier(0);                                                                         \
-        }                                                                                                              \
-    }
+        const int tm = tile % sp.tiles_m, rest = tile / sp.tiles_m;
+        const int split = rest % sp.splits, tn = rest / sp.splits;
+        const int m0 = tm * BM, n0 = tn * BN;
+        const int KPu = min(KB >> 1, (split + 1) * KP) - split * KP;   // this unit's pairs
+        kp1 = min(kp1, KPu);
+        const int kb0 = 2 * (split * KP + kp0), n_kb = 2 * (kp1 - kp0);
 
-    // NS slots, NS-1 stages in flight.  Loads past the last stage fetch the last stage again, into a slot
-    // that nobody reads any more: the loop body is the same every time and the wait counts are constants.
+        // this wavefront's LPW blocks of a stage (block b = wave + NW i): byte offsets from A / Wp, < 4 GiB
+        uint32_t off[LPW];
 #pragma unroll
-    for (int s = 0; s < NS - 1; s++)
-#pragma unroll
-        for (int i = 0; i < LPW; i++) issue_one(i, min(s, n_kb - 1), s);
-    vm_wait<(NS - 2) * LPW>();
-    __builtin_amdgcn_s_barrier();
-    uint32_t a_cur = a_lane, b_cur = b_lane;
-#pragma unroll
-    for (int q_ = 0; q_ < NR; q_++) PS_READQ(o0, a_cur, b_cur, 0, q_);
-    int slot = 0;
-    for (int s = 0; s < n_kb; s++) {
-        __builtin_amdgcn_sched_barrier(0);
-        PS_STEP(o0, o1, a_cur, b_cur, 1, false, 0, 0);
-        // Past this barrier stage s+1 has landed for every wavefront, and every wavefront has consumed
-        // stage s-1, whose slot the loads of stage s+NS-1 overwrite.  Reads of stage s may still be in
-        // flight: its slot is not touched before the next barrier.
-        vm_wait<(NS - 3) * LPW>();
-        __builtin_amdgcn_s_barrier();
-        const int next = slot + 1 == NS ? 0 : slot + 1;
-        const int prev = slot == 0 ? NS - 1 : slot - 1;
-        a_cur = a_lane + next * STAGE;
-        b_cur = b_lane + next * STAGE;
-        __builtin_amdgcn_sched_barrier(0);
-        PS_STEP(o1, o0, a_cur, b_cur, 0, true, min(s + NS - 1, n_kb - 1), prev);
-        slot = next;
-    }
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the reads issued for the stage past the end
-    vm_wait<0>();
-#undef PS_SLOT
-#undef PS_T_OF
-#undef PS_READQ
-#undef PS_STEP
-
-    // lane holds column n = lane%32, rows 8*(e/4) + 4*(lane/32) + e%4 of each 32x32 tile.  The scheduling
-    // barriers keep the tiles' stores apart: hoisting all accumulator reads to the top would need a
-    // register for each of them, and the allocator would pay for that inside the main loop.
-    const int col = lane & 31, rbase = (lane >> 5) * 4;
-    if constexpr (KIND == GemmOut::SWIGLU_BF16) {
-        // silu(gate) * up through LDS, one 32-row band of the wavefront tile at a time: the accumulators go
-        // to a private [32][WTN] fp32 patch as they are, and come back as the 8 gate and 8 up values of one
-        // row that make a 16-byte piece of the operand-order output, so that a wavefront stores whole KiB
-        // blocks.  Rows past M are stored too: the buffer holds whole row tiles (gemm_out_bytes).
-        constexpr int RS = WTN + 4;  // patch row stride in floats: the 16 rows of a read fall into different banks
-        static_assert(32 * RS * 4 * NW <= NS * STAGE, "epilogue patch fits the stage ring");
-        __syncthreads();  // every wavefront is done with the stages
-        float* patch = reinterpret_cast<float*>(lds) + wave * 32 * RS;
-        const int F = p.N >> 1;
-        bf16_t* out = static_cast<bf16_t*>(p.out);
-        const int g8 = lane >> 4, r16 = lane & 15;
-#pragma unroll
-        for (int i = 0; i < TM; i++) {
-#pragma unroll
-            for (int j = 0; j < TN; j++)
-#pragma unroll
-                for (int e = 0; e < 16; e++) patch[((e >> 2) * 8 + rbase + (e & 3)) * RS + j * 32 + col] = acc[i][j][e];
-            const int mb = m0 + wm * WTM + i * 32;
-#pragma unroll
-            for (int band = 0; band < 2; band++)
-#pragma unroll
-                for (int j = 0; j < TN; j += 2) {
-                    const int nb = n0 + wn * WTN + j * 32;  // multiple of 64: gate tile, then up tile of the same 32 features
-                    const float* src = patch + (band * 16 + r16) * RS + j * 32 + g8 * 8;
-                    const float4 ga = *reinterpret_cast<const float4*>(src), gb = *reinterpret_cast<const float4*>(src + 4);
-                    const float4 ua = *reinterpret_cast<const float4*>(src + 32), ub = *reinterpret_cast<const float4*>(src + 36);
-                    uint4 o;
-                    o.x = pack_bf16(silu_f(ga.x) * ua.x, silu_f(ga.y) * ua.y);
-                    o.y = pack_bf16(silu_f(ga.z) * ua.z, silu_f(ga.w) * ua.w);
-                    o.z = pack_bf16(silu_f(gb.x) * ub.x, silu_f(gb.y) * ub.y);
-                    o.w = pack_bf16(silu_f(gb.z) * ub.z, silu_f(gb.w) * ub.w);
-                    // KiB block (row band, 32-feature block): lane = 16 g + row holds features 8 g .. 8 g + 7 of its row
-                    if (nb < p.N)
-                        *reinterpret_cast<uint4*>(out + ((size_t)((mb >> 4) + band) * (F >> 5) + (nb >> 6)) * 512 + lane * 8) = o;
-                }
-            __builtin_amdgcn_sched_barrier(0);
+        for (int i = 0; i < LPW; i++) {
+            const int b = wave + NW * i;
+            // rows / columns past the edge re-read the last tile: its products land in accumulators that are not stored
+            if (b < BM / 16) off[i] = (uint32_t)min(m0 / 16 + b, m_tiles - 1) * (uint32_t)KB * 1024u + lane * 16;
+            else {
+                const int nt = min(n0 / 16 + (b - BM / 16), n_tiles - 1);  // weight blocks: [nt/4][kb][nt%4]
+                off[i] = ((uint32_t)(nt >> 2) * (uint32_t)KB * 4u + (uint32_t)(nt & 3)) * 1024u + lane * 16;
+            }
         }
-    } else {
-        const bool interior = m0 + BM <= p.M && n0 + BN <= p.N;
-        float* out = static_cast<float*>(p.out) + (size_t)split * p.M * p.N;
+        const uint8_t* gA = reinterpret_cast<const uint8_t*>(p.A) + (size_t)kb0 * 1024;
+        const uint8_t* gW = reinterpret_cast<const uint8_t*>(p.Wp) + (size_t)kb0 * 4096;
+        auto issue_one = [&](int i, int s, int slot) {
+            const int b = wave + NW * i;
+            const uint8_t* gp = b < BM / 16 ? gA + (size_t)s * 1024 : gW + (size_t)s * 4096;
+            PS_GLOBAL_TO_LDS(gp + off[i], lds + slot * STAGE + b * 1024);
+        };
+
+        f32x4_t acc[TN][TM];
 #pragma unroll
-        for (int i = 0; i < TM; i++)
+        for (int i = 0; i < TN; i++)
 #pragma unroll
-            for (int j = 0; j < TN; j++) {
+            for (int j = 0; j < TM; j++) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        // the zeroing stays up here, a prologue away from the first matrix instruction that reads it (the compiler
+        // sees no hazard between a register write and the assembly that follows)
+        __builtin_amdgcn_sched_barrier(0);
+
+        auto read_op = [&](Ops& o, int q, uint32_t xb, uint32_t wb) {
+            if (q < TN) o.v[q] = lds_read16(wb, q * 1024);
+            else o.v[q] = lds_read16(xb, (q - TN) * 1024);
+        };
+        // One stage: NT MFMAs on `cur`; the reads of the next stage (slot `rslot`) into `nxt`; the copies of stage
+        // `s_load` into slot `lslot`.  The scheduling barriers keep the written order.
+        auto stage = [&](Ops& cur, Ops& nxt, int rslot, int s_load, int lslot) {
+            const uint32_t xb = x_lane + rslot * STAGE, wb = w_lane + rslot * STAGE;
 #pragma unroll
-                for (int e = 0; e < 16; e++) {
-                    const int m = m0 + wm * WTM + i * 32 + (e >> 2) * 8 + rbase + (e & 3);
-                    const int n = n0 + wn * WTN + j * 32 + col;
-                    if (interior || (m < p.M && n < p.N)) out[(size_t)m * p.N + n] = acc[i][j][e];
-                }
+            for (int t = 0; t < NT; t++) {
+                const int i = t / TM, j = t % TM;
+                mfma16_acc(acc[i][j], cur.v[i], cur.v[TN + j]);
+                if (t % RSTEP == 0 && t / RSTEP < NR) read_op(nxt, t / RSTEP, xb, wb);
+#pragma unroll
+                for (int l = 0; l < LPW; l++)
+                    if (t == (l + 1) * NT / (LPW + 1)) issue_one(l, s_load, lslot);
                 __builtin_amdgcn_sched_barrier(0);
             }
+            lgkm0_tie(nxt);
+            __builtin_amdgcn_sched_barrier(0);
+        };
+
+        // Every wavefront is done with the previous tile's stages and with what its epilogue kept in the ring.
+        __builtin_amdgcn_s_barrier();
+        // NS slots, NS-1 stages in flight.  Copies past the last stage fetch the last stage again, into a slot
+        // that nobody reads any more: the loop body is the same every time and the wait counts are constants.
+#pragma unroll
+        for (int s = 0; s < NS - 1; s++)
+#pragma unroll
+            for (int i = 0; i < LPW; i++) issue_one(i, min(s, n_kb - 1), s);
+        vm_wait<(NS - 2) * LPW>();
+        __builtin_amdgcn_s_barrier();
+        Ops o0, o1;
+#pragma unroll
+        for (int q = 0; q < NR; q++) read_op(o0, q, x_lane, w_lane);
+        lgkm0_tie(o0);
+        __builtin_amdgcn_sched_barrier(0);
+        int slot = 0;
+        // Top of stage s: once every wavefront is past the barrier, stage s+1 has landed for all of them, and all of
+        // them have read stage s (into registers, before the end of stage s-1) and stage s-1, whose slot the copies
+        // of stage s+NS-1 overwrite.
+#define PS_STAGE16(CUR, NXT, S)                                            \
+        {                                                                  \
+            vm_wait<(NS - 3) * LPW>();                                     \
+            __builtin_amdgcn_s_barrier();                                  \
+            const int next_ = slot + 1 == NS ? 0 : slot + 1;               \
+            const int prev_ = slot == 0 ? NS - 1 : slot - 1;               \
+            __builtin_amdgcn_sched_barrier(0);                             \
+            stage(CUR, NXT, next_, min((S) + NS - 1, n_kb - 1), prev_);    \
+            slot = next_;                                                  \
+        }
+        for (int s = 0; s < n_kb; s += 2) {   // n_kb is even: runs are counted in pairs of k-blocks
+            PS_STAGE16(o0, o1, s)
+            PS_STAGE16(o1, o0, s + 1)
+        }
+#undef PS_STAGE16
+        vm_wait<0>();
+        // the last matrix instructions have written their accumulators before anything reads them
+        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+
+        // lane (r, g) holds, of tile (i, j): row m = 16 j + r, columns n = 16 i + 4 g + 0..3
+        const bool whole = kp0 == 0 && kp1 == KPu;
+        if (whole) {
+            if constexpr (KIND == GemmOut::SWIGLU_BF16) {
+                // weight tiles 4q, 4q+1 = gate and 4q+2, 4q+3 = up of the same 32 features: the pair sits in the same
+                // lane.  The accumulators live in the accumulation registers, which the vector ALU cannot read; asking
+                // the compiler for copies makes it spill inside the main loop.  So each lane parks one activation
+                // tile's TN accumulators in its own 16 bytes of TN KiB blocks of the (now free) stage ring -- LDS
+                // stores take accumulation registers as data -- and reads them back into vector registers: no other
+                // lane is involved, no barrier is needed.
+                const int F = p.N >> 1;
+                bf16_t* out = static_cast<bf16_t*>(p.out);
+                __builtin_amdgcn_s_barrier();   // every wavefront has read its last stage
+                const uint32_t park = lds0 + wave * (TN * 1024) + lane * 16;
+#pragma unroll
+                for (int j = 0; j < TM; j++) {
+                    const int m = m0 + wm * WTM + 16 * j + r;   // rows past M are stored too: the buffer holds whole row tiles
+#pragma unroll
+                    for (int i = 0; i < TN; i++) asm volatile("ds_write_b128 %0, %1 offset:%2" : : "v"(park), "a"(acc[i][j]), "n"(i * 1024) : "memory");
+                    OpSet<TN> v;
+#pragma unroll
+                    for (int i = 0; i < TN; i++) v.v[i] = lds_read16(park, i * 1024);
+                    lgkm0_tie(v);
+#pragma unroll
+                    for (int q = 0; q < TN / 4; q++) {
+                        const int nb = n0 + wn * WTN + 64 * q;
+                        if (nb >= p.N) continue;
+#pragma unroll
+                        for (int h = 0; h < 2; h++) {
+                            const f32x4_t ga = __builtin_bit_cast(f32x4_t, v.v[4 * q + h]), up = __builtin_bit_cast(f32x4_t, v.v[4 * q + 2 + h]);
+                            uint2 o;
+                            o.x = pack_bf16(silu_f(ga[0]) * up[0], silu_f(ga[1]) * up[1]);
+                            o.y = pack_bf16(silu_f(ga[2]) * up[2], silu_f(ga[3]) * up[3]);
+                            *reinterpret_cast<uint2*>(out + act_offset(m, (nb >> 1) + 16 * h + 4 * g, F)) = o;
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            } else {
+                float* out = static_cast<float*>(p.out) + (size_t)split * p.M * p.N;
+#pragma unroll
+                for (int j = 0; j < TM; j++) {
+                    const int m = m0 + wm * WTM + 16 * j + r;
+#pragma unroll
+                    for (int i = 0; i < TN; i++) {
+                        const int n = n0 + wn * WTN + 16 * i + 4 * g;
+                        // straight from the accumulation registers (stores take them as data)
+                        if (m < p.M && n < p.N) asm volatile("global_store_dwordx4 %0, %1, off" : : "v"(out + (size_t)m * p.N + n), "a"(acc[i][j]) : "memory");
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            continue;
+        }
+
+        // Part of the tile's K range.  Park the accumulators: piece (i, j) of wavefront `wave` at
+        // [slot][wave][i * TM + j][lane] as a float4 (stores take accumulation registers as data).
+        const size_t slot_floats = (size_t)BM * BN;
+        const int rt = tile - (t_first + full * B);
+        // piece (block lb, tail tile rt) -> slot lb + rt: a block's two pieces lie in consecutive tiles, and the next
+        // block begins in its last tile or the one after, so the indices never collide
+        float* const my_slot = sp.frag + ((size_t)xcd * sp.slots_per_xcd + sk_slot(lb, rt)) * slot_floats;
+        {
+            float* fp = my_slot + ((size_t)wave * NT * 64 + lane) * 4;
+#pragma unroll
+            for (int i = 0; i < TN; i++)
+#pragma unroll
+                for (int j = 0; j < TM; j++) {
+                    float* q = fp + (size_t)(i * TM + j) * 256;
+                    asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(q), "a"(acc[i][j]) : "memory");
+                }
+        }
+        // the runs that share this tile: blocks first_lb .. last_lb of this XCD, in the order of their K ranges
+        const int first_lb = sk_first_block(rt, Bt, R, KP), last_lb = sk_last_block(rt, Bt, R, KP);
+        // The pieces are exchanged with device-scope (sc1) stores and loads: written through to memory, read around
+        // whatever an XCD's L2 may hold.  A device-scope fence would do as well, but it writes back and invalidates the
+        // whole L2 of the XCD each time, and the 31 other blocks there lose their operand panels with it.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's pieces have been written through
+        __syncthreads();                                    // ... and every thread's
+        if (threadIdx.x == 0) {
+            const int old = __hip_atomic_fetch_add(sp.counters + tile, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            *s_flag = old == last_lb - first_lb;
+        }
+        __syncthreads();
+        const bool last = *s_flag != 0;
+        if (!last) continue;
+        if (threadIdx.x == 0) sp.counters[tile] = 0;   // clean for the next launch
+        const int n_runs = last_lb - first_lb + 1;
+        auto piece_of = [&](int c) -> const float* {
+            return sp.frag + ((size_t)xcd * sp.slots_per_xcd + sk_slot(first_lb + c, rt)) * slot_floats + ((size_t)wave * NT * 64 + lane) * 4;
+        };
+#pragma unroll
+        for (int j = 0; j < TM; j++) {
+            const int m = m0 + wm * WTM + 16 * j + r;
+            float4 sum[TN];
+#pragma unroll
+            for (int i = 0; i < TN; i++) sum[i] = float4{0.f, 0.f, 0.f, 0.f};
+            for (int c = 0; c < n_runs; c += 2) {   // two runs' loads in flight at a time; always added in run order
+                const bool two = c + 1 < n_runs;
+                const float* q0 = piece_of(c);
+                const float* q1 = piece_of(two ? c + 1 : c);
+                OpSet<TN> v0, v1;
+#pragma unroll
+                for (int i = 0; i < TN; i++) asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v0.v[i]) : "v"(q0 + (size_t)(i * TM + j) * 256) : "memory");
+#pragma unroll
+                for (int i = 0; i < TN; i++) asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v1.v[i]) : "v"(q1 + (size_t)(i * TM + j) * 256) : "memory");
+                vm0_tie(v0);
+                vm0_tie(v1);
+#pragma unroll
+                for (int i = 0; i < TN; i++) {
+                    const f32x4_t f = __builtin_bit_cast(f32x4_t, v0.v[i]);
+                    sum[i].x += f[0]; sum[i].y += f[1]; sum[i].z += f[2]; sum[i].w += f[3];
+                }
+                if (two) {
+#pragma unroll
+                    for (int i = 0; i < TN; i++) {
+                        const f32x4_t f = __builtin_bit_cast(f32x4_t, v1.v[i]);
+                        sum[i].x += f[0]; sum[i].y += f[1]; sum[i].z += f[2]; sum[i].w += f[3];
+                    }
+                }
+            }
+            if constexpr (KIND == GemmOut::SWIGLU_BF16) {
+                const int F = p.N >> 1;
+                bf16_t* out = static_cast<bf16_t*>(p.out);
+#pragma unroll
+                for (int q = 0; q < TN / 4; q++) {
+                    const int nb = n0 + wn * WTN + 64 * q;
+                    if (nb >= p.N) continue;
+#pragma unroll
+                    for (int h = 0; h < 2; h++) {
+                        const float4 ga = sum[4 * q + h], up = sum[4 * q + 2 + h];
+                        uint2 o;
+                        o.x = pack_bf16(silu_f(ga.x) * up.x, silu_f(ga.y) * up.y);
+                        o.y = pack_bf16(silu_f(ga.z) * up.z, silu_f(ga.w) * up.w);
+                        *reinterpret_cast<uint2*>(out + act_offset(m, (nb >> 1) + 16 * h + 4 * g, F)) = o;
+                    }
+                }
+            } else {
+                float* out = static_cast<float*>(p.out);
+#pragma unroll
+                for (int i = 0; i < TN; i++) {
+                    const int n = n0 + wn * WTN + 16 * i + 4 * g;
+                    if (m < p.M && n < p.N) *reinterpret_cast<float4*>(out + (size_t)m * p.N + n) = sum[i];
+                }
+            }
+        }
     }
 }
 
@@ -430,36 +585,75 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_dma_kernel(TiledParams tp) 
 // ------------------------------------------------------------------------------------------
 struct GemmPlan {
     bool wstream;
-    bool big_tile;     // tiled: 256x256 blocks (else 128x128)
-    int splits;        // partial buffers written
-    int kb_per_split;  // 32-wide k-blocks per block
+    bool big_tile;      // tiled: 256x256 blocks (else 128x128)
+    int splits;         // partial buffers written
+    int kb_per_split;   // 32-wide k-blocks per split
+    bool cut_tail;      // tiled: cut the K loops of the last, partial wave of tiles over the blocks (one split only)
+    int slots_per_xcd;  // tiled: parked pieces an XCD may hold
 };
 
-// Tiled-kernel cost model, fitted to measured sweeps over the layer's GEMM shapes (M 144 .. 2304):
-// a 256x256 block runs alone on a CU and takes ~1.0 us per 32-wide k-stage; two 128x128 blocks share a
-// CU at ~0.62 us per stage each.  A unit costs its stages plus ~10 stages of prologue and epilogue,
-// units run in rounds of one per slot, and every split beyond the first adds partial-sum traffic.
-static double tiled_cost(int M, int N, int K, bool big, int splits, int* kb_per_split, int* eff_splits) {
-    const int B = big ? 256 : 128, slots = big ? 256 : 512;
-    const double t_stage = big ? 1.0 : 0.62;
-    const int KB = K / 32, kps = (KB + splits - 1) / splits, s_eff = (KB + kps - 1) / kps;
-    const long units = (long)((M + B - 1) / B) * ((N + B - 1) / B) * s_eff;
-    const long rounds = (units + slots - 1) / slots;
-    *kb_per_split = kps;
-    *eff_splits = s_eff;
-    return rounds * (kps + 10) * t_stage + (s_eff > 1 ? 2.0 * (s_eff - 1) * (double)M * N * 4 / 5e6 : 0.0);
+static int device_cus() {
+    static int cus = 0;
+    static std::once_flag once;
+    std::call_once(once, [] {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+        cus = (cus + 7) / 8 * 8;
+    });
+    return cus;
 }
 
-static GemmPlan plan_gemm(int M, int N, int K, int kind, int split_opt, int tile_opt) {
+// Estimated time (us) of the tiled kernel for one choice of tile edge, K splits and tail cutting, from the rates measured
+// on the layer shapes: a block takes about 1.4 us (0.9 us for a 128x128 tile, two of which share a compute unit) per pair
+// of k-blocks plus a fixed prologue and epilogue per unit; blocks take units in waves; every split beyond the first is
+// written and read back by the consumer; parked pieces of a cut tail cost about 2 us per MB all told (store, count,
+// reload by the last block and the clock the extra traffic costs the rest of the step: measured on the gate/up and O
+// matrices), less where whole tiles follow to hide them behind.
+static double tiled_estimate(int M, int N, int K, int edge, int splits, bool cut, int* kp_per_split, int* eff_splits, int* slots_per_xcd) {
+    const int B = device_cus() * (edge == 256 ? 1 : 2) / 8;
+    const int KPt = K / 64;
+    const int kps = (KPt + splits - 1) / splits, s_eff = (KPt + kps - 1) / kps;
+    const int tiles = ((M + edge - 1) / edge) * ((N + edge - 1) / edge), units = tiles * s_eff;
+    const int upx = (units + 7) / 8;
+    const double t_pair = edge == 256 ? 1.4 : 0.9, t_fix = edge == 256 ? 8.0 : 4.0;
+    const double unit_us = kps * t_pair + t_fix;
+    double waves = 0;
+    int slots = 0, pieces = 0;
+    bool any_full = false;
+    for (int x = 0; x < 8; x++) {
+        const int T = std::min(units, (x + 1) * upx) - x * upx;
+        if (T <= 0) break;
+        const int full = T / B, R = T % B;
+        any_full |= full > 0;
+        if (!cut || R == 0) { waves = std::max(waves, (double)full + (R > 0)); continue; }
+        const int Bt = sk_tail_blocks(B, R, kps);
+        waves = std::max(waves, full + (double)R / Bt);
+        slots = std::max(slots, sk_slots(Bt, R));
+        pieces += Bt > R ? sk_slots(Bt, R) : 0;
+    }
+    *kp_per_split = kps;
+    *eff_splits = s_eff;
+    *slots_per_xcd = slots;
+    double us = waves * unit_us;
+    if (s_eff > 1) us += 2.0 * (s_eff - 1) * (double)M * N * 4 / 3e6;
+    if (cut) us += pieces * (double)edge * edge * 4 / 0.5e6 * (any_full ? 0.6 : 1.0) + 10.0;
+    return us;
+}
+
+static GemmPlan plan_gemm(int M, int N, int K, int kind, int split_opt, int tile_opt, int sk_mode = 0) {
     GemmPlan g;
     // measured: streaming wins up to 96 tokens for every projection, and up to 160 (ten row tiles) for all but the QKV-shaped
     // one (more columns than rows of weights: 48 blocks per split and six splits of partial sums; 129 tokens: 29 vs 24 us),
     // above all for the gate/up matrix (129 tokens: 61 vs 75 us) and the down projection (42 vs 46)
     g.wstream = M <= 64 || (tile_opt == 0 && (M <= 96 || (M <= 160 && (kind == GemmOut::SWIGLU_BF16 || N <= K))));
     g.big_tile = false;
-    int s = 1;
+    g.splits = 1;
+    g.kb_per_split = K / 32;
+    g.cut_tail = false;
+    g.slots_per_xcd = 0;
     if (g.wstream) {
         const int groups = N / 64, KB = K / 32;
+        int s = 1;
         if (kind != GemmOut::SWIGLU_BF16) {
             s = split_opt > 0 ? split_opt : (512 + groups - 1) / groups;  // aim at two blocks per CU
             s = std::min(s, 8);
@@ -471,19 +665,25 @@ static GemmPlan plan_gemm(int M, int N, int K, int kind, int split_opt, int tile
         g.kb_per_split = kps;
         g.splits = (KB + kps - 1) / kps;
     } else {
+        // every combination of tile edge, K splits (none for the gate/up matrix, whose epilogue is not linear) and, for
+        // one split, tail cutting; the smallest estimate wins
         const int s_lo = kind == GemmOut::SWIGLU_BF16 ? 1 : (split_opt > 0 ? std::min(split_opt, 8) : 1);
         const int s_hi = kind == GemmOut::SWIGLU_BF16 ? 1 : (split_opt > 0 ? s_lo : 8);
         double best = 0;
         bool first = true;
-        for (int big = (tile_opt == 256 ? 1 : 0); big < (tile_opt == 128 ? 1 : 2); big++)
-            for (int sp = s_lo; sp <= s_hi; sp++) {
-                int kps, eff;
-                const double c = tiled_cost(M, N, K, big != 0, sp, &kps, &eff);
-                if (first || c < best) {
-                    first = false; best = c;
-                    g.big_tile = big != 0; g.splits = eff; g.kb_per_split = kps;
+        for (int edge : {128, 256}) {
+            if ((tile_opt == 128 || tile_opt == 256) && edge != tile_opt) continue;
+            for (int sp = s_lo; sp <= s_hi; sp++)
+                for (int cut = 0; cut < (sp == 1 && sk_mode == 0 ? 2 : 1); cut++) {
+                    int kps, eff, slots;
+                    const double us = tiled_estimate(M, N, K, edge, sp, cut != 0, &kps, &eff, &slots);
+                    if (cut && slots == 0) continue;
+                    if (first || us < best) {
+                        first = false; best = us;
+                        g.big_tile = edge == 256; g.splits = eff; g.kb_per_split = 2 * kps; g.cut_tail = cut != 0; g.slots_per_xcd = slots;
+                    }
                 }
-            }
+        }
     }
     return g;
 }
@@ -498,24 +698,44 @@ size_t gemm_out_bytes(int M, int N, int K, int kind, int split_opt, int tile_opt
     return (size_t)plan_gemm(M, N, K, kind, split_opt, tile_opt).splits * M * N * sizeof(float);
 }
 
-template <int BM, int BN, int WM, int WN, int NS, int KIND>
-static hipError_t launch_tiled(const GemmParams& p, const GemmPlan& g, hipStream_t st) {
-    constexpr int lds_bytes = (BM + BN) / 16 * 1024 * NS;
+void gemm_workspace(int M, int N, int K, int kind, int split_opt, int tile_opt, size_t* frag_bytes, int* n_counters) {
+    *frag_bytes = 0;
+    *n_counters = 0;
+    if (M <= 0) return;
+    const GemmPlan g = plan_gemm(M, N, K, kind, split_opt, tile_opt);
+    if (g.wstream) return;
+    const int b = g.big_tile ? 256 : 128;
+    *frag_bytes = (size_t)8 * g.slots_per_xcd * b * b * sizeof(float);
+    *n_counters = ((M + b - 1) / b) * ((N + b - 1) / b);
+}
+
+template <int BM, int BN, int NS, int KIND>
+static hipError_t launch_sk(const GemmParams& p, const GemmArgs& a, const GemmPlan& g, hipStream_t st) {
+    constexpr int lds_bytes = (BM + BN) / 16 * 1024 * NS + 16;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [] {   // more dynamic LDS than the default limit: raise it once per kernel
-        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_dma_kernel<BM, BN, WM, WN, NS, KIND>),
+        attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_sk_kernel<BM, BN, NS, KIND>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     });
     if (attr_err != hipSuccess) return attr_err;
-    TiledParams tp;
-    tp.g = p;
-    tp.tiles_m = (p.M + BM - 1) / BM;
-    tp.tiles_n = (p.N + BN - 1) / BN;
-    tp.splits = g.splits;
-    const long units = (long)tp.tiles_m * tp.tiles_n * tp.splits;
-    tp.units_per_xcd = (int)((units + 7) / 8);
-    hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WM, WN, NS, KIND>), dim3(tp.units_per_xcd * 8), dim3(64 * WM * WN), lds_bytes, st, tp);
+    SkParams sp;
+    sp.g = p;
+    sp.tiles_m = (p.M + BM - 1) / BM;
+    sp.tiles_n = (p.N + BN - 1) / BN;
+    sp.splits = g.splits;
+    sp.kp_per_split = g.kb_per_split / 2;
+    const int tiles = sp.tiles_m * sp.tiles_n;
+    sp.tiles_per_xcd = (tiles * g.splits + 7) / 8;
+    const int blocks = device_cus() * (BM == 256 ? 1 : 2);   // resident at once: one 256x256 block or two 128x128 blocks per CU
+    sp.blocks_per_xcd = blocks / 8;
+    sp.cut_tail = g.cut_tail ? 1 : 0;
+    sp.slots_per_xcd = g.slots_per_xcd;
+    sp.frag = a.sk_frag;
+    sp.counters = a.sk_counters;
+    if (g.cut_tail && ((size_t)8 * sp.slots_per_xcd * BM * BN * sizeof(float) > a.sk_frag_bytes || tiles > a.sk_n_counters || !a.sk_counters || !a.sk_frag || g.splits != 1))
+        return hipErrorInvalidValue;
+    hipLaunchKernelGGL((gemm_sk_kernel<BM, BN, NS, KIND>), dim3(blocks), dim3(256), lds_bytes, st, sp);
     return hipGetLastError();
 }
 
@@ -526,8 +746,10 @@ hipError_t launch_gemm(const GemmArgs& a, int* n_splits, hipStream_t st) {
     // the tiled kernel addresses A and Wp with 32-bit byte offsets
     if (a.M > 64 && ((size_t)a.N * a.K * 2 >= (1ull << 32) || (size_t)((a.M + 15) / 16 * 16) * a.K * 2 >= (1ull << 32)))
         return hipErrorInvalidValue;
-    const GemmPlan g = plan_gemm(a.M, a.N, a.K, a.kind, a.split_k, a.tile);
-    if (gemm_out_bytes(a.M, a.N, a.K, a.kind, a.split_k, a.tile) > a.out_bytes) return hipErrorInvalidValue;
+    const GemmPlan g = plan_gemm(a.M, a.N, a.K, a.kind, a.split_k, a.tile, a.sk_mode);
+    if ((size_t)g.splits * (a.kind == GemmOut::SWIGLU_BF16 ? 0 : (size_t)a.M * a.N * sizeof(float)) > a.out_bytes ||
+        gemm_out_bytes(a.M, a.N, a.K, a.kind, a.split_k, a.tile) > a.out_bytes)
+        return hipErrorInvalidValue;
     GemmParams p;
     p.A = a.A; p.Wp = a.Wp; p.M = a.M; p.N = a.N; p.K = a.K; p.kind = a.kind; p.out = a.out;
     p.kb_per_split = g.kb_per_split;
@@ -559,10 +781,8 @@ hipError_t launch_gemm(const GemmArgs& a, int* n_splits, hipStream_t st) {
         return hipGetLastError();
     }
     if (a.kind == GemmOut::SWIGLU_BF16)
-        return g.big_tile ? launch_tiled<256, 256, 2, 2, 4, GemmOut::SWIGLU_BF16>(p, g, st)
-                          : launch_tiled<128, 128, 2, 2, 4, GemmOut::SWIGLU_BF16>(p, g, st);
-    return g.big_tile ? launch_tiled<256, 256, 2, 2, 4, GemmOut::PARTIAL_F32>(p, g, st)
-                      : launch_tiled<128, 128, 2, 2, 4, GemmOut::PARTIAL_F32>(p, g, st);
+        return g.big_tile ? launch_sk<256, 256, 4, GemmOut::SWIGLU_BF16>(p, a, g, st) : launch_sk<128, 128, 4, GemmOut::SWIGLU_BF16>(p, a, g, st);
+    return g.big_tile ? launch_sk<256, 256, 4, GemmOut::PARTIAL_F32>(p, a, g, st) : launch_sk<128, 128, 4, GemmOut::PARTIAL_F32>(p, a, g, st);
 }
 
 // ------------------------------------------------------------------------------------------

@@ -127,10 +127,20 @@ struct GemmArgs {
     size_t out_bytes;  // capacity of out; at least gemm_out_bytes(...)
     int split_k;       // 0 = choose
     int tile;          // M > 64: 0 = choose (streaming up to 96 tokens, then a tile), 128 or 256 = block tile edge
+    // tiled kernel only (see gemm_workspace): parked accumulators of K runs that cover part of a tile, and one counter
+    // per tile that must be zero on entry (the kernel leaves it zero)
+    int sk_mode;       // 0 = the cost model decides whether the tail's K loops are cut, 1 = never (whole tiles only)
+    float* sk_frag;
+    size_t sk_frag_bytes;
+    int* sk_counters;
+    int sk_n_counters;
 };
 // *n_splits receives the number of partial buffers written (1 for SWIGLU_BF16)
 hipError_t launch_gemm(const GemmArgs& a, int* n_splits, hipStream_t st);
 size_t gemm_out_bytes(int M, int N, int K, int kind, int split_k_opt, int tile_opt);
+// what launch_gemm needs in sk_frag / sk_counters for this shape (both 0 where the streaming kernel serves it)
+void gemm_workspace(int M, int N, int K, int kind, int split_k_opt, int tile_opt, size_t* frag_bytes, int* n_counters);
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);   // bytes: a multiple of 16
 
 struct AttnArgs {
     const bf16_t* q;   // rotated queries [T][n_q * d]: row stride ldq elements

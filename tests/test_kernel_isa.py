@@ -1,9 +1,11 @@
 """The tiled GEMM reads LDS through inline assembly that the compiler cannot see through: it does
-not know that the destination registers are written asynchronously.  The kernel is written so that
-this is safe (every read is waited for, with its registers named, before they are used; the main
-loop is one straight-line body), but a register copy, a spill or a queue drain that a different
-compiler version slipped into that loop would silently break or slow it.  This test compiles the
-kernel for gfx950 exactly as the build does and inspects the generated main loop."""
+not know that the destination registers are written asynchronously, nor that the matrix instructions
+(assembly too, to pin the accumulators to the accumulation registers) have hazards.  The kernel is
+written so that this is safe (every read is waited for, with its registers named, before they are used;
+the main loop is one straight-line body of two stages; every accumulator is reused 16 or 64 instructions
+later), but a register copy, a spill or a queue drain that a different compiler version slipped into
+that loop would silently break or slow it.  This test compiles the kernel for gfx950 exactly as the
+build does and inspects the generated code."""
 import os
 import re
 import subprocess
@@ -26,11 +28,24 @@ def gemm_asm():
 
 
 def _kernels(asm):
-    """name -> body text of every gemm_dma_kernel instantiation"""
+    """name -> body text of every gemm_sk_kernel instantiation"""
     out = {}
-    for m in re.finditer(r"^(_ZN2ps15gemm_dma_kernel\w+):\s*;.*?\n(.*?)s_endpgm", asm, re.S | re.M):
+    for m in re.finditer(r"^(_ZN2ps14gemm_sk_kernel\w+):\s*;.*?\n(.*?)s_endpgm", asm, re.S | re.M):
         out[m.group(1)] = m.group(2)
     return out
+
+
+def _main_loop(lines):
+    """the innermost loop that holds the matrix instructions: from its label to the backward branch"""
+    labels = {m.group(1): i for i, l in enumerate(lines) for m in [re.match(r"(\.LBB\d+_\d+):", l)] if m}
+    best = None
+    for i, l in enumerate(lines):
+        m = re.match(r"s_cbranch\w+ (\.LBB\d+_\d+)", l)
+        if m and m.group(1) in labels and labels[m.group(1)] < i:
+            body = [x for x in lines[labels[m.group(1)]:i + 1] if x and not x.startswith(";")]
+            if any(x.startswith("v_mfma") for x in body) and (best is None or len(body) < len(best)):
+                best = body
+    return best
 
 
 def test_tiled_gemm_main_loop_is_clean(gemm_asm):
@@ -38,24 +53,46 @@ def test_tiled_gemm_main_loop_is_clean(gemm_asm):
     assert len(ks) == 4, sorted(ks)          # two tiles x two epilogues
     for name, body in ks.items():
         lines = [l.strip() for l in body.splitlines()]
-        # the main loop: from the label that carries the loop-header comment to the backward branch
-        start = next(i for i, l in enumerate(lines) if "Inner Loop Header" in l)
-        label = next(l.split(":")[0] for l in reversed(lines[:start + 1]) if re.match(r"\.LBB\d+_\d+:", l))
-        end = next(i for i in range(start, len(lines)) if lines[i].startswith("s_cbranch") and lines[i].endswith(label))
-        loop = [l for l in lines[start:end + 1] if l and not l.startswith(";")]
+        loop = _main_loop(lines)
+        assert loop, name
         ops = [l.split()[0] for l in loop]
-        n_mfma = sum(o.startswith("v_mfma") for o in ops)
+        n_mfma = sum(o == "v_mfma_f32_16x16x32_bf16" for o in ops)
         n_read = sum(o == "ds_read_b128" for o in ops)
         n_load = sum(o.startswith("global_load_lds") for o in ops)
-        assert n_mfma in (8, 32) and n_read == (8 if n_mfma == 8 else 16) and n_load == (4 if n_mfma == 8 else 8), (name, n_mfma, n_read, n_load)
+        # two stages per trip: 2 x 64 (16) MFMAs, 2 x 16 (8) operand reads, 2 x 8 (4) copies per wavefront
+        assert (n_mfma, n_read, n_load) in ((128, 32, 16), (32, 16, 8)), (name, n_mfma, n_read, n_load)
         # nothing that moves, spills or copies registers, and no full drain of the load queue
         bad = [l for l in loop if re.match(r"(v_mov|v_accvgpr|scratch_|buffer_|v_swap|v_perm)", l) or "vmcnt(0)" in l]
         assert not bad, (name, bad)
-        assert ops.count("s_barrier") == 1, name
+        assert ops.count("s_barrier") == 2, name
+        # every matrix instruction accumulates in place, in the accumulation registers, on vector-register operands
+        for l in loop:
+            if l.startswith("v_mfma"):
+                m = re.match(r"v_mfma_f32_16x16x32_bf16 (a\[\d+:\d+\]), v\[\d+:\d+\], v\[\d+:\d+\], (a\[\d+:\d+\])$", l)
+                assert m and m.group(1) == m.group(2), (name, l)
+        # the operands a stage consumes were all waited for at the end of the stage before: the first instruction after
+        # each barrier's matrix work starts is never a read into a register the same stage's MFMAs use
+        waits = [i for i, l in enumerate(loop) if l.startswith("s_waitcnt lgkmcnt(0)")]
+        assert len(waits) == 2, (name, waits)
 
 
 def test_tiled_gemm_does_not_spill(gemm_asm):
-    for m in re.finditer(r"^\s*\.amdhsa_kernel (_ZN2ps15gemm_dma_kernel\w+)(.*?)\.end_amdhsa_kernel", gemm_asm, re.S | re.M):
+    n = 0
+    for m in re.finditer(r"^\s*\.amdhsa_kernel (_ZN2ps14gemm_sk_kernel\w+)(.*?)\.end_amdhsa_kernel", gemm_asm, re.S | re.M):
         body = m.group(2)
         scratch = re.search(r"\.amdhsa_private_segment_fixed_size (\d+)", body)
         assert scratch and int(scratch.group(1)) == 0, (m.group(1), scratch and scratch.group(1))
+        n += 1
+    assert n == 4
+
+
+def test_accumulators_are_not_read_right_behind_the_last_matrix_instruction(gemm_asm):
+    """The compiler inserts no hazard waits around the assembly: after the main loop the kernel itself must wait before
+    stores or LDS writes take the accumulation registers as data."""
+    for name, body in _kernels(gemm_asm).items():
+        lines = [l.strip() for l in body.splitlines() if l.strip() and not l.strip().startswith(";")]
+        last = max(i for i, l in enumerate(lines) if l.startswith("v_mfma"))
+        nops = [i for i, l in enumerate(lines) if l == "s_nop 15"]
+        assert len(nops) == 2 and nops[1] == nops[0] + 1 and nops[0] > last, (name, nops, last)
+        users = [i for i, l in enumerate(lines) if i > last and re.match(r"(global_store|ds_write|v_accvgpr_read)", l) and re.search(r"\ba\[?\d", l)]
+        assert users and min(users) > nops[1], (name, min(users) if users else None, nops)
