@@ -172,7 +172,7 @@ def percentiles(ms):
 
 
 def timed_steps(eng, call, steps, warmup):
-    """W untimed steps, then K steps each bracketed by an event pair on the stream the library launches on (torch's
+    """W untimed steps, then K steps with an event at every step boundary on the stream the library launches on (torch's
     current stream, handed to ps_create), the whole region bracketed by synchronisations.  call(i) enqueues step i.
     Returns per-step GPU times (ms; consecutive pairs tile the stream's timeline, so an idle GPU waiting for the host
     counts against the step), per-call host times (us) and the wall time of the region."""
@@ -181,19 +181,21 @@ def timed_steps(eng, call, steps, warmup):
         call(i)
     eng.ctx.sync()
     torch.cuda.synchronize()
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    # one event per step boundary: the end of step i is the start of step i + 1 (a record costs the stream a few
+    # microseconds, which is part of what is measured)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     host_us = []
     t0 = time.perf_counter()
+    evs[0].record(eng.stream)
     for i in range(steps):
-        evs[i][0].record(eng.stream)
         h0 = time.perf_counter()
         call(warmup + i)
         host_us.append((time.perf_counter() - h0) * 1e6)
-        evs[i][1].record(eng.stream)
+        evs[i + 1].record(eng.stream)
     eng.ctx.sync()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
-    return [b0.elapsed_time(b1) for b0, b1 in evs], host_us, wall_ms
+    return [evs[i].elapsed_time(evs[i + 1]) for i in range(steps)], host_us, wall_ms
 
 
 def cpu_baseline_cfg4(batch, seed, n_layers):

@@ -546,14 +546,11 @@ struct StagingGuard {
 
 // Copy `bytes` of staging slot `index` to its device slot on the copy stream and make the main
 // stream wait for it.  *dev receives the device address.
-static ps_status upload_meta(ps_ctx* c, const Staging* sg, int index, size_t bytes, const char** dev) {
-    if (!c->copy_stream) {
-        HIP_TRY(c, hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking));
-        for (auto& e : c->meta_ready) HIP_TRY(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
-    }
+// Device slot `index` of the metadata ring, grown to hold `bytes`.
+static ps_status dev_meta_slot(ps_ctx* c, int index, size_t bytes, char** dev) {
     if (c->dev_meta_slot < bytes) {
         HIP_TRY(c, hipStreamSynchronize(c->stream));
-        HIP_TRY(c, hipStreamSynchronize(c->copy_stream));
+        if (c->copy_stream) HIP_TRY(c, hipStreamSynchronize(c->copy_stream));
         if (c->dev_meta) (void)hipFree(c->dev_meta);
         c->dev_meta = nullptr;
         c->dev_meta_slot = 0;
@@ -562,7 +559,18 @@ static ps_status upload_meta(ps_ctx* c, const Staging* sg, int index, size_t byt
         if (st != PS_OK) return st;
         c->dev_meta_slot = want;
     }
-    char* d = c->dev_meta + (size_t)index * c->dev_meta_slot;
+    *dev = c->dev_meta + (size_t)index * c->dev_meta_slot;
+    return PS_OK;
+}
+
+static ps_status upload_meta(ps_ctx* c, const Staging* sg, int index, size_t bytes, const char** dev) {
+    if (!c->copy_stream) {
+        HIP_TRY(c, hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking));
+        for (auto& e : c->meta_ready) HIP_TRY(c, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    }
+    char* d = nullptr;
+    ps_status st0 = dev_meta_slot(c, index, bytes, &d);
+    if (st0 != PS_OK) return st0;
     HIP_TRY(c, hipMemcpyAsync(d, sg->host, bytes, hipMemcpyHostToDevice, c->copy_stream));
     HIP_TRY(c, hipEventRecord(c->meta_ready[index], c->copy_stream));
     HIP_TRY(c, hipStreamWaitEvent(c->stream, c->meta_ready[index], 0));
@@ -911,13 +919,20 @@ static ps_status step_impl(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const 
         int32_t* lr = reinterpret_cast<int32_t*>(hb + ml.last_rows);  // last new token of every sequence
         for (int i = 0; i < p.n_seqs; i++) lr[i] = p.cu_seqlens[i + 1] - 1;
     }
+    // How the metadata reaches the device.  A step on hidden states: extra blocks of its first kernel (the RMS
+    // normalisation, which needs none of it) copy it out of the pinned buffer.  A step on token ids needs it in its
+    // very first kernel (the embedding gather): copy engine, on the copy stream.
     const char* db = nullptr;
+    const void* fetch_src = nullptr;
+    void* fetch_dst = nullptr;
     if (use_static) {
-        // on the step's own stream: ordered behind the kernels of the previous step, which read the same device copy
-        HIP_TRY(c, hipMemcpyAsync(W.meta, hb, ml.total, hipMemcpyHostToDevice, c->stream));
-        HIP_TRY(c, hipEventRecord(c->static_ev[sg_idx], c->stream));
-        c->static_pending[sg_idx] = true;
         db = W.meta;
+        fetch_src = hb; fetch_dst = W.meta;
+    } else if (!tio) {
+        char* dslot = nullptr;
+        if ((st = dev_meta_slot(c, sg_idx, ml.total, &dslot)) != PS_OK) return st;
+        db = dslot;
+        fetch_src = hb; fetch_dst = dslot;
     } else if ((st = upload_meta(c, sg, sg_idx, ml.total, &db)) != PS_OK) return st;
     const int32_t* d_pos = reinterpret_cast<const int32_t*>(db + ml.positions);
     const int32_t* d_slots = reinterpret_cast<const int32_t*>(db + ml.slots);
@@ -967,7 +982,7 @@ static ps_status step_impl(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const 
         };
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[e], s));
         // 0: RMSNorm of the layer input (layers after the first get it from the previous layer's last kernel)
-        if (l == l_begin) HIP_TRY(c, launch_rmsnorm(x_cur, x_cur_f32, L.g_attn, W.xn, T, H, d.rms_eps, s));
+        if (l == l_begin) HIP_TRY(c, launch_rmsnorm(x_cur, x_cur_f32, L.g_attn, W.xn, T, H, d.rms_eps, s, nullptr, fetch_src, fetch_dst, fetch_src ? ml.total : 0));
         if (tap && c->taps.xn) HIP_TRY(c, launch_untile(W.xn, static_cast<bf16_t*>(c->taps.xn), T, H, s));
         if (tap && c->taps.x_in && l > l_begin) HIP_TRY(c, launch_copy_bytes(x_cur, c->taps.x_in, (size_t)T * H * 4, s));
         if (stats) HIP_TRY(c, hipEventRecord(c->ev[++e], s));
@@ -1110,7 +1125,12 @@ static ps_status step_impl(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const 
             for (int i = 0; i < 3; i++) HIP_TRY(c, hipEventElapsedTime(&tio->ms[i], c->ev_head[i], c->ev_head[i + 1]));
         }
     }
-    if (use_static) { guard.committed = true; return PS_OK; }
+    if (use_static) {   // the pinned slot may be refilled once the first kernel has read it; the step's end is a safe mark
+        HIP_TRY(c, hipEventRecord(c->static_ev[sg_idx], c->stream));
+        c->static_pending[sg_idx] = true;
+        guard.committed = true;
+        return PS_OK;
+    }
     if ((st = staging_commit(c, sg_idx)) == PS_OK) guard.committed = true;
     return st;
 }

@@ -84,8 +84,11 @@ struct GemmOut {
 // ------------------------------------------------------------------ launchers (device side)
 // All take the stream explicitly and return hipGetLastError() of the launch.
 // out is written in operand order (act_offset)
+// src_rows: output row i normalises input row src_rows[i].  meta_*: extra blocks of the launch copy meta_bytes (a multiple
+// of 16) from device-visible host memory to device memory (the step's metadata, see rmsnorm_kernel)
 hipError_t launch_rmsnorm(const void* x, bool x_is_f32, const bf16_t* gain, bf16_t* out, int T, int H, float eps,
-                          hipStream_t st, const int32_t* src_rows = nullptr);  // src_rows: output row i normalises input row src_rows[i]
+                          hipStream_t st, const int32_t* src_rows = nullptr, const void* meta_src = nullptr, void* meta_dst = nullptr,
+                          size_t meta_bytes = 0);
 hipError_t launch_embed_gather(const bf16_t* table, const int32_t* ids, bf16_t* out, int T, int H, hipStream_t st);
 hipError_t launch_argmax_rows(const float* x, int M, int N, int32_t* out, hipStream_t st);
 // operand-order [M][K] bf16 matrix -> row-major (for the debug taps)

@@ -20,10 +20,20 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
     return tot;
 }
 
+// The step's first kernel also brings the step's integer metadata over: blocks past the n_rows normalising ones copy
+// it from the pinned host buffer the planner filled (mapped into the device's address space) to its device slot, 16
+// bytes per thread and trip.  The kernels that read it come later in the stream; a copy engine transfer in its place
+// sat between two steps for some 16 us (it only started once the previous step's last kernel had ended).
 template <bool X_F32>
 __global__ __launch_bounds__(1024) void rmsnorm_kernel(const void* __restrict__ xin, const bf16_t* __restrict__ gain,
                                                        bf16_t* __restrict__ out, int H, float eps,
-                                                       const int32_t* __restrict__ src_rows) {
+                                                       const int32_t* __restrict__ src_rows, int n_rows,
+                                                       const uint4* __restrict__ meta_src, uint4* __restrict__ meta_dst, uint32_t meta_n16) {
+    if ((int)blockIdx.x >= n_rows) {
+        const uint32_t stride = (gridDim.x - n_rows) * blockDim.x;
+        for (uint32_t i = (blockIdx.x - n_rows) * blockDim.x + threadIdx.x; i < meta_n16; i += stride) meta_dst[i] = meta_src[i];
+        return;
+    }
     const int orow = blockIdx.x;                            // output row
     const int row = src_rows ? src_rows[orow] : orow;       // input row (the head normalises selected rows only)
     const int c = threadIdx.x * 8;
@@ -59,14 +69,19 @@ __global__ __launch_bounds__(1024) void rmsnorm_kernel(const void* __restrict__ 
 }
 
 hipError_t launch_rmsnorm(const void* x, bool x_is_f32, const bf16_t* gain, bf16_t* out, int T, int H, float eps,
-                          hipStream_t st, const int32_t* src_rows) {
+                          hipStream_t st, const int32_t* src_rows, const void* meta_src, void* meta_dst, size_t meta_bytes) {
     if (T <= 0) return hipSuccess;
-    if (H > 8192 || H % 8) return hipErrorInvalidValue;
+    if (H > 8192 || H % 8 || (meta_bytes & 15) || meta_bytes >= ((size_t)1 << 32)) return hipErrorInvalidValue;
     const int nt = ((H / 8 + 63) / 64) * 64;
+    const uint32_t n16 = (uint32_t)(meta_bytes / 16);
+    // enough copying blocks to have the whole buffer in flight at once (the reads cross the host link), 64 at most
+    const int nc = n16 ? (int)std::min<uint32_t>(64, (n16 + nt - 1) / nt) : 0;
+    const uint4* ms = static_cast<const uint4*>(meta_src);
+    uint4* md = static_cast<uint4*>(meta_dst);
     if (x_is_f32)
-        hipLaunchKernelGGL(rmsnorm_kernel<true>, dim3(T), dim3(nt), 0, st, x, gain, out, H, eps, src_rows);
+        hipLaunchKernelGGL(rmsnorm_kernel<true>, dim3(T + nc), dim3(nt), 0, st, x, gain, out, H, eps, src_rows, T, ms, md, n16);
     else
-        hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3(T), dim3(nt), 0, st, x, gain, out, H, eps, src_rows);
+        hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3(T + nc), dim3(nt), 0, st, x, gain, out, H, eps, src_rows, T, ms, md, n16);
     return hipGetLastError();
 }
 
