@@ -145,6 +145,8 @@ const char* ps_last_error(const ps_ctx* ctx);
  * that a real stack of layers would have flushed).
  * "time_attention" (N >= 1: bracket the attention kernel launch of every Nth step with HIP
  * events, see ps_attention_times; the two event records cost a few microseconds of stream time),
+ * "poison_workspaces" (1: before every step all of the library's workspaces are filled with bfloat16 NaN, so that a kernel
+ * reading what the step has not written shows in the output; for tests),
  * "time_gemm" (N >= 1: the same around each of the four projection launches of every layer of every Nth step, see
  * ps_gemm_times).  PS_EINVAL for an unknown name or bad value. */
 ps_status ps_set_option(ps_ctx* ctx, const char* name, int64_t value);

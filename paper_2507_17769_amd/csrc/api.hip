@@ -92,6 +92,7 @@ struct ps_ctx {
     int opt_gemm_split_k = 0;
     int opt_gemm_tile = 0;
     int opt_gemm_whole_tiles = 0;
+    bool opt_poison = false;
     int opt_only_layer = -1;
     bool opt_out_f32 = false;
     int tap_layer = -1;
@@ -322,6 +323,11 @@ extern "C" ps_status ps_set_option(ps_ctx* c, const char* name, int64_t value) {
     if (!strcmp(name, "gemm_tile")) {
         if (value != 0 && value != 128 && value != 256) return fail(c, PS_EINVAL, "gemm_tile must be 0, 128 or 256");
         c->opt_gemm_tile = (int)value;
+        return PS_OK;
+    }
+    if (!strcmp(name, "poison_workspaces")) {
+        if (value != 0 && value != 1) return fail(c, PS_EINVAL, "poison_workspaces must be 0 or 1");
+        c->opt_poison = value != 0;
         return PS_OK;
     }
     if (!strcmp(name, "gemm_whole_tiles")) {
@@ -885,6 +891,22 @@ static ps_status step_impl(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const 
         W.xn = c->ws_xn; W.q = c->ws_q; W.attn = c->ws_attn; W.act = c->ws_act; W.x1 = c->ws_x1; W.xmid = c->ws_xmid;
         W.part = c->ws_part; W.part_o = c->part_o; W.part_ml = c->part_ml; W.part_bytes = c->part_bytes; W.act_bytes = c->act_bytes;
         W.skfrag = c->ws_skfrag; W.skfrag_bytes = c->skfrag_bytes; W.skcnt = c->ws_skcnt; W.skcnt_n = c->skcnt_n;
+    }
+    if (c->opt_poison) {
+        // every buffer the step's kernels write before they read: bf16 NaN (0x7FC0) everywhere, which as fp32 words is a
+        // NaN too.  A kernel that reads what no kernel of this step wrote carries it into the output.
+        const uint32_t nan2 = 0x7FC07FC0u;
+        const size_t T16 = (size_t)((T + 15) & ~15);
+        HIP_TRY(c, launch_fill_words(W.xn, T16 * H * 2, nan2, c->stream));
+        HIP_TRY(c, launch_fill_words(W.q, (size_t)T * NQ * 2, nan2, c->stream));
+        HIP_TRY(c, launch_fill_words(W.attn, T16 * NQ * 2, nan2, c->stream));
+        HIP_TRY(c, launch_fill_words(W.act, W.act_bytes, nan2, c->stream));
+        HIP_TRY(c, launch_fill_words(W.x1, (size_t)T * H * 4, nan2, c->stream));
+        if (W.xmid) HIP_TRY(c, launch_fill_words(W.xmid, (size_t)T * H * 4, nan2, c->stream));
+        HIP_TRY(c, launch_fill_words(W.part, W.part_bytes, nan2, c->stream));
+        HIP_TRY(c, launch_fill_words(W.part_o, (size_t)p.n_partial_slots * 16 * d.head_dim * 4, nan2, c->stream));
+        HIP_TRY(c, launch_fill_words(W.part_ml, (size_t)p.n_partial_slots * 16 * 2 * 4, nan2, c->stream));
+        HIP_TRY(c, launch_fill_words(W.skfrag, W.skfrag_bytes, nan2, c->stream));
     }
     // the array of a static step keeps whatever the previous call left where this call's tile counters lie
     if (use_static && W.skcnt_n > 0) HIP_TRY(c, launch_fill_zero(W.skcnt, (size_t)W.skcnt_n * sizeof(int), c->stream));

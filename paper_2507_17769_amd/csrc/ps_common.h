@@ -143,7 +143,8 @@ hipError_t launch_gemm(const GemmArgs& a, int* n_splits, hipStream_t st);
 size_t gemm_out_bytes(int M, int N, int K, int kind, int split_k_opt, int tile_opt);
 // what launch_gemm needs in sk_frag / sk_counters for this shape (both 0 where the streaming kernel serves it)
 void gemm_workspace(int M, int N, int K, int kind, int split_k_opt, int tile_opt, size_t* frag_bytes, int* n_counters);
-hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);   // bytes: a multiple of 16
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);   // bytes: rounded down to a multiple of 16
+hipError_t launch_fill_words(void* p, size_t bytes, uint32_t word, hipStream_t st);
 
 struct AttnArgs {
     const bf16_t* q;   // rotated queries [T][n_q * d]: row stride ldq elements

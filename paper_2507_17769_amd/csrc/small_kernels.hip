@@ -485,17 +485,18 @@ hipError_t launch_stream_read_probe(const void* buf, size_t bytes, int blocks, u
     return hipGetLastError();
 }
 
-__global__ __launch_bounds__(256) void fill_zero_kernel(uint4* __restrict__ p, size_t n16) {
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) p[i] = uint4{0u, 0u, 0u, 0u};
+__global__ __launch_bounds__(256) void fill_words_kernel(uint4* __restrict__ p, size_t n16, uint32_t word) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) p[i] = uint4{word, word, word, word};
 }
 
-hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st) {
+hipError_t launch_fill_words(void* p, size_t bytes, uint32_t word, hipStream_t st) {
     const size_t n16 = bytes / 16;
-    if (n16 == 0) return hipSuccess;
-    const int blocks = (int)((n16 + 255) / 256 < 1024 ? (n16 + 255) / 256 : 1024);
-    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, st, static_cast<uint4*>(p), n16);
+    if (n16 == 0 || !p) return hipSuccess;
+    const int blocks = (int)((n16 + 255) / 256 < 4096 ? (n16 + 255) / 256 : 4096);
+    hipLaunchKernelGGL(fill_words_kernel, dim3(blocks), dim3(256), 0, st, static_cast<uint4*>(p), n16, word);
     return hipGetLastError();
 }
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st) { return launch_fill_words(p, bytes, 0u, st); }
 
 hipError_t launch_copy_bytes(const void* src, void* dst, size_t n, hipStream_t st) {
     const size_t n16 = n / 16;

@@ -78,13 +78,24 @@ class Case:
     """One batch on both sides.  After run(): self.err maps tensor name -> max|err|/RMS."""
 
     def __init__(self, batch, n_layers=1, n_kv_layers=1, weight_seed=0, options=None, model_override=None,
-                 weight_std=W.WEIGHT_STD):
+                 weight_std=W.WEIGHT_STD, guard=True):
+        """guard: the library fills its workspaces with bf16 NaN before every step, the harness does the same with
+        every output and tap buffer, and the pool gets one more page at either end, filled with a seeded pattern that
+        no sequence owns (the batch's page ids are shifted by one): a kernel that reads what the step has not written,
+        or writes a page too far at either end of the pool, fails the comparisons that follow."""
+        self.guard = guard
+        if guard:
+            import dataclasses
+            batch = dataclasses.replace(batch, seqs=[dataclasses.replace(s, pages=(np.asarray(s.pages) + 1).astype(np.int32)) for s in batch.seqs],
+                                        n_pool_pages=batch.n_pool_pages + 2)
         self.batch = batch
         self.model = model_override or W.MODELS[batch.model]
         self.n_layers, self.n_kv_layers = n_layers, n_kv_layers
         self.layers = [W.layer_weights(self.model, weight_seed, l, weight_std) for l in range(n_layers)]
         self.eng = Engine(self.model, batch.n_pool_pages, n_layers, n_kv_layers,
                           max_position=max(16 * 8, max(s.kv_len for s in batch.seqs) + 16))
+        if guard:
+            self.eng.ctx.set_option("poison_workspaces", 1)
         for k, v in (options or {}).items():
             self.eng.ctx.set_option(k, v)
         for l, w in enumerate(self.layers):
@@ -97,6 +108,15 @@ class Case:
                     k, v = batch.prefix_kv(i, slot)
                     self.eng.write_kv(slot, s.pages, 0, k, v)
                     self.pool.write_bits(slot, [int(p) for p in s.pages], 0, k, v)
+        if guard:   # the two pages nobody owns
+            rng = np.random.default_rng(12345)
+            m = self.model
+            for slot in range(n_kv_layers):
+                for page in (0, batch.n_pool_pages - 1):
+                    k = rng.integers(0, 0x7F80, size=(16, m["n_kv"], m["head_dim"])).astype(np.uint16)
+                    v = rng.integers(0, 0x7F80, size=(16, m["n_kv"], m["head_dim"])).astype(np.uint16)
+                    self.eng.write_kv(slot, np.array([page], dtype=np.int32), 0, k, v)
+                    self.pool.write_bits(slot, [page], 0, k, v)
         self.x_bits = batch.activations()
 
     def run(self, tap_layer=0, dtype=np.float32, stages=True):
@@ -107,19 +127,27 @@ class Case:
         T = b.n_tokens
         self.tap_layer = tap_layer
         taps = eng.alloc_taps(T)
+        if self.guard:
+            for t in taps.values():
+                t.fill_(float("nan") if t.dtype == torch.float32 else 0x7FC0)
         eng.ctx.set_taps(tap_layer, **{k: t.data_ptr() for k, t in taps.items()})
         x_dev = bits_to_dev(self.x_bits, eng.device)
         # the step twice (it is idempotent for a fixed batch): fp32 output with taps, then bf16 output
-        out32_dev = torch.empty((T, self.model["hidden"]), dtype=torch.float32, device=eng.device)
+        out32_dev = torch.full((T, self.model["hidden"]), float("nan"), dtype=torch.float32, device=eng.device)
         eng.ctx.set_option("out_f32", 1)
         _, self.stats = eng.step(b.seqs, x_dev, out32_dev, want_stats=True)
         eng.ctx.sync()
         eng.ctx.set_taps(0)
         eng.ctx.set_option("out_f32", 0)
-        out_dev, _ = eng.step(b.seqs, x_dev)
+        out_dev, _ = eng.step(b.seqs, x_dev, torch.full_like(x_dev, 0x7FC0))
         eng.ctx.sync()
         self.out_bits = dev_to_bits(out_dev)
         self.out32 = out32_dev.cpu().numpy()
+        assert np.isfinite(self.out32).all() and np.isfinite(f32(self.out_bits)).all(), "NaN in the step's output"
+        for k in ("xn", "q", "attn", "xn2", "act", "x1"):
+            tv = taps[k].cpu().numpy()
+            assert np.isfinite(tv if tv.dtype == np.float32 else f32(tv.view(np.uint16))).all(), f"NaN in the {k} tap: something read an unwritten buffer"
+
         # the bf16 output is the fp32 output rounded once, nothing else
         assert np.array_equal(self.out_bits, obf.to_bits(self.out32)), "bf16 x_out is not RNE(fp32 x_out)"
         import copy

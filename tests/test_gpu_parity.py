@@ -103,11 +103,12 @@ def test_split_plans_agree_and_runs_are_deterministic():
     for split in (0, 1, 3, 16, 100, 5000):
         c = Case(b, options={"attn_workers": split})
         errs = c.run()
+        b_run = c.batch      # the case's own copy of the batch (page ids shifted past the guard page)
         _assert_errs(errs, f"split={split}")
         first = c.out_bits.copy()
         # same plan twice: bitwise identical
         x_dev = bits_to_dev(c.x_bits, c.eng.device)
-        again, _ = c.eng.step(b.seqs, x_dev)
+        again, _ = c.eng.step(b_run.seqs, x_dev)
         c.eng.ctx.sync()
         assert np.array_equal(dev_to_bits(again), first)
         outs.append(c.out32.copy())
@@ -122,6 +123,7 @@ def test_chunked_prefill_on_gpu_matches_one_shot_and_oracle():
     base = W.custom_batch("tiny", 9, L, 0, [], name="oneshot")
     one = Case(base)
     errs = one.run()
+    pages = one.batch.seqs[0].pages      # as the case holds them (shifted past the guard page)
     _assert_errs(errs, "one-shot")
     x_bits = one.x_bits
     ref = f32(one.out_bits)
@@ -130,7 +132,7 @@ def test_chunked_prefill_on_gpu_matches_one_shot_and_oracle():
         c = Case(base)                       # same pages, weights; we drive the chunks by hand
         outs, done = [], 0
         for n in chunks:
-            seqs = [(7, n, done + n, base.seqs[0].pages)]
+            seqs = [(7, n, done + n, pages)]
             x_dev = bits_to_dev(x_bits[done:done + n], c.eng.device)
             o, _ = c.eng.step(seqs, x_dev)
             c.eng.ctx.sync()
@@ -141,8 +143,8 @@ def test_chunked_prefill_on_gpu_matches_one_shot_and_oracle():
         rms = np.sqrt(np.mean(w64 * w64))
         assert np.all(np.abs(got - w64) <= TOL * rms + hb * np.abs(w64))
         assert np.all(np.abs(got - ref) <= TOL * rms + 2 * hb * np.abs(ref))
-        k1, v1 = one.eng.read_kv(0, base.seqs[0].pages, 0, L)
-        k2, v2 = c.eng.read_kv(0, base.seqs[0].pages, 0, L)
+        k1, v1 = one.eng.read_kv(0, pages, 0, L)
+        k2, v2 = c.eng.read_kv(0, pages, 0, L)
         # both caches hold bf16 roundings of fp32 sums of the same products (the normalised input does not depend on
         # the chunking): one rounding flip plus twice the rounding-error bound of such a sum
         for a_, b_, bound in zip((k1, v1), (k2, v2), one.kv_sum_bounds()):
@@ -155,6 +157,7 @@ def test_chunked_prefill_on_gpu_matches_one_shot_and_oracle():
 def test_decode_with_kv_len_one_returns_v():
     b = W.custom_batch("tiny", 2, 0, 0, [1, 1, 1], name="kv1")
     c = Case(b)
+    b = c.batch
     T = 3
     taps = c.eng.alloc_taps(T)
     c.eng.ctx.set_taps(0, **{k: t.data_ptr() for k, t in taps.items()})
@@ -181,6 +184,7 @@ def test_three_layer_stack_with_two_kv_slots():
 def test_kv_write_read_roundtrip_is_exact():
     b = W.custom_batch("tiny", 6, 0, 0, [77], name="rt")
     c = Case(b)
+    b = c.batch
     rng = np.random.default_rng(0)
     k = rng.integers(0, 0x7F80, size=(50, 2, 64)).astype(np.uint16)
     v = rng.integers(0, 0x7F80, size=(50, 2, 64)).astype(np.uint16)
@@ -253,6 +257,7 @@ def test_teacher_forced_layer_inside_an_aliased_stack():
     c = Case(b, n_layers=4, n_kv_layers=2)
     errs = c.run(tap_layer=3)
     _assert_errs(errs, "aliased stack")
+    b = c.batch
     eng, T, H = c.eng, b.n_tokens, 256
     xin = torch.zeros((T, H), dtype=torch.float32, device=eng.device)
     xout = torch.zeros((T, H), dtype=torch.float32, device=eng.device)
