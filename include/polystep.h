@@ -128,11 +128,13 @@ void ps_destroy(ps_ctx* ctx);
  * recent failing ps_create on this thread).  Never null; valid until the next call. */
 const char* ps_last_error(const ps_ctx* ctx);
 
-/* Tuning knobs, mainly for tests: "attn_workers" (number of wavefront-workers the attention
- * KV streams are cut across, 0 = one per resident wavefront; different values cut the streams
- * in different places and must give the same results within rounding),
- * "attn_prefill_weight" (cost the attention planner charges for a pair of pages of a prefill
- * query block, where a decode token's pair costs 2; it only moves the cuts),
+/* Tuning knobs, mainly for tests: "attn_workers" (number of workers of either kind the attention
+ * KV streams are cut across, 0 = share the resident blocks between the kinds; different values cut
+ * the streams in different places and must give the same results within rounding),
+ * "attn_teams" (> 0: this many four-wavefront teams for the prefill query blocks of a step that also has
+ * decodes, the other resident blocks streaming the decodes' KV; 0 = one per CU, more if the teams would
+ * outlast the streams), "attn_prefill_weight" (what the planner charges a team for a pair of pages, in
+ * units of 100 ns, when it decides whether more than one team per CU is needed; it only moves the cuts),
  * "gemm_split_k" (0 = automatic; the weight-streaming kernel's K splits), "gemm_whole_tiles" (1: the tiled GEMM kernel gives
  * every tile to one block instead of cutting the K loops of a last, partial wave of tiles over all blocks; same results up
  * to fp32 summation order), "gemm_tile" (block tile edge of the tiled GEMM kernel, which
@@ -262,8 +264,10 @@ ps_status ps_step_indices(ps_ctx* ctx, const ps_seq* seqs, int32_t n_seqs, int32
 /* The attention work list the step would launch, host only.  Each item is 8 int32:
  * {seq index, kv head, first new-token index of its query block, number of query tokens,
  *  first KV page (logical), one past last KV page, partial slot or -1 when the item
- *  writes final output, worker}.  Items are listed worker by worker; every worker's items
- * carry (nearly) the same total KV weight.  Writes min(*n_items, cap) items. */
+ *  writes final output, worker}.  Items are listed worker by worker.  Query blocks of sequences with more
+ * new tokens than one 16-row tile holds (16 / (n_q_heads / n_kv_heads)) belong to teams (blocks of four
+ * wavefronts; eight tiles per item), which come first; the others to single wavefronts.  Within either
+ * kind every worker's items carry (nearly) the same number of KV pages.  Writes min(*n_items, cap) items. */
 ps_status ps_plan_attention(ps_ctx* ctx, const ps_seq* seqs, int32_t n_seqs, int32_t* items, int32_t cap, int32_t* n_items);
 
 /* Durations (ms) of the attention kernel launches (one per layer per step, split merge

@@ -87,7 +87,8 @@ struct ps_ctx {
 
     // options / debug
     int opt_attn_workers = 0;
-    int opt_attn_prefill_weight = 3;
+    int opt_attn_teams = 0;
+    int opt_attn_prefill_weight = 18;
     int worker_slots = 2048;
     int opt_gemm_split_k = 0;
     int opt_gemm_tile = 0;
@@ -176,8 +177,9 @@ static PlanConfig plan_config(const ps_ctx* c) {
     pc.max_position = c->desc.max_position;
     pc.n_pool_pages = c->n_pool_pages;
     pc.n_workers = c->opt_attn_workers;
-    pc.prefill_weight = c->opt_attn_prefill_weight;
-    pc.worker_slots = c->worker_slots;
+    pc.n_teams = c->opt_attn_teams;
+    pc.team_pair_ns = 100.0 * c->opt_attn_prefill_weight;
+    pc.block_slots = c->worker_slots / 4;
     pc.prefill_tokens = attn_prefill_tokens_per_item(pc.group);
     return pc;
 }
@@ -308,6 +310,11 @@ extern "C" ps_status ps_set_option(ps_ctx* c, const char* name, int64_t value) {
     if (!strcmp(name, "attn_prefill_weight")) {
         if (value < 1 || value > 64) return fail(c, PS_EINVAL, "attn_prefill_weight must be in [1, 64]");
         c->opt_attn_prefill_weight = (int)value;
+        return PS_OK;
+    }
+    if (!strcmp(name, "attn_teams")) {
+        if (value < 0 || value > (1 << 20)) return fail(c, PS_EINVAL, "attn_teams must be in [0, 2^20]");
+        c->opt_attn_teams = (int)value;
         return PS_OK;
     }
     if (!strcmp(name, "attn_workers")) {
@@ -1030,6 +1037,7 @@ static ps_status step_impl(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const 
         a.n_items = (int)p.items.size();
         a.worker_begin = reinterpret_cast<const int32_t*>(db + ml.workers);
         a.n_workers = (int)p.worker_begin.size() - 1;
+        a.n_team = p.n_team_workers;
         a.groups = reinterpret_cast<const MergeGroup*>(db + ml.groups);
         a.n_groups = (int)p.groups.size();
         a.max_splits = 0;

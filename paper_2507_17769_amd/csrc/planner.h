@@ -18,7 +18,9 @@ struct StepPlan {
     std::vector<SeqInfo> seqs;        // [n_seqs]
     std::vector<int32_t> pages;       // flat page lists (only the ceil(kv_len/16) pages in use)
     std::vector<AttnItem> items;        // grouped by worker, in worker order
-    std::vector<int32_t> worker_begin;  // [n_workers + 1]
+    std::vector<int32_t> worker_begin;  // [n_workers + 1]; the first n_team_workers workers are teams (blocks of four
+                                        // wavefronts), the others single wavefronts
+    int n_team_workers = 0;
     std::vector<MergeGroup> groups;
     int n_partial_slots = 0;
     int n_partial_items = 0;
@@ -29,10 +31,14 @@ struct PlanConfig {
     int group = 1;             // n_q_heads / n_kv_heads
     int max_position = 0;
     int n_pool_pages = -1;     // < 0: unknown (host-only context without a pool)
-    int n_workers = 0;         // attention workers; 0 = one per resident wavefront slot
-    int worker_slots = 2048;   // wavefronts of the attention kernel resident at once
-    int prefill_tokens = 8;    // query tokens per multi-tile attention item
-    int prefill_weight = 3;    // cost of a page pair of a multi-tile item; a single-tile (decode) pair costs 2
+    int n_workers = 0;         // workers of each kind; 0 = share the resident blocks between the kinds by cost
+    int n_teams = 0;           // > 0: this many teams when a step has both kinds of work (0 = by cost)
+    int block_slots = 512;     // blocks (of four wavefronts) of the attention kernel resident at once
+    int prefill_tokens = 32;   // query tokens per team item (all its tiles)
+    // cost model behind the split of the blocks: nanoseconds a team spends on a pair of pages while it has its CU's
+    // matrix units to itself and the streams keep HBM busy, the relative growth of that when two teams share every CU, HBM time of a pair streamed
+    // by a single wavefront (all of them together), time a lone wavefront needs for a pair
+    double team_pair_ns = 1800.0, team_crowding = 0.85, hbm_pair_ns = 2.75, wave_pair_ns = 2000.0;
 };
 
 // Validates the batch (see ps_seq in polystep.h).  On failure returns PS_EINVAL / PS_ERANGE

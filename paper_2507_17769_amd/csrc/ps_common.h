@@ -156,6 +156,8 @@ struct AttnArgs {
     int n_items;
     const int32_t* worker_begin;  // [n_workers + 1]: items of worker w are [worker_begin[w], worker_begin[w+1])
     int n_workers;
+    int n_team;        // the first n_team workers are teams (one block each), the rest single wavefronts
+    int team_per_xcd, wave_blocks_per_xcd;   // set by launch_attention
     const MergeGroup* groups;
     int n_groups;
     int max_splits;    // largest n_splits of any group: sizes the merge kernel's blocks

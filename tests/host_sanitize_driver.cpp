@@ -21,9 +21,10 @@ static int run_plan(FILE* f) {
     ps::StepPlan plan;
     for (int c = 0; c < n_cases; c++) {
         ps::PlanConfig pc;
-        int n_seqs = 0;
+        int n_seqs = 0, team_weight = 0;
         if (fscanf(f, "%d %d %d %d %d %d %d %d %d", &pc.n_kv_heads, &pc.group, &pc.max_position, &pc.n_pool_pages, &pc.n_workers,
-                   &pc.worker_slots, &pc.prefill_tokens, &pc.prefill_weight, &n_seqs) != 9) return 2;
+                   &pc.block_slots, &pc.prefill_tokens, &team_weight, &n_seqs) != 9) return 2;
+        pc.team_pair_ns = 100.0 * team_weight;
         std::vector<ps_seq> seqs(n_seqs);
         std::vector<std::vector<int32_t>> tables(n_seqs);
         for (int s = 0; s < n_seqs; s++) {

@@ -141,6 +141,9 @@ def test_allocator_matches_oracle_bit_exact():
     assert e.value.status == B.PS_EINVAL
 
 
+TEAM_TILES = 8   # query tiles of a team item: four wavefronts with two tiles each
+
+
 def _check_plan_covers(b, c, workers=None):
     """Every (sequence, kv head, query token, kv page needed by that token) is covered by exactly
     one work item, ranges start on even pages, partial slots do not collide, items are listed by
@@ -162,7 +165,7 @@ def _check_plan_covers(b, c, workers=None):
         assert (part < 0) == full
         per_seg.setdefault((seq, h, q0), []).append((p0, p1, part))
         if part >= 0:
-            nt = 1 if qn <= 16 // G else 2
+            nt = 1 if s.n_new <= 16 // G else TEAM_TILES
             for k in range(nt):
                 assert part + k not in slots_used
                 slots_used.add(part + k)
@@ -182,11 +185,17 @@ def _check_plan_covers(b, c, workers=None):
     return items
 
 
-def _worker_weights(items, G):
-    w = {}
+
+
+
+def _worker_weights(items, b, G):
+    """page pairs per worker, for the team workers (prefill query blocks) and the single-wavefront workers (decodes)"""
+    team, wave = {}, {}
     for seq, h, q0, qn, p0, p1, part, worker in items.tolist():
-        w[worker] = w.get(worker, 0) + ((p1 - p0 + 1) // 2) * (2 if qn <= 16 // G else 3)
-    return np.array(list(w.values()))
+        w = team if b.seqs[seq].n_new > 16 // G else wave
+        w[worker] = w.get(worker, 0) + (p1 - p0 + 1) // 2
+    assert not team or not wave or max(team) < min(wave)       # team workers come first
+    return np.array(list(team.values())), np.array(list(wave.values()))
 
 
 def test_attention_plan_covers_everything_once():
@@ -201,5 +210,9 @@ def test_attention_plan_covers_everything_once():
     for cfg in (1, 2):
         b8 = W.config_batch(cfg)
         items = _check_plan_covers(b8, c8)
-        w = _worker_weights(items, 4)
-        assert len(w) == 2048 and w.max() - w.min() <= 6, (len(w), w.min(), w.max())
+        team, wave = _worker_weights(items, b8, 4)
+        # all 512 resident blocks are used: a team is one block, four single-wavefront workers share one
+        assert len(team) + len(wave) // 4 == 512 and len(wave) % 4 == 0, (len(team), len(wave))
+        assert (len(team) > 0) == (cfg == 2)
+        for w in (team, wave):
+            assert len(w) == 0 or w.max() - w.min() <= 2, (len(w), w.min(), w.max())
