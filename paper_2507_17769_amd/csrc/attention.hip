@@ -34,12 +34,8 @@ struct PairRegs {
     uint4 ka[KS], kb[KS], va[KS], vb[KS];
 };
 
-// Decode streams read every byte once: the loads carry the non-temporal hint, so that they do not push out of L2
-// what the teams of the same launch re-read (the keys and values of the prefill chunk's prefix).
-__device__ __forceinline__ uint4 ldg16_stream(const void* p) {
-    return __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p)));
-}
-
+// Decode streams read every byte once: they load with the non-temporal hint (ldg16_stream), so that they do not push
+// out of L2 what the teams of the same launch re-read (the keys and values of the prefill chunk's prefix).
 template <int D>
 __device__ __forceinline__ void load_pair(PairRegs<D / 32>& p, const bf16_t* pool_lane, size_t page_stride, int pa, int pb) {
     constexpr int KS = D / 32;

@@ -121,8 +121,8 @@ __global__ __launch_bounds__(64 * (4 * NG + 1)) void gemm_wstream_kernel(GemmPar
     const uint8_t* w_src = reinterpret_cast<const uint8_t*>(p.Wp) + (((size_t)ng * KB + kb0) * 4 + cw) * 1024 + lane * 16;
     auto load_w = [&](uint4 (&w)[2], int st) {
         const uint8_t* gp = w_src + (size_t)min(st, n_st - 1) * 8192;
-        w[0] = ldg16(gp);
-        w[1] = ldg16(gp + 4096);
+        w[0] = ldg16_stream(gp);
+        w[1] = ldg16_stream(gp + 4096);
     };
     f32x4_t acc[MT];
 #pragma unroll

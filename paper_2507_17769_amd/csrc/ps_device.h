@@ -26,6 +26,11 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float x) { return (bf16_t)(pack_bf
 __device__ __forceinline__ bf16x8_t as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8_t, v); }
 
 __device__ __forceinline__ uint4 ldg16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
+// the same with the non-temporal hint: for data that is read once (streamed weights, decode KV)
+__device__ __forceinline__ uint4 ldg16_stream(const void* p) {
+    typedef unsigned u32x4_nt_t __attribute__((ext_vector_type(4)));
+    return __builtin_bit_cast(uint4, __builtin_nontemporal_load(reinterpret_cast<const u32x4_nt_t*>(p)));
+}
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
