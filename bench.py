@@ -92,21 +92,22 @@ def cpu_baseline(batch, weights, n_runs=2):
 
 
 def measured_traffic(workload, seed):
-    """HBM bytes per attention launch from the committed rocprofv3 counter runs (FETCH_SIZE and
-    WRITE_SIZE, each scaled by what the same counter reads for a plain copy).  None when there is no
-    record for this workload or the kernel source has changed since the counters were taken."""
+    """HBM bytes per launch of the workload's dominant kernel from the committed rocprofv3 counter runs
+    (FETCH_SIZE and WRITE_SIZE, each scaled by what the same counter reads for a plain copy).  None when
+    there is no record for this workload or the kernel source has changed since the counters were taken."""
     import hashlib
     path = os.path.join(ROOT, "paper_2507_17769_amd", "measured_traffic.json")
     try:
-        rec = json.load(open(path))
-        if rec.get("workload") != f"{workload} seed {seed}":
-            return None
-        for rel, sha in rec["source_sha256"].items():
-            if hashlib.sha256(open(os.path.join(ROOT, rel), "rb").read()).hexdigest() != sha:
-                return None
-        return float(rec["fetch_bytes"]) + float(rec["write_bytes"])
+        for rec in json.load(open(path))["records"]:
+            if rec.get("workload") != f"{workload} seed {seed}":
+                continue
+            for rel, sha in rec["source_sha256"].items():
+                if hashlib.sha256(open(os.path.join(ROOT, rel), "rb").read()).hexdigest() != sha:
+                    return None
+            return float(rec["fetch_bytes"]) + float(rec["write_bytes"])
     except Exception:
-        return None
+        pass
+    return None
 
 
 def run_grid(a):
@@ -311,9 +312,12 @@ def run_cfg4(a):
                                   f"16-token pages, seed {a.seed}", "n_tokens": T, "total_kv": total_kv, "n_layers": L},
            "ms_per_step_events": percentiles(ms), "wall_ms_per_step": wall_ms / a.steps,
            "host_us_per_step": round(float(np.median(host_us)), 1),
-           "roofline": {"bound": "mfma", "kernel": "gemm_dma_kernel: the four projection launches of one layer (QKV, O, gate/up + SwiGLU, down)",
+           "roofline": {"bound": "mfma", "kernel": "gemm_sk_kernel: the four projection launches of one layer (QKV, O, gate/up + SwiGLU, down)",
                         "achieved": tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tflops / MFMA_BF16_PEAK_TFLOPS,
-                        "traffic": None, "algorithmic_flop_per_launch_group": flop_layer, "avg_launch_group_ms": gemm_layer_ms,
+                        "traffic": measured_traffic("cfg4", a.seed),
+                        "traffic_note": "HBM bytes of the four launches of one layer: stored reading of the rocprofv3 FETCH_SIZE / WRITE_SIZE "
+                                        "counters on a two-layer stack of this workload (null once the kernel source has changed since)",
+                        "algorithmic_flop_per_launch_group": flop_layer, "avg_launch_group_ms": gemm_layer_ms,
                         "avg_launch_ms": {n: round(float(v), 4) for n, v in zip(("qkv", "o", "gate_up", "down"), gemm_recs.mean(axis=0))} if len(gemm_recs) else None,
                         "launch_groups_timed": int(len(gemm_recs)),
                         "note": "event pairs on the step's stream around each launch, in every 5th step of the timed region"},

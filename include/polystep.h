@@ -216,9 +216,11 @@ ps_status ps_step(ps_ctx* ctx, const ps_seq* seqs, int32_t n_seqs, const void* x
  * events are made by ps_create); host-side planning arrays live on the process heap.  Results are
  * bit-identical to ps_step's for the same batch and options.
  * Limits: the buffers of the step must fit the array and its metadata 512 KiB, otherwise PS_ERANGE and nothing
- * is launched (an 8B-shaped layer fits about 200 decode tokens with a few hundred thousand cached tokens; a
- * message states the bytes needed).  No per-stage statistics.  All contexts of a process on one GPU share
- * that GPU's array, which keeps the previous call's contents (nothing in it has to start at zero): static
+ * is launched (decode batches: an 8B-shaped layer fits 160 one-token sequences, a 70B-shaped one 96; steps with
+ * a prefill chunk of hundreds of tokens do not fit; the message states the bytes needed).  No per-stage
+ * statistics.  All contexts of a process on one GPU share that GPU's array, which keeps the previous call's
+ * contents (the one piece that has to start at zero, the arrival counters of the tiled GEMM, the call clears
+ * itself with a fill kernel): static
  * steps that overlap on one GPU -- two contexts on different streams -- race and must be serialised by the
  * caller; steps on one stream are ordered by the stream.  Other errors as ps_step. */
 #define PS_STATIC_SCRATCH_BYTES (64u << 20)

@@ -50,7 +50,7 @@ struct AttnItem {
     int32_t page_begin;  // logical KV pages [page_begin, page_end)
     int32_t page_end;
     int32_t partial;     // first partial slot, or -1: the item covers its whole KV span
-    int32_t worker;      // wavefront-worker the item is assigned to
+    int32_t worker;      // worker the item is assigned to: a team (block of four wavefronts) or a single wavefront
     int32_t tok_g0;      // global token index of the block's first query token
     int32_t pos0;        // cache position of that token
     int32_t page_off;    // offset of the sequence's page list in the flat page array
