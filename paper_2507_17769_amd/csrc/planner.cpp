@@ -179,6 +179,12 @@ void build_attention_plan(const PlanConfig& cfg, StepPlan& plan) {
             for (int t = n_team + 1; t < B; t++)
                 if (cost(t) < 0.98 * best) { best = cost(t); n_team = t; }
             n_wave = 4 * (B - n_team);
+            // Few decodes beside a large chunk: no more wavefronts than keep the streams inside the teams' time with a
+            // margin, so that a short stream is not cut into hundreds of pieces for the merge to put together again.
+            const double crowd = n_team <= B / 2 ? 0.0 : (double)(n_team - B / 2) / (B / 2);
+            const double t_team = pairs_team * cfg.team_pair_ns * (1.0 + cfg.team_crowding * crowd) / n_team;
+            const double need = 2.0 * pairs_wave * cfg.wave_pair_ns / std::max(t_team, 1.0);
+            if (need < n_wave) n_wave = std::max(8, (int)need);
         }
     }
     // do not spread thinner than ~4 page pairs per worker
