@@ -136,8 +136,8 @@ const char* ps_last_error(const ps_ctx* ctx);
  * outlast the streams), "attn_prefill_weight" (what the planner charges a team for a pair of pages, in
  * units of 100 ns, when it decides whether more than one team per CU is needed; it only moves the cuts),
  * "gemm_split_k" (0 = automatic; the weight-streaming kernel's K splits), "gemm_whole_tiles" (1: the tiled GEMM kernel gives
- * every tile to one block instead of cutting the K loops of a last, partial wave of tiles over all blocks; same results up
- * to fp32 summation order), "gemm_tile" (block tile edge of the tiled GEMM kernel, which
+ * every tile to one block instead of cutting the K loops of a last, partial wave of tiles over all blocks; 2: it cuts
+ * every such tail that can be cut, also where the cost model would not; same results up to fp32 summation order), "gemm_tile" (block tile edge of the tiled GEMM kernel, which
  * serves more than 64 tokens: 0 = automatic (the weight-streaming kernel stays in charge up to 96
  * tokens, up to 160 for all projections but the QKV one), 128 or 256), "out_f32" (1: ps_step writes x_out as fp32 [T][hidden],
  * the precision the residual stream is kept in, instead of rounding it to bf16).

@@ -338,7 +338,7 @@ extern "C" ps_status ps_set_option(ps_ctx* c, const char* name, int64_t value) {
         return PS_OK;
     }
     if (!strcmp(name, "gemm_whole_tiles")) {
-        if (value != 0 && value != 1) return fail(c, PS_EINVAL, "gemm_whole_tiles must be 0 or 1");
+        if (value < 0 || value > 2) return fail(c, PS_EINVAL, "gemm_whole_tiles must be 0, 1 or 2");
         c->opt_gemm_whole_tiles = (int)value;
         return PS_OK;
     }
@@ -687,14 +687,14 @@ static void sk_need(const ps_ctx* c, int T, int head_rows, size_t* frag_bytes, i
     for (const auto& sh : shapes) {
         size_t fb = 0;
         int nc = 0;
-        gemm_workspace(T, sh[0], sh[1], sh[2], c->opt_gemm_split_k, c->opt_gemm_tile, &fb, &nc);
+        gemm_workspace(T, sh[0], sh[1], sh[2], c->opt_gemm_split_k, c->opt_gemm_tile, c->opt_gemm_whole_tiles, &fb, &nc);
         *frag_bytes = std::max(*frag_bytes, fb);
         *n_counters = std::max(*n_counters, nc);
     }
     if (head_rows > 0) {   // the output projection: one row per sequence
         size_t fb = 0;
         int nc = 0;
-        gemm_workspace(head_rows, c->vocab, H, GemmOut::PARTIAL_F32, 1, c->opt_gemm_tile, &fb, &nc);
+        gemm_workspace(head_rows, c->vocab, H, GemmOut::PARTIAL_F32, 1, c->opt_gemm_tile, c->opt_gemm_whole_tiles, &fb, &nc);
         *frag_bytes = std::max(*frag_bytes, fb);
         *n_counters = std::max(*n_counters, nc);
     }
@@ -1144,6 +1144,7 @@ static ps_status step_impl(ps_ctx* c, const ps_seq* seqs, int32_t n_seqs, const 
         g.out = logits; g.out_bytes = (size_t)M * V * sizeof(float);
         g.split_k = 1;  // one partial buffer: it is the logits
         g.tile = c->opt_gemm_tile;
+        g.sk_mode = c->opt_gemm_whole_tiles;
         g.sk_frag = W.skfrag; g.sk_frag_bytes = W.skfrag_bytes; g.sk_counters = W.skcnt; g.sk_n_counters = W.skcnt_n;
         int n_splits = 1;
         HIP_TRY(c, launch_gemm(g, &n_splits, s));

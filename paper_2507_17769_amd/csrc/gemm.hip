@@ -679,10 +679,11 @@ static GemmPlan plan_gemm(int M, int N, int K, int kind, int split_opt, int tile
         for (int edge : {128, 256}) {
             if ((tile_opt == 128 || tile_opt == 256) && edge != tile_opt) continue;
             for (int sp = s_lo; sp <= s_hi; sp++)
-                for (int cut = 0; cut < (sp == 1 && sk_mode == 0 ? 2 : 1); cut++) {
+                for (int cut = 0; cut < (sp == 1 && sk_mode != 1 ? 2 : 1); cut++) {
                     int kps, eff, slots;
-                    const double us = tiled_estimate(M, N, K, edge, sp, cut != 0, &kps, &eff, &slots);
+                    double us = tiled_estimate(M, N, K, edge, sp, cut != 0, &kps, &eff, &slots);
                     if (cut && slots == 0) continue;
+                    if (cut && sk_mode == 2) us -= 1e9;   // test knob: a tail that can be cut is cut
                     if (first || us < best) {
                         first = false; best = us;
                         g.big_tile = edge == 256; g.splits = eff; g.kb_per_split = 2 * kps; g.cut_tail = cut != 0; g.slots_per_xcd = slots;
@@ -703,11 +704,11 @@ size_t gemm_out_bytes(int M, int N, int K, int kind, int split_opt, int tile_opt
     return (size_t)plan_gemm(M, N, K, kind, split_opt, tile_opt).splits * M * N * sizeof(float);
 }
 
-void gemm_workspace(int M, int N, int K, int kind, int split_opt, int tile_opt, size_t* frag_bytes, int* n_counters) {
+void gemm_workspace(int M, int N, int K, int kind, int split_opt, int tile_opt, int sk_mode, size_t* frag_bytes, int* n_counters) {
     *frag_bytes = 0;
     *n_counters = 0;
     if (M <= 0) return;
-    const GemmPlan g = plan_gemm(M, N, K, kind, split_opt, tile_opt);
+    const GemmPlan g = plan_gemm(M, N, K, kind, split_opt, tile_opt, sk_mode);
     if (g.wstream) return;
     const int b = g.big_tile ? 256 : 128;
     *frag_bytes = (size_t)8 * g.slots_per_xcd * b * b * sizeof(float);

@@ -132,7 +132,7 @@ struct GemmArgs {
     int tile;          // M > 64: 0 = choose (streaming up to 96 tokens, then a tile), 128 or 256 = block tile edge
     // tiled kernel only (see gemm_workspace): parked accumulators of K runs that cover part of a tile, and one counter
     // per tile that must be zero on entry (the kernel leaves it zero)
-    int sk_mode;       // 0 = the cost model decides whether the tail's K loops are cut, 1 = never (whole tiles only)
+    int sk_mode;       // 0 = the cost model decides whether the tail's K loops are cut, 1 = never (whole tiles only), 2 = wherever possible
     float* sk_frag;
     size_t sk_frag_bytes;
     int* sk_counters;
@@ -142,7 +142,7 @@ struct GemmArgs {
 hipError_t launch_gemm(const GemmArgs& a, int* n_splits, hipStream_t st);
 size_t gemm_out_bytes(int M, int N, int K, int kind, int split_k_opt, int tile_opt);
 // what launch_gemm needs in sk_frag / sk_counters for this shape (both 0 where the streaming kernel serves it)
-void gemm_workspace(int M, int N, int K, int kind, int split_k_opt, int tile_opt, size_t* frag_bytes, int* n_counters);
+void gemm_workspace(int M, int N, int K, int kind, int split_k_opt, int tile_opt, int sk_mode, size_t* frag_bytes, int* n_counters);
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t st);   // bytes: rounded down to a multiple of 16
 hipError_t launch_fill_words(void* p, size_t bytes, uint32_t word, hipStream_t st);
 

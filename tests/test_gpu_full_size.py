@@ -22,6 +22,22 @@ def test_8b_layer_full_size(cfg):
     c.close()
 
 
+@pytest.mark.parametrize("tails", [1, 2])
+def test_8b_layer_tiled_gemm_tails_cut_everywhere_or_nowhere(tails):
+    """The tiled GEMM's cut tails need K loops of at least 2048 to engage, so the tiny model never takes them: here every
+    projection of the 8B shape at 300 + 20 tokens (ragged row tiles) has its last wave of tiles cut over all blocks
+    (parked fp32 pieces, arrival counters, the last block sums them), or none has; the cost model's own choice is the
+    cfg 2 case above."""
+    b = W.custom_batch("8b", 5, 300, 700, [900] * 20, name="tails")
+    c = Case(b, options={"gemm_whole_tiles": tails})
+    errs = c.run()
+    print(f"tails={tails}: errors {errs}", flush=True)
+    bad = {k: v for k, v in errs.items() if not v <= TOL}
+    assert not bad, bad
+    c.check_pool()
+    c.close()
+
+
 def test_largest_latency_grid_cell_full_size():
     """The largest cell of the latency grid (2048-token chunk at its drawn prefix + 256 decodes, 8B-shaped layer): the
     tiled GEMMs with 256x256 tiles, the longest prefill work items and the decode items in one attention launch."""

@@ -100,11 +100,11 @@ def test_gqa_group_sizes_and_head_dims(n_q, n_kv, d):
 def test_split_plans_agree_and_runs_are_deterministic():
     b = W.custom_batch("tiny", 3, 40, 200, [1, 33, 500, 1000], name="splits")
     outs = []
-    for split in (0, 1, 3, 16, 100, 5000):
-        c = Case(b, options={"attn_workers": split})
+    for split, teams in ((0, 0), (1, 0), (3, 0), (16, 0), (100, 0), (5000, 0), (0, 1), (0, 3), (0, 400)):
+        c = Case(b, options={"attn_workers": split, "attn_teams": teams})
         errs = c.run()
         b_run = c.batch      # the case's own copy of the batch (page ids shifted past the guard page)
-        _assert_errs(errs, f"split={split}")
+        _assert_errs(errs, f"split={split} teams={teams}")
         first = c.out_bits.copy()
         # same plan twice: bitwise identical
         x_dev = bits_to_dev(c.x_bits, c.eng.device)
@@ -307,17 +307,19 @@ def test_every_stage_on_its_own_tiny_and_mixed():
         c.close()
 
 
-@pytest.mark.parametrize("tile,split", [(128, 0), (128, 1), (128, 3), (256, 0), (256, 1), (256, 2), (256, 8)])
-def test_tiled_gemm_tile_sizes_and_k_splits(tile, split):
+@pytest.mark.parametrize("tile,split,tails", [(128, 0, 0), (128, 1, 0), (128, 3, 0), (256, 0, 0), (256, 1, 0), (256, 2, 0), (256, 8, 0),
+                                              (128, 1, 2), (256, 1, 2), (0, 0, 2), (128, 1, 1)])
+def test_tiled_gemm_tile_sizes_and_k_splits(tile, split, tails):
     # more than 64 tokens take the tiled GEMM: both block tiles, automatic and forced K splits, on token
     # counts that leave ragged row tiles (65: one row past a 64-row wavefront tile; 300: 256 + 44;
     # 530: two full 256-row tiles + 18) and on widths that leave ragged column tiles (704-wide FFN:
-    # 1408 = 5.5 x 256 gate/up columns; 256-wide hidden = one column tile)
+    # 1408 = 5.5 x 256 gate/up columns; 256-wide hidden = one column tile); tails: 2 = every last, partial wave of tiles has
+    # its K loops cut over all blocks (parked pieces, arrival counters, the last block adds them up), 1 = none has
     for chunk, decodes in ((65, []), (280, [7] * 20), (500, [40] * 30)):
         b = W.custom_batch("tiny", 17, chunk, 32, decodes, name="tiles")
-        c = Case(b, options={"gemm_tile": tile, "gemm_split_k": split})
+        c = Case(b, options={"gemm_tile": tile, "gemm_split_k": split, "gemm_whole_tiles": tails})
         errs = c.run()
-        _assert_errs(errs, f"tile={tile} split={split} T={b.n_tokens}")
+        _assert_errs(errs, f"tile={tile} split={split} tails={tails} T={b.n_tokens}")
         c.check_pool()
         c.close()
 
