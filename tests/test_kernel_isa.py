@@ -96,3 +96,50 @@ def test_accumulators_are_not_read_right_behind_the_last_matrix_instruction(gemm
         assert len(nops) == 2 and nops[1] == nops[0] + 1 and nops[0] > last, (name, nops, last)
         users = [i for i, l in enumerate(lines) if i > last and re.match(r"(global_store|ds_write|v_accvgpr_read)", l) and re.search(r"\ba\[?\d", l)]
         assert users and min(users) > nops[1], (name, min(users) if users else None, nops)
+
+
+@pytest.fixture(scope="module")
+def attn_asm():
+    with tempfile.TemporaryDirectory() as tmp:
+        out = os.path.join(tmp, "attention.s")
+        flags = [f for f in B.FLAGS if f != "-fPIC"]
+        cmd = [B.HIPCC] + flags + ["--cuda-device-only", "-S", os.path.join(B.CSRC, "attention.hip"), "-o", out]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
+        return open(out).read()
+
+
+def test_attention_kernel_keeps_two_blocks_per_compute_unit(attn_asm):
+    """The attention plan counts on every block of the launch being resident at once: two blocks of four wavefronts per
+    compute unit, i.e. at most 256 registers per lane and no more than half the LDS per block, and nothing spilled.  The
+    teams' LDS reads are assembly whose waits the kernel places itself: the loop that holds the barrier must not drain
+    the copy queue (a wait for all outstanding loads would undo the two pairs kept in flight)."""
+    n = 0
+    for m in re.finditer(r"^\s*\.amdhsa_kernel (_ZN2ps11attn_kernel\w+)(.*?)\.end_amdhsa_kernel", attn_asm, re.S | re.M):
+        body = m.group(2)
+        get = lambda key: int(re.search(key + r" (\d+)", body).group(1))
+        assert get(r"\.amdhsa_private_segment_fixed_size") == 0, m.group(1)
+        assert get(r"\.amdhsa_next_free_vgpr") <= 256, (m.group(1), get(r"\.amdhsa_next_free_vgpr"))
+        assert get(r"\.amdhsa_group_segment_fixed_size") <= 80 * 1024, m.group(1)
+        n += 1
+    assert n == 10          # head dims 64 and 128 x group sizes 1, 2, 4, 8, 16
+    for m in re.finditer(r"^(_ZN2ps11attn_kernelILi128E\w+):\s*;.*?\n(.*?)s_endpgm", attn_asm, re.S | re.M):
+        lines = [l.strip() for l in m.group(2).splitlines() if l.strip() and not l.strip().startswith(";")]
+        labels = {mm.group(1): i for i, l in enumerate(lines) for mm in [re.match(r"(\.LBB\d+_\d+):", l)] if mm}
+        loops = []
+        for i, l in enumerate(lines):
+            mm = re.match(r"s_c?branch\w* (\.LBB\d+_\d+)$", l)
+            if mm and mm.group(1) in labels and labels[mm.group(1)] < i:
+                body = lines[labels[mm.group(1)]:i + 1]
+                if any(x == "s_barrier" for x in body) and any(x.startswith("v_mfma") for x in body):
+                    loops.append(body)
+        assert loops, m.group(1)
+        team = min(loops, key=len)           # the innermost loop with a barrier and matrix instructions: a team's pair loop
+        ops = [l.split()[0] for l in team]
+        assert ops.count("s_barrier") == 1, (m.group(1), ops.count("s_barrier"))
+        assert sum(o.startswith("global_load_lds") for o in ops) == 4, m.group(1)       # a quarter of a pair per wavefront
+        assert sum(o == "v_mfma_f32_16x16x32_bf16" for o in ops) == 34, m.group(1)      # 16 for the scores, 16 + 2 for P.V and the row sums
+        assert not any(o.startswith("scratch_") for o in ops), m.group(1)
+        # the only full drain of the load queue sits in the rarely taken branch that reloads the page-id table
+        drains = [i for i, l in enumerate(team) if l.startswith("s_waitcnt") and "vmcnt(0)" in l]
+        assert len(drains) <= 1, (m.group(1), drains)
