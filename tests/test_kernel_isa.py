@@ -143,3 +143,58 @@ def test_attention_kernel_keeps_two_blocks_per_compute_unit(attn_asm):
         # the only full drain of the load queue sits in the rarely taken branch that reloads the page-id table
         drains = [i for i, l in enumerate(team) if l.startswith("s_waitcnt") and "vmcnt(0)" in l]
         assert len(drains) <= 1, (m.group(1), drains)
+
+
+def _regs(text):
+    out = set()
+    for m in re.finditer(r"\bv\[(\d+):(\d+)\]", text):
+        out.update(range(int(m.group(1)), int(m.group(2)) + 1))
+    for m in re.finditer(r"\bv(\d+)\b", text):
+        out.add(int(m.group(1)))
+    return out
+
+
+def _touched_before_their_wait(lines):
+    """Vector registers that an LDS read is still writing when another instruction names them.  LDS operations retire
+    in order, so `s_waitcnt lgkmcnt(n)` leaves the last n outstanding; the scan follows the code in layout order."""
+    pending, bad = [], []
+    for i, l in enumerate(lines):
+        if not l or l.startswith(".LBB") or l.startswith(";"):
+            continue
+        op = l.split()[0]
+        if op == "s_waitcnt":
+            m = re.search(r"lgkmcnt\((\d+)\)", l)
+            if m:
+                n = int(m.group(1))
+                pending = pending[len(pending) - n:] if n > 0 else []
+            continue
+        is_read = op.startswith("ds_read")
+        touched = _regs(",".join(l.split(",")[1:])) if is_read else _regs(l)
+        if any(p & touched for p in pending):
+            bad.append((i, l))
+        if op.startswith("ds_"):
+            pending.append(_regs(l.split(",")[0]) if is_read else set())
+    return bad
+
+
+def test_the_scan_for_early_uses_finds_a_planted_one():
+    ok = ["ds_read_b128 v[4:7], v2 offset:16", "v_add_f32_e32 v9, v8, v8", "s_waitcnt lgkmcnt(0)", "v_mov_b32_e32 v9, v5"]
+    assert not _touched_before_their_wait(ok)
+    early = ["ds_read_b128 v[4:7], v2 offset:16", "v_mov_b32_e32 v9, v5", "s_waitcnt lgkmcnt(0)"]
+    assert _touched_before_their_wait(early) == [(1, early[1])]
+    partial = ["ds_read_b64 v[4:5], v2", "ds_read_b64 v[6:7], v2 offset:8", "s_waitcnt lgkmcnt(1)", "v_mov_b32_e32 v9, v4", "v_mov_b32_e32 v9, v6"]
+    assert _touched_before_their_wait(partial) == [(4, partial[4])]
+
+
+def test_no_register_is_used_while_an_lds_read_is_still_writing_it(gemm_asm, attn_asm):
+    """The tiled GEMM and the attention teams read LDS through assembly whose results the compiler believes valid at
+    once; the kernels wait for them with statements that name the registers.  Anywhere in these kernels, loop or not, a
+    register copy or an operand use that the compiler slipped in between a read and its wait would read stale data."""
+    n = 0
+    for asm, pat in ((gemm_asm, "gemm_sk_kernel"), (gemm_asm, "gemm_wstream_kernel"), (attn_asm, "attn_kernel")):
+        for m in re.finditer(r"^(\S*" + pat + r"\S*):\s*;.*?\n(.*?)s_endpgm", asm, re.S | re.M):
+            lines = [x.strip() for x in m.group(2).splitlines()]
+            bad = _touched_before_their_wait(lines)
+            assert not bad, (m.group(1), bad[:3])
+            n += 1
+    assert n >= 4 + 10
