@@ -268,7 +268,7 @@ ps_status ps_step_indices(ps_ctx* ctx, const ps_seq* seqs, int32_t n_seqs, int32
  *  first KV page (logical), one past last KV page, partial slot or -1 when the item
  *  writes final output, worker}.  Items are listed worker by worker.  Query blocks of sequences with more
  * new tokens than one 16-row tile holds (16 / (n_q_heads / n_kv_heads)) belong to teams (blocks of four
- * wavefronts; eight tiles per item), which come first; the others to single wavefronts.  Within either
+ * wavefronts; twelve tiles per item), which come first; the others to single wavefronts.  Within either
  * kind every worker's items carry (nearly) the same number of KV pages.  Writes min(*n_items, cap) items. */
 ps_status ps_plan_attention(ps_ctx* ctx, const ps_seq* seqs, int32_t n_seqs, int32_t* items, int32_t cap, int32_t* n_items);
 

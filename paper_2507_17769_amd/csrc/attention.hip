@@ -9,7 +9,8 @@
 // the current pair is consumed.  The query blocks of a prefill chunk belong to teams: the four
 // wavefronts of a block take TEAM_NT query tiles each and share every pair of pages through a ring
 // in LDS that global_load_lds fills two pairs ahead, so a pair is fetched from L2 once per 4 TEAM_NT
-// tiles and needs no registers while in flight.  A query
+// tiles and needs no registers while in flight (three tiles are what the register file holds: the
+// accumulators of the tiles, their queries and one set of K and V operands).  A query
 // tile is 16 rows = (16/G tokens) x (G query heads of the kv head), so every K/V byte is
 // read once for the whole GQA group.  Per pair of 16-token pages:
 //     S^T[key][row]  = K . Q^T      (MFMA 16x16x32, K chunk is the A operand)
@@ -282,10 +283,9 @@ __device__ __forceinline__ void attn_item(const AttnArgs& a, const AttnItem it) 
 
 // ---- teams: the query blocks of a prefill chunk ---------------------------------------------------
 constexpr int TEAM_WAVES = 4;
-constexpr int TEAM_NT = 2;     // query tiles per wavefront
+constexpr int TEAM_NT = 3;     // query tiles per wavefront
 constexpr int TEAM_RING = 3;   // pairs of pages in LDS: the one in use, and two on their way
 
-typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ u32x2_t lds_read8(uint32_t addr, int off) {
     u32x2_t v;
     asm volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(off) : "memory");
@@ -345,7 +345,7 @@ __device__ __forceinline__ bf16x8_t team_softmax(bool mask, const f32x4_t& sa, c
 // the V operand of a d-tile is the same 8-byte half of the two V blocks, read as such, so no register is moved.
 template <int D, int NT>
 __device__ __forceinline__ void team_pair(TileState<D, NT>& st, f32x4_t (&lacc)[NT], uint32_t addr, const bf16x8_t (&qf)[NT][D / 32],
-                                          const int (&pq)[NT], int kpos_a, float scale2, bool mask) {
+                                          int pos_row, int tok_step, int pos_max, int kpos_a, float scale2, bool mask) {
     constexpr int KS = D / 32, DT = D / 16;
     u32x4_t kk[2 * KS];
 #pragma unroll
@@ -377,7 +377,7 @@ __device__ __forceinline__ void team_pair(TileState<D, NT>& st, f32x4_t (&lacc)[
     bf16x8_t pf[NT];
     float alpha[NT];
 #pragma unroll
-    for (int nt = 0; nt < NT; nt++) pf[nt] = team_softmax(mask, sa[nt], sb[nt], st.m[nt], alpha[nt], pq[nt], kpos_a, scale2);
+    for (int nt = 0; nt < NT; nt++) pf[nt] = team_softmax(mask, sa[nt], sb[nt], st.m[nt], alpha[nt], min(pos_row + nt * tok_step, pos_max), kpos_a, scale2);
     if constexpr (DT == 8)
         asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(va[0]), "+v"(va[1]), "+v"(va[2]), "+v"(va[3]), "+v"(va[4]), "+v"(va[5]), "+v"(va[6]), "+v"(va[7]),
                      "+v"(vb[0]), "+v"(vb[1]), "+v"(vb[2]), "+v"(vb[3]), "+v"(vb[4]), "+v"(vb[5]), "+v"(vb[6]), "+v"(vb[7]));
@@ -420,17 +420,15 @@ __device__ __forceinline__ void team_item(const AttnArgs& a, const AttnItem it, 
     const int32_t* pages = a.pages + it.page_off;
     const int head = it.kv_head * G + (r % G);
 
-    int qi[NT], pq[NT];
-    bool rvalid[NT];
+    // Row (lane r) of tile nt of this wavefront is token (wave NT + nt) TQ + r / G of the block, clamped to the block's
+    // last token (rows past it compute on that token's data and are not stored).  Only the queries stay in registers:
+    // positions for the masks and token indices for the stores are formed again where they are needed.
+    const int tok_row = wave * NT * TQ + r / G;
     bf16x8_t qf[NT][KS];
 #pragma unroll
     for (int nt = 0; nt < NT; nt++) {
-        const int ql = (wave * NT + nt) * TQ + r / G;  // token of the row within the block
-        rvalid[nt] = ql < it.q_ntok;
-        const int qc = min(ql, it.q_ntok - 1);
-        qi[nt] = it.tok_g0 + qc;
-        pq[nt] = it.pos0 + qc;
-        const bf16_t* qrow = a.q + (size_t)qi[nt] * a.ldq + head * D + 8 * g;
+        const int qc = min(tok_row + nt * TQ, it.q_ntok - 1);
+        const bf16_t* qrow = a.q + (size_t)(it.tok_g0 + qc) * a.ldq + head * D + 8 * g;
 #pragma unroll
         for (int s = 0; s < KS; s++) qf[nt][s] = as_bf16x8(ldg16(qrow + 32 * s));
     }
@@ -496,7 +494,8 @@ __device__ __forceinline__ void team_item(const AttnArgs& a, const AttnItem it, 
         __builtin_amdgcn_s_barrier();
         issue(i + 2, slot >= 1 ? slot - 1 : TEAM_RING - 1);     // (i + 2) % 3
         const int kpos0 = (it.page_begin + 2 * i) * 16;
-        team_pair<D, NT>(st, lacc, ring0 + slot * PAIR_BYTES + lane * 16, qf, pq, kpos0 + 4 * g, scale2, kpos0 + 31 > pos_first);
+        team_pair<D, NT>(st, lacc, ring0 + slot * PAIR_BYTES + lane * 16, qf, it.pos0 + tok_row, TQ, it.pos0 + it.q_ntok - 1, kpos0 + 4 * g, scale2,
+                         kpos0 + 31 > pos_first);
         slot = slot + 1 == TEAM_RING ? 0 : slot + 1;
     }
     for (int i = n_mine; i < n_pairs; i++) {
@@ -506,8 +505,14 @@ __device__ __forceinline__ void team_item(const AttnArgs& a, const AttnItem it, 
         slot = slot + 1 == TEAM_RING ? 0 : slot + 1;
     }
     vm_wait<0>();   // the surplus copies have landed before the ring is used again
+    int qi[NT];
+    bool rvalid[NT];
 #pragma unroll
-    for (int nt = 0; nt < NT; nt++) st.lsum[nt] = lacc[nt][0];
+    for (int nt = 0; nt < NT; nt++) {
+        st.lsum[nt] = lacc[nt][0];
+        rvalid[nt] = tok_row + nt * TQ < it.q_ntok;
+        qi[nt] = it.tok_g0 + min(tok_row + nt * TQ, it.q_ntok - 1);
+    }
     if (wave_has_rows) store_tiles<D, G, NT>(a, it, st, qi, rvalid, wave * NT, lane);
 }
 

@@ -141,7 +141,7 @@ def test_allocator_matches_oracle_bit_exact():
     assert e.value.status == B.PS_EINVAL
 
 
-TEAM_TILES = 8   # query tiles of a team item: four wavefronts with two tiles each
+TEAM_TILES = 12   # query tiles of a team item: four wavefronts with three tiles each
 
 
 def _check_plan_covers(b, c, workers=None):
