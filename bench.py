@@ -290,6 +290,16 @@ def run_cfg4(a):
     eng.ctx.set_option("time_gemm", 5)
     eng.ctx.set_option("time_attention", 5)
     ms, host_us, wall_ms = timed_steps(eng, lambda i: eng.ctx.step(seqs, x.data_ptr(), out.data_ptr()), a.steps, a.warmup)
+    # The host's own work per step (plan, metadata, 800 launches): a call into an empty queue, three times.  Inside the timed
+    # region the host runs one step ahead and then waits for room in the launch queue, so its time per call there equals
+    # the device's.
+    idle_us = []
+    for i in range(3):
+        eng.ctx.sync()
+        h0 = time.perf_counter()
+        eng.ctx.step(seqs, x.data_ptr(), out.data_ptr())
+        idle_us.append((time.perf_counter() - h0) * 1e6)
+    eng.ctx.sync()
     gemm_recs = np.array(eng.ctx.gemm_times(), dtype=np.float64).reshape(-1, 4)
     attn_ms = eng.ctx.attention_times()
     eng.ctx.set_option("time_gemm", 0)
@@ -312,6 +322,7 @@ def run_cfg4(a):
                                   f"16-token pages, seed {a.seed}", "n_tokens": T, "total_kv": total_kv, "n_layers": L},
            "ms_per_step_events": percentiles(ms), "wall_ms_per_step": wall_ms / a.steps,
            "host_us_per_step": round(float(np.median(host_us)), 1),
+           "host_us_per_step_into_an_empty_queue": round(float(np.median(idle_us)), 1),
            "roofline": {"bound": "mfma", "kernel": "gemm_sk_kernel: the four projection launches of one layer (QKV, O, gate/up + SwiGLU, down)",
                         "achieved": tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tflops / MFMA_BF16_PEAK_TFLOPS,
                         "traffic": measured_traffic("cfg4", a.seed),
