@@ -88,7 +88,7 @@ struct ps_ctx {
     // options / debug
     int opt_attn_workers = 0;
     int opt_attn_teams = 0;
-    int opt_attn_prefill_weight = 25;
+    int opt_attn_prefill_weight = 22;
     int worker_slots = 2048;
     int opt_gemm_split_k = 0;
     int opt_gemm_tile = 0;

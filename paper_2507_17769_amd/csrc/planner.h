@@ -38,7 +38,7 @@ struct PlanConfig {
     // cost model behind the split of the blocks: nanoseconds a team spends on a pair of pages while it has its CU's
     // matrix units to itself and the streams keep HBM busy, the relative growth of that when two teams share every CU, HBM time of a pair streamed
     // by a single wavefront (all of them together), time a lone wavefront needs for a pair
-    double team_pair_ns = 2500.0, team_crowding = 0.85, hbm_pair_ns = 2.75, wave_pair_ns = 2000.0;
+    double team_pair_ns = 2200.0, team_crowding = 0.85, hbm_pair_ns = 2.75, wave_pair_ns = 2000.0;
 };
 
 // Validates the batch (see ps_seq in polystep.h).  On failure returns PS_EINVAL / PS_ERANGE

@@ -73,7 +73,7 @@ def test_planner_under_sanitizers_matches_the_library(driver):
             elif k == 5 and len(seqs) > 1: seqs[0][0] = seqs[-1][0]
             if k == 4 and len(seqs) > 1 and s[3] and rng.random() < 0.5: s[3][0] = seqs[0][3][-1] if seqs[0] is not s and seqs[0][3] else n_pool + 3   # a shared page
         cases.append((n_kv, group, max_pos, n_pool, n_workers, seqs))
-        lines.append(f"{n_kv} {group} {max_pos} {n_pool} {n_workers} 512 {12 * (16 // group)} 25 {len(seqs)}")
+        lines.append(f"{n_kv} {group} {max_pos} {n_pool} {n_workers} 512 {12 * (16 // group)} 22 {len(seqs)}")
         for rid, n_new, kv_len, pages in seqs:
             lines.append(f"{rid} {n_new} {kv_len} {len(pages)} " + " ".join(str(p) for p in pages))
     out = _run(driver, "plan", f"{len(cases)}\n" + "\n".join(lines) + "\n")
